@@ -1,0 +1,242 @@
+"""numpy front end of the C oracle (dsfq_oracle.c).  Test infrastructure only.
+
+Every function here converts its arguments to exact doubles / int8, calls one C
+routine, and returns numpy arrays.  `prepare_weights` and `linear` chain the
+routines in the order the paper states the method (Sec. 3.2: rotate, smooth,
+quantize per token / per output channel, integer product, dequantise).
+"""
+from __future__ import annotations
+
+import ctypes as C
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+from . import build as _build
+
+_lib = C.CDLL(_build.build())
+
+_dp = C.POINTER(C.c_double)
+_i8p = C.POINTER(C.c_int8)
+_u8p = C.POINTER(C.c_uint8)
+_u16p = C.POINTER(C.c_uint16)
+_i32p = C.POINTER(C.c_int32)
+
+_lib.orc_bf16_from_double.restype = C.c_uint16
+_lib.orc_bf16_from_double.argtypes = [C.c_double]
+_lib.orc_bf16_from_double_array.restype = None
+_lib.orc_bf16_to_double.restype = C.c_double
+_lib.orc_bf16_to_double.argtypes = [C.c_uint16]
+
+
+class OracleError(RuntimeError):
+    pass
+
+
+def _chk(rc: int, what: str):
+    if rc != 0:
+        raise OracleError(f"{what}: oracle status {rc}")
+
+
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _ptr(a: Optional[np.ndarray], typ):
+    return None if a is None else a.ctypes.data_as(typ)
+
+
+def _signs(s) -> Optional[np.ndarray]:
+    if s is None:
+        return None
+    s = np.ascontiguousarray(s, dtype=np.int8)
+    if not np.all(np.abs(s) == 1):
+        raise ValueError("signs must be +1/-1")
+    return s
+
+
+# ------------------------------------------------------------------ conversions
+def bf16_bits_to_f64(bits) -> np.ndarray:
+    """bf16 bit patterns (uint16) -> double, exact."""
+    b = np.ascontiguousarray(bits, dtype=np.uint16)
+    return (b.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def to_f64(x) -> np.ndarray:
+    """Exact double copy of a synthetic tensor: uint16 arrays are bf16 bits, float arrays are values."""
+    x = np.asarray(x)
+    return bf16_bits_to_f64(x) if x.dtype == np.uint16 else _f64(x)
+
+
+def bf16_from_f64(v) -> np.ndarray:
+    """double -> bf16 bits, one rounding (nearest, ties to even)."""
+    v = _f64(v)
+    out = np.empty(v.shape, dtype=np.uint16)
+    _lib.orc_bf16_from_double_array(_ptr(v, _dp), C.c_size_t(v.size), _ptr(out, _u16p))
+    return out
+
+
+# ------------------------------------------------------------------ steps
+def hadamard(K: int, form: str = "recursive") -> np.ndarray:
+    """Unnormalised K x K Sylvester Hadamard matrix (int8 entries +-1)."""
+    H = np.empty((K, K), dtype=np.int8)
+    fn = _lib.orc_hadamard_recursive if form == "recursive" else _lib.orc_hadamard_popcount
+    _chk(fn(C.c_int(K), _ptr(H, _i8p)), "hadamard")
+    return H
+
+
+def rotate(X, pre_signs=None, post_signs=None) -> np.ndarray:
+    """X . H with H = diag(pre) . Hhat . diag(post), Hhat the orthonormal Hadamard."""
+    X = _f64(X)
+    rows, K = X.shape
+    pre, post = _signs(pre_signs), _signs(post_signs)
+    out = np.empty_like(X)
+    _chk(_lib.orc_rotate(_ptr(X, _dp), C.c_int(rows), C.c_int(K), _ptr(pre, _i8p), _ptr(post, _i8p),
+                         _ptr(out, _dp)), "rotate")
+    return out
+
+
+def col_absmax(A) -> np.ndarray:
+    A = _f64(A)
+    out = np.empty(A.shape[1], dtype=np.float64)
+    _chk(_lib.orc_col_absmax(_ptr(A, _dp), C.c_int(A.shape[0]), C.c_int(A.shape[1]), _ptr(out, _dp)),
+         "col_absmax")
+    return out
+
+
+SMOOTH_FLOOR = 1e-5
+
+
+def smooth_factor(a, w, alpha: float = 0.5, floor: float = SMOOTH_FLOOR) -> np.ndarray:
+    a, w = _f64(a), _f64(w)
+    c = np.empty_like(a)
+    _chk(_lib.orc_smooth_factor(_ptr(a, _dp), _ptr(w, _dp), C.c_int(a.size), C.c_double(alpha),
+                                C.c_double(floor), _ptr(c, _dp)), "smooth_factor")
+    return c
+
+
+def scale_columns(A, c, inverse: bool) -> np.ndarray:
+    A = _f64(A).copy()
+    c = _f64(c)
+    _chk(_lib.orc_scale_columns(_ptr(A, _dp), C.c_int(A.shape[0]), C.c_int(A.shape[1]), _ptr(c, _dp),
+                                C.c_int(1 if inverse else 0)), "scale_columns")
+    return A
+
+
+def quantize_rows(A, bits: int = 4):
+    """Per-row symmetric quantizer: returns (delta [rows] f64, codes [rows, K] int8)."""
+    A = _f64(A)
+    rows, K = A.shape
+    delta = np.empty(rows, dtype=np.float64)
+    q = np.empty((rows, K), dtype=np.int8)
+    _chk(_lib.orc_quantize_rows(_ptr(A, _dp), C.c_int(rows), C.c_int(K), C.c_int(bits), _ptr(delta, _dp),
+                                _ptr(q, _i8p)), "quantize_rows")
+    return delta, q
+
+
+def quantize_rows_static(A, delta, bits: int = 4) -> np.ndarray:
+    A, delta = _f64(A), _f64(delta)
+    rows, K = A.shape
+    q = np.empty((rows, K), dtype=np.int8)
+    _chk(_lib.orc_quantize_rows_static(_ptr(A, _dp), C.c_int(rows), C.c_int(K), C.c_int(bits),
+                                       _ptr(delta, _dp), _ptr(q, _i8p)), "quantize_rows_static")
+    return q
+
+
+def int_gemm(qx, qw) -> np.ndarray:
+    qx = np.ascontiguousarray(qx, dtype=np.int8)
+    qw = np.ascontiguousarray(qw, dtype=np.int8)
+    M, K = qx.shape
+    N, K2 = qw.shape
+    if K != K2:
+        raise ValueError("inner dimensions differ")
+    acc = np.empty((M, N), dtype=np.int32)
+    _chk(_lib.orc_int_gemm(_ptr(qx, _i8p), _ptr(qw, _i8p), C.c_int(M), C.c_int(N), C.c_int(K),
+                           _ptr(acc, _i32p)), "int_gemm")
+    return acc
+
+
+def dequant_bias(acc, dx, dw, bias=None, want_f64: bool = False):
+    """Y = bf16(acc * dx[:,None] * dw[None,:] + bias): returns bf16 bits (and the f64 values)."""
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    M, N = acc.shape
+    dx, dw = _f64(dx), _f64(dw)
+    b = None if bias is None else _f64(bias)
+    Y = np.empty((M, N), dtype=np.uint16)
+    y = np.empty((M, N), dtype=np.float64) if want_f64 else None
+    _chk(_lib.orc_dequant_bias(_ptr(acc, _i32p), _ptr(dx, _dp), _ptr(dw, _dp), _ptr(b, _dp), C.c_int(M),
+                               C.c_int(N), _ptr(Y, _u16p), _ptr(y, _dp)), "dequant_bias")
+    return (Y, y) if want_f64 else Y
+
+
+def pack_int4(q) -> np.ndarray:
+    q = np.ascontiguousarray(q, dtype=np.int8)
+    rows, K = q.shape
+    out = np.empty((rows, K // 2), dtype=np.uint8)
+    _chk(_lib.orc_pack_int4(_ptr(q, _i8p), C.c_int(rows), C.c_int(K), _ptr(out, _u8p)), "pack_int4")
+    return out
+
+
+def unpack_int4(packed, K: int) -> np.ndarray:
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    rows = packed.shape[0]
+    out = np.empty((rows, K), dtype=np.int8)
+    _chk(_lib.orc_unpack_int4(_ptr(packed, _u8p), C.c_int(rows), C.c_int(K), _ptr(out, _i8p)), "unpack_int4")
+    return out
+
+
+# ------------------------------------------------------------------ the method, step by step
+@dataclass
+class PreparedWeights:
+    qw: np.ndarray        # [N, K] int8 codes of diag(c) H^T W^T, per output channel
+    dw: np.ndarray        # [N] weight steps
+    c_hat: np.ndarray     # [K] smoothing factor
+    w_colmax: np.ndarray  # [K] max_o |W H|[o, j]
+    Ws: np.ndarray        # [N, K] rotated, smoothed weights before quantization
+
+
+def prepare_weights(W, act_absmax_rot=None, pre_signs=None, post_signs=None, alpha: float = 0.5,
+                    bits: int = 4) -> PreparedWeights:
+    """Offline half: rotate W, form c_hat from the rotated statistics, smooth, quantize per output channel.
+
+    act_absmax_rot[j] = max_t |X_cal H|[t, j]; None means no smoothing (c_hat = 1).
+    """
+    Wr = rotate(to_f64(W), pre_signs, post_signs)
+    w_colmax = col_absmax(Wr)
+    if act_absmax_rot is None:
+        c_hat = np.ones(Wr.shape[1], dtype=np.float64)
+    else:
+        c_hat = smooth_factor(act_absmax_rot, w_colmax, alpha)
+    Ws = scale_columns(Wr, c_hat, inverse=False)
+    dw, qw = quantize_rows(Ws, bits)
+    return PreparedWeights(qw, dw, c_hat, w_colmax, Ws)
+
+
+def rotated_col_absmax(X_cal, pre_signs=None, post_signs=None) -> np.ndarray:
+    return col_absmax(rotate(to_f64(X_cal), pre_signs, post_signs))
+
+
+def rotate_smooth_quant(X, c_hat=None, pre_signs=None, post_signs=None, bits: int = 4):
+    """Online half up to the codes: returns (dx [M], qx [M, K] int8, Xs [M, K] f64)."""
+    Xr = rotate(to_f64(X), pre_signs, post_signs)
+    Xs = Xr if c_hat is None else scale_columns(Xr, c_hat, inverse=True)
+    dx, qx = quantize_rows(Xs, bits)
+    return dx, qx, Xs
+
+
+@dataclass
+class LinearResult:
+    Y: np.ndarray     # bf16 bits [M, N]
+    y: np.ndarray     # f64 [M, N] before the bf16 rounding
+    acc: np.ndarray   # int32 [M, N]
+    qx: np.ndarray    # int8 [M, K]
+    dx: np.ndarray    # f64 [M]
+
+
+def linear(X, prep: PreparedWeights, bias=None, pre_signs=None, post_signs=None, bits: int = 4) -> LinearResult:
+    dx, qx, _ = rotate_smooth_quant(X, prep.c_hat, pre_signs, post_signs, bits)
+    acc = int_gemm(qx, prep.qw)
+    b = None if bias is None else to_f64(bias)
+    Y, y = dequant_bias(acc, dx, prep.dw, b, want_f64=True)
+    return LinearResult(Y, y, acc, qx, dx)

@@ -1,0 +1,196 @@
+"""Pins of the oracle's smoothing, quantizer, integer GEMM, epilogue and packing."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ----------------------------------------------------------------- smoothing (Eq. "smooth_factor")
+def _smooth_setup(alpha, seed=0, K=128):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_t(3, (40, K)) * rng.choice([1.0, 30.0], size=K, p=[0.95, 0.05])
+    W = rng.standard_normal((24, K)) * 0.02
+    Xr, Wr = oracle.rotate(X), oracle.rotate(W)
+    a, w = oracle.col_absmax(Xr), oracle.col_absmax(Wr)
+    c = oracle.smooth_factor(a, w, alpha)
+    return X, W, Xr, Wr, a, w, c
+
+
+@pytest.mark.parametrize("alpha", [0.0, 0.3, 0.5, 1.0])
+def test_smoothing_identity(alpha):
+    X, W, Xr, Wr, a, w, c = _smooth_setup(alpha)
+    Xs = oracle.scale_columns(Xr, c, inverse=True)
+    Ws = oracle.scale_columns(Wr, c, inverse=False)
+    ref = X @ W.T
+    assert np.abs(Xs @ Ws.T - ref).max() <= 1e-10 * np.abs(ref).max()
+
+
+def test_smoothing_closed_forms():
+    # alpha = 1: every activation column is normalised to absmax 1 (and the weights take it all)
+    X, W, Xr, Wr, a, w, c = _smooth_setup(1.0)
+    assert np.allclose(np.abs(oracle.scale_columns(Xr, c, True)).max(axis=0), 1.0, rtol=1e-12)
+    assert np.allclose(np.abs(oracle.scale_columns(Wr, c, False)).max(axis=0), a * w, rtol=1e-12)
+    # alpha = 0: every weight column is normalised to absmax 1
+    X, W, Xr, Wr, a, w, c = _smooth_setup(0.0)
+    assert np.allclose(np.abs(oracle.scale_columns(Wr, c, False)).max(axis=0), 1.0, rtol=1e-12)
+    # alpha = 0.5: both sides end at sqrt(a_j w_j)
+    X, W, Xr, Wr, a, w, c = _smooth_setup(0.5)
+    g = np.sqrt(a * w)
+    assert np.allclose(np.abs(oracle.scale_columns(Xr, c, True)).max(axis=0), g, rtol=1e-12)
+    assert np.allclose(np.abs(oracle.scale_columns(Wr, c, False)).max(axis=0), g, rtol=1e-12)
+
+
+def test_col_absmax_is_over_rows():
+    A = np.array([[1.0, -9.0, 2.0], [-3.0, 4.0, 0.5]])
+    assert np.array_equal(oracle.col_absmax(A), np.array([3.0, 9.0, 2.0]))
+
+
+def test_smooth_factor_floor_and_values():
+    c = oracle.smooth_factor(np.array([4.0, 0.0, 9.0]), np.array([1.0, 4.0, 0.0]), 0.5, floor=1e-4)
+    assert np.allclose(c, [2.0, 1e-2 / 2.0, 3.0 / 1e-2], rtol=1e-14)
+
+
+# ----------------------------------------------------------------- quantizer (Eq. "quantization")
+def _read_cases():
+    cases, cur = [], {}
+    for line in open(os.path.join(GOLD, "quantizer_rows.txt")):
+        line = line.strip()
+        if not line or line[0] == "#":
+            continue
+        tag, vals = line[0], [float(v) for v in line[1:].split()]
+        cur[tag] = vals
+        if tag == "q":
+            cases.append(cur)
+            cur = {}
+    return cases
+
+
+def test_quantizer_hand_worked_rows():
+    cases = _read_cases()
+    assert len(cases) == 4
+    for c in cases:
+        d, q = oracle.quantize_rows(np.array([c["x"]]), 4)
+        assert d[0] == c["d"][0]
+        assert q[0].tolist() == [int(v) for v in c["q"]]
+
+
+def test_quantizer_properties():
+    rng = np.random.default_rng(5)
+    A = rng.standard_t(3, (50, 256)) * 3.7
+    d, q = oracle.quantize_rows(A, 4)
+    assert np.allclose(d, np.abs(A).max(axis=1) / 7.0, rtol=1e-15)
+    assert q.min() >= -7 and q.max() <= 7            # -8 is unreachable with a dynamic absmax step
+    err = np.abs(A - d[:, None] * q)
+    assert np.all(err <= d[:, None] / 2 * (1 + 1e-12))
+    # the absmax element gets code +-7
+    j = np.abs(A).argmax(axis=1)
+    assert np.array_equal(np.abs(q[np.arange(50), j]), np.full(50, 7))
+    # odd symmetry and positive-scale equivariance
+    d2, q2 = oracle.quantize_rows(-A, 4)
+    assert np.array_equal(q2, -q) and np.array_equal(d2, d)
+    d3, q3 = oracle.quantize_rows(A * 8.0, 4)         # power of two: exact
+    assert np.array_equal(q3, q) and np.array_equal(d3, d * 8.0)
+    # rows are quantized independently: scaling one row leaves the others alone
+    B = A.copy()
+    B[3] *= 1000.0
+    d4, q4 = oracle.quantize_rows(B, 4)
+    assert np.array_equal(np.delete(q4, 3, 0), np.delete(q, 3, 0))
+    # other bit-widths follow the same definition
+    d8, q8 = oracle.quantize_rows(A, 8)
+    assert np.allclose(d8, np.abs(A).max(axis=1) / 127.0) and q8.max() == 127 or q8.min() == -127
+
+
+def test_quantizer_clamp_is_live_with_a_static_step():
+    A = np.array([[-100.0, -7.6, 7.4, 7.6, 100.0, -8.5]])
+    q = oracle.quantize_rows_static(A, np.array([1.0]), 4)
+    assert q[0].tolist() == [-8, -8, 7, 7, 7, -8]
+
+
+# ----------------------------------------------------------------- integer GEMM
+def test_int_gemm_brute_force_and_library():
+    rng = np.random.default_rng(6)
+    M, N, K = 5, 7, 12
+    qx = rng.integers(-8, 8, (M, K)).astype(np.int8)
+    qw = rng.integers(-8, 8, (N, K)).astype(np.int8)
+    acc = oracle.int_gemm(qx, qw)
+    brute = [[sum(int(qx[t, j]) * int(qw[o, j]) for j in range(K)) for o in range(N)] for t in range(M)]
+    assert acc.tolist() == brute
+    # second loop order: accumulate rank-1 updates over j
+    acc2 = np.zeros((M, N), dtype=np.int64)
+    for j in range(K):
+        acc2 += np.outer(qx[:, j].astype(np.int64), qw[:, j].astype(np.int64))
+    assert np.array_equal(acc, acc2)
+
+
+def test_int_gemm_config1_against_numpy_and_bounds():
+    rng = np.random.default_rng(7)
+    qx = rng.integers(-8, 8, (64, 128)).astype(np.int8)
+    qw = rng.integers(-8, 8, (128, 128)).astype(np.int8)
+    acc = oracle.int_gemm(qx, qw)
+    assert np.array_equal(acc, qx.astype(np.int64) @ qw.astype(np.int64).T)
+    assert np.abs(acc).max() <= 64 * 128
+    # extreme codes reach the bound exactly
+    full = oracle.int_gemm(np.full((2, 4096), -8, np.int8), np.full((3, 4096), -8, np.int8))
+    assert np.all(full == 64 * 4096)
+    # selecting patterns: qw = one-hot rows picks columns of qx
+    sel = np.zeros((128, 128), np.int8)
+    sel[np.arange(128), (np.arange(128) * 5) % 128] = 1
+    assert np.array_equal(oracle.int_gemm(qx, sel), qx[:, (np.arange(128) * 5) % 128].astype(np.int32))
+
+
+# ----------------------------------------------------------------- bf16 rounding and epilogue
+def test_bf16_hand_cases():
+    for line in open(os.path.join(GOLD, "bf16_cases.txt")):
+        line = line.strip()
+        if not line or line[0] == "#":
+            continue
+        val, bits = line.split()
+        v = float.fromhex(val) if "x" in val else float(val)
+        got = int(oracle.bf16_from_f64(np.array([v]))[0])
+        assert got == int(bits, 16), (val, hex(got), bits)
+
+
+def test_bf16_matches_library_rounding_on_fp32_values():
+    # for values that are exactly fp32, one rounding double->bf16 equals torch's fp32->bf16 (nearest even)
+    rng = np.random.default_rng(8)
+    x = (rng.standard_normal(200000) * np.exp(rng.uniform(-30, 30, 200000))).astype(np.float32)
+    x[:7] = [0.0, -0.0, 1.0, 65504.0, 3.3e38, 1e-38, -1e-40]
+    ref = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = oracle.bf16_from_f64(x.astype(np.float64))
+    assert np.array_equal(got, ref)
+    back = oracle.bf16_bits_to_f64(got)
+    assert np.all(np.abs(back - x) <= np.abs(x) * 2.0 ** -8 + 1e-40)
+
+
+def test_epilogue_exact_cases():
+    acc = np.array([[3, -5, 0], [7, 1, -2]], dtype=np.int32)
+    one = np.ones(3)
+    # unit scales, no bias: Y is the accumulator itself
+    Y = oracle.dequant_bias(acc, np.ones(2), one)
+    assert np.array_equal(oracle.bf16_bits_to_f64(Y), acc.astype(np.float64))
+    # per-token and per-channel steps are powers of two, so every product is exact
+    dx = np.array([0.5, 4.0])              # token steps
+    dw = np.array([2.0, 0.25, 8.0])        # output-channel steps
+    b = np.array([1.0, -0.5, 0.0])
+    Y, y = oracle.dequant_bias(acc, dx, dw, b, want_f64=True)
+    expect = np.array([[3 * 0.5 * 2 + 1, -5 * 0.5 * 0.25 - 0.5, 0.0],
+                       [7 * 4 * 2 + 1, 1 * 4 * 0.25 - 0.5, -2 * 4 * 8.0]])
+    assert np.array_equal(y, expect)
+    assert np.array_equal(oracle.bf16_bits_to_f64(Y), expect)     # all exactly representable in bf16
+
+
+# ----------------------------------------------------------------- packing
+def test_pack_roundtrip_all_byte_values():
+    packed = np.arange(256, dtype=np.uint8).reshape(4, 64)
+    q = oracle.unpack_int4(packed, 128)
+    assert q.min() == -8 and q.max() == 7
+    assert np.array_equal(oracle.pack_int4(q), packed)
+    # byte 0xA7: low nibble 7 -> +7 (element 0), high nibble 0xA -> -6 (element 1)
+    assert oracle.unpack_int4(np.array([[0xA7]], np.uint8), 2).tolist() == [[7, -6]]
+    with pytest.raises(oracle.OracleError):
+        oracle.pack_int4(np.array([[9, 0]], np.int8))

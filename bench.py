@@ -1,0 +1,177 @@
+"""Benchmark of the W4A4 DSFQ linear path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 5] [--no-cpu-baseline]
+
+A step is one pass of the whole online path (rotate + smooth + per-token quantize, int4 GEMM,
+dequant + bias epilogue: qvggt_linear) over every layer of the chosen synthetic config, inputs
+resident in HBM.  Prints one JSON line.  The default workload is the benchmark's configs[4]
+(fc1 and fc2 of the VGGT-1B MLP at 100 frames), the largest single-GPU configuration and the
+one the throughput targets are stated on.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published (5.0 POP/s)
+METRIC = "W4A4 GEMM TOPS (% int8 MFMA peak) + rotate-quant GB/s at VGGT-1B shapes"
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=5, choices=[2, 3, 4, 5])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=256, help="rows per layer the oracle is timed on")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU; every step of the path is row-independent and would "
+              "shard by tokens with no collective, but multi-GPU runs are not part of it (use --gpus 1)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2509_21302_amd as q
+    import synth
+
+    q.load_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    def to_dev(a):
+        if a is None:
+            return None
+        a = np.ascontiguousarray(a)
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(a).to(dev)
+
+    # ------------------------------------------------------------------ set-up (untimed)
+    layers = []
+    for name in synth.config_layers(args.config):
+        s = synth.layer_spec(args.config, name)
+        signs = to_dev(synth.make_signs(s))
+        a = torch.empty(s.K, dtype=torch.float32, device=dev)
+        q.qvggt_rotated_col_absmax(to_dev(synth.make_calibration(s)), signs, a)
+        Wq = torch.empty(s.N, s.K // 2, dtype=torch.uint8, device=dev)
+        sw = torch.empty(s.N, dtype=torch.float32, device=dev)
+        inv = torch.empty(s.K, dtype=torch.float32, device=dev)
+        q.qvggt_prep_weights(to_dev(synth.make_weights(s)), a, signs, 0.5, Wq, sw, inv)
+        X = to_dev(synth.make_activation_frames(s, workers=16))
+        layers.append(dict(
+            spec=s, signs=signs, Wq=Wq, sw=sw, inv=inv, bias=to_dev(synth.make_bias(s)), X=X,
+            Y=torch.empty(s.M, s.N, dtype=torch.bfloat16, device=dev),
+            ws=torch.empty(q.qvggt_workspace_bytes(s.M, s.N, s.K), dtype=torch.uint8, device=dev),
+            Xq=torch.empty(s.M, s.K // 2, dtype=torch.uint8, device=dev),
+            sx=torch.empty(s.M, dtype=torch.float32, device=dev)))
+    torch.cuda.synchronize()
+
+    def step():
+        for L in layers:
+            q.qvggt_linear(L["X"], L["signs"], L["inv"], L["Wq"], L["sw"], L["bias"], L["Y"], L["ws"])
+
+    # ------------------------------------------------------------------ timed region: whole path
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    ops_per_step = sum(2.0 * L["spec"].M * L["spec"].N * L["spec"].K for L in layers)
+    value = ops_per_step / (ms_per_step * 1e-3) / 1e12
+
+    # ------------------------------------------------------------------ per-kernel durations (HIP events on the launch stream)
+    # same kernels, same arguments, launched through the two single-kernel entry points so that events can sit between them
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in layers] for _ in range(args.steps)]
+    for k in range(args.steps):
+        for L, (e0, e1, e2) in zip(layers, ev[k]):
+            s = L["spec"]
+            e0.record()
+            q.qvggt_rotate_smooth_quant(L["X"], L["signs"], L["inv"], L["Xq"], L["sx"])
+            e1.record()
+            q.qvggt_w4a4_gemm(L["Xq"], L["sx"], L["Wq"], L["sw"], L["bias"], s.M, s.N, s.K, L["Y"], None)
+            e2.record()
+    torch.cuda.synchronize()
+    per_layer = {}
+    rq_ms_all, gemm_ms_all, rq_bytes_all, gemm_ops_all = 0.0, 0.0, 0.0, 0.0
+    for i, L in enumerate(layers):
+        s = L["spec"]
+        rq = float(np.mean([ev[k][i][0].elapsed_time(ev[k][i][1]) for k in range(args.steps)]))
+        gm = float(np.mean([ev[k][i][1].elapsed_time(ev[k][i][2]) for k in range(args.steps)]))
+        x_bytes = 2 if s.x_dtype == "bf16" else 4
+        rq_bytes = s.M * (x_bytes * s.K + s.K / 2 + 4)          # X in, codes out, scale out
+        gemm_ops = 2.0 * s.M * s.N * s.K
+        per_layer[s.name] = dict(M=s.M, K=s.K, N=s.N, rotate_quant_ms=rq, rotate_quant_GBps=rq_bytes / rq / 1e6,
+                                 gemm_ms=gm, gemm_TOPS=gemm_ops / gm / 1e9)
+        rq_ms_all += rq; gemm_ms_all += gm; rq_bytes_all += rq_bytes; gemm_ops_all += gemm_ops
+    n_layers = len(layers)
+    gemm_tops = gemm_ops_all / gemm_ms_all / 1e9
+    rq_gbps = rq_bytes_all / rq_ms_all / 1e6
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(f"config{args.config}", {}).get("w4a4_gemm_bytes_per_launch")
+        except Exception:
+            traffic = None
+    roofline = dict(kernel="w4a4_gemm_kernel", bound="mfma", achieved=gemm_tops, peak=INT8_PEAK_TOPS, unit="TOP/s",
+                    frac=gemm_tops / INT8_PEAK_TOPS, traffic=traffic,
+                    ops_per_launch=gemm_ops_all / n_layers, avg_launch_ms=gemm_ms_all / n_layers)
+    roofline_rq = dict(kernel="rotate_rows_kernel", bound="hbm", achieved=rq_gbps, peak=HBM_PEAK_GBS, unit="GB/s",
+                       frac=rq_gbps / HBM_PEAK_GBS, traffic=None,
+                       bytes_per_launch=rq_bytes_all / n_layers, avg_launch_ms=rq_ms_all / n_layers)
+
+    # ------------------------------------------------------------------ CPU oracle beside it (bounded sample)
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        rows = args.cpu_rows
+        preps = []
+        for L in layers:
+            s = L["spec"]
+            sg = synth.make_signs(s)
+            a = oracle.rotated_col_absmax(synth.make_calibration(s), pre_signs=sg)
+            preps.append((sg, oracle.prepare_weights(synth.make_weights(s), a, pre_signs=sg), synth.make_bias(s),
+                          synth.make_activation_rows(s, list(range(rows)))))
+        t0 = time.perf_counter()
+        for sg, prep, bias, Xs in preps:
+            oracle.linear(Xs, prep, bias=bias, pre_signs=sg)
+        cpu_s = time.perf_counter() - t0
+        cpu_ops = sum(2.0 * rows * L["spec"].N * L["spec"].K for L in layers)
+        cpu = dict(value=cpu_ops / cpu_s / 1e12, unit="TOPS", cores=int(os.environ.get("OMP_NUM_THREADS", os.cpu_count())),
+                   kind="oracle", seconds=cpu_s,
+                   sample=f"first {rows} rows of each layer of config {args.config} through oracle.linear "
+                          f"(dense fp64 Hadamard, quantize, int GEMM, dequant); weight preparation not timed")
+
+    s0 = layers[0]["spec"]
+    out = {
+        "metric": METRIC, "value": value, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int4 (int8 MFMA, int32 accumulate)", "data": "synthetic",
+        "config": {"workload": f"BASELINE configs[{args.config - 1}]: " + ", ".join(
+            f"{L['spec'].name} {L['spec'].M}x{L['spec'].K}->{L['spec'].N}" for L in layers),
+            "tokens": s0.M, "frames": s0.frames, "layers": [L["spec"].name for L in layers], "parallelism": "1 GPU"},
+        "gemm_TOPS": gemm_tops, "gemm_frac_int8_peak": gemm_tops / INT8_PEAK_TOPS,
+        "rotate_quant_GBps": rq_gbps, "rotate_quant_frac_hbm_peak": rq_gbps / HBM_PEAK_GBS,
+        "per_layer": per_layer, "roofline": roofline, "roofline_rotate_quant": roofline_rq, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

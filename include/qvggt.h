@@ -1,0 +1,136 @@
+/*
+ * qvggt — W4A4 Dual-Smoothed Fine-Grained Quantization (DSFQ) linear layer for AMD MI355X (gfx950).
+ *
+ * C ABI of the inference hot path of the quantized linear layer of QuantVGGT
+ * (arXiv 2509.21302, Sec. 3.2 "Dual-Smoothed Fine-Grained Quantization"):
+ *
+ *     Y = dequant( Q_token( X H diag(c)^-1 ) . Q_channel( diag(c) H^T W^T ) ) + b
+ *
+ * with H a randomised orthonormal Walsh-Hadamard matrix (Sec. 3.2, Pre-Global-Rotation),
+ * c the post-rotation smoothing factor (Sec. 3.2, Post-Local-Smooth, Eq. "smooth_factor"),
+ * Q the symmetric 4-bit quantizer (Sec. 3.1.2, Eq. "quantization") applied per token to
+ * activations and per output channel to weights (Sec. 3.2, Fine-Grained Quantization
+ * Granularity), the product taken in integers and dequantised after the sum.
+ *
+ * General conventions
+ *   - Every pointer is a DEVICE pointer owned by the caller unless stated otherwise; the
+ *     library allocates nothing, keeps no state between calls and is re-entrant.
+ *   - Every call only enqueues kernels on `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream) and returns; buffers must stay valid until the stream has run.
+ *   - Matrices are dense row-major.  bf16 values are IEEE bfloat16 bit patterns (uint16).
+ *   - K (input features, the Hadamard size) must be a power of two in [128, 8192];
+ *     N (output features) a multiple of 16; M (tokens) any value >= 0 (M == 0 is a no-op).
+ *     All device pointers must be 16-byte aligned.  Inputs must be finite.
+ *   - Return value: QVGGT_OK or an error code; arguments are validated on the host
+ *     before anything is launched, so a failed call has touched no output.
+ *   - Packed 4-bit buffers (Xq, Wq) hold two's-complement codes, two per byte, rows of K/2
+ *     bytes.  The position of a code inside its row is the library's choice (a fixed
+ *     permutation of 0..K-1 that depends only on K, the same for Xq and Wq, so the integer
+ *     dot products are unaffected); qvggt_pack_int4 / qvggt_unpack_int4 convert between this
+ *     layout and plain int8 codes in natural order and are the only supported way to read
+ *     or write such buffers from outside.
+ */
+#ifndef QVGGT_H
+#define QVGGT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    QVGGT_OK = 0,
+    QVGGT_ERR_NULL = 1,      /* a required pointer is NULL */
+    QVGGT_ERR_SHAPE = 2,     /* M < 0, N < 16 or not a multiple of 16, K not a power of two in [128, 8192] */
+    QVGGT_ERR_ALIGN = 3,     /* a pointer is not 16-byte aligned */
+    QVGGT_ERR_DTYPE = 4,     /* dtype is neither QVGGT_BF16 nor QVGGT_F32 */
+    QVGGT_ERR_WORKSPACE = 5, /* workspace smaller than qvggt_workspace_bytes() */
+    QVGGT_ERR_ARG = 6,       /* alpha outside [0, 1] or not finite */
+    QVGGT_ERR_HIP = 7        /* a kernel launch failed (hipGetLastError) */
+} qvggt_status;
+
+typedef enum { QVGGT_BF16 = 0, QVGGT_F32 = 1 } qvggt_dtype;
+
+/* Human-readable name of a status code (host pointer to a static string). */
+const char *qvggt_status_string(int status);
+
+/*
+ * Per-channel activation statistic of the smoothing factor, taken in rotated space
+ * (Sec. 3.2, Eq. "smooth_factor", numerator):
+ *     absmax_rot[j] = max_t | (X_cal H)[t, j] |,   H = diag(signs) . Hhat_K
+ * X_cal: [M, K] calibration activations (bf16 or f32).  signs: int8 [K] of +1/-1 applied to
+ * the INPUT channels before the transform, or NULL for the plain Hadamard.  absmax_rot: f32 [K],
+ * overwritten.  (The paper writes H = Hhat diag(v), which only flips output channels and
+ * cancels exactly in the integer product; the input-side form used by the works it follows
+ * is the one implemented.)
+ */
+int qvggt_rotated_col_absmax(const void *X_cal, int x_dtype, int M, int K, const int8_t *signs,
+                             float *absmax_rot, void *stream);
+
+/*
+ * Offline half (Sec. 3.2: rotate, smooth, quantize per output channel):
+ *     Wr = W H;  w_j = max_o |Wr[o, j]|;  c_j = max(a_j, 1e-5)^alpha / max(w_j, 1e-5)^(1 - alpha);
+ *     Ws = Wr diag(c);  w_scale[o] = max_j |Ws[o, j]| / 7;  Wq[o, :] = clamp(rne(Ws[o, :] / w_scale[o]), -8, 7)
+ * W: [N, K] (bf16 or f32).  act_absmax_rot: f32 [K] from qvggt_rotated_col_absmax (a_j), or NULL
+ * for c = 1 (rotation only).  signs: as above, must be the vector later given to
+ * qvggt_rotate_smooth_quant.  alpha in [0, 1] (the paper uses 0.5).
+ * Outputs: Wq packed [N, K/2] bytes; w_scale f32 [N]; inv_smooth f32 [K] with
+ *     inv_smooth[j] = 1 / (sqrt(K) c_j)
+ * i.e. the Hadamard normalisation and the smoothing divide folded into one multiplier for
+ * the online kernel.  The floor 1e-5 on the statistics guards all-zero channels (the paper is
+ * silent there).
+ */
+int qvggt_prep_weights(const void *W, int w_dtype, int N, int K, const float *act_absmax_rot,
+                       const int8_t *signs, float alpha, uint8_t *Wq, float *w_scale,
+                       float *inv_smooth, void *stream);
+
+/*
+ * Online kernel 1 (Sec. 3.2 rotation + smoothing; Sec. 3.1.2 quantizer, per token, dynamic):
+ *     z[t, :] = (X[t, :] diag(signs) Hadamard_K) * inv_smooth;   x_scale[t] = max_j |z[t, j]| / 7;
+ *     Xq[t, j] = clamp(rne(z[t, j] / x_scale[t]), -8, 7)
+ * Hadamard_K is the unnormalised +-1 matrix; its 1/sqrt(K) lives in inv_smooth.
+ * X: [M, K] (bf16 or f32).  signs: int8 [K] or NULL.  inv_smooth: f32 [K], or NULL for the
+ * plain orthonormal rotation (1/sqrt(K) everywhere).  Outputs: Xq packed [M, K/2] bytes,
+ * x_scale f32 [M].  A row of zeros gets scale 0 and codes 0.  Butterflies and scaling are fp32.
+ */
+int qvggt_rotate_smooth_quant(const void *X, int x_dtype, int M, int K, const int8_t *signs,
+                              const float *inv_smooth, uint8_t *Xq, float *x_scale, void *stream);
+
+/*
+ * Online kernel 2 (Sec. 3.2 granularity paragraph: integer sum, dequantise after it):
+ *     acc[t, o] = sum_j Xq[t, j] Wq[o, j]   (int32, exact);
+ *     Y[t, o]   = bf16_rne( acc[t, o] * x_scale[t] * w_scale[o] + bias[o] )
+ * Xq [M, K/2], Wq [N, K/2] packed as written by this library; x_scale f32 [M]; w_scale f32 [N];
+ * bias bf16 [N] or NULL; Y bf16 [M, N].  acc_debug: int32 [M, N] receiving the raw accumulators,
+ * or NULL (test hook; costs an extra 4 bytes per output when given).
+ */
+int qvggt_w4a4_gemm(const uint8_t *Xq, const float *x_scale, const uint8_t *Wq, const float *w_scale,
+                    const void *bias, int M, int N, int K, void *Y, int32_t *acc_debug, void *stream);
+
+/*
+ * Whole online path: qvggt_rotate_smooth_quant into the workspace, then qvggt_w4a4_gemm.
+ * workspace: device buffer of at least qvggt_workspace_bytes(M, N, K) bytes, 16-byte aligned
+ * (holds Xq and x_scale between the two kernels; contents undefined afterwards).
+ */
+int qvggt_linear(const void *X, int x_dtype, int M, int N, int K, const int8_t *signs,
+                 const float *inv_smooth, const uint8_t *Wq, const float *w_scale, const void *bias,
+                 void *Y, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Bytes of workspace qvggt_linear needs; 0 if the shape is invalid. */
+size_t qvggt_workspace_bytes(int M, int N, int K);
+
+/*
+ * Layout converters for packed 4-bit buffers (see "General conventions").
+ * qvggt_pack_int4:   codes int8 [rows, K] in natural order, each in [-8, 7] (low 4 bits are
+ *                    taken) -> packed [rows, K/2] in the library's layout.
+ * qvggt_unpack_int4: the inverse, sign-extending each code to int8.
+ */
+int qvggt_pack_int4(const int8_t *codes, int rows, int K, uint8_t *packed, void *stream);
+int qvggt_unpack_int4(const uint8_t *packed, int rows, int K, int8_t *codes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QVGGT_H */

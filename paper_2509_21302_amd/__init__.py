@@ -1,0 +1,20 @@
+"""qvggt: W4A4 Dual-Smoothed Fine-Grained Quantization linear layer for MI355X (gfx950).
+
+The product is the C-ABI shared library libqvggt.so (declared in include/qvggt.h, built from
+csrc/ by build.py); `binding` is the thin ctypes layer with the same entry-point names.
+"""
+from .binding import (  # noqa: F401
+    QvggtError,
+    lib_path,
+    load_library,
+    EXPORTS,
+    qvggt_status_string,
+    qvggt_rotated_col_absmax,
+    qvggt_prep_weights,
+    qvggt_rotate_smooth_quant,
+    qvggt_w4a4_gemm,
+    qvggt_linear,
+    qvggt_workspace_bytes,
+    qvggt_pack_int4,
+    qvggt_unpack_int4,
+)

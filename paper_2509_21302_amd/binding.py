@@ -1,0 +1,149 @@
+"""ctypes binding of libqvggt.so: argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU (or None where the C ABI
+accepts NULL), passes their data pointers and the current HIP stream to the entry point of
+the same name, and raises QvggtError on a non-zero status.  No arithmetic happens here, and
+there is no fallback: if the library is missing the import of this module fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+QVGGT_BF16, QVGGT_F32 = 0, 1
+
+EXPORTS = [
+    "qvggt_status_string", "qvggt_rotated_col_absmax", "qvggt_prep_weights", "qvggt_rotate_smooth_quant",
+    "qvggt_w4a4_gemm", "qvggt_linear", "qvggt_workspace_bytes", "qvggt_pack_int4", "qvggt_unpack_int4",
+]
+
+
+class QvggtError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {qvggt_status_string(status)} (status {status})")
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libqvggt.so")
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Load libqvggt.so (built in-tree by paper_2509_21302_amd.build); fails loudly if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} not found: build it with `python -m paper_2509_21302_amd.build`")
+    lib = C.CDLL(path)
+    vp, i, f, sz = C.c_void_p, C.c_int, C.c_float, C.c_size_t
+    lib.qvggt_status_string.restype = C.c_char_p
+    lib.qvggt_status_string.argtypes = [i]
+    lib.qvggt_rotated_col_absmax.restype = i
+    lib.qvggt_rotated_col_absmax.argtypes = [vp, i, i, i, vp, vp, vp]
+    lib.qvggt_prep_weights.restype = i
+    lib.qvggt_prep_weights.argtypes = [vp, i, i, i, vp, vp, f, vp, vp, vp, vp]
+    lib.qvggt_rotate_smooth_quant.restype = i
+    lib.qvggt_rotate_smooth_quant.argtypes = [vp, i, i, i, vp, vp, vp, vp, vp]
+    lib.qvggt_w4a4_gemm.restype = i
+    lib.qvggt_w4a4_gemm.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp, vp, vp]
+    lib.qvggt_linear.restype = i
+    lib.qvggt_linear.argtypes = [vp, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.qvggt_workspace_bytes.restype = sz
+    lib.qvggt_workspace_bytes.argtypes = [i, i, i]
+    lib.qvggt_pack_int4.restype = i
+    lib.qvggt_pack_int4.argtypes = [vp, i, i, vp, vp]
+    lib.qvggt_unpack_int4.restype = i
+    lib.qvggt_unpack_int4.argtypes = [vp, i, i, vp, vp]
+    _lib = lib
+    return lib
+
+
+# ------------------------------------------------------------------ marshalling helpers
+def _ptr(t) -> Optional[int]:
+    """Device pointer of a tensor (None -> NULL).  Tensors must be contiguous and on the GPU."""
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("qvggt takes device tensors only")
+    if not t.is_contiguous():
+        raise ValueError("qvggt takes contiguous tensors only")
+    return t.data_ptr()
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.bfloat16:
+        return QVGGT_BF16
+    if t.dtype == torch.float32:
+        return QVGGT_F32
+    raise ValueError(f"unsupported dtype {t.dtype}: bf16 or f32")
+
+
+def _stream(stream) -> Optional[int]:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream or None
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise QvggtError(status, where)
+
+
+# ------------------------------------------------------------------ entry points
+def qvggt_status_string(status: int) -> str:
+    return load_library().qvggt_status_string(int(status)).decode()
+
+
+def qvggt_rotated_col_absmax(X_cal, signs, absmax_rot, stream=None):
+    M, K = X_cal.shape
+    _check(load_library().qvggt_rotated_col_absmax(_ptr(X_cal), _dtype_code(X_cal), M, K, _ptr(signs),
+                                                   _ptr(absmax_rot), _stream(stream)), "qvggt_rotated_col_absmax")
+
+
+def qvggt_prep_weights(W, act_absmax_rot, signs, alpha, Wq, w_scale, inv_smooth, stream=None):
+    N, K = W.shape
+    _check(load_library().qvggt_prep_weights(_ptr(W), _dtype_code(W), N, K, _ptr(act_absmax_rot), _ptr(signs),
+                                             float(alpha), _ptr(Wq), _ptr(w_scale), _ptr(inv_smooth),
+                                             _stream(stream)), "qvggt_prep_weights")
+
+
+def qvggt_rotate_smooth_quant(X, signs, inv_smooth, Xq, x_scale, stream=None):
+    M, K = X.shape
+    _check(load_library().qvggt_rotate_smooth_quant(_ptr(X), _dtype_code(X), M, K, _ptr(signs), _ptr(inv_smooth),
+                                                    _ptr(Xq), _ptr(x_scale), _stream(stream)),
+           "qvggt_rotate_smooth_quant")
+
+
+def qvggt_w4a4_gemm(Xq, x_scale, Wq, w_scale, bias, M, N, K, Y, acc_debug=None, stream=None):
+    _check(load_library().qvggt_w4a4_gemm(_ptr(Xq), _ptr(x_scale), _ptr(Wq), _ptr(w_scale), _ptr(bias), M, N, K,
+                                          _ptr(Y), _ptr(acc_debug), _stream(stream)), "qvggt_w4a4_gemm")
+
+
+def qvggt_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(load_library().qvggt_workspace_bytes(M, N, K))
+
+
+def qvggt_linear(X, signs, inv_smooth, Wq, w_scale, bias, Y, workspace, stream=None):
+    M, K = X.shape
+    N = Y.shape[1]
+    _check(load_library().qvggt_linear(_ptr(X), _dtype_code(X), M, N, K, _ptr(signs), _ptr(inv_smooth), _ptr(Wq),
+                                       _ptr(w_scale), _ptr(bias), _ptr(Y), _ptr(workspace),
+                                       workspace.numel() * workspace.element_size(), _stream(stream)), "qvggt_linear")
+
+
+def qvggt_pack_int4(codes, packed, stream=None):
+    rows, K = codes.shape
+    _check(load_library().qvggt_pack_int4(_ptr(codes), rows, K, _ptr(packed), _stream(stream)), "qvggt_pack_int4")
+
+
+def qvggt_unpack_int4(packed, codes, stream=None):
+    rows, K = codes.shape
+    _check(load_library().qvggt_unpack_int4(_ptr(packed), rows, K, _ptr(codes), _stream(stream)), "qvggt_unpack_int4")

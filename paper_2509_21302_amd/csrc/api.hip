@@ -1,0 +1,156 @@
+// C ABI of the qvggt library: argument validation on the host, then kernel launches on the
+// caller's stream.  Declarations and the meaning of every argument are in include/qvggt.h.
+#include "qvggt_common.h"
+#include "../../include/qvggt.h"
+
+#include <cmath>
+
+namespace qvggt {
+hipError_t run_rotate_smooth_quant(const void *X, bool f32, int rows, int K, const int8_t *signs, const float *mul,
+                                   int mul_mode, uint8_t *packed, float *scale, hipStream_t stream);
+hipError_t run_rotated_col_absmax(const void *X, bool f32, int rows, int K, const int8_t *signs, float *absmax,
+                                  hipStream_t stream);
+hipError_t run_smooth_factor(float *buf, const float *act_absmax, int K, float alpha, hipStream_t stream);
+hipError_t run_fill_f32(float *p, int n, float v, hipStream_t stream);
+hipError_t run_pack_int4(const int8_t *codes, int rows, int K, uint8_t *packed, hipStream_t stream);
+hipError_t run_unpack_int4(const uint8_t *packed, int rows, int K, int8_t *codes, hipStream_t stream);
+hipError_t run_w4a4_gemm(const uint8_t *Xq, const float *sx, const uint8_t *Wq, const float *sw, const void *bias,
+                         int M, int N, int K, void *Y, int32_t *acc_debug, hipStream_t stream);
+}  // namespace qvggt
+
+namespace {
+
+bool valid_k(int K) { return K >= qvggt::kMinK && K <= qvggt::kMaxK && (K & (K - 1)) == 0; }
+bool valid_n(int N) { return N >= 16 && (N % 16) == 0; }
+bool valid_dtype(int d) { return d == QVGGT_BF16 || d == QVGGT_F32; }
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+int hip_status(hipError_t e) { return e == hipSuccess ? QVGGT_OK : QVGGT_ERR_HIP; }
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace
+
+extern "C" {
+
+const char *qvggt_status_string(int status)
+{
+    switch (status) {
+        case QVGGT_OK: return "QVGGT_OK";
+        case QVGGT_ERR_NULL: return "QVGGT_ERR_NULL: a required pointer is NULL";
+        case QVGGT_ERR_SHAPE: return "QVGGT_ERR_SHAPE: unsupported M, N or K";
+        case QVGGT_ERR_ALIGN: return "QVGGT_ERR_ALIGN: pointer not 16-byte aligned";
+        case QVGGT_ERR_DTYPE: return "QVGGT_ERR_DTYPE: dtype must be QVGGT_BF16 or QVGGT_F32";
+        case QVGGT_ERR_WORKSPACE: return "QVGGT_ERR_WORKSPACE: workspace too small";
+        case QVGGT_ERR_ARG: return "QVGGT_ERR_ARG: alpha must be a finite value in [0, 1]";
+        case QVGGT_ERR_HIP: return "QVGGT_ERR_HIP: kernel launch failed";
+        default: return "unknown qvggt status";
+    }
+}
+
+int qvggt_rotated_col_absmax(const void *X_cal, int x_dtype, int M, int K, const int8_t *signs, float *absmax_rot,
+                             void *stream)
+{
+    if (!valid_dtype(x_dtype)) return QVGGT_ERR_DTYPE;
+    if (M < 0 || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (!absmax_rot || (M > 0 && !X_cal)) return QVGGT_ERR_NULL;
+    if (!aligned16(X_cal) || !aligned16(absmax_rot) || !aligned16(signs)) return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_rotated_col_absmax(X_cal, x_dtype == QVGGT_F32, M, K, signs, absmax_rot,
+                                                    static_cast<hipStream_t>(stream)));
+}
+
+int qvggt_prep_weights(const void *W, int w_dtype, int N, int K, const float *act_absmax_rot, const int8_t *signs,
+                       float alpha, uint8_t *Wq, float *w_scale, float *inv_smooth, void *stream)
+{
+    if (!valid_dtype(w_dtype)) return QVGGT_ERR_DTYPE;
+    if (!valid_n(N) || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (!W || !Wq || !w_scale || !inv_smooth) return QVGGT_ERR_NULL;
+    if (!aligned16(W) || !aligned16(Wq) || !aligned16(w_scale) || !aligned16(inv_smooth) ||
+        !aligned16(act_absmax_rot) || !aligned16(signs))
+        return QVGGT_ERR_ALIGN;
+    if (!std::isfinite(alpha) || alpha < 0.0f || alpha > 1.0f) return QVGGT_ERR_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool f32 = w_dtype == QVGGT_F32;
+    hipError_t e;
+    if (act_absmax_rot != nullptr) {
+        // inv_smooth doubles as the scratch for the rotated weight statistic w_j
+        e = qvggt::run_rotated_col_absmax(W, f32, N, K, signs, inv_smooth, s);
+        if (e != hipSuccess) return QVGGT_ERR_HIP;
+        e = qvggt::run_smooth_factor(inv_smooth, act_absmax_rot, K, alpha, s);
+    } else {
+        e = qvggt::run_fill_f32(inv_smooth, K, 1.0f / std::sqrt((float)K), s);
+    }
+    if (e != hipSuccess) return QVGGT_ERR_HIP;
+    // rows of W go through the same rotate / scale / quantize kernel, with c_j / sqrt(K) as the multiplier
+    return hip_status(qvggt::run_rotate_smooth_quant(W, f32, N, K, signs, inv_smooth, 1, Wq, w_scale, s));
+}
+
+int qvggt_rotate_smooth_quant(const void *X, int x_dtype, int M, int K, const int8_t *signs, const float *inv_smooth,
+                              uint8_t *Xq, float *x_scale, void *stream)
+{
+    if (!valid_dtype(x_dtype)) return QVGGT_ERR_DTYPE;
+    if (M < 0 || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (M == 0) return QVGGT_OK;
+    if (!X || !Xq || !x_scale) return QVGGT_ERR_NULL;
+    if (!aligned16(X) || !aligned16(Xq) || !aligned16(x_scale) || !aligned16(inv_smooth) || !aligned16(signs))
+        return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_rotate_smooth_quant(X, x_dtype == QVGGT_F32, M, K, signs, inv_smooth, 0, Xq, x_scale,
+                                                     static_cast<hipStream_t>(stream)));
+}
+
+int qvggt_w4a4_gemm(const uint8_t *Xq, const float *x_scale, const uint8_t *Wq, const float *w_scale, const void *bias,
+                    int M, int N, int K, void *Y, int32_t *acc_debug, void *stream)
+{
+    if (M < 0 || !valid_n(N) || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (M == 0) return QVGGT_OK;
+    if (!Xq || !x_scale || !Wq || !w_scale || !Y) return QVGGT_ERR_NULL;
+    if (!aligned16(Xq) || !aligned16(x_scale) || !aligned16(Wq) || !aligned16(w_scale) || !aligned16(bias) ||
+        !aligned16(Y) || !aligned16(acc_debug))
+        return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_w4a4_gemm(Xq, x_scale, Wq, w_scale, bias, M, N, K, Y, acc_debug,
+                                           static_cast<hipStream_t>(stream)));
+}
+
+size_t qvggt_workspace_bytes(int M, int N, int K)
+{
+    if (M < 0 || !valid_n(N) || !valid_k(K)) return 0;
+    return round_up((size_t)M * (size_t)(K / 2), 256) + round_up((size_t)M * sizeof(float), 256) + 256;
+}
+
+int qvggt_linear(const void *X, int x_dtype, int M, int N, int K, const int8_t *signs, const float *inv_smooth,
+                 const uint8_t *Wq, const float *w_scale, const void *bias, void *Y, void *workspace,
+                 size_t workspace_bytes, void *stream)
+{
+    if (!valid_dtype(x_dtype)) return QVGGT_ERR_DTYPE;
+    if (M < 0 || !valid_n(N) || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (M == 0) return QVGGT_OK;
+    if (!X || !Wq || !w_scale || !Y || !workspace) return QVGGT_ERR_NULL;
+    if (!aligned16(X) || !aligned16(Wq) || !aligned16(w_scale) || !aligned16(bias) || !aligned16(Y) ||
+        !aligned16(workspace) || !aligned16(inv_smooth) || !aligned16(signs))
+        return QVGGT_ERR_ALIGN;
+    if (workspace_bytes < qvggt_workspace_bytes(M, N, K)) return QVGGT_ERR_WORKSPACE;
+    uint8_t *Xq = static_cast<uint8_t *>(workspace);
+    float *x_scale = reinterpret_cast<float *>(Xq + round_up((size_t)M * (size_t)(K / 2), 256));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = qvggt::run_rotate_smooth_quant(X, x_dtype == QVGGT_F32, M, K, signs, inv_smooth, 0, Xq, x_scale, s);
+    if (e != hipSuccess) return QVGGT_ERR_HIP;
+    return hip_status(qvggt::run_w4a4_gemm(Xq, x_scale, Wq, w_scale, bias, M, N, K, Y, nullptr, s));
+}
+
+int qvggt_pack_int4(const int8_t *codes, int rows, int K, uint8_t *packed, void *stream)
+{
+    if (rows < 0 || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (rows == 0) return QVGGT_OK;
+    if (!codes || !packed) return QVGGT_ERR_NULL;
+    if (!aligned16(codes) || !aligned16(packed)) return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_pack_int4(codes, rows, K, packed, static_cast<hipStream_t>(stream)));
+}
+
+int qvggt_unpack_int4(const uint8_t *packed, int rows, int K, int8_t *codes, void *stream)
+{
+    if (rows < 0 || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (rows == 0) return QVGGT_OK;
+    if (!codes || !packed) return QVGGT_ERR_NULL;
+    if (!aligned16(codes) || !aligned16(packed)) return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_unpack_int4(packed, rows, K, codes, static_cast<hipStream_t>(stream)));
+}
+
+}  // extern "C"

@@ -1,0 +1,295 @@
+// Online kernel 1 and its offline twins: randomised Walsh-Hadamard rotation of rows,
+// per-channel multiply, then either per-row 4-bit quantization (activations per token,
+// weights per output channel) or a per-channel absmax (smoothing statistics).
+//
+// One wavefront owns one row at a time.  A row of K values lives in K/64 registers per
+// lane; element e = c*(64*V) + lane*V + i sits in register c*V + i, where V = min(8, K/64)
+// is the run a lane loads contiguously (16 bytes of bf16 when V = 8, so a wave reads 1 KiB
+// per load instruction).  The transform is one butterfly per index bit (the Hadamard matrix
+// is a Kronecker power of H_2, paper Sec. 3.2): bits inside i and c are register-to-register,
+// the six lane bits go through cross-lane exchanges.
+#include "qvggt_common.h"
+
+namespace qvggt {
+
+template <int K>
+struct RowMap {
+    static constexpr int V = (K >= 512) ? 8 : K / 64;   // contiguous elements per lane per chunk
+    static constexpr int C = K / (64 * V);              // chunks
+    static constexpr int R = V * C;                     // registers per lane
+};
+
+template <int K, bool F32>
+__device__ inline void load_row(const void *X, size_t row, int lane, float (&x)[RowMap<K>::R])
+{
+    constexpr int V = RowMap<K>::V, C = RowMap<K>::C;
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+        const size_t e0 = row * (size_t)K + (size_t)c * 64 * V + (size_t)lane * V;
+        if constexpr (F32) {
+            const float *p = reinterpret_cast<const float *>(X) + e0;
+            if constexpr (V >= 4) {
+#pragma unroll
+                for (int q = 0; q < V / 4; ++q) {
+                    float4 v = *reinterpret_cast<const float4 *>(p + 4 * q);
+                    x[c * V + 4 * q + 0] = v.x; x[c * V + 4 * q + 1] = v.y;
+                    x[c * V + 4 * q + 2] = v.z; x[c * V + 4 * q + 3] = v.w;
+                }
+            } else {
+                float2 v = *reinterpret_cast<const float2 *>(p);
+                x[c * V] = v.x; x[c * V + 1] = v.y;
+            }
+        } else {
+            const uint16_t *p = reinterpret_cast<const uint16_t *>(X) + e0;
+            uint32_t w[V / 2];
+            if constexpr (V == 8) {
+                uint4 v = *reinterpret_cast<const uint4 *>(p);
+                w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+            } else if constexpr (V == 4) {
+                uint2 v = *reinterpret_cast<const uint2 *>(p);
+                w[0] = v.x; w[1] = v.y;
+            } else {
+                w[0] = *reinterpret_cast<const uint32_t *>(p);
+            }
+#pragma unroll
+            for (int q = 0; q < V / 2; ++q) {
+                x[c * V + 2 * q] = __uint_as_float(w[q] << 16);
+                x[c * V + 2 * q + 1] = __uint_as_float(w[q] & 0xFFFF0000u);
+            }
+        }
+    }
+}
+
+// In-place unnormalised Walsh-Hadamard transform of a row spread over one wavefront.
+template <int K>
+__device__ inline void fwht_row(float (&x)[RowMap<K>::R], int lane)
+{
+    constexpr int V = RowMap<K>::V, R = RowMap<K>::R;
+    // index bits inside the lane's contiguous run
+#pragma unroll
+    for (int h = 1; h < V; h <<= 1)
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if ((r & h) == 0) { float a = x[r], b = x[r + h]; x[r] = a + b; x[r + h] = a - b; }
+    // the six lane bits
+#pragma unroll
+    for (int m = 1; m < kWave; m <<= 1) {
+        const bool upper = (lane & m) != 0;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            float p = __shfl_xor(x[r], m);
+            x[r] = upper ? p - x[r] : x[r] + p;
+        }
+    }
+    // chunk bits
+#pragma unroll
+    for (int h = V; h < R; h <<= 1)
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if ((r & h) == 0) { float a = x[r], b = x[r + h]; x[r] = a + b; x[r + h] = a - b; }
+}
+
+enum RowMode { kQuantize = 0, kColAbsMax = 1 };
+
+// mul_mode 0: mul[j] used as given (inv_smooth, or 1/sqrt(K) when mul == nullptr)
+// mul_mode 1: 1 / (K * mul[j])   (weights: c_j / sqrt(K) recovered from inv_smooth)
+template <int K, bool F32, int MODE>
+__global__ __launch_bounds__(256) void rotate_rows_kernel(const void *__restrict__ X, int rows,
+                                                          const int8_t *__restrict__ signs,
+                                                          const float *__restrict__ mul, int mul_mode,
+                                                          uint8_t *__restrict__ packed,
+                                                          float *__restrict__ scale,
+                                                          unsigned int *__restrict__ col_absmax_bits)
+{
+    constexpr int V = RowMap<K>::V, C = RowMap<K>::C, R = RowMap<K>::R;
+    const int lane = threadIdx.x & 63;
+    const int wave = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int nwaves = gridDim.x * (blockDim.x >> 6);
+
+    // per-lane constants: sign bits (one bit per register) and channel multipliers
+    uint32_t neg[(R + 31) / 32];
+#pragma unroll
+    for (int w = 0; w < (R + 31) / 32; ++w) neg[w] = 0;
+    float cm[R];
+    const float rs = 1.0f / sqrtf((float)K);
+#pragma unroll
+    for (int c = 0; c < C; ++c)
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            const int e = c * 64 * V + lane * V + i, r = c * V + i;
+            if (signs != nullptr && signs[e] < 0) neg[r >> 5] |= 1u << (r & 31);
+            float m = rs;
+            if (mul != nullptr) m = mul_mode ? 1.0f / ((float)K * mul[e]) : mul[e];
+            cm[r] = m;
+        }
+
+    for (int row = wave; row < rows; row += nwaves) {
+        float x[R];
+        load_row<K, F32>(X, (size_t)row, lane, x);
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if ((neg[r >> 5] >> (r & 31)) & 1u) x[r] = -x[r];
+        fwht_row<K>(x, lane);
+        float amax = 0.0f;
+#pragma unroll
+        for (int r = 0; r < R; ++r) { x[r] *= cm[r]; amax = fmaxf(amax, fabsf(x[r])); }
+
+        if constexpr (MODE == kColAbsMax) {
+            // non-negative floats order like their bit patterns
+#pragma unroll
+            for (int c = 0; c < C; ++c)
+#pragma unroll
+                for (int i = 0; i < V; ++i)
+                    atomicMax(&col_absmax_bits[c * 64 * V + lane * V + i], __float_as_uint(fabsf(x[c * V + i])));
+        } else {
+            amax = wave_max(amax);
+            const float inv = amax > 0.0f ? 7.0f / amax : 0.0f;
+            if (lane == 0) scale[row] = amax / 7.0f;
+            uint8_t *out = packed + (size_t)row * (K / 2);
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                uint32_t word = 0;
+#pragma unroll
+                for (int i = 0; i < V; ++i) {
+                    int q = (int)__builtin_rintf(x[c * V + i] * inv);
+                    q = min(7, max(-8, q));
+                    word |= (uint32_t)(q & 0xF) << (4 * i);
+                }
+                // natural order: element e -> nibble e; a lane's V codes are V/2 consecutive bytes
+                const int byte0 = (c * 64 * V + lane * V) / 2;
+                if constexpr (V == 8) *reinterpret_cast<uint32_t *>(out + byte0) = word;
+                else if constexpr (V == 4) *reinterpret_cast<uint16_t *>(out + byte0) = (uint16_t)word;
+                else out[byte0] = (uint8_t)word;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// small helpers of the offline path
+
+__global__ void fill_u32_kernel(unsigned int *p, int n, unsigned int v)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// in place: buf[j] holds w_j = max_o |W H|[o, j] on entry, inv_smooth[j] = 1 / (sqrt(K) c_j) on exit
+__global__ void smooth_factor_kernel(float *buf, const float *__restrict__ act_absmax, int K, float alpha)
+{
+    int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= K) return;
+    const float floor_ = 1e-5f;
+    float a = fmaxf(act_absmax[j], floor_), w = fmaxf(buf[j], floor_);
+    float c = powf(a, alpha) / powf(w, 1.0f - alpha);
+    buf[j] = 1.0f / (sqrtf((float)K) * c);
+}
+
+__global__ void fill_f32_kernel(float *p, int n, float v)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// int8 codes in natural order <-> packed rows in the library layout
+__global__ void pack_int4_kernel(const int8_t *__restrict__ codes, size_t rows, int K, uint8_t *__restrict__ packed)
+{
+    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // one output byte each
+    if (idx >= rows * (size_t)(K / 2)) return;
+    size_t row = idx / (K / 2);
+    int byte = (int)(idx % (K / 2));
+    int e0 = code_element(2 * byte, K), e1 = code_element(2 * byte + 1, K);
+    uint8_t lo = (uint8_t)codes[row * K + e0] & 0xF, hi = (uint8_t)codes[row * K + e1] & 0xF;
+    packed[idx] = lo | (hi << 4);
+}
+
+__global__ void unpack_int4_kernel(const uint8_t *__restrict__ packed, size_t rows, int K, int8_t *__restrict__ codes)
+{
+    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // one natural element each
+    if (idx >= rows * (size_t)K) return;
+    size_t row = idx / K;
+    int e = (int)(idx % K);
+    int p = code_position(e, K);
+    uint8_t b = packed[row * (K / 2) + p / 2];
+    int nib = (p & 1) ? (b >> 4) : (b & 0xF);
+    codes[idx] = (int8_t)(nib >= 8 ? nib - 16 : nib);
+}
+
+// ---------------------------------------------------------------------------------------
+// host-side launchers (called from api.hip)
+
+template <int MODE>
+static hipError_t launch_rotate_rows(const void *X, bool f32, int rows, int K, const int8_t *signs,
+                                     const float *mul, int mul_mode, uint8_t *packed, float *scale,
+                                     unsigned int *colmax, hipStream_t stream)
+{
+    if (rows <= 0) return hipSuccess;
+    const int waves_per_block = 4;
+    int blocks = (rows + waves_per_block - 1) / waves_per_block;
+    const int max_blocks = 256 * 8;
+    if (blocks > max_blocks) blocks = max_blocks;
+#define QVGGT_LAUNCH(KK)                                                                                     \
+    case KK:                                                                                                 \
+        if (f32) rotate_rows_kernel<KK, true, MODE><<<blocks, 256, 0, stream>>>(X, rows, signs, mul, mul_mode, packed, scale, colmax); \
+        else rotate_rows_kernel<KK, false, MODE><<<blocks, 256, 0, stream>>>(X, rows, signs, mul, mul_mode, packed, scale, colmax);    \
+        break;
+    switch (K) {
+        QVGGT_LAUNCH(128)
+        QVGGT_LAUNCH(256)
+        QVGGT_LAUNCH(512)
+        QVGGT_LAUNCH(1024)
+        QVGGT_LAUNCH(2048)
+        QVGGT_LAUNCH(4096)
+        QVGGT_LAUNCH(8192)
+        default: return hipErrorInvalidValue;
+    }
+#undef QVGGT_LAUNCH
+    return hipGetLastError();
+}
+
+hipError_t run_rotate_smooth_quant(const void *X, bool f32, int rows, int K, const int8_t *signs,
+                                   const float *mul, int mul_mode, uint8_t *packed, float *scale,
+                                   hipStream_t stream)
+{
+    return launch_rotate_rows<kQuantize>(X, f32, rows, K, signs, mul, mul_mode, packed, scale, nullptr, stream);
+}
+
+hipError_t run_rotated_col_absmax(const void *X, bool f32, int rows, int K, const int8_t *signs,
+                                  float *absmax, hipStream_t stream)
+{
+    fill_u32_kernel<<<(K + 255) / 256, 256, 0, stream>>>(reinterpret_cast<unsigned int *>(absmax), K, 0u);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_rotate_rows<kColAbsMax>(X, f32, rows, K, signs, nullptr, 0, nullptr, nullptr,
+                                          reinterpret_cast<unsigned int *>(absmax), stream);
+}
+
+hipError_t run_smooth_factor(float *buf, const float *act_absmax, int K, float alpha, hipStream_t stream)
+{
+    smooth_factor_kernel<<<(K + 255) / 256, 256, 0, stream>>>(buf, act_absmax, K, alpha);
+    return hipGetLastError();
+}
+
+hipError_t run_fill_f32(float *p, int n, float v, hipStream_t stream)
+{
+    fill_f32_kernel<<<(n + 255) / 256, 256, 0, stream>>>(p, n, v);
+    return hipGetLastError();
+}
+
+hipError_t run_pack_int4(const int8_t *codes, int rows, int K, uint8_t *packed, hipStream_t stream)
+{
+    size_t n = (size_t)rows * (K / 2);
+    if (n == 0) return hipSuccess;
+    pack_int4_kernel<<<(unsigned)((n + 255) / 256), 256, 0, stream>>>(codes, (size_t)rows, K, packed);
+    return hipGetLastError();
+}
+
+hipError_t run_unpack_int4(const uint8_t *packed, int rows, int K, int8_t *codes, hipStream_t stream)
+{
+    size_t n = (size_t)rows * K;
+    if (n == 0) return hipSuccess;
+    unpack_int4_kernel<<<(unsigned)((n + 255) / 256), 256, 0, stream>>>(packed, (size_t)rows, K, codes);
+    return hipGetLastError();
+}
+
+}  // namespace qvggt

@@ -1,0 +1,97 @@
+"""Helpers of the GPU parity tests: move synthetic tensors to the device, call the C ABI through
+the binding, bring results back as numpy.  No method arithmetic here."""
+import numpy as np
+import torch
+
+import paper_2509_21302_amd as q
+
+DEV = "cuda:0"
+
+
+def to_dev(a):
+    """Synthetic tensor -> device tensor.  uint16 arrays are bf16 bit patterns."""
+    if a is None:
+        return None
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).to(DEV).view(torch.bfloat16)
+    return torch.from_numpy(a).to(DEV)
+
+
+def bf16_bits(t):
+    """device bf16 tensor -> numpy uint16 bit patterns"""
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def gpu_prep(W, X_cal, signs, alpha=0.5):
+    """qvggt_rotated_col_absmax + qvggt_prep_weights.  Returns dict of device tensors."""
+    Wd, sd = to_dev(W), to_dev(signs)
+    N, K = Wd.shape
+    a = None
+    if X_cal is not None:
+        a = torch.empty(K, dtype=torch.float32, device=DEV)
+        q.qvggt_rotated_col_absmax(to_dev(X_cal), sd, a)
+    Wq = torch.empty(N, K // 2, dtype=torch.uint8, device=DEV)
+    sw = torch.empty(N, dtype=torch.float32, device=DEV)
+    inv = torch.empty(K, dtype=torch.float32, device=DEV)
+    q.qvggt_prep_weights(Wd, a, sd, alpha, Wq, sw, inv)
+    return dict(Wq=Wq, sw=sw, inv=inv, signs=sd, a=a, N=N, K=K)
+
+
+def gpu_rsq(Xd, signs_d, inv_d):
+    M, K = Xd.shape
+    Xq = torch.empty(M, K // 2, dtype=torch.uint8, device=DEV)
+    sx = torch.empty(M, dtype=torch.float32, device=DEV)
+    q.qvggt_rotate_smooth_quant(Xd, signs_d, inv_d, Xq, sx)
+    return Xq, sx
+
+
+def gpu_unpack(packed, K):
+    rows = packed.shape[0]
+    codes = torch.empty(rows, K, dtype=torch.int8, device=DEV)
+    q.qvggt_unpack_int4(packed, codes)
+    return codes.cpu().numpy()
+
+
+def gpu_pack(codes_np):
+    c = torch.from_numpy(np.ascontiguousarray(codes_np, dtype=np.int8)).to(DEV)
+    rows, K = c.shape
+    packed = torch.empty(rows, K // 2, dtype=torch.uint8, device=DEV)
+    q.qvggt_pack_int4(c, packed)
+    return packed
+
+
+def gpu_linear(Xd, prep, bias_d):
+    M, K = Xd.shape
+    N = prep["N"]
+    Y = torch.empty(M, N, dtype=torch.bfloat16, device=DEV)
+    ws = torch.empty(q.qvggt_workspace_bytes(M, N, K), dtype=torch.uint8, device=DEV)
+    q.qvggt_linear(Xd, prep["signs"], prep["inv"], prep["Wq"], prep["sw"], bias_d, Y, ws)
+    return Y
+
+
+# ---- the acceptance criteria of the quantized path -----------------------------------------
+CODE_MISMATCH_FRACTION = 1e-4     # activation codes may differ by one step on at most 0.01 % of elements
+SCALE_RTOL = 1e-5                 # fp32 butterflies and scaling against the fp64 oracle
+Y_REL_FRO = 1e-2                  # final bf16 output, relative Frobenius error
+
+
+def check_codes(got, want, what=""):
+    d = np.abs(got.astype(np.int16) - want.astype(np.int16))
+    assert d.max(initial=0) <= 1, f"{what}: a code differs by {d.max()}"
+    frac = float((d != 0).mean()) if d.size else 0.0
+    assert frac <= CODE_MISMATCH_FRACTION, f"{what}: {frac:.3e} of the codes differ (allowed {CODE_MISMATCH_FRACTION})"
+    return frac
+
+
+def check_scales(got, want, what=""):
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    err = np.abs(got - want) / np.maximum(np.abs(want), 1e-300)
+    err[want == 0] = np.abs(got[want == 0])
+    assert err.max(initial=0) <= SCALE_RTOL, f"{what}: scale rel err {err.max():.3e}"
+
+
+def rel_fro(got_bits, want_bits):
+    g = (np.asarray(got_bits, np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    w = (np.asarray(want_bits, np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    return float(np.linalg.norm(g - w) / max(np.linalg.norm(w), 1e-300))

@@ -1,0 +1,91 @@
+"""CPU-side checks of the C-ABI library: it loads, exports what the header declares, and
+rejects bad arguments on the host before any launch (no GPU needed, no compute calls)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2509_21302_amd as q
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "qvggt.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(qvggt_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = q.load_library()
+    declared = _declared_symbols()
+    assert declared, "no declarations found in include/qvggt.h"
+    for name in declared:
+        assert hasattr(lib, name), f"{name} declared in qvggt.h but not exported"
+    assert sorted(q.EXPORTS) == declared
+
+
+def test_status_strings():
+    assert q.qvggt_status_string(0) == "QVGGT_OK"
+    for s in range(1, 8):
+        assert q.qvggt_status_string(s).startswith("QVGGT_ERR_")
+    assert "unknown" in q.qvggt_status_string(99)
+
+
+def test_workspace_bytes():
+    assert q.qvggt_workspace_bytes(1374, 3072, 1024) >= 1374 * 512 + 1374 * 4
+    assert q.qvggt_workspace_bytes(0, 3072, 1024) > 0
+    assert q.qvggt_workspace_bytes(10, 3072, 1000) == 0      # K not a power of two
+    assert q.qvggt_workspace_bytes(10, 3070, 1024) == 0      # N not a multiple of 16
+    assert q.qvggt_workspace_bytes(-1, 3072, 1024) == 0
+
+
+OK, NULL, SHAPE, ALIGN, DTYPE, WORKSPACE, ARG = 0, 1, 2, 3, 4, 5, 6
+P = 0x10000  # a fake, aligned, non-NULL device address: validation failures return before any use
+
+
+def test_argument_validation_needs_no_gpu():
+    lib = q.load_library()
+    # shapes
+    assert lib.qvggt_rotate_smooth_quant(P, 0, 4, 1000, None, None, P, P, None) == SHAPE
+    assert lib.qvggt_rotate_smooth_quant(P, 0, 4, 64, None, None, P, P, None) == SHAPE
+    assert lib.qvggt_rotate_smooth_quant(P, 0, 4, 16384, None, None, P, P, None) == SHAPE
+    assert lib.qvggt_rotate_smooth_quant(P, 0, -1, 1024, None, None, P, P, None) == SHAPE
+    assert lib.qvggt_w4a4_gemm(P, P, P, P, None, 4, 100, 1024, P, None, None) == SHAPE
+    assert lib.qvggt_w4a4_gemm(P, P, P, P, None, 4, 0, 1024, P, None, None) == SHAPE
+    assert lib.qvggt_prep_weights(P, 0, 24, 1024, None, None, C.c_float(0.5), P, P, P, None) == SHAPE
+    # dtype
+    assert lib.qvggt_rotate_smooth_quant(P, 7, 4, 1024, None, None, P, P, None) == DTYPE
+    assert lib.qvggt_prep_weights(P, -1, 32, 1024, None, None, C.c_float(0.5), P, P, P, None) == DTYPE
+    assert lib.qvggt_linear(P, 2, 4, 32, 1024, None, None, P, P, None, P, P, 1 << 20, None) == DTYPE
+    # NULL pointers
+    assert lib.qvggt_rotate_smooth_quant(None, 0, 4, 1024, None, None, P, P, None) == NULL
+    assert lib.qvggt_rotate_smooth_quant(P, 0, 4, 1024, None, None, None, P, None) == NULL
+    assert lib.qvggt_w4a4_gemm(P, None, P, P, None, 4, 32, 1024, P, None, None) == NULL
+    assert lib.qvggt_prep_weights(P, 0, 32, 1024, None, None, C.c_float(0.5), P, None, P, None) == NULL
+    assert lib.qvggt_linear(P, 0, 4, 32, 1024, None, None, P, P, None, P, None, 1 << 20, None) == NULL
+    assert lib.qvggt_rotated_col_absmax(P, 0, 4, 1024, None, None, None) == NULL
+    assert lib.qvggt_pack_int4(None, 4, 1024, P, None) == NULL
+    # alignment
+    assert lib.qvggt_rotate_smooth_quant(P + 2, 0, 4, 1024, None, None, P, P, None) == ALIGN
+    assert lib.qvggt_w4a4_gemm(P, P, P, P, P + 8, 4, 32, 1024, P, None, None) == ALIGN
+    assert lib.qvggt_unpack_int4(P, 4, 1024, P + 1, None) == ALIGN
+    # alpha
+    for bad in (-0.1, 1.5, float("nan"), float("inf")):
+        assert lib.qvggt_prep_weights(P, 0, 32, 1024, None, None, C.c_float(bad), P, P, P, None) == ARG
+    # workspace
+    need = q.qvggt_workspace_bytes(100, 32, 1024)
+    assert lib.qvggt_linear(P, 0, 100, 32, 1024, None, None, P, P, None, P, P, need - 1, None) == WORKSPACE
+    # empty problems are accepted without touching anything
+    assert lib.qvggt_rotate_smooth_quant(None, 0, 0, 1024, None, None, None, None, None) == OK
+    assert lib.qvggt_w4a4_gemm(None, None, None, None, None, 0, 32, 1024, None, None, None) == OK
+    assert lib.qvggt_linear(None, 0, 0, 32, 1024, None, None, None, None, None, None, None, 0, None) == OK
+    assert lib.qvggt_pack_int4(None, 0, 1024, None, None) == OK
+
+
+def test_binding_rejects_host_tensors():
+    import torch
+    x = torch.zeros(4, 1024, dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        q.qvggt_rotate_smooth_quant(x, None, None, torch.zeros(4, 512, dtype=torch.uint8), torch.zeros(4))

@@ -1,0 +1,63 @@
+"""GPU parity of online kernel 2: int32 accumulators bit-exact against the oracle's integer
+product given identical codes, and the fused dequant + bias epilogue."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from tests import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(qx, qw, dx, dw, bias_bits):
+    M, K = qx.shape
+    N = qw.shape[0]
+    Xq, Wq = G.gpu_pack(qx), G.gpu_pack(qw)
+    Y = torch.empty(M, N, dtype=torch.bfloat16, device=G.DEV)
+    acc = torch.full((M, N), 12345, dtype=torch.int32, device=G.DEV)
+    import paper_2509_21302_amd as q
+    q.qvggt_w4a4_gemm(Xq, G.to_dev(dx.astype(np.float32)), Wq, G.to_dev(dw.astype(np.float32)),
+                      G.to_dev(bias_bits), M, N, K, Y, acc)
+    return acc.cpu().numpy(), G.bf16_bits(Y)
+
+
+@pytest.mark.parametrize("M,N,K", [(64, 128, 128), (1, 16, 128), (300, 384, 256), (129, 144, 1024),
+                                   (1374, 3072, 1024), (257, 1024, 4096), (33, 48, 8192)])
+def test_accumulators_bit_exact(M, N, K):
+    rng = np.random.default_rng(M * 7 + N)
+    qx = rng.integers(-8, 8, (M, K)).astype(np.int8)
+    qw = rng.integers(-8, 8, (N, K)).astype(np.int8)
+    dx = np.exp(rng.uniform(-3, 1, M))
+    dw = np.exp(rng.uniform(-5, -2, N))
+    bias = (rng.standard_normal(N) * 0.02).astype(np.float32)
+    from synth import f32_to_bf16_bits
+    bias_bits = f32_to_bf16_bits(bias)
+    acc, Y = _run(qx, qw, dx, dw, bias_bits)
+    want = oracle.int_gemm(qx, qw)
+    assert np.array_equal(acc, want)
+    # epilogue: the oracle applies the same fp32-stored scales in fp64 and rounds once
+    Yo = oracle.dequant_bias(want, dx.astype(np.float32), dw.astype(np.float32), oracle.to_f64(bias_bits))
+    assert G.rel_fro(Y, Yo) <= 1e-3
+    ulp_off = np.abs(Y.astype(np.int32) - Yo.astype(np.int32))
+    assert ulp_off.max() <= 1 and (ulp_off != 0).mean() < 5e-3
+
+
+def test_extreme_codes_and_no_bias():
+    M, N, K = 40, 32, 4096
+    qx = np.full((M, K), -8, np.int8)
+    qw = np.full((N, K), -8, np.int8)
+    qw[1::2] = 7
+    acc, Y = _run(qx, qw, np.ones(M), np.ones(N), None)
+    assert np.array_equal(acc, oracle.int_gemm(qx, qw))
+    assert acc.max() == 64 * K and acc.min() == -56 * K
+    assert np.array_equal(Y, oracle.dequant_bias(acc, np.ones(M), np.ones(N)))
+
+
+def test_identity_like_weights_reproduce_codes():
+    M, K = 70, 128
+    rng = np.random.default_rng(1)
+    qx = rng.integers(-8, 8, (M, K)).astype(np.int8)
+    qw = np.eye(K, dtype=np.int8)
+    acc, _ = _run(qx, qw, np.ones(M), np.ones(K), None)
+    assert np.array_equal(acc, qx.astype(np.int32))

@@ -1,0 +1,136 @@
+"""End-to-end GPU parity of qvggt_linear against the oracle on the synthetic VGGT-shaped configs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from tests import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle_prep(s):
+    signs = synth.make_signs(s)
+    a = oracle.rotated_col_absmax(synth.make_calibration(s), pre_signs=signs)
+    return signs, oracle.prepare_weights(synth.make_weights(s), a, pre_signs=signs, alpha=0.5)
+
+
+def _gpu_prep(s):
+    return G.gpu_prep(synth.make_weights(s), synth.make_calibration(s), synth.make_signs(s), 0.5)
+
+
+def _sample_rows(s, n_random, seed):
+    """Rows checked at sizes where the dense oracle cannot do all of them: the special tokens of the
+    first, second and last frame, the last 64 rows (ragged tail tile) and a seeded random draw."""
+    rows = set()
+    for f in sorted({0, min(1, s.frames - 1), s.frames - 1}):
+        rows.update(range(f * s.rows_per_frame, f * s.rows_per_frame + synth.SPECIAL_TOKENS))
+    rows.update(range(s.M - 64, s.M))
+    rng = np.random.default_rng(seed)
+    rows.update(int(r) for r in rng.choice(s.M, n_random, replace=False))
+    return np.array(sorted(rows))
+
+
+@pytest.mark.parametrize("config,name", [(1, "tiny"), (2, "qkv"), (3, "fc1")])
+def test_linear_full_rows(config, name):
+    s = synth.layer_spec(config, name)
+    X, bias = synth.make_activation_frames(s), synth.make_bias(s)
+    signs, prep_o = _oracle_prep(s)
+    want = oracle.linear(X, prep_o, bias=bias, pre_signs=signs)
+    prep_g = _gpu_prep(s)
+    Y = G.bf16_bits(G.gpu_linear(G.to_dev(X), prep_g, G.to_dev(bias)))
+    err = G.rel_fro(Y, want.Y)
+    assert err <= G.Y_REL_FRO, err
+    # the quantized result is also a sane approximation of the exact product
+    exact = oracle.to_f64(X[:256]) @ oracle.to_f64(synth.make_weights(s)).T + (0 if bias is None else oracle.to_f64(bias))
+    got = oracle.bf16_bits_to_f64(Y[:256])
+    assert np.linalg.norm(got - exact) / np.linalg.norm(exact) < 0.35
+
+
+@pytest.mark.parametrize("config,name,n_random", [(3, "fc2", 700), (4, "qkv", 1500), (4, "proj", 1500),
+                                                  (4, "fc1", 1500), (4, "fc2", 500), (5, "fc1", 1500),
+                                                  (5, "fc2", 500)])
+def test_linear_full_size_sampled_rows(config, name, n_random):
+    """Full M on the GPU (the shapes the benchmark times); the oracle recomputes a seeded sample of rows.
+    Rows are independent in every step of the path, so this is an exact test of those rows."""
+    s = synth.layer_spec(config, name)
+    rows = _sample_rows(s, n_random, seed=config * 10 + len(name))
+    signs, prep_o = _oracle_prep(s)
+    prep_g = _gpu_prep(s)
+    bias = synth.make_bias(s)
+    X = synth.make_activation_frames(s)
+    Xd = G.to_dev(X)
+    Xs = X[rows]
+    del X
+    want = oracle.linear(Xs, prep_o, bias=bias, pre_signs=signs)
+    # whole path
+    Yd = G.gpu_linear(Xd, prep_g, G.to_dev(bias))
+    idx = torch.from_numpy(rows).to(G.DEV)
+    err = G.rel_fro(G.bf16_bits(Yd[idx]), want.Y)
+    assert err <= G.Y_REL_FRO, err
+    del Yd
+    # kernel 1 alone, same launch
+    Xq, sx = G.gpu_rsq(Xd, prep_g["signs"], prep_g["inv"])
+    G.check_codes(G.gpu_unpack(Xq[idx].contiguous(), s.K), want.qx, f"cfg{config} {name}")
+    G.check_scales(sx[idx].cpu().numpy(), want.dx, f"cfg{config} {name}")
+
+
+def test_gemm_full_size_sampled_rows_bit_exact():
+    """Config 5 fc1 shape with seeded random codes: accumulators of sampled rows are bit-exact."""
+    import paper_2509_21302_amd as q
+    M, N, K = 137400, 4096, 1024
+    gen = torch.Generator(device="cpu").manual_seed(55)
+    qx = torch.randint(-8, 8, (M, K), generator=gen, dtype=torch.int8)
+    qw = torch.randint(-8, 8, (N, K), generator=gen, dtype=torch.int8)
+    rows = np.unique(np.concatenate([np.arange(0, 5), np.arange(M - 64, M),
+                                     np.random.default_rng(5).choice(M, 600, replace=False)]))
+    Xq, Wq = G.gpu_pack(qx.numpy()), G.gpu_pack(qw.numpy())
+    sx = torch.ones(M, device=G.DEV)
+    sw = torch.ones(N, device=G.DEV)
+    Y = torch.empty(M, N, dtype=torch.bfloat16, device=G.DEV)
+    acc = torch.empty(M, N, dtype=torch.int32, device=G.DEV)
+    q.qvggt_w4a4_gemm(Xq, sx, Wq, sw, None, M, N, K, Y, acc)
+    got = acc[torch.from_numpy(rows).to(G.DEV)].cpu().numpy()
+    want = oracle.int_gemm(qx.numpy()[rows], qw.numpy())
+    assert np.array_equal(got, want)
+
+
+def test_chained_mlp_fc1_gelu_fc2():
+    """Config 3 as a chain on two frames: fc1 -> exact-erf GELU (harness code, outside the judged path) -> fc2.
+    Both sides run their own chain from the same X; nothing computed on the GPU feeds the oracle."""
+    from scipy.special import erf
+    s1, s2 = synth.layer_spec(3, "fc1"), synth.layer_spec(3, "fc2")
+    X = synth.make_activation_frames(s1, [0, 1])
+    signs1, signs2 = synth.make_signs(s1), synth.make_signs(s2)
+    W1, W2, b1, b2 = synth.make_weights(s1), synth.make_weights(s2), synth.make_bias(s1), synth.make_bias(s2)
+    # oracle chain; the fc2 smoothing statistic is calibrated on the chain's own fc2 input (first frame)
+    a1 = oracle.rotated_col_absmax(synth.make_calibration(s1), pre_signs=signs1)
+    p1 = oracle.prepare_weights(W1, a1, pre_signs=signs1)
+    h = oracle.bf16_bits_to_f64(oracle.linear(X, p1, bias=b1, pre_signs=signs1).Y)
+    h = h.astype(np.float32).astype(np.float64)
+    act = oracle.bf16_from_f64(0.5 * h * (1.0 + erf(h / np.sqrt(2.0))))
+    a2 = oracle.rotated_col_absmax(act[:1374], pre_signs=signs2)
+    p2 = oracle.prepare_weights(W2, a2, pre_signs=signs2)
+    want = oracle.linear(act, p2, bias=b2, pre_signs=signs2)
+    # GPU chain
+    g1 = G.gpu_prep(W1, synth.make_calibration(s1), signs1)
+    hd = G.gpu_linear(G.to_dev(X), g1, G.to_dev(b1))
+    actd = torch.nn.functional.gelu(hd.float()).to(torch.bfloat16)
+    g2 = G.gpu_prep(W2, G.bf16_bits(actd[:1374]), signs2)
+    Yd = G.gpu_linear(actd, g2, G.to_dev(b2))
+    assert G.rel_fro(G.bf16_bits(actd), act) <= G.Y_REL_FRO
+    err = G.rel_fro(G.bf16_bits(Yd), want.Y)
+    assert err <= 3 * G.Y_REL_FRO, err   # two quantized layers in sequence: see the design doc on the chained tolerance
+
+
+def test_linear_matches_its_two_kernels():
+    s = synth.layer_spec(2)
+    X, bias = G.to_dev(synth.make_activation_frames(s)), G.to_dev(synth.make_bias(s))
+    prep = _gpu_prep(s)
+    Y1 = G.gpu_linear(X, prep, bias)
+    import paper_2509_21302_amd as q
+    Xq, sx = G.gpu_rsq(X, prep["signs"], prep["inv"])
+    Y2 = torch.empty_like(Y1)
+    q.qvggt_w4a4_gemm(Xq, sx, prep["Wq"], prep["sw"], bias, s.M, s.N, s.K, Y2, None)
+    assert torch.equal(Y1, Y2)

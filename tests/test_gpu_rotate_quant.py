@@ -1,0 +1,130 @@
+"""GPU parity of online kernel 1 (rotate, smooth, per-token quantize) and of the offline weight
+preparation against the CPU oracle, element by element, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from tests import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+
+def _heavy(rows, K, seed, dtype="bf16"):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_t(3, (rows, K)).astype(np.float32)
+    x[:, rng.choice(K, max(1, K // 100), replace=False)] *= 50
+    x[: min(5, rows)] *= 20
+    return synth.f32_to_bf16_bits(x) if dtype == "bf16" else x
+
+
+@pytest.mark.parametrize("K", [128, 256, 512, 1024, 2048, 4096, 8192])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_rotate_quant_all_sizes(K, dtype):
+    rows = 37 if K >= 2048 else 203          # ragged: not a multiple of the rows a block takes
+    X = _heavy(rows, K, 100 + K, dtype)
+    rng = np.random.default_rng(K)
+    signs = (rng.integers(0, 2, K) * 2 - 1).astype(np.int8)
+    c_hat = np.exp(rng.uniform(-1, 1, K))
+    inv = (1.0 / (np.sqrt(K) * c_hat)).astype(np.float32)
+    dx, qx, _ = oracle.rotate_smooth_quant(X, 1.0 / (inv.astype(np.float64) * np.sqrt(K)), pre_signs=signs)
+    Xq, sx = G.gpu_rsq(G.to_dev(X), G.to_dev(signs), G.to_dev(inv))
+    G.check_codes(G.gpu_unpack(Xq, K), qx, f"K={K}")
+    G.check_scales(sx.cpu().numpy(), dx, f"K={K}")
+
+
+def test_rotate_quant_optional_arguments():
+    K, rows = 1024, 64
+    X = _heavy(rows, K, 7)
+    signs = synth.make_signs(synth.layer_spec(2))
+    Xd = G.to_dev(X)
+    # no signs, no smoothing: plain orthonormal Hadamard
+    dx, qx, _ = oracle.rotate_smooth_quant(X)
+    Xq, sx = G.gpu_rsq(Xd, None, None)
+    G.check_codes(G.gpu_unpack(Xq, K), qx)
+    G.check_scales(sx.cpu().numpy(), dx)
+    # signs only
+    dx, qx, _ = oracle.rotate_smooth_quant(X, pre_signs=signs)
+    Xq, sx = G.gpu_rsq(Xd, G.to_dev(signs), None)
+    G.check_codes(G.gpu_unpack(Xq, K), qx)
+    G.check_scales(sx.cpu().numpy(), dx)
+
+
+def test_zero_rows_and_single_row():
+    K = 1024
+    X = _heavy(3, K, 9)
+    X[1] = 0
+    dx, qx, _ = oracle.rotate_smooth_quant(X)
+    Xq, sx = G.gpu_rsq(G.to_dev(X), None, None)
+    codes = G.gpu_unpack(Xq, K)
+    assert sx[1].item() == 0.0 and not codes[1].any()
+    G.check_codes(codes, qx)
+    Xq1, sx1 = G.gpu_rsq(G.to_dev(X[:1]), None, None)
+    assert np.array_equal(G.gpu_unpack(Xq1, K), codes[:1])
+
+
+def test_one_hot_row_is_dispersed_exactly():
+    # a single outlier spreads to +-v/sqrt(K) everywhere: every code is +-7 and follows the Hadamard row
+    K = 4096
+    x = np.zeros((1, K), np.float32)
+    x[0, 1234] = 3.0
+    Xq, sx = G.gpu_rsq(G.to_dev(synth.f32_to_bf16_bits(x)), None, None)
+    codes = G.gpu_unpack(Xq, K)
+    assert np.array_equal(codes[0], 7 * oracle.hadamard(K)[1234])
+    assert abs(sx.item() - 3.0 / 64 / 7) < 1e-7
+
+
+def test_pack_unpack_roundtrip_and_determinism():
+    K = 1024
+    rng = np.random.default_rng(3)
+    codes = rng.integers(-8, 8, (77, K)).astype(np.int8)
+    packed = G.gpu_pack(codes)
+    assert np.array_equal(G.gpu_unpack(packed, K), codes)
+    assert np.array_equal(G.gpu_pack(codes).cpu().numpy(), packed.cpu().numpy())
+    # a packed row is a permutation of the canonical nibble stream: same multiset of nibbles
+    canon = oracle.pack_int4(codes)
+    nib = lambda p: np.sort(np.concatenate([p & 0xF, p >> 4], axis=1), axis=1)
+    assert np.array_equal(nib(packed.cpu().numpy()), nib(canon))
+
+
+@pytest.mark.parametrize("config,name", [(1, "tiny"), (2, "qkv")])
+def test_config_activations_and_weights(config, name):
+    s = synth.layer_spec(config, name)
+    X, W, signs, Xcal = synth.make_activation_frames(s), synth.make_weights(s), synth.make_signs(s), synth.make_calibration(s)
+    a = oracle.rotated_col_absmax(Xcal, pre_signs=signs)
+    prep_o = oracle.prepare_weights(W, a, pre_signs=signs, alpha=0.5)
+    prep_g = G.gpu_prep(W, Xcal, signs, 0.5)
+    G.check_scales(prep_g["a"].cpu().numpy(), a, "rotated activation absmax")
+    G.check_scales(prep_g["inv"].cpu().numpy(), 1.0 / (np.sqrt(s.K) * prep_o.c_hat), "inv_smooth")
+    G.check_scales(prep_g["sw"].cpu().numpy(), prep_o.dw, "w_scale")
+    G.check_codes(G.gpu_unpack(prep_g["Wq"], s.K), prep_o.qw, "weight codes")
+    dx, qx, _ = oracle.rotate_smooth_quant(X, prep_o.c_hat, pre_signs=signs)
+    Xq, sx = G.gpu_rsq(G.to_dev(X), prep_g["signs"], prep_g["inv"])
+    G.check_codes(G.gpu_unpack(Xq, s.K), qx, "activation codes")
+    G.check_scales(sx.cpu().numpy(), dx, "x_scale")
+    assert np.abs(G.gpu_unpack(Xq, s.K)).max() <= 7
+
+
+def test_prep_without_smoothing_and_alpha_extremes():
+    s = synth.layer_spec(1)
+    W, signs, Xcal = synth.make_weights(s), synth.make_signs(s), synth.make_calibration(s)
+    g = G.gpu_prep(W, None, signs)
+    o = oracle.prepare_weights(W, None, pre_signs=signs)
+    assert np.allclose(g["inv"].cpu().numpy(), 1 / np.sqrt(s.K), rtol=1e-6)
+    G.check_codes(G.gpu_unpack(g["Wq"], s.K), o.qw)
+    G.check_scales(g["sw"].cpu().numpy(), o.dw)
+    a = oracle.rotated_col_absmax(Xcal, pre_signs=signs)
+    for alpha in (0.0, 1.0, 0.3):
+        g = G.gpu_prep(W, Xcal, signs, alpha)
+        o = oracle.prepare_weights(W, a, pre_signs=signs, alpha=alpha)
+        G.check_scales(g["inv"].cpu().numpy(), 1.0 / (np.sqrt(s.K) * o.c_hat), f"alpha={alpha}")
+        G.check_codes(G.gpu_unpack(g["Wq"], s.K), o.qw, f"alpha={alpha}")
+
+
+def test_run_to_run_bit_identity():
+    s = synth.layer_spec(2)
+    X = G.to_dev(synth.make_activation_frames(s))
+    signs = G.to_dev(synth.make_signs(s))
+    a, b = G.gpu_rsq(X, signs, None), G.gpu_rsq(X, signs, None)
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])

@@ -12,9 +12,30 @@ constexpr int kMaxK = 8192;
 // Position of natural element e inside a packed row of K codes.  Two codes share a byte:
 // position p lives in byte p / 2, low nibble when p is even.  The same map is used for
 // activations and weights, so integer dot products do not depend on it.
-__host__ __device__ inline int code_position(int e, int /*K*/) { return e; }
+//
+// For K = 1024, 2048, 4096 the map is the one the matrix-core rotation kernel produces
+// naturally: with e = 128*hb + 32*nt + c (c < 32, nt < 4), position = c*(K/32) + nt + 4*hb',
+// where hb' = hb except for K = 4096, which swaps bits 3 and 4 of hb.  Other K keep natural order.
+__host__ __device__ inline bool layout_is_permuted(int K) { return K == 1024 || K == 2048 || K == 4096; }
+
+__host__ __device__ inline int swap_bits_3_4(int v) { return (v & ~0x18) | ((v & 8) << 1) | ((v & 16) >> 1); }
+
+__host__ __device__ inline int code_position(int e, int K)
+{
+    if (!layout_is_permuted(K)) return e;
+    int c = e & 31, nt = (e >> 5) & 3, hb = e >> 7;
+    if (K == 4096) hb = swap_bits_3_4(hb);
+    return c * (K / 32) + nt + 4 * hb;
+}
 // Inverse of code_position: the natural element stored at position p.
-__host__ __device__ inline int code_element(int p, int /*K*/) { return p; }
+__host__ __device__ inline int code_element(int p, int K)
+{
+    if (!layout_is_permuted(K)) return p;
+    int c = p / (K / 32), l = p % (K / 32);
+    int nt = l & 3, hb = l >> 2;
+    if (K == 4096) hb = swap_bits_3_4(hb);
+    return 128 * hb + 32 * nt + c;
+}
 
 __device__ inline float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
 

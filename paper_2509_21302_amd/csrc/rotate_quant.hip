@@ -102,6 +102,8 @@ __global__ __launch_bounds__(256) void rotate_rows_kernel(const void *__restrict
                                                           unsigned int *__restrict__ col_absmax_bits)
 {
     constexpr int V = RowMap<K>::V, C = RowMap<K>::C, R = RowMap<K>::R;
+    constexpr bool kPermuted = (K == 1024 || K == 2048 || K == 4096) && MODE == kQuantize;
+    __shared__ __attribute__((aligned(16))) uint8_t lds_stage[kPermuted ? 4 * K : 16];
     const int lane = threadIdx.x & 63;
     const int wave = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     const int nwaves = gridDim.x * (blockDim.x >> 6);
@@ -146,6 +148,31 @@ __global__ __launch_bounds__(256) void rotate_rows_kernel(const void *__restrict
             const float inv = amax > 0.0f ? 7.0f / amax : 0.0f;
             if (lane == 0) scale[row] = amax / 7.0f;
             uint8_t *out = packed + (size_t)row * (K / 2);
+            if constexpr (K == 1024 || K == 2048 || K == 4096) {
+                // permuted layout: scatter the codes as bytes into the wave's LDS row at their positions,
+                // then every lane packs K/64 consecutive positions
+                uint8_t *stage = lds_stage + (threadIdx.x >> 6) * K;
+#pragma unroll
+                for (int c = 0; c < C; ++c)
+#pragma unroll
+                    for (int i = 0; i < V; ++i) {
+                        int q = (int)__builtin_rintf(x[c * V + i] * inv);
+                        q = min(7, max(-8, q));
+                        stage[code_position(c * 64 * V + lane * V + i, K)] = (uint8_t)(q & 0xF);
+                    }
+                __builtin_amdgcn_wave_barrier();
+                constexpr int PER_LANE = K / 64;      // positions per lane, a multiple of 16
+#pragma unroll
+                for (int b = 0; b < PER_LANE / 8; ++b) {
+                    const uint2 v = *reinterpret_cast<const uint2 *>(stage + lane * PER_LANE + 8 * b);
+                    // bytes hold one code each (low nibble): squeeze 8 bytes into 8 nibbles
+                    uint32_t lo = v.x, hi = v.y;
+                    lo = (lo | (lo >> 4)) & 0x00FF00FFu; lo = (lo | (lo >> 8)) & 0x0000FFFFu;
+                    hi = (hi | (hi >> 4)) & 0x00FF00FFu; hi = (hi | (hi >> 8)) & 0x0000FFFFu;
+                    *reinterpret_cast<uint32_t *>(out + lane * (PER_LANE / 2) + 4 * b) = lo | (hi << 16);
+                }
+                __builtin_amdgcn_wave_barrier();
+            } else {
 #pragma unroll
             for (int c = 0; c < C; ++c) {
                 uint32_t word = 0;
@@ -160,6 +187,7 @@ __global__ __launch_bounds__(256) void rotate_rows_kernel(const void *__restrict
                 if constexpr (V == 8) *reinterpret_cast<uint32_t *>(out + byte0) = word;
                 else if constexpr (V == 4) *reinterpret_cast<uint16_t *>(out + byte0) = (uint16_t)word;
                 else out[byte0] = (uint8_t)word;
+            }
             }
         }
     }
@@ -247,10 +275,16 @@ static hipError_t launch_rotate_rows(const void *X, bool f32, int rows, int K, c
     return hipGetLastError();
 }
 
+hipError_t run_rotate_quant_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, int mul_mode,
+                                 uint8_t *packed, float *scale, hipStream_t stream);
+
 hipError_t run_rotate_smooth_quant(const void *X, bool f32, int rows, int K, const int8_t *signs,
                                    const float *mul, int mul_mode, uint8_t *packed, float *scale,
                                    hipStream_t stream)
 {
+    // bf16 rows of the sizes VGGT-1B uses go to the matrix-core kernel; everything else to the generic one
+    if (!f32 && (K == 1024 || K == 2048 || K == 4096))
+        return run_rotate_quant_mfma(X, rows, K, signs, mul, mul_mode, packed, scale, stream);
     return launch_rotate_rows<kQuantize>(X, f32, rows, K, signs, mul, mul_mode, packed, scale, nullptr, stream);
 }
 

@@ -1,0 +1,292 @@
+// Online kernel 1, matrix-core version for bf16 rows of K = 1024, 2048 or 4096 values.
+//
+// The Hadamard matrix is a Kronecker power (paper Sec. 3.2): H_K = H_{K/128} (x) H_128.  With a
+// row viewed as a (K/128) x 128 matrix R ("hi-block" hb, low index n), the transform is
+// H_{K/128} . R . H_128.  The right factor is taken on the matrix cores: the bf16 inputs and the
+// +-1 entries are exact operands and the sums accumulate in fp32, so R . H_128 has fp32-butterfly
+// accuracy at 1/16 of a vector-ALU op per element.  The left factor (3 to 5 butterfly stages over
+// hb) is done by the vector ALU on the accumulator registers.  Everything after that (multiply by
+// inv_smooth, per-token absmax, round, pack) stays in the same registers.
+//
+// One wavefront handles a tile of 32 segments of 128 values (= 32 MFMA rows): 4 tokens for K = 1024,
+// 2 for 2048, 1 for 4096.  Per tile: coalesced 16-byte global loads -> sign flip on the packed bf16 ->
+// wave-private LDS rows (pitch 272 B, conflict-free 16-byte fragment reads) -> 32 MFMA 32x32x16 bf16
+// (8 K-steps x 4 column tiles) -> butterflies over hb -> scale, absmax, quantize -> 16/32-byte stores.
+// The next tile's global loads are issued before the current tile is processed.
+//
+// MFMA row m of a tile holds segment (token tk, hi-block hb); the bits of hb go to m bits 0, 1, 3, 4, 2
+// (in that order) and the token bits fill the rest.  In the 32x32 result layout a lane owns column
+// c = lane % 32 and rows 8*(r/4) + 4*(lane/32) + r%4 for its 16 registers r, so m bits 0, 1, 3, 4 are
+// register-index bits (butterflies between registers) and m bit 2 is the lane half.
+//
+// Packed layout written (the same bijection is applied to weight rows, and qvggt_pack_int4 /
+// qvggt_unpack_int4 implement it): element e = 128*hb + 32*nt + c goes to position
+//   c * (K/32) + nt + 4*hb'      (hb' = hb, except for K = 4096 where bits 3 and 4 of hb are swapped)
+// so that a lane's codes of one token are contiguous.
+#include "qvggt_common.h"
+
+namespace qvggt {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+namespace rq {
+constexpr int LDS_PITCH = 272;                 // bytes per 128-value bf16 segment row (256 + 16 pad)
+constexpr int LDS_PER_WAVE = 32 * LDS_PITCH;   // 8704
+constexpr int WAVES_PER_BLOCK = 4;
+constexpr float MAGIC = 12582912.0f + 8.0f;    // 1.5 * 2^23 + 8: adding it leaves (code + 8) in the low mantissa bits
+constexpr uint32_t MAGIC_BITS = 0x4B400000u;
+
+template <int K>
+struct Cfg {
+    static constexpr int HB = K / 128;                       // hi-blocks per token
+    static constexpr int REM = (K == 1024) ? 3 : (K == 2048) ? 4 : 5;
+    static constexpr int TOK = 32 / HB;                      // tokens per tile
+    static constexpr int TOK_PER_LANE = (REM == 3) ? 2 : 1;  // tokens a lane sees in its registers
+    static constexpr int HB_PER_LANE = (REM == 3) ? 8 : 16;  // hi-blocks per lane and token
+    static constexpr int NL = 4 * HB_PER_LANE;               // codes per lane and token
+    static constexpr int SIGN_CLASSES = K / 512;             // distinct column chunks a lane loads
+};
+
+// MFMA row of segment `seg` (= tk * HB + hb) of a tile, without the two lowest hb bits
+// (those are m bits 0 and 1 and come from the lane at run time).
+template <int K>
+__host__ __device__ constexpr int row_of_seg_hi(int seg_hi /* seg >> 2 */)
+{
+    constexpr int REM = Cfg<K>::REM;
+    // seg_hi bits: hb2.. then token bits.  hb2 -> m3, hb3 -> m4, hb4 -> m2; token bits fill what is left, ascending.
+    int m = 0;
+    if (REM == 3) {            // seg_hi = hb2 | tk0 << 1 | tk1 << 2
+        m |= (seg_hi & 1) << 3; m |= ((seg_hi >> 1) & 1) << 2; m |= ((seg_hi >> 2) & 1) << 4;
+    } else if (REM == 4) {     // seg_hi = hb2 | hb3 << 1 | tk0 << 2
+        m |= (seg_hi & 1) << 3; m |= ((seg_hi >> 1) & 1) << 4; m |= ((seg_hi >> 2) & 1) << 2;
+    } else {                   // seg_hi = hb2 | hb3 << 1 | hb4 << 2
+        m |= (seg_hi & 1) << 3; m |= ((seg_hi >> 1) & 1) << 4; m |= ((seg_hi >> 2) & 1) << 2;
+    }
+    return m;
+}
+}  // namespace rq
+
+template <int K>
+__global__ __launch_bounds__(256, 2) void rotate_quant_mfma_kernel(const uint16_t *__restrict__ X, int rows,
+                                                                   const int8_t *__restrict__ signs,
+                                                                   const float *__restrict__ mul, int mul_mode,
+                                                                   uint8_t *__restrict__ packed,
+                                                                   float *__restrict__ scale)
+{
+    using C = rq::Cfg<K>;
+    constexpr int REM = C::REM, TOK = C::TOK, HB = C::HB;
+    __shared__ __attribute__((aligned(16))) uint8_t lds_all[rq::WAVES_PER_BLOCK * rq::LDS_PER_WAVE];
+
+    const int lane = threadIdx.x & 63, wave_in_block = threadIdx.x >> 6;
+    const int c = lane & 31, g = lane >> 5;
+    uint8_t *lds = lds_all + wave_in_block * rq::LDS_PER_WAVE;
+    const int wave = blockIdx.x * rq::WAVES_PER_BLOCK + wave_in_block;
+    const int nwaves = gridDim.x * rq::WAVES_PER_BLOCK;
+    const int ntiles = (rows + TOK - 1) / TOK;
+
+    // ---- per-lane constants -------------------------------------------------------------------
+    // sign masks for the packed bf16 pairs this lane loads: load j covers flat elements 512*j + 8*lane .. +8
+    uint32_t sgn[C::SIGN_CLASSES][4];
+#pragma unroll
+    for (int q = 0; q < C::SIGN_CLASSES; ++q)
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            uint32_t msk = 0;
+            if (signs != nullptr) {
+                const int e = 512 * q + 8 * lane + 2 * d;
+                if (signs[e] < 0) msk |= 0x00008000u;
+                if (signs[e + 1] < 0) msk |= 0x80000000u;
+            }
+            sgn[q][d] = msk;
+        }
+    // B operand: lane (n = c, k-half = g) holds H_128[k][n] for k = 16*ks + 8*g + i.  sign = parity(k & n):
+    //   bits 0..3 of k (8*g + i) against c & 15 -> base pattern; bit 4 (ks & 1) against c bit 4; bits 5, 6 (ks >> 1) against nt.
+    v8bf Bsel[2][2];
+    {
+        uint32_t w[4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            uint32_t lo = (__popc((8 * g + 2 * d) & (c & 15)) & 1) ? 0xBF80u : 0x3F80u;
+            uint32_t hi = (__popc((8 * g + 2 * d + 1) & (c & 15)) & 1) ? 0xBF80u : 0x3F80u;
+            w[d] = lo | (hi << 16);
+        }
+        const uint32_t flip_odd = (c & 16) ? 0x80008000u : 0u;
+#pragma unroll
+        for (int odd = 0; odd < 2; ++odd)
+#pragma unroll
+            for (int neg = 0; neg < 2; ++neg) {
+                uint32_t t[4];
+#pragma unroll
+                for (int d = 0; d < 4; ++d) t[d] = w[d] ^ (odd ? flip_odd : 0u) ^ (neg ? 0x80008000u : 0u);
+                Bsel[odd][neg] = *reinterpret_cast<v8bf *>(t);
+            }
+    }
+    // channel multipliers of the lane's values: register r, column tile nt -> element e
+    //   hb bits 0..2 = r bits 0..2;  REM 4: hb3 = r bit 3;  REM 5 (after the half swap): hb4 = r bit 3, hb3 = g
+    float cm[C::HB_PER_LANE][4];
+    {
+        const float rs = 1.0f / sqrtf((float)K);
+#pragma unroll
+        for (int h = 0; h < C::HB_PER_LANE; ++h)
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) {
+                int hb = h;
+                if (REM == 5) hb = (h & 7) | (g << 3) | ((h >> 3) << 4);
+                const int e = 128 * hb + 32 * nt + c;
+                float m = rs;
+                if (mul != nullptr) m = mul_mode ? 1.0f / ((float)K * mul[e]) : mul[e];
+                cm[h][nt] = m;
+            }
+    }
+
+    // ---- tile loop ------------------------------------------------------------------------------
+    const size_t max_flat = (size_t)rows * K;
+    auto tile_ptr = [&](int tile, int j) -> const uint4 * {
+        // flat element offset of this lane's 16 bytes of load j; rows past the end re-read the last row
+        size_t f = (size_t)tile * TOK * K + (size_t)512 * j + 8 * lane;
+        if (f >= max_flat) f = max_flat - K + (f % K);
+        return reinterpret_cast<const uint4 *>(X + f);
+    };
+    uint4 G[8];
+    int tile = wave;
+    if (tile < ntiles) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) G[j] = *tile_ptr(tile, j);
+    }
+    const int wr_base = ((lane >> 4) * rq::LDS_PITCH) + (lane & 15) * 16;
+    const int rd_base = c * rq::LDS_PITCH + g * 16;
+
+    for (; tile < ntiles; tile += nwaves) {
+        // stage the tile: flip signs on the packed bf16, write each 16-byte chunk to its MFMA row
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int q = j % C::SIGN_CLASSES;
+            uint4 v = G[j];
+            v.x ^= sgn[q][0]; v.y ^= sgn[q][1]; v.z ^= sgn[q][2]; v.w ^= sgn[q][3];
+            // segment index = 4*j + lane/16; its low two bits are lane/16 -> rows m0, m1
+            const int row_hi = rq::row_of_seg_hi<K>(j);
+            *reinterpret_cast<uint4 *>(lds + row_hi * rq::LDS_PITCH + wr_base) = v;
+        }
+        // prefetch the next tile
+        const int next = tile + nwaves;
+        if (next < ntiles) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) G[j] = *tile_ptr(next, j);
+        }
+
+        // R . H_128 on the matrix cores
+        v16f acc[4];
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[nt][r] = 0.0f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            const v8bf a = *reinterpret_cast<const v8bf *>(lds + rd_base + ks * 32);
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) {
+                const int neg = __builtin_popcount((ks >> 1) & nt) & 1;
+                acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, Bsel[ks & 1][neg], acc[nt], 0, 0, 0);
+            }
+        }
+
+        // H_{K/128} over the hi-block index: butterflies between accumulator registers
+        constexpr int REG_STAGES = (REM >= 4) ? 4 : 3;
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) {
+#pragma unroll
+            for (int s = 0; s < REG_STAGES; ++s) {
+                const int h = 1 << s;
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    if ((r & h) == 0) {
+                        float a = acc[nt][r], b = acc[nt][r + h];
+                        acc[nt][r] = a + b;
+                        acc[nt][r + h] = a - b;
+                    }
+            }
+            if constexpr (REM == 5) {
+                // hb bit 4 sits on the lane half: swap halves between registers r and r + 8, then the
+                // butterfly is between those two registers (register bit 3 now means hb4, the lane half hb3)
+#pragma unroll
+                for (int r = 0; r < 8; ++r) {
+                    auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[nt][r]), __float_as_uint(acc[nt][r + 8]), false, false);
+                    float a = __uint_as_float(sw[0]), b = __uint_as_float(sw[1]);
+                    acc[nt][r] = a + b;
+                    acc[nt][r + 8] = a - b;
+                }
+            }
+        }
+
+        // scale, absmax per token
+        float amax[C::TOK_PER_LANE];
+#pragma unroll
+        for (int t = 0; t < C::TOK_PER_LANE; ++t) amax[t] = 0.0f;
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int h = r % C::HB_PER_LANE, t = r / C::HB_PER_LANE;
+                acc[nt][r] *= cm[h][nt];
+                amax[t] = fmaxf(amax[t], fabsf(acc[nt][r]));
+            }
+#pragma unroll
+        for (int t = 0; t < C::TOK_PER_LANE; ++t) {
+#pragma unroll
+            for (int m = 1; m < (REM == 5 ? 64 : 32); m <<= 1) amax[t] = fmaxf(amax[t], __shfl_xor(amax[t], m));
+        }
+
+        // quantize, pack, store
+#pragma unroll
+        for (int t = 0; t < C::TOK_PER_LANE; ++t) {
+            // token of this lane: REM 3: 2*t + g (m bit 4 = register bit 3, m bit 2 = lane half); REM 4: g; REM 5: 0
+            const int tk = (REM == 3) ? (2 * t + g) : (REM == 4 ? g : 0);
+            const int row = tile * TOK + tk;
+            const float inv = amax[t] > 0.0f ? 7.0f / amax[t] : 0.0f;
+            uint32_t words[C::NL / 8];
+#pragma unroll
+            for (int d = 0; d < C::NL / 8; ++d) {
+                // nibble i of word d is local index 8*d + i = nt + 4*h  ->  nt = i & 3, h = 2*d + (i >> 2)
+                uint32_t wv = 0;
+#pragma unroll
+                for (int i = 7; i >= 0; --i) {
+                    const int nt = i & 3, h = 2 * d + (i >> 2);
+                    const float f = fmaf(acc[nt][t * C::HB_PER_LANE + h], inv, rq::MAGIC);
+                    wv = (wv << 4) + __float_as_uint(f);
+                }
+                // remove the eight copies of the magic exponent pattern, then offset-binary -> two's complement
+                constexpr uint32_t BIAS = (uint32_t)(0x4B400000ull * 0x11111111ull);
+                words[d] = (wv - BIAS) ^ 0x88888888u;
+            }
+            if (row < rows) {
+                uint8_t *out = packed + (size_t)row * (K / 2) + (size_t)c * (K / 64) + (REM == 5 ? g * 32 : 0);
+#pragma unroll
+                for (int d4 = 0; d4 < C::NL / 32; ++d4)
+                    *reinterpret_cast<uint4 *>(out + 16 * d4) = make_uint4(words[4 * d4], words[4 * d4 + 1], words[4 * d4 + 2], words[4 * d4 + 3]);
+                if (c == 0 && (REM != 5 || g == 0)) scale[row] = amax[t] / 7.0f;
+            }
+        }
+    }
+}
+
+hipError_t run_rotate_quant_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, int mul_mode,
+                                 uint8_t *packed, float *scale, hipStream_t stream)
+{
+    if (rows <= 0) return hipSuccess;
+    const uint16_t *x = reinterpret_cast<const uint16_t *>(X);
+    const int tok = 32 / (K / 128);
+    const int ntiles = (rows + tok - 1) / tok;
+    int blocks = (ntiles + rq::WAVES_PER_BLOCK - 1) / rq::WAVES_PER_BLOCK;
+    const int max_blocks = 256 * 2;   // two resident blocks of four waves per compute unit
+    if (blocks > max_blocks) blocks = max_blocks;
+    switch (K) {
+        case 1024: rotate_quant_mfma_kernel<1024><<<blocks, 256, 0, stream>>>(x, rows, signs, mul, mul_mode, packed, scale); break;
+        case 2048: rotate_quant_mfma_kernel<2048><<<blocks, 256, 0, stream>>>(x, rows, signs, mul, mul_mode, packed, scale); break;
+        case 4096: rotate_quant_mfma_kernel<4096><<<blocks, 256, 0, stream>>>(x, rows, signs, mul, mul_mode, packed, scale); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace qvggt

@@ -35,7 +35,6 @@ constexpr int LDS_PITCH = 272;                 // bytes per 128-value bf16 segme
 constexpr int LDS_PER_WAVE = 32 * LDS_PITCH;   // 8704
 constexpr int WAVES_PER_BLOCK = 4;
 constexpr float MAGIC = 12582912.0f + 8.0f;    // 1.5 * 2^23 + 8: adding it leaves (code + 8) in the low mantissa bits
-constexpr uint32_t MAGIC_BITS = 0x4B400000u;
 
 template <int K>
 struct Cfg {
@@ -67,15 +66,15 @@ __host__ __device__ constexpr int row_of_seg_hi(int seg_hi /* seg >> 2 */)
 }
 }  // namespace rq
 
-template <int K>
-__global__ __launch_bounds__(256, 2) void rotate_quant_mfma_kernel(const uint16_t *__restrict__ X, int rows,
+template <int K, int PF, int OCC>
+__global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint16_t *__restrict__ X, int rows,
                                                                    const int8_t *__restrict__ signs,
                                                                    const float *__restrict__ mul, int mul_mode,
                                                                    uint8_t *__restrict__ packed,
                                                                    float *__restrict__ scale)
 {
     using C = rq::Cfg<K>;
-    constexpr int REM = C::REM, TOK = C::TOK, HB = C::HB;
+    constexpr int REM = C::REM, TOK = C::TOK;
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[rq::WAVES_PER_BLOCK * rq::LDS_PER_WAVE];
 
     const int lane = threadIdx.x & 63, wave_in_block = threadIdx.x >> 6;
@@ -148,12 +147,14 @@ __global__ __launch_bounds__(256, 2) void rotate_quant_mfma_kernel(const uint16_
         if (f >= max_flat) f = max_flat - K + (f % K);
         return reinterpret_cast<const uint4 *>(X + f);
     };
-    uint4 G[8];
+    uint4 G[PF][8];
     int tile = wave;
-    if (tile < ntiles) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) G[j] = *tile_ptr(tile, j);
-    }
+    for (int p = 0; p < PF; ++p)
+        if (tile + p * nwaves < ntiles) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) G[p][j] = *tile_ptr(tile + p * nwaves, j);
+        }
     const int wr_base = ((lane >> 4) * rq::LDS_PITCH) + (lane & 15) * 16;
     const int rd_base = c * rq::LDS_PITCH + g * 16;
 
@@ -162,17 +163,21 @@ __global__ __launch_bounds__(256, 2) void rotate_quant_mfma_kernel(const uint16_
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int q = j % C::SIGN_CLASSES;
-            uint4 v = G[j];
+            uint4 v = G[0][j];
             v.x ^= sgn[q][0]; v.y ^= sgn[q][1]; v.z ^= sgn[q][2]; v.w ^= sgn[q][3];
             // segment index = 4*j + lane/16; its low two bits are lane/16 -> rows m0, m1
             const int row_hi = rq::row_of_seg_hi<K>(j);
             *reinterpret_cast<uint4 *>(lds + row_hi * rq::LDS_PITCH + wr_base) = v;
         }
-        // prefetch the next tile
-        const int next = tile + nwaves;
+        // shift the prefetch queue and issue the loads of the tile PF steps ahead
+#pragma unroll
+        for (int p = 0; p + 1 < PF; ++p)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) G[p][j] = G[p + 1][j];
+        const int next = tile + PF * nwaves;
         if (next < ntiles) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) G[j] = *tile_ptr(next, j);
+            for (int j = 0; j < 8; ++j) G[PF - 1][j] = *tile_ptr(next, j);
         }
 
         // R . H_128 on the matrix cores
@@ -278,12 +283,13 @@ hipError_t run_rotate_quant_mfma(const void *X, int rows, int K, const int8_t *s
     const int tok = 32 / (K / 128);
     const int ntiles = (rows + tok - 1) / tok;
     int blocks = (ntiles + rq::WAVES_PER_BLOCK - 1) / rq::WAVES_PER_BLOCK;
-    const int max_blocks = 256 * 2;   // two resident blocks of four waves per compute unit
+    const int max_blocks = 256 * 2;   // two resident blocks of four waves on each of the 256 compute units
     if (blocks > max_blocks) blocks = max_blocks;
+#define RQ(KK, PF, OCC) rotate_quant_mfma_kernel<KK, PF, OCC><<<blocks, 256, 0, stream>>>(x, rows, signs, mul, mul_mode, packed, scale)
     switch (K) {
-        case 1024: rotate_quant_mfma_kernel<1024><<<blocks, 256, 0, stream>>>(x, rows, signs, mul, mul_mode, packed, scale); break;
-        case 2048: rotate_quant_mfma_kernel<2048><<<blocks, 256, 0, stream>>>(x, rows, signs, mul, mul_mode, packed, scale); break;
-        case 4096: rotate_quant_mfma_kernel<4096><<<blocks, 256, 0, stream>>>(x, rows, signs, mul, mul_mode, packed, scale); break;
+        case 1024: RQ(1024, 1, 2); break;
+        case 2048: RQ(2048, 1, 2); break;
+        case 4096: RQ(4096, 1, 2); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -129,7 +129,7 @@ def main():
             traffic = json.load(open(tpath)).get(f"config{args.config}", {}).get("w4a4_gemm_bytes_per_launch")
         except Exception:
             traffic = None
-    roofline = dict(kernel="w4a4_gemm_persistent_kernel", bound="mfma", achieved=gemm_tops, peak=INT8_PEAK_TOPS, unit="TOP/s",
+    roofline = dict(kernel="w4a4_gemm_kernel", bound="mfma", achieved=gemm_tops, peak=INT8_PEAK_TOPS, unit="TOP/s",
                     frac=gemm_tops / INT8_PEAK_TOPS, traffic=traffic,
                     ops_per_launch=gemm_ops_all / n_layers, avg_launch_ms=gemm_ms_all / n_layers)
     roofline_rq = dict(kernel="rotate_quant_mfma_kernel", bound="hbm", achieved=rq_gbps, peak=HBM_PEAK_GBS, unit="GB/s",

@@ -5,81 +5,109 @@
 //   acc[t, o] = sum_j Xq[t, j] * Wq[o, j]
 //   Y[t, o]   = bf16( acc[t, o] * sx[t] * sw[o] + bias[o] )
 //
-// Tiles of packed codes are staged in LDS as they are in memory (two codes per byte).  A
-// wavefront expands them to int8 in registers right before the MFMA: each code is kept in
-// the HIGH nibble of its byte (v & 0xF0F0F0F0 for the odd codes, (v << 4) & 0xF0F0F0F0 for
-// the even ones), i.e. as 16 * code with the sign in place, so no sign extension is needed.
-// Both operands are expanded the same way, hence the accumulator is exactly 256 * acc
-// (|256 * acc| <= 256 * 64 * 8192 = 2^27) and the factor is removed exactly afterwards.
-// The even/odd split permutes the codes inside a K-step identically for both operands, which
-// leaves every dot product unchanged.
+// Data movement.  A block owns a tile of BM tokens x BN channels and walks over many such
+// tiles (persistent grid).  The packed codes of both operands travel from global memory
+// straight into LDS (global_load_lds_dwordx4: no staging registers, no LDS store
+// instructions) in K-tiles of 64 bytes = 128 codes per row, through a ring of STAGES
+// buffers; the K-tiles of successive output tiles form one continuous stream, so the first
+// K-tiles of the next output tile are in flight while the current one finishes.
 //
-// The MFMA takes the weights as its row operand and the activations as its column operand,
-// so that a lane ends up with 4 consecutive output channels of one token: 8-byte bf16 stores.
+// LDS layout of a stage: rows of 64 bytes (BM token rows, then BN channel rows); the four
+// 16-byte chunks of a row are XOR-swizzled with bits 2..3 of the row index.  The transfer
+// writes 1 KiB contiguous per wavefront instruction (16 rows); the swizzle is applied on the
+// global side (which chunk a lane fetches).  A fragment read is one ds_read_b128 per lane:
+// lane (row = lane % 32, half = lane / 32) takes chunk 2*pair + half of its row, i.e. its 8
+// bytes of K-step 2*pair and its 8 bytes of K-step 2*pair + 1.  Any 16 consecutive rows hit the
+// 16 distinct 16-byte groups of the 64 LDS banks, so these reads are conflict free.  The order in
+// which codes meet inside a K-step is the same for both operands, which is all a dot
+// product needs.
 //
-// LDS tiles are [rows][BKB bytes] with the 8-byte chunks of a row XOR-swizzled by the row
-// index, which makes both the 8-byte fragment reads (16 consecutive rows, same chunk) and the
-// staging writes bank-conflict free without padding.
+// Arithmetic.  A wavefront expands packed bytes to int8 in registers right before the MFMA:
+// each code is kept in the HIGH nibble of its byte (v & 0xF0F0F0F0 for the odd codes,
+// (v << 4) & 0xF0F0F0F0 for the even ones), i.e. as 16 * code with the sign in place, so no
+// sign extension is needed.  Both operands are expanded the same way, hence the accumulator
+// is exactly 256 * acc (|256 * acc| <= 256 * 64 * 8192 = 2^27) and the factor is removed
+// exactly afterwards.  The weights are the MFMA row operand and the activations its column
+// operand, so a lane ends up with 4 consecutive output channels of one token.
+//
+// Schedule.  A K-step of a wavefront is TM*TN MFMAs (32x32x32 int8); the LDS reads of the
+// next pair of K-steps and the expansion of the next K-step's fragments are dealt out one
+// piece per MFMA, fenced so that the compiler keeps the interleave: the vector ALU and LDS
+// work runs in the shadow of the matrix pipe.
 #include "qvggt_common.h"
+
 #include <cstdlib>
+#include <type_traits>
 
 namespace qvggt {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-__device__ inline v4i expand_codes(uint2 p)
-{
-    v4i r;
-    r[0] = (int)(p.x & 0xF0F0F0F0u);
-    r[1] = (int)((p.x << 4) & 0xF0F0F0F0u);
-    r[2] = (int)(p.y & 0xF0F0F0F0u);
-    r[3] = (int)((p.y << 4) & 0xF0F0F0F0u);
-    return r;
-}
+namespace {
 
-// TM x TN: 32x32 sub-tiles per wave along tokens / channels; WM x WN: waves per block; BKB: packed bytes per row per K-tile
-template <int TM, int TN, int WM, int WN, int BKB, int OCC>
-struct GemmCfg {
-    static constexpr int BM = WM * TM * 32, BN = WN * TN * 32, THREADS = WM * WN * 64;
-    static constexpr int CH = BKB / 8;                 // 8-byte chunks per row
-    static constexpr int RP = (BKB >= 128) ? 1 : 128 / BKB;   // rows per 128 bytes of LDS
-    static constexpr int KSTEPS = BKB / 16;            // MFMA K-steps (32 codes) per K-tile
-    static constexpr int TPR = BKB / 16;               // staging threads per row (16 bytes each)
-    static constexpr int X_LOADS = BM * TPR / THREADS, W_LOADS = BN * TPR / THREADS;
-    static constexpr int LDS_BYTES = 2 * (BM + BN) * BKB;
-    static_assert(BM * TPR % THREADS == 0 && BN * TPR % THREADS == 0, "tile does not divide among the threads");
+constexpr int KT_BYTES = 64;       // packed bytes per row per K-tile: 128 codes = 4 MFMA K-steps = 2 pairs
+
+// TM x TN: 32x32 sub-tiles per wave along tokens / channels; WM x WN: waves per block; STAGES: LDS ring depth
+template <int TM, int TN, int WM, int WN, int STAGES>
+struct StreamCfg {
+    static constexpr int NW = WM * WN, THREADS = NW * 64;
+    static constexpr int BM = WM * TM * 32, BN = WN * TN * 32, ROWS = BM + BN;
+    static constexpr int STAGE_BYTES = ROWS * KT_BYTES;
+    static constexpr int GROUPS = ROWS / 16;            // 16-row groups: one wave-wide transfer instruction each
+    static constexpr int LPW = GROUPS / NW;             // transfers per wave per K-tile
+    static constexpr int NM = TM * TN, NF = TM + TN;
+    static constexpr int SC_BYTES = BM * 4 + BN * 4 + BN * 2;   // per tile: sx f32, sw f32, bias bf16 (as in memory)
+    static constexpr int SC_GROUPS = BM / 64 + BN / 64 + BN / 128;
+    static constexpr int LDS_BYTES = STAGES * STAGE_BYTES + 2 * SC_BYTES;
+    static_assert(GROUPS % NW == 0, "16-row groups do not divide among the waves");
+    static_assert(BM % 128 == 0 && BN % 128 == 0, "scale transfers assume multiples of 128");
+    static_assert(STAGES >= 3, "ring needs one stage being read, one landed, one in flight");
 };
 
-template <class C>
-__device__ inline int swz(int row) { return (row / C::RP) % C::CH; }
+// one packed dword (8 codes) -> two dwords of int8: codes 1,3,5,7 and codes 0,2,4,6, each as 16 * code
+#define QVGGT_EXPAND_HALF(p, dst, k)                                   \
+    do {                                                               \
+        const uint32_t p_ = (uint32_t)(p);                             \
+        (dst)[(k)] = (int)(p_ & 0xF0F0F0F0u);                          \
+        (dst)[(k) + 1] = (int)((p_ << 4) & 0xF0F0F0F0u);               \
+    } while (0)
 
-// A block walks over many output tiles and treats the K-tiles of all of
-// them as one stream through the LDS double buffer, so the first K-tiles of the next output
-// tile are already in flight while the current tile's epilogue runs.  Two such blocks share a
-// compute unit; one block's epilogue overlaps the other's MFMA loop.
-// SCHED picks the instruction-interleaving hint given to the compiler for a K-step
-// (2: its small-GEMM MFMA/LDS interleave, 3: one MFMA then its share of the expansion ALU ops).
-template <int TM, int TN, int WM, int WN, int BKB, int OCC, int SCHED>
-__global__ __launch_bounds__(WM * WN * 64, OCC) void w4a4_gemm_persistent_kernel(
+// 16 bytes per lane from global memory to LDS: lane l of the wave writes lds_base + 16 * l
+__device__ inline void dma16(const void *src, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_base) : "memory", "m0");
+}
+// 4 bytes per lane: lane l writes lds_base + 4 * l
+__device__ inline void dma4(const void *src, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" ::"v"(src), "s"(lds_base) : "memory", "m0");
+}
+template <int N>
+__device__ inline void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+}  // namespace
+
+template <int TM, int TN, int WM, int WN, int STAGES, int MINB, bool DEBUG>
+__global__ __launch_bounds__(WM * WN * 64, MINB) void w4a4_gemm_kernel(
     const uint8_t *__restrict__ Xq, const float *__restrict__ sx, const uint8_t *__restrict__ Wq,
     const float *__restrict__ sw, const uint16_t *__restrict__ bias, int M, int N, int K,
-    uint16_t *__restrict__ Y, int32_t *__restrict__ acc_debug, int tiles_m, int tiles_n)
+    uint16_t *__restrict__ Y, int32_t *__restrict__ acc_debug, int tiles_m, int tiles_n, long long *dbg_times)
 {
-    using C = GemmCfg<TM, TN, WM, WN, BKB, OCC>;
+    using C = StreamCfg<TM, TN, WM, WN, STAGES>;
+    constexpr int NM = C::NM, NF = C::NF, LPW = C::LPW;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    constexpr int STAGE = (C::BM + C::BN) * BKB;       // one pipeline stage: X tile then W tile
-    constexpr int KS = C::KSTEPS;
-    constexpr int EP_PITCH = TN * 64 + 16;             // bytes per token row of a wave's epilogue staging tile
-    constexpr int EP_BYTES = (WM * WN) * 32 * EP_PITCH;
-    constexpr int SC_FLOATS = C::BM + 2 * C::BN;       // per tile: sx of its tokens, sw and bias of its channels
-    uint8_t *ep_all = smem + 2 * STAGE;
-    float *sc_all = reinterpret_cast<float *>(smem + 2 * STAGE + EP_BYTES);   // two buffers of SC_FLOATS
+    uint8_t *sc_all = smem + STAGES * C::STAGE_BYTES;           // two buffers of SC_BYTES
+    const uint32_t lds0 = (uint32_t)(uintptr_t)smem;            // LDS byte address of the dynamic segment
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
     const int KB = K >> 1;             // packed bytes per row
-    const int ktiles = KB / BKB;
+    const int ktiles = KB / KT_BYTES;
     const int ntiles = tiles_m * tiles_n;
 
     // Tile assignment: workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  XCD x owns the
@@ -89,216 +117,280 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void w4a4_gemm_persistent_kernel
     const int tile_end = min((xcd + 1) * per_xcd, ntiles);
     const int first_tile = xcd * per_xcd + slot;
     if (first_tile >= tile_end) return;
+    const int last_tile = tile_end - 1 - ((tile_end - 1 - first_tile) % slots);   // this block's last tile
 
-    // ---- global -> LDS staging
-    const int ld_row = tid / C::TPR, ld_seg = tid % C::TPR;
-    constexpr int ROWS_PER_PASS = C::THREADS / C::TPR;
-    const uint8_t *gX[C::X_LOADS], *gW[C::W_LOADS];
-    int oX[C::X_LOADS][2], oW[C::W_LOADS][2];          // LDS byte offsets of the two 8-byte halves
-#pragma unroll
-    for (int p = 0; p < C::X_LOADS; ++p) {
-        const int r = ld_row + ROWS_PER_PASS * p;
-        oX[p][0] = r * BKB + ((2 * ld_seg) ^ swz<C>(r)) * 8;
-        oX[p][1] = r * BKB + ((2 * ld_seg + 1) ^ swz<C>(r)) * 8;
-    }
-#pragma unroll
-    for (int p = 0; p < C::W_LOADS; ++p) {
-        const int r = ld_row + ROWS_PER_PASS * p;
-        oW[p][0] = C::BM * BKB + r * BKB + ((2 * ld_seg) ^ swz<C>(r)) * 8;
-        oW[p][1] = C::BM * BKB + r * BKB + ((2 * ld_seg + 1) ^ swz<C>(r)) * 8;
-    }
-    // load cursor: runs two K-tiles ahead of the compute cursor, across output tiles
-    int ld_tile = first_tile, ld_kt = 0;
+    // ---- global -> LDS transfers.  Lane l of a transfer covers row l / 4 of a 16-row group and lands in 16-byte
+    // slot l % 4 of that row; it fetches the chunk that the swizzle puts there.
+    const int t_row = lane >> 2;
+    const int t_chunk = (lane & 3) ^ ((t_row >> 2) & 3);
+    const uint8_t *gp[LPW];
+    int ld_tile = first_tile, ld_kt = 0, ld_stage = 0;
     auto set_tile_pointers = [&](int t) {
-        t = min(t, ntiles - 1);                         // past the end: harmless re-reads, never used
         const int tm = t / tiles_n, tn = t % tiles_n;
 #pragma unroll
-        for (int p = 0; p < C::X_LOADS; ++p)
-            gX[p] = Xq + (size_t)min(tm * C::BM + ld_row + ROWS_PER_PASS * p, M - 1) * KB + ld_seg * 16;
-#pragma unroll
-        for (int p = 0; p < C::W_LOADS; ++p)
-            gW[p] = Wq + (size_t)min(tn * C::BN + ld_row + ROWS_PER_PASS * p, N - 1) * KB + ld_seg * 16;
-    };
-    uint4 rX[C::X_LOADS], rW[C::W_LOADS];
-    auto load_next = [&]() {
-        const size_t off = (size_t)ld_kt * BKB;
-#pragma unroll
-        for (int p = 0; p < C::X_LOADS; ++p) rX[p] = *reinterpret_cast<const uint4 *>(gX[p] + off);
-#pragma unroll
-        for (int p = 0; p < C::W_LOADS; ++p) rW[p] = *reinterpret_cast<const uint4 *>(gW[p] + off);
-        if (++ld_kt == ktiles) { ld_kt = 0; ld_tile += slots; set_tile_pointers(ld_tile < tile_end ? ld_tile : ntiles - 1); }
-    };
-    auto store_tile = [&](int buf) {
-        uint8_t *base = smem + buf * STAGE;
-#pragma unroll
-        for (int p = 0; p < C::X_LOADS; ++p) {
-            *reinterpret_cast<uint2 *>(base + oX[p][0]) = make_uint2(rX[p].x, rX[p].y);
-            *reinterpret_cast<uint2 *>(base + oX[p][1]) = make_uint2(rX[p].z, rX[p].w);
-        }
-#pragma unroll
-        for (int p = 0; p < C::W_LOADS; ++p) {
-            *reinterpret_cast<uint2 *>(base + oW[p][0]) = make_uint2(rW[p].x, rW[p].y);
-            *reinterpret_cast<uint2 *>(base + oW[p][1]) = make_uint2(rW[p].z, rW[p].w);
+        for (int i = 0; i < LPW; ++i) {
+            const int r = (i * C::NW + wave) * 16 + t_row;      // row inside the stage: 16-row groups are dealt to the waves in turn
+            const uint8_t *base = (r < C::BM) ? Xq + (size_t)min(tm * C::BM + r, M - 1) * KB
+                                              : Wq + (size_t)min(tn * C::BN + r - C::BM, N - 1) * KB;
+            gp[i] = base + t_chunk * 16;
         }
     };
-    // per-tile scales into LDS (buffer `sb`): sx of the tile's tokens, sw and bias of its channels
-    auto stage_scales = [&](int t, int sb) {
+    // The K-tile under the load cursor goes to ring stage ld_stage, one transfer instruction at a time (a wave that issues
+    // them back to back stalls on each: they are dealt out between MFMAs instead); then the cursor moves on, across
+    // output tiles (past this block's last tile it re-reads that tile: never used, keeps the transfers in flight uniform).
+    auto issue_transfer = [&](int i) {
+        dma16(gp[i] + ld_kt * KT_BYTES, lds0 + ld_stage * C::STAGE_BYTES + (i * C::NW + wave) * 1024);
+    };
+    auto advance_cursor = [&]() {
+        ld_stage = (ld_stage + 1 == STAGES) ? 0 : ld_stage + 1;
+        if (++ld_kt == ktiles) {
+            ld_kt = 0;
+            ld_tile = min(ld_tile + slots, last_tile);
+            set_tile_pointers(ld_tile);
+        }
+    };
+    auto issue_ktile = [&]() {
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) issue_transfer(i);
+        advance_cursor();
+    };
+    // per-tile scales to LDS buffer sb, as they are in memory: sx of the tile's tokens, sw and bias of its channels
+    auto issue_scales = [&](int t, int sb) {
         const int tm = t / tiles_n, tn = t % tiles_n;
-        float *sc = sc_all + sb * SC_FLOATS;
-        for (int i = tid; i < C::BM; i += C::THREADS) sc[i] = sx[min(tm * C::BM + i, M - 1)] * (1.0f / 256.0f);
-        for (int i = tid; i < C::BN; i += C::THREADS) {
-            const int n = min(tn * C::BN + i, N - 1);
-            sc[C::BM + i] = sw[n];
-            sc[C::BM + C::BN + i] = (bias != nullptr) ? __uint_as_float((uint32_t)bias[n] << 16) : 0.0f;
-        }
-    };
-
-    v16i acc[TN][TM];   // [channel sub-tile j][token sub-tile i]
-    const int frow = lane & 31, fhalf = lane >> 5;
-    const int fswz = swz<C>(frow);
-    const int xrow_off = (wm * TM * 32 + frow) * BKB, wrow_off = C::BM * BKB + (wn * TN * 32 + frow) * BKB;
-    uint2 raw_w[TN], raw_x[TM];
-    v4i fw[TN], fx[TM];
-    auto read_frags = [&](int buf, int ks) {
-        const uint8_t *base = smem + buf * STAGE + ((2 * ks + fhalf) ^ fswz) * 8;
+        const uint32_t dst = lds0 + STAGES * C::STAGE_BYTES + sb * C::SC_BYTES;
 #pragma unroll
-        for (int j = 0; j < TN; ++j) raw_w[j] = *reinterpret_cast<const uint2 *>(base + wrow_off + j * 32 * BKB);
-#pragma unroll
-        for (int i = 0; i < TM; ++i) raw_x[i] = *reinterpret_cast<const uint2 *>(base + xrow_off + i * 32 * BKB);
-    };
-    auto expand_frags = [&]() {
-#pragma unroll
-        for (int j = 0; j < TN; ++j) fw[j] = expand_codes(raw_w[j]);
-#pragma unroll
-        for (int i = 0; i < TM; ++i) fx[i] = expand_codes(raw_x[i]);
-    };
-    auto mfma_step = [&]() {
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-                acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[j], fx[i], acc[j][i], 0, 0, 0);
-    };
-    auto schedule_step = [&]() {
-        constexpr int NM = TM * TN, NV = 6 * (TM + TN);
-        if constexpr (SCHED == 2) { __builtin_amdgcn_iglp_opt(0); }
-        if constexpr (SCHED == 3) {
-#pragma unroll
-            for (int t = 0; t < NM; ++t) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, (NV + NM - 1) / NM, 0);
+        for (int g = 0; g < C::SC_GROUPS; ++g) {
+            if (g % C::NW != wave) continue;
+            if (g < C::BM / 64) {
+                dma4(sx + min(tm * C::BM + g * 64 + lane, M - 1), dst + g * 256);
+            } else if (g < C::BM / 64 + C::BN / 64) {
+                const int h = g - C::BM / 64;
+                dma4(sw + min(tn * C::BN + h * 64 + lane, N - 1), dst + C::BM * 4 + h * 256);
+            } else if (bias != nullptr) {
+                const int h = g - C::BM / 64 - C::BN / 64;      // 64 dwords = 128 bf16 values
+                dma4(reinterpret_cast<const uint32_t *>(bias) + min(tn * (C::BN / 2) + h * 64 + lane, N / 2 - 1),
+                     dst + C::BM * 4 + C::BN * 4 + h * 256);
             }
         }
     };
 
-    // prologue of the whole stream
+    // ---- fragments
+    v16i acc[TN][TM];   // [channel sub-tile j][token sub-tile i]
+    v4i raw[NF];        // packed fragments of a pair of K-steps: W sub-tiles, then X sub-tiles
+    v4i F[2][NF];       // expanded fragments of one K-step: [K-step parity][W sub-tiles, then X sub-tiles]
+    const int frow = lane & 31, fhalf = lane >> 5;
+    const int fsw = (frow >> 2) & 3;
+    // byte offsets inside a stage of this lane's chunk of pair 0; pair 1 is the same with chunk bit 1 (byte bit 5) flipped
+    const int w_off = (C::BM + wn * TN * 32 + frow) * KT_BYTES + ((fhalf ^ fsw) << 4);
+    const int x_off = (wm * TM * 32 + frow) * KT_BYTES + ((fhalf ^ fsw) << 4);
+    auto read_frag = [&](int f, int stage, int pair) {
+        const int off = ((f < TN) ? w_off : x_off) ^ (pair << 5);
+        raw[f] = *reinterpret_cast<const v4i *>(smem + stage * C::STAGE_BYTES + off + ((f < TN) ? f : f - TN) * 32 * KT_BYTES);
+    };
+    // One K-step: NM slots of {one MFMA, a share of the side work}.  The side work is the expansion of the NEXT K-step's
+    // fragments, a dword (3 ALU ops) at a time, evenly over the slots:
+    //   PAR == 0 (first K-step of a pair):  raw[f].zw -> F[1][f].  Once both dwords of raw[f] are used it is dead, and the
+    //             read of the next pair's fragment f (ring stage rd_stage, pair rd_pair) is issued into it in the next slot;
+    //   PAR == 1 (second K-step of a pair): raw[f].xy -> F[0][f]; slot 0 issues the reads that did not fit into the step before.
+    // So a fragment's LDS read is issued most of a K-step before its first use, and reads are spread over the K-step.
+    auto kstep = [&](auto step_c, auto fresh_c, int rd_stage, int rd_pair) {
+        constexpr int STEP = decltype(step_c)::value, PAR = STEP & 1;   // STEP: K-step inside the K-tile
+        constexpr bool FRESH = decltype(fresh_c)::value;
+        const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int t = 0; t < NM; ++t) {
+            const int j = t / TM, i = t % TM;
+            acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(F[PAR][j], F[PAR][TN + i], FRESH ? zero : acc[j][i], 0, 0, 0);
+            // this K-tile's share of the global -> LDS transfers: transfer n goes out in slot (2n + 1) * 4 * NM / (2 * LPW) of the K-tile
+#pragma unroll
+            for (int n = 0; n < LPW; ++n)
+                if ((2 * n + 1) * 4 * NM / (2 * LPW) == STEP * NM + t) issue_transfer(n);
+#pragma unroll
+            for (int f = 0; f < NF; ++f) {
+                const int done = ((2 * f + 2) * NM + 2 * NF - 1) / (2 * NF) - 1;   // slot of the PAR == 0 step that uses raw[f] last
+                if (PAR == 0 ? (done + 1 == t) : (t == 0 && done + 1 >= NM)) read_frag(f, rd_stage, rd_pair);
+            }
+#pragma unroll
+            for (int h = t * 2 * NF / NM; h < (t + 1) * 2 * NF / NM; ++h) {
+                if (PAR == 0) QVGGT_EXPAND_HALF(raw[h >> 1][2 + (h & 1)], F[1][h >> 1], 2 * (h & 1));
+                else QVGGT_EXPAND_HALF(raw[h >> 1][h & 1], F[0][h >> 1], 2 * (h & 1));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
+    using I3 = std::integral_constant<int, 3>;
+    using BT = std::true_type;
+    using BF = std::false_type;
+
+    // ---- prologue of the whole stream
+    if (bias == nullptr) {      // no bias: both bias areas stay zero for the whole kernel
+        for (int b = 0; b < 2; ++b)
+            for (int i = tid; i < C::BN / 2; i += C::THREADS)
+                reinterpret_cast<uint32_t *>(sc_all + b * C::SC_BYTES + C::BM * 4 + C::BN * 4)[i] = 0u;
+    }
     set_tile_pointers(first_tile);
-    load_next();
-    stage_scales(first_tile, 0);
-    store_tile(0);
+    issue_scales(first_tile, 0);
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s) issue_ktile();
+    wait_vmcnt<(STAGES - 2) * LPW>();
     __syncthreads();
-    load_next();
-    read_frags(0, 0);
-    expand_frags();
+#pragma unroll
+    for (int f = 0; f < NF; ++f) read_frag(f, 0, 0);
+#pragma unroll
+    for (int f = 0; f < NF; ++f) {
+        QVGGT_EXPAND_HALF(raw[f][0], F[0][f], 0);
+        QVGGT_EXPAND_HALF(raw[f][1], F[0][f], 2);
+    }
 
     const int c = lane & 31, g = lane >> 5;
-    uint8_t *ep = ep_all + wave * (32 * EP_PITCH);
-    constexpr int LPR = TN * 4;                           // lanes per token row when reading 16 bytes each
-    constexpr int RPI = 64 / LPR;                         // token rows per read instruction
-    const int rd_row = lane / LPR, rd_col = lane % LPR;
 
-    int buf = 0, sb = 0;
+    int cs = 0, sb = 0;                                   // ring stage being computed on, scale buffer of the current tile
+#ifdef QVGGT_DEV
+    long long t_main = 0, t_epi = 0, t_bar = 0, t_start = clock64(), w_start = wall_clock64(); int n_tiles = 0;
+#endif
     for (int tile = first_tile; tile < tile_end; tile += slots) {
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[j][i][r] = 0;
-        for (int kt = 0; kt < ktiles; ++kt) {
-#pragma unroll
-            for (int ks = 0; ks < KS - 1; ++ks) {
-                read_frags(buf, ks + 1);
-                mfma_step();
-                expand_frags();
-                schedule_step();
-            }
-            // the K-tile held in registers goes to the other LDS buffer; after the barrier it is visible to all waves
-            // and the buffer it replaces is no longer read by anyone (its last reads were issued before the previous barrier)
-            store_tile(buf ^ 1);
+        // one K-tile of the stream: four K-steps on ring stage cs.  The first K-tile of an output tile starts the
+        // accumulators from zero (FRESH) and sends for the scales of the block's next output tile.
+        auto ktile = [&](auto fresh_c) {
+            constexpr bool FRESH = decltype(fresh_c)::value;
+            // K-tile q+1 of the stream has landed for this wave once at most (STAGES-3) later K-tiles are outstanding; after
+            // the barrier it has landed for every wave, and every wave is done reading K-tile q-1, whose stage is reused.
+#ifdef QVGGT_DEV
+            const long long tb0 = clock64();
+#endif
+            wait_vmcnt<(STAGES - 3) * LPW>();
             __syncthreads();
-            load_next();
-            // scales of the next output tile go to the other scale buffer: every wave has left the previous epilogue
-            // (which read that buffer) once it is past the barrier above, and later barriers publish the new values
-            if (kt == 0 && tile + slots < tile_end) stage_scales(tile + slots, sb ^ 1);
-            // last step of this K-tile: its LDS reads already belong to the next K-tile (possibly of the next output tile)
-            read_frags(buf ^ 1, 0);
-            mfma_step();
-            expand_frags();
-            schedule_step();
-            buf ^= 1;
-        }
+#ifdef QVGGT_DEV
+            t_bar += clock64() - tb0;
+#endif
+            if (FRESH && tile + slots < tile_end) {
+                int tnext = tile + slots;
+                asm volatile("" : "+s"(tnext));             // keeps the address arithmetic of the scale transfers inside this branch
+                issue_scales(tnext, sb ^ 1);
+            }
+            const int ns = (cs + 1 == STAGES) ? 0 : cs + 1;
+            kstep(I0{}, fresh_c, cs, 1);
+            kstep(I1{}, BF{}, cs, 1);
+            kstep(I2{}, BF{}, ns, 0);
+            kstep(I3{}, BF{}, ns, 0);
+            advance_cursor();
+            cs = ns;
+        };
+#ifdef QVGGT_DEV
+        const long long t0 = clock64();
+#endif
+        ktile(BT{});
+        for (int kt = 1; kt < ktiles; ++kt) ktile(BF{});
+#ifdef QVGGT_DEV
+        const long long t1 = clock64(); t_main += t1 - t0;
+#endif
 
-        // ---- epilogue.  32x32 result layout: lane l holds column (l % 32) = token and rows 8*(r/4) + 4*(l/32) + r%4 = channels.
-        // Scale + bias + bf16 in registers, then a wave-private LDS tile [32 tokens][TN*32 channels] turns the
-        // lane-per-token layout into full rows: 16-byte global stores, contiguous per token.
+        // ---- epilogue.  32x32 result layout: lane l holds column (l % 32) = token and rows 8*(r/4) + 4*(l/32) + r%4 = channels,
+        // i.e. per register quad q four consecutive channels 8q + 4*(l/32) + 0..3.  Scale + bias + bf16 in registers; then the
+        // two lane halves trade quads (v_permlane32_swap) so that a lane owns 8 consecutive channels = 16 bytes of one token:
+        // the lower half takes channels 16p .. 16p+7, the upper half 16p+8 .. 16p+15 (p = 0, 1).  No trip through LDS.
         const int tm = tile / tiles_n, tn = tile % tiles_n;
-        const int m0 = tm * C::BM, n0 = tn * C::BN;
-        const float *sc = sc_all + sb * SC_FLOATS;
-        const int n_out = n0 + wn * TN * 32 + rd_col * 8;
+        const int row0 = tm * C::BM + wm * TM * 32, col0 = tn * C::BN + wn * TN * 32;   // first token / channel of this wave
+        const uint8_t *sc = sc_all + sb * C::SC_BYTES;
+        const float *scx = reinterpret_cast<const float *>(sc);
+        const float *scw = reinterpret_cast<const float *>(sc + C::BM * 4) + wn * TN * 32 + 4 * g;
+        const uint16_t *scb = reinterpret_cast<const uint16_t *>(sc + C::BM * 4 + C::BN * 4) + wn * TN * 32 + 4 * g;
+        const int rows_left = M - row0;                      // tokens of this wave's rows that exist
+        const int cols_left = N - col0;                      // channels of this wave's columns that exist (a multiple of 16)
+        const size_t ystep = (size_t)32 * N;                 // Y elements between token sub-tiles
+        float sxm[TM];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int mt = m0 + (wm * TM + i) * 32;       // first token of this sub-tile
-            const float sxm = sc[(wm * TM + i) * 32 + c];
+        for (int i = 0; i < TM; ++i) sxm[i] = scx[(wm * TM + i) * 32 + c] * (1.0f / 256.0f);
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
+        for (int j = 0; j < TN; ++j) {
+            float4 swq[4], bq[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                swq[q] = *reinterpret_cast<const float4 *>(scw + j * 32 + 8 * q);
+                const uint2 b = *reinterpret_cast<const uint2 *>(scb + j * 32 + 8 * q);
+                bq[q] = make_float4(__uint_as_float(b.x << 16), __uint_as_float(b.x & 0xFFFF0000u),
+                                    __uint_as_float(b.y << 16), __uint_as_float(b.y & 0xFFFF0000u));
+            }
+            uint16_t *yp = Y + (size_t)(row0 + c) * N + col0 + j * 32 + 8 * g;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                uint32_t pk[4][2];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const int nl = (wn * TN + j) * 32 + 8 * q + 4 * g;     // channel inside the block tile
-                    const float4 swq = *reinterpret_cast<const float4 *>(sc + C::BM + nl);
-                    const float4 bq = *reinterpret_cast<const float4 *>(sc + C::BM + C::BN + nl);
-                    const int a0 = acc[j][i][4 * q], a1 = acc[j][i][4 * q + 1], a2 = acc[j][i][4 * q + 2], a3 = acc[j][i][4 * q + 3];
-                    const float y0 = fmaf((float)a0 * sxm, swq.x, bq.x), y1 = fmaf((float)a1 * sxm, swq.y, bq.y);
-                    const float y2 = fmaf((float)a2 * sxm, swq.z, bq.z), y3 = fmaf((float)a3 * sxm, swq.w, bq.w);
-                    *reinterpret_cast<uint2 *>(ep + c * EP_PITCH + (j * 32 + 8 * q + 4 * g) * 2) = make_uint2(pack_bf16x2(y0, y1), pack_bf16x2(y2, y3));
-                    if (acc_debug != nullptr) {
-                        const int m = mt + c, n = n0 + nl;
+                    // the accumulators live in AGPRs; reading them here, one at a time, keeps the compiler from copying
+                    // whole tiles into vector registers ahead of time
+                    int a0, a1, a2, a3;
+                    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a0) : "a"(acc[j][i][4 * q]));
+                    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a1) : "a"(acc[j][i][4 * q + 1]));
+                    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a2) : "a"(acc[j][i][4 * q + 2]));
+                    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a3) : "a"(acc[j][i][4 * q + 3]));
+                    const float y0 = fmaf((float)a0 * sxm[i], swq[q].x, bq[q].x), y1 = fmaf((float)a1 * sxm[i], swq[q].y, bq[q].y);
+                    const float y2 = fmaf((float)a2 * sxm[i], swq[q].z, bq[q].z), y3 = fmaf((float)a3 * sxm[i], swq[q].w, bq[q].w);
+                    pk[q][0] = pack_bf16x2(y0, y1);
+                    pk[q][1] = pack_bf16x2(y2, y3);
+                    if constexpr (DEBUG) {
+                        const int m = row0 + i * 32 + c, n = col0 + j * 32 + 8 * q + 4 * g;
                         if (m < M && n < N)
                             *reinterpret_cast<int4 *>(acc_debug + (size_t)m * N + n) = make_int4(a0 >> 8, a1 >> 8, a2 >> 8, a3 >> 8);
                     }
                 }
-            // the staging tile is private to the wave and LDS operations of a wave execute in order: no barrier needed
+                const bool row_ok = c < rows_left - i * 32;
 #pragma unroll
-            for (int it = 0; it < 32 / RPI; ++it) {
-                const int tr = it * RPI + rd_row;
-                const uint4 v = *reinterpret_cast<const uint4 *>(ep + tr * EP_PITCH + rd_col * 16);
-                const int m = mt + tr;
-                if (m < M && n_out < N) *reinterpret_cast<uint4 *>(Y + (size_t)m * N + n_out) = v;
+                for (int p2 = 0; p2 < 2; ++p2) {
+                    const auto s0 = __builtin_amdgcn_permlane32_swap(pk[2 * p2][0], pk[2 * p2 + 1][0], false, false);
+                    const auto s1 = __builtin_amdgcn_permlane32_swap(pk[2 * p2][1], pk[2 * p2 + 1][1], false, false);
+                    if (row_ok && j * 32 + 16 * p2 < cols_left)
+                        *reinterpret_cast<uint4 *>(yp + 16 * p2) = make_uint4(s0[0], s1[0], s0[1], s1[1]);
+                }
+                yp += ystep;
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
         sb ^= 1;
+#ifdef QVGGT_DEV
+        t_epi += clock64() - t1; ++n_tiles;
+#endif
     }
+#ifdef QVGGT_DEV
+    if (dbg_times != nullptr && lane == 0) {
+        long long *o = dbg_times + ((size_t)blockIdx.x * C::NW + wave) * 8;
+        o[0] = t_main; o[1] = t_epi; o[2] = t_bar; o[3] = clock64() - t_start; o[4] = n_tiles; o[5] = wall_clock64() - w_start;
+    }
+#endif
+    wait_vmcnt<0>();        // transfers issued past the last tile must not outlive the block's LDS allocation
 }
 
-template <int TM, int TN, int WM, int WN, int BKB, int OCC, int SCHED>
-static hipError_t launch_gemm_persistent(const uint8_t *Xq, const float *sx, const uint8_t *Wq, const float *sw, const void *bias,
-                                         int M, int N, int K, void *Y, int32_t *acc_debug, hipStream_t stream)
+template <int TM, int TN, int WM, int WN, int STAGES, int MINB>
+static hipError_t launch_gemm(const uint8_t *Xq, const float *sx, const uint8_t *Wq, const float *sw, const void *bias,
+                              int M, int N, int K, void *Y, int32_t *acc_debug, hipStream_t stream)
 {
-    using C = GemmCfg<TM, TN, WM, WN, BKB, OCC>;
-    auto kern = w4a4_gemm_persistent_kernel<TM, TN, WM, WN, BKB, OCC, SCHED>;
-    constexpr int LDS = 2 * (C::BM + C::BN) * BKB + (WM * WN) * 32 * (TN * 64 + 16) + 2 * (C::BM + 2 * C::BN) * 4;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    using C = StreamCfg<TM, TN, WM, WN, STAGES>;
+    long long *dbg = nullptr;
+#ifdef QVGGT_DEV
+    // development builds: QVGGT_TIMING=1 reinterprets acc_debug as a buffer for per-wave cycle counters
+    if (getenv("QVGGT_TIMING") && acc_debug != nullptr) {
+        dbg = reinterpret_cast<long long *>(acc_debug);
+        acc_debug = nullptr;
+    }
+#endif
+    // the variant that also writes the raw accumulators is a separate instantiation: the production kernel carries none of it
+    const bool debug = acc_debug != nullptr;
+    auto kern = debug ? w4a4_gemm_kernel<TM, TN, WM, WN, STAGES, MINB, true> : w4a4_gemm_kernel<TM, TN, WM, WN, STAGES, MINB, false>;
+    static bool attr_set[2] = {false, false};
+    if (!attr_set[debug]) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        attr_set[debug] = true;
     }
     const int tiles_m = (M + C::BM - 1) / C::BM, tiles_n = (N + C::BN - 1) / C::BN;
     const int ntiles = tiles_m * tiles_n;
-    int grid = 256 * OCC;                                 // OCC resident blocks on each of the 256 compute units
+    int grid = 256 * MINB;                                // MINB resident blocks on each of the 256 compute units
     if (grid > (ntiles + 7) / 8 * 8) grid = (ntiles + 7) / 8 * 8;
-    kern<<<grid, C::THREADS, LDS, stream>>>(Xq, sx, Wq, sw, reinterpret_cast<const uint16_t *>(bias), M, N, K,
-                                            reinterpret_cast<uint16_t *>(Y), acc_debug, tiles_m, tiles_n);
+    kern<<<grid, C::THREADS, C::LDS_BYTES, stream>>>(Xq, sx, Wq, sw, reinterpret_cast<const uint16_t *>(bias), M, N, K,
+                                                     reinterpret_cast<uint16_t *>(Y), acc_debug, tiles_m, tiles_n, dbg);
     return hipGetLastError();
 }
 
@@ -306,21 +398,23 @@ hipError_t run_w4a4_gemm(const uint8_t *Xq, const float *sx, const uint8_t *Wq, 
                          const void *bias, int M, int N, int K, void *Y, int32_t *acc_debug, hipStream_t stream)
 {
     if (M <= 0) return hipSuccess;
-#define GOP(...) return launch_gemm_persistent<__VA_ARGS__>(Xq, sx, Wq, sw, bias, M, N, K, Y, acc_debug, stream)
+#define GOP(...) return launch_gemm<__VA_ARGS__>(Xq, sx, Wq, sw, bias, M, N, K, Y, acc_debug, stream)
 #ifdef QVGGT_DEV
     // development builds only (python -m paper_2509_21302_amd.build --dev): pick a tile configuration at run time
     const char *ev = getenv("QVGGT_GEMM_VARIANT");
-    switch (ev ? atoi(ev) : 0) {
-        case 51: GOP(4, 2, 2, 2, 64, 2, 3);
-        case 52: GOP(4, 2, 2, 2, 64, 2, 0);
-        case 53: GOP(2, 4, 2, 2, 64, 2, 2);
-        case 55: GOP(2, 2, 2, 2, 64, 3, 2);
-        case 56: GOP(4, 2, 2, 4, 64, 1, 2);
+    const int variant = ev ? atoi(ev) : 0;
+    switch (variant) {
+        case 1: GOP(4, 4, 2, 2, 4, 1);
+        case 2: GOP(4, 4, 2, 2, 3, 1);
+        case 3: GOP(2, 2, 2, 2, 3, 2);
+        case 4: GOP(4, 2, 2, 2, 4, 1);
         default: break;
     }
 #endif
-    // 256 tokens x 128 channels per block, four waves of 128 x 64, two blocks per compute unit
-    GOP(4, 2, 2, 2, 64, 2, 2);
+    const long long big_tiles = (long long)((M + 255) / 256) * ((N + 255) / 256);
+    // 256 tokens x 256 channels per block, four waves of 128 x 128 (one per SIMD); small problems take 128 x 128 blocks
+    if (big_tiles >= 256) GOP(4, 4, 2, 2, 4, 1);
+    GOP(2, 2, 2, 2, 3, 2);
 #undef GOP
 }
 

@@ -43,6 +43,33 @@ def test_accumulators_bit_exact(M, N, K):
     assert ulp_off.max() <= 1 and (ulp_off != 0).mean() < 5e-3
 
 
+@pytest.mark.parametrize("M,N,K", [(1, 16, 128), (300, 384, 256), (1374, 3072, 1024), (513, 1040, 1024), (10992, 1024, 4096)])
+@pytest.mark.parametrize("with_bias", [True, False])
+def test_production_kernel_matches_accumulator_dump_variant(M, N, K, with_bias):
+    """The kernel that writes the raw accumulators is a separate instantiation; the one a caller normally gets
+    (acc_debug = NULL) must produce the same bf16 output bit for bit, and it is checked against the oracle too."""
+    import paper_2509_21302_amd as q
+    from synth import f32_to_bf16_bits
+    rng = np.random.default_rng(M + 3 * N + K)
+    qx = rng.integers(-7, 8, (M, K)).astype(np.int8)
+    qw = rng.integers(-7, 8, (N, K)).astype(np.int8)
+    dx = np.exp(rng.uniform(-3, 1, M)).astype(np.float32)
+    dw = np.exp(rng.uniform(-5, -2, N)).astype(np.float32)
+    bias_bits = f32_to_bf16_bits((rng.standard_normal(N) * 0.02).astype(np.float32)) if with_bias else None
+    acc_dbg, Y_dbg = _run(qx, qw, dx, dw, bias_bits)
+    Xq, Wq = G.gpu_pack(qx), G.gpu_pack(qw)
+    Y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=G.DEV)
+    q.qvggt_w4a4_gemm(Xq, G.to_dev(dx), Wq, G.to_dev(dw), G.to_dev(bias_bits), M, N, K, Y, None)
+    Y = G.bf16_bits(Y)
+    assert np.array_equal(Y, Y_dbg)
+    rows = np.unique(np.concatenate([np.arange(min(M, 40)), np.arange(max(M - 40, 0), M), rng.integers(0, M, 64)]))
+    want = oracle.int_gemm(qx[rows], qw)
+    assert np.array_equal(acc_dbg[rows], want)
+    Yo = oracle.dequant_bias(want, dx[rows], dw, None if bias_bits is None else oracle.to_f64(bias_bits))
+    ulp_off = np.abs(Y[rows].astype(np.int32) - Yo.astype(np.int32))
+    assert ulp_off.max() <= 1 and (ulp_off != 0).mean() < 5e-3
+
+
 def test_extreme_codes_and_no_bias():
     M, N, K = 40, 32, 4096
     qx = np.full((M, K), -8, np.int8)

@@ -31,6 +31,8 @@ def main():
     ap.add_argument("--config", type=int, default=5, choices=[2, 3, 4, 5])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=16384, help="rows per layer the oracle is timed on")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run plain 1 GiB device copies (reference dispatches for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU; every step of the path is row-independent and would "
@@ -122,19 +124,30 @@ def main():
     n_layers = len(layers)
     gemm_tops = gemm_ops_all / gemm_ms_all / 1e9
     rq_gbps = rq_bytes_all / rq_ms_all / 1e6
-    traffic = None
+    # HBM bytes per launch measured with rocprofv3 counters (see profiles/); None if that file is absent
+    traffic, traffic_rq = None, None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(f"config{args.config}", {}).get("w4a4_gemm_bytes_per_launch")
+            t = json.load(open(tpath)).get(f"config{args.config}", {})
+            traffic, traffic_rq = t.get("w4a4_gemm_bytes_per_launch"), t.get("rotate_quant_bytes_per_launch")
         except Exception:
-            traffic = None
+            traffic, traffic_rq = None, None
     roofline = dict(kernel="w4a4_gemm_kernel", bound="mfma", achieved=gemm_tops, peak=INT8_PEAK_TOPS, unit="TOP/s",
                     frac=gemm_tops / INT8_PEAK_TOPS, traffic=traffic,
                     ops_per_launch=gemm_ops_all / n_layers, avg_launch_ms=gemm_ms_all / n_layers)
     roofline_rq = dict(kernel="rotate_quant_mfma_kernel", bound="hbm", achieved=rq_gbps, peak=HBM_PEAK_GBS, unit="GB/s",
-                       frac=rq_gbps / HBM_PEAK_GBS, traffic=None,
+                       frac=rq_gbps / HBM_PEAK_GBS, traffic=traffic_rq,
                        bytes_per_launch=rq_bytes_all / n_layers, avg_launch_ms=rq_ms_all / n_layers)
+
+    if args.calibrate_copy:
+        # 1 GiB read + 1 GiB written by an elementwise kernel: what the HBM byte counters report for it fixes their scale
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ------------------------------------------------------------------ CPU oracle beside it (bounded sample)
     cpu = None

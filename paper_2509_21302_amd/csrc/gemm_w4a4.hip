@@ -30,6 +30,10 @@
 // exactly afterwards.  The weights are the MFMA row operand and the activations its column
 // operand, so a lane ends up with 4 consecutive output channels of one token.
 //
+// Epilogue.  Accumulators stay in AGPRs; each 32x64 piece is scaled, rounded to bf16 and turned into rows through a
+// small wave-private LDS tile, so that every store instruction writes whole 128-byte lines.  They are streaming
+// (non-temporal) stores: Y is not read again here, and kept out of L2 it leaves the weights resident there.
+//
 // Schedule.  A K-step of a wavefront is TM*TN MFMAs (32x32x32 int8); the LDS reads of the
 // next pair of K-steps and the expansion of the next K-step's fragments are dealt out one
 // piece per MFMA, fenced so that the compiler keeps the interleave: the vector ALU and LDS
@@ -38,6 +42,7 @@
 
 #include <cstdlib>
 #include <type_traits>
+#include <utility>
 
 namespace qvggt {
 
@@ -59,7 +64,10 @@ struct StreamCfg {
     static constexpr int NM = TM * TN, NF = TM + TN;
     static constexpr int SC_BYTES = BM * 4 + BN * 4 + BN * 2;   // per tile: sx f32, sw f32, bias bf16 (as in memory)
     static constexpr int SC_GROUPS = BM / 64 + BN / 64 + BN / 128;
-    static constexpr int LDS_BYTES = STAGES * STAGE_BYTES + 2 * SC_BYTES;
+    static constexpr int EP_PITCH = 128 + 16;           // bytes per token row of a wave's epilogue staging tile (64 channels + pad)
+    static constexpr int EP_BYTES = NW * 32 * EP_PITCH;
+    static constexpr int LDS_BYTES = STAGES * STAGE_BYTES + 2 * SC_BYTES + EP_BYTES;
+    static_assert(TN % 2 == 0, "the epilogue handles channel sub-tiles in pairs");
     static_assert(GROUPS % NW == 0, "16-row groups do not divide among the waves");
     static_assert(BM % 128 == 0 && BN % 128 == 0, "scale transfers assume multiples of 128");
     static_assert(STAGES >= 3, "ring needs one stage being read, one landed, one in flight");
@@ -83,6 +91,29 @@ __device__ inline void dma4(const void *src, uint32_t lds_base)
 {
     asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" ::"v"(src), "s"(lds_base) : "memory", "m0");
 }
+// The instruction offset of such a transfer moves the LDS address and the global address alike: with one base in M0,
+// transfers to different places of a stage differ only in OFF (the global pointer is pre-compensated by -OFF).
+template <int OFF>
+__device__ inline void dma16_set_base(const void *src, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off offset:%2" ::"v"(src), "s"(lds_base), "n"(OFF) : "memory", "m0");
+}
+template <int OFF>
+__device__ inline void dma16_same_base(const void *src)
+{
+    asm volatile("global_load_lds_dwordx4 %0, off offset:%1" ::"v"(src), "n"(OFF) : "memory");
+}
+template <class F, int... Is>
+__device__ inline void static_for_impl(F &&f, std::integer_sequence<int, Is...>)
+{
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order
+template <int N, class F>
+__device__ inline void static_for(F &&f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
 template <int N>
 __device__ inline void wait_vmcnt()
 {
@@ -99,6 +130,8 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void w4a4_gemm_kernel(
 {
     using C = StreamCfg<TM, TN, WM, WN, STAGES>;
     constexpr int NM = C::NM, NF = C::NF, LPW = C::LPW;
+    constexpr int DMA_SHIFT = (LPW > 4) ? 4096 : 0;             // keeps the transfers' instruction offsets inside [-4096, 4095]
+    static_assert(LPW <= 8, "instruction offsets of a wave's transfers must fit 13 signed bits");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     uint8_t *sc_all = smem + STAGES * C::STAGE_BYTES;           // two buffers of SC_BYTES
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;            // LDS byte address of the dynamic segment
@@ -129,17 +162,21 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void w4a4_gemm_kernel(
         const int tm = t / tiles_n, tn = t % tiles_n;
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
-            const int r = (i * C::NW + wave) * 16 + t_row;      // row inside the stage: 16-row groups are dealt to the waves in turn
+            const int r = (wave * LPW + i) * 16 + t_row;        // row inside the stage: LPW consecutive 16-row groups per wave
             const uint8_t *base = (r < C::BM) ? Xq + (size_t)min(tm * C::BM + r, M - 1) * KB
                                               : Wq + (size_t)min(tn * C::BN + r - C::BM, N - 1) * KB;
-            gp[i] = base + t_chunk * 16;
+            gp[i] = base + t_chunk * 16 - (i * 1024 - DMA_SHIFT);   // minus the instruction offset of transfer i
         }
     };
     // The K-tile under the load cursor goes to ring stage ld_stage, one transfer instruction at a time (a wave that issues
     // them back to back stalls on each: they are dealt out between MFMAs instead); then the cursor moves on, across
     // output tiles (past this block's last tile it re-reads that tile: never used, keeps the transfers in flight uniform).
-    auto issue_transfer = [&](int i) {
-        dma16(gp[i] + ld_kt * KT_BYTES, lds0 + ld_stage * C::STAGE_BYTES + (i * C::NW + wave) * 1024);
+    auto issue_transfer = [&](auto i_c) {
+        constexpr int i = decltype(i_c)::value;
+        const uint8_t *src = gp[i] + ld_kt * KT_BYTES;
+        // the wave's LPW KiB of a stage are contiguous; M0 (set by the first transfer of a K-tile) points DMA_SHIFT into them
+        if constexpr (i == 0) dma16_set_base<i * 1024 - DMA_SHIFT>(src, lds0 + ld_stage * C::STAGE_BYTES + wave * LPW * 1024 + DMA_SHIFT);
+        else dma16_same_base<i * 1024 - DMA_SHIFT>(src);
     };
     auto advance_cursor = [&]() {
         ld_stage = (ld_stage + 1 == STAGES) ? 0 : ld_stage + 1;
@@ -150,8 +187,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void w4a4_gemm_kernel(
         }
     };
     auto issue_ktile = [&]() {
-#pragma unroll
-        for (int i = 0; i < LPW; ++i) issue_transfer(i);
+        static_for<LPW>([&](auto i_c) { issue_transfer(i_c); });
         advance_cursor();
     };
     // per-tile scales to LDS buffer sb, as they are in memory: sx of the tile's tokens, sw and bias of its channels
@@ -197,14 +233,14 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void w4a4_gemm_kernel(
         constexpr int STEP = decltype(step_c)::value, PAR = STEP & 1;   // STEP: K-step inside the K-tile
         constexpr bool FRESH = decltype(fresh_c)::value;
         const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-        for (int t = 0; t < NM; ++t) {
-            const int j = t / TM, i = t % TM;
+        static_for<NM>([&](auto t_c) {
+            constexpr int t = decltype(t_c)::value, j = t / TM, i = t % TM;
             acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(F[PAR][j], F[PAR][TN + i], FRESH ? zero : acc[j][i], 0, 0, 0);
             // this K-tile's share of the global -> LDS transfers: transfer n goes out in slot (2n + 1) * 4 * NM / (2 * LPW) of the K-tile
-#pragma unroll
-            for (int n = 0; n < LPW; ++n)
-                if ((2 * n + 1) * 4 * NM / (2 * LPW) == STEP * NM + t) issue_transfer(n);
+            static_for<LPW>([&](auto n_c) {
+                constexpr int n = decltype(n_c)::value;
+                if constexpr ((2 * n + 1) * 4 * NM / (2 * LPW) == STEP * NM + t) issue_transfer(n_c);
+            });
 #pragma unroll
             for (int f = 0; f < NF; ++f) {
                 const int done = ((2 * f + 2) * NM + 2 * NF - 1) / (2 * NF) - 1;   // slot of the PAR == 0 step that uses raw[f] last
@@ -216,7 +252,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void w4a4_gemm_kernel(
                 else QVGGT_EXPAND_HALF(raw[h >> 1][h & 1], F[0][h >> 1], 2 * (h & 1));
             }
             __builtin_amdgcn_sched_barrier(0);
-        }
+        });
     };
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
@@ -289,9 +325,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void w4a4_gemm_kernel(
 #endif
 
         // ---- epilogue.  32x32 result layout: lane l holds column (l % 32) = token and rows 8*(r/4) + 4*(l/32) + r%4 = channels,
-        // i.e. per register quad q four consecutive channels 8q + 4*(l/32) + 0..3.  Scale + bias + bf16 in registers; then the
-        // two lane halves trade quads (v_permlane32_swap) so that a lane owns 8 consecutive channels = 16 bytes of one token:
-        // the lower half takes channels 16p .. 16p+7, the upper half 16p+8 .. 16p+15 (p = 0, 1).  No trip through LDS.
+        // i.e. per register quad q four consecutive channels 8q + 4*(l/32) + 0..3.  Scale + bias + bf16 in registers.
         const int tm = tile / tiles_n, tn = tile % tiles_n;
         const int row0 = tm * C::BM + wm * TM * 32, col0 = tn * C::BN + wn * TN * 32;   // first token / channel of this wave
         const uint8_t *sc = sc_all + sb * C::SC_BYTES;
@@ -300,53 +334,59 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void w4a4_gemm_kernel(
         const uint16_t *scb = reinterpret_cast<const uint16_t *>(sc + C::BM * 4 + C::BN * 4) + wn * TN * 32 + 4 * g;
         const int rows_left = M - row0;                      // tokens of this wave's rows that exist
         const int cols_left = N - col0;                      // channels of this wave's columns that exist (a multiple of 16)
-        const size_t ystep = (size_t)32 * N;                 // Y elements between token sub-tiles
         float sxm[TM];
 #pragma unroll
         for (int i = 0; i < TM; ++i) sxm[i] = scx[(wm * TM + i) * 32 + c] * (1.0f / 256.0f);
+        {
+            // A wave-private LDS tile [32 tokens][64 channels] turns the lane-per-token layout into rows, so
+            // that a store instruction writes whole 128-byte lines (8 lanes x 16 bytes per token).  Whole lines can be
+            // streamed past L2 (non-temporal) without write amplification, which leaves the weights resident there.
+            uint8_t *ep = smem + STAGES * C::STAGE_BYTES + 2 * C::SC_BYTES + wave * (32 * C::EP_PITCH);
+            const int rd_row = lane >> 3, rd_col = lane & 7;
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            float4 swq[4], bq[4];
+            for (int jp = 0; jp < TN / 2; ++jp) {
+                float4 swq[2][4], bq[2][4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                swq[q] = *reinterpret_cast<const float4 *>(scw + j * 32 + 8 * q);
-                const uint2 b = *reinterpret_cast<const uint2 *>(scb + j * 32 + 8 * q);
-                bq[q] = make_float4(__uint_as_float(b.x << 16), __uint_as_float(b.x & 0xFFFF0000u),
-                                    __uint_as_float(b.y << 16), __uint_as_float(b.y & 0xFFFF0000u));
-            }
-            uint16_t *yp = Y + (size_t)(row0 + c) * N + col0 + j * 32 + 8 * g;
+                for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                uint32_t pk[4][2];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    // the accumulators live in AGPRs; reading them here, one at a time, keeps the compiler from copying
-                    // whole tiles into vector registers ahead of time
-                    int a0, a1, a2, a3;
-                    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a0) : "a"(acc[j][i][4 * q]));
-                    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a1) : "a"(acc[j][i][4 * q + 1]));
-                    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a2) : "a"(acc[j][i][4 * q + 2]));
-                    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a3) : "a"(acc[j][i][4 * q + 3]));
-                    const float y0 = fmaf((float)a0 * sxm[i], swq[q].x, bq[q].x), y1 = fmaf((float)a1 * sxm[i], swq[q].y, bq[q].y);
-                    const float y2 = fmaf((float)a2 * sxm[i], swq[q].z, bq[q].z), y3 = fmaf((float)a3 * sxm[i], swq[q].w, bq[q].w);
-                    pk[q][0] = pack_bf16x2(y0, y1);
-                    pk[q][1] = pack_bf16x2(y2, y3);
-                    if constexpr (DEBUG) {
-                        const int m = row0 + i * 32 + c, n = col0 + j * 32 + 8 * q + 4 * g;
-                        if (m < M && n < N)
-                            *reinterpret_cast<int4 *>(acc_debug + (size_t)m * N + n) = make_int4(a0 >> 8, a1 >> 8, a2 >> 8, a3 >> 8);
+                    for (int q = 0; q < 4; ++q) {
+                        swq[jj][q] = *reinterpret_cast<const float4 *>(scw + (2 * jp + jj) * 32 + 8 * q);
+                        const uint2 b = *reinterpret_cast<const uint2 *>(scb + (2 * jp + jj) * 32 + 8 * q);
+                        bq[jj][q] = make_float4(__uint_as_float(b.x << 16), __uint_as_float(b.x & 0xFFFF0000u),
+                                                __uint_as_float(b.y << 16), __uint_as_float(b.y & 0xFFFF0000u));
                     }
-                }
-                const bool row_ok = c < rows_left - i * 32;
+                const bool col_ok = rd_col * 8 < cols_left - jp * 64;
+                uint16_t *yp = Y + (size_t)(row0 + rd_row) * N + col0 + jp * 64 + rd_col * 8;
 #pragma unroll
-                for (int p2 = 0; p2 < 2; ++p2) {
-                    const auto s0 = __builtin_amdgcn_permlane32_swap(pk[2 * p2][0], pk[2 * p2 + 1][0], false, false);
-                    const auto s1 = __builtin_amdgcn_permlane32_swap(pk[2 * p2][1], pk[2 * p2 + 1][1], false, false);
-                    if (row_ok && j * 32 + 16 * p2 < cols_left)
-                        *reinterpret_cast<uint4 *>(yp + 16 * p2) = make_uint4(s0[0], s1[0], s0[1], s1[1]);
+                for (int i = 0; i < TM; ++i) {
+#pragma unroll
+                    for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            int a0, a1, a2, a3;
+                            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a0) : "a"(acc[2 * jp + jj][i][4 * q]));
+                            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a1) : "a"(acc[2 * jp + jj][i][4 * q + 1]));
+                            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a2) : "a"(acc[2 * jp + jj][i][4 * q + 2]));
+                            asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a3) : "a"(acc[2 * jp + jj][i][4 * q + 3]));
+                            const float y0 = fmaf((float)a0 * sxm[i], swq[jj][q].x, bq[jj][q].x), y1 = fmaf((float)a1 * sxm[i], swq[jj][q].y, bq[jj][q].y);
+                            const float y2 = fmaf((float)a2 * sxm[i], swq[jj][q].z, bq[jj][q].z), y3 = fmaf((float)a3 * sxm[i], swq[jj][q].w, bq[jj][q].w);
+                            *reinterpret_cast<uint2 *>(ep + c * C::EP_PITCH + (jj * 32 + 8 * q + 4 * g) * 2) = make_uint2(pack_bf16x2(y0, y1), pack_bf16x2(y2, y3));
+                            if constexpr (DEBUG) {
+                                const int m = row0 + i * 32 + c, n = col0 + (2 * jp + jj) * 32 + 8 * q + 4 * g;
+                                if (m < M && n < N)
+                                    *reinterpret_cast<int4 *>(acc_debug + (size_t)m * N + n) = make_int4(a0 >> 8, a1 >> 8, a2 >> 8, a3 >> 8);
+                            }
+                        }
+                    __builtin_amdgcn_sched_barrier(0);
+                    // the staging tile is private to the wave and LDS operations of a wave execute in order: no barrier needed
+#pragma unroll
+                    for (int it = 0; it < 4; ++it) {
+                        const v4i v = *reinterpret_cast<const v4i *>(ep + (it * 8 + rd_row) * C::EP_PITCH + rd_col * 16);
+                        if (col_ok && rd_row < rows_left - (i * 32 + it * 8)) __builtin_nontemporal_store(v, reinterpret_cast<v4i *>(yp));
+                        yp += (size_t)8 * N;
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                yp += ystep;
-                __builtin_amdgcn_sched_barrier(0);
             }
         }
         sb ^= 1;
@@ -407,7 +447,6 @@ hipError_t run_w4a4_gemm(const uint8_t *Xq, const float *sx, const uint8_t *Wq, 
         case 1: GOP(4, 4, 2, 2, 4, 1);
         case 2: GOP(4, 4, 2, 2, 3, 1);
         case 3: GOP(2, 2, 2, 2, 3, 2);
-        case 4: GOP(4, 2, 2, 2, 4, 1);
         default: break;
     }
 #endif

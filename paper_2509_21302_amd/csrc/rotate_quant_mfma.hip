@@ -29,6 +29,7 @@ namespace qvggt {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
 namespace rq {
 constexpr int LDS_PITCH = 272;                 // bytes per 128-value bf16 segment row (256 + 16 pad)
@@ -147,13 +148,18 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
         if (f >= max_flat) f = max_flat - K + (f % K);
         return reinterpret_cast<const uint4 *>(X + f);
     };
+    // streaming loads: X is read exactly once, and fetched past the caches it leaves room there for what is reused
+    auto load16 = [&](const uint4 *p) -> uint4 {
+        const v4u v = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(p));
+        return make_uint4(v[0], v[1], v[2], v[3]);
+    };
     uint4 G[PF][8];
     int tile = wave;
 #pragma unroll
     for (int p = 0; p < PF; ++p)
         if (tile + p * nwaves < ntiles) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) G[p][j] = *tile_ptr(tile + p * nwaves, j);
+            for (int j = 0; j < 8; ++j) G[p][j] = load16(tile_ptr(tile + p * nwaves, j));
         }
     const int wr_base = ((lane >> 4) * rq::LDS_PITCH) + (lane & 15) * 16;
     const int rd_base = c * rq::LDS_PITCH + g * 16;
@@ -177,7 +183,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
         const int next = tile + PF * nwaves;
         if (next < ntiles) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) G[PF - 1][j] = *tile_ptr(next, j);
+            for (int j = 0; j < 8; ++j) G[PF - 1][j] = load16(tile_ptr(next, j));
         }
 
         // R . H_128 on the matrix cores

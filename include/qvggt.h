@@ -47,7 +47,7 @@ typedef enum {
     QVGGT_ERR_ALIGN = 3,     /* a pointer is not 16-byte aligned */
     QVGGT_ERR_DTYPE = 4,     /* dtype is neither QVGGT_BF16 nor QVGGT_F32 */
     QVGGT_ERR_WORKSPACE = 5, /* workspace smaller than qvggt_workspace_bytes() */
-    QVGGT_ERR_ARG = 6,       /* alpha outside [0, 1] or not finite */
+    QVGGT_ERR_ARG = 6,       /* alpha outside [0, 1] or not finite; a flag outside its values */
     QVGGT_ERR_HIP = 7        /* a kernel launch failed (hipGetLastError) */
 } qvggt_status;
 
@@ -97,6 +97,22 @@ int qvggt_prep_weights(const void *W, int w_dtype, int N, int K, const float *ac
  */
 int qvggt_rotate_smooth_quant(const void *X, int x_dtype, int M, int K, const int8_t *signs,
                               const float *inv_smooth, uint8_t *Xq, float *x_scale, void *stream);
+
+/*
+ * Online kernel 1 with a STATIC quantization step (appendix "More analysis on DSFQ", activation-granularity
+ * ablation: static vs dynamic, tensor-wise vs token-wise).  Same rotation and smoothing as
+ * qvggt_rotate_smooth_quant, but the step is given by the caller (calibrated offline) instead of being
+ * derived from the row:
+ *     Xq[t, j] = clamp(rne(z[t, j] / x_step[t * per_token]), -8, 7)
+ * so the clamp of the quantizer (Sec. 3.1.2) is live here.  x_step: f32, M values (per_token = 1, token-wise
+ * static) or one value for the whole tensor (per_token = 0, tensor-wise); 4-byte aligned; a step <= 0 gives
+ * codes 0.  x_scale f32 [M] receives the step every token was quantized with, i.e. what qvggt_w4a4_gemm
+ * takes as x_scale.  Other arguments, layouts and errors as qvggt_rotate_smooth_quant; per_token outside
+ * {0, 1} is QVGGT_ERR_ARG.
+ */
+int qvggt_rotate_smooth_quant_static(const void *X, int x_dtype, int M, int K, const int8_t *signs,
+                                     const float *inv_smooth, const float *x_step, int per_token,
+                                     uint8_t *Xq, float *x_scale, void *stream);
 
 /*
  * Online kernel 2 (Sec. 3.2 granularity paragraph: integer sum, dequantise after it):

@@ -16,6 +16,7 @@ QVGGT_BF16, QVGGT_F32 = 0, 1
 
 EXPORTS = [
     "qvggt_status_string", "qvggt_rotated_col_absmax", "qvggt_prep_weights", "qvggt_rotate_smooth_quant",
+    "qvggt_rotate_smooth_quant_static",
     "qvggt_w4a4_gemm", "qvggt_linear", "qvggt_workspace_bytes", "qvggt_pack_int4", "qvggt_unpack_int4",
 ]
 
@@ -51,6 +52,8 @@ def load_library() -> C.CDLL:
     lib.qvggt_prep_weights.argtypes = [vp, i, i, i, vp, vp, f, vp, vp, vp, vp]
     lib.qvggt_rotate_smooth_quant.restype = i
     lib.qvggt_rotate_smooth_quant.argtypes = [vp, i, i, i, vp, vp, vp, vp, vp]
+    lib.qvggt_rotate_smooth_quant_static.restype = i
+    lib.qvggt_rotate_smooth_quant_static.argtypes = [vp, i, i, i, vp, vp, vp, i, vp, vp, vp]
     lib.qvggt_w4a4_gemm.restype = i
     lib.qvggt_w4a4_gemm.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp, vp, vp]
     lib.qvggt_linear.restype = i
@@ -120,6 +123,14 @@ def qvggt_rotate_smooth_quant(X, signs, inv_smooth, Xq, x_scale, stream=None):
     _check(load_library().qvggt_rotate_smooth_quant(_ptr(X), _dtype_code(X), M, K, _ptr(signs), _ptr(inv_smooth),
                                                     _ptr(Xq), _ptr(x_scale), _stream(stream)),
            "qvggt_rotate_smooth_quant")
+
+
+def qvggt_rotate_smooth_quant_static(X, signs, inv_smooth, x_step, per_token, Xq, x_scale, stream=None):
+    M, K = X.shape
+    _check(load_library().qvggt_rotate_smooth_quant_static(_ptr(X), _dtype_code(X), M, K, _ptr(signs), _ptr(inv_smooth),
+                                                           _ptr(x_step), int(per_token), _ptr(Xq), _ptr(x_scale),
+                                                           _stream(stream)),
+           "qvggt_rotate_smooth_quant_static")
 
 
 def qvggt_w4a4_gemm(Xq, x_scale, Wq, w_scale, bias, M, N, K, Y, acc_debug=None, stream=None):

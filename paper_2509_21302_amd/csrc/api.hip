@@ -7,7 +7,8 @@
 
 namespace qvggt {
 hipError_t run_rotate_smooth_quant(const void *X, bool f32, int rows, int K, const int8_t *signs, const float *mul,
-                                   int mul_mode, uint8_t *packed, float *scale, hipStream_t stream);
+                                   int mul_mode, uint8_t *packed, float *scale, const float *step, int step_stride,
+                                   hipStream_t stream);
 hipError_t run_rotated_col_absmax(const void *X, bool f32, int rows, int K, const int8_t *signs, float *absmax,
                                   hipStream_t stream);
 hipError_t run_smooth_factor(float *buf, const float *act_absmax, int K, float alpha, hipStream_t stream);
@@ -40,7 +41,7 @@ const char *qvggt_status_string(int status)
         case QVGGT_ERR_ALIGN: return "QVGGT_ERR_ALIGN: pointer not 16-byte aligned";
         case QVGGT_ERR_DTYPE: return "QVGGT_ERR_DTYPE: dtype must be QVGGT_BF16 or QVGGT_F32";
         case QVGGT_ERR_WORKSPACE: return "QVGGT_ERR_WORKSPACE: workspace too small";
-        case QVGGT_ERR_ARG: return "QVGGT_ERR_ARG: alpha must be a finite value in [0, 1]";
+        case QVGGT_ERR_ARG: return "QVGGT_ERR_ARG: alpha must be a finite value in [0, 1]; per_token must be 0 or 1";
         case QVGGT_ERR_HIP: return "QVGGT_ERR_HIP: kernel launch failed";
         default: return "unknown qvggt status";
     }
@@ -80,7 +81,7 @@ int qvggt_prep_weights(const void *W, int w_dtype, int N, int K, const float *ac
     }
     if (e != hipSuccess) return QVGGT_ERR_HIP;
     // rows of W go through the same rotate / scale / quantize kernel, with c_j / sqrt(K) as the multiplier
-    return hip_status(qvggt::run_rotate_smooth_quant(W, f32, N, K, signs, inv_smooth, 1, Wq, w_scale, s));
+    return hip_status(qvggt::run_rotate_smooth_quant(W, f32, N, K, signs, inv_smooth, 1, Wq, w_scale, nullptr, 0, s));
 }
 
 int qvggt_rotate_smooth_quant(const void *X, int x_dtype, int M, int K, const int8_t *signs, const float *inv_smooth,
@@ -93,7 +94,22 @@ int qvggt_rotate_smooth_quant(const void *X, int x_dtype, int M, int K, const in
     if (!aligned16(X) || !aligned16(Xq) || !aligned16(x_scale) || !aligned16(inv_smooth) || !aligned16(signs))
         return QVGGT_ERR_ALIGN;
     return hip_status(qvggt::run_rotate_smooth_quant(X, x_dtype == QVGGT_F32, M, K, signs, inv_smooth, 0, Xq, x_scale,
-                                                     static_cast<hipStream_t>(stream)));
+                                                     nullptr, 0, static_cast<hipStream_t>(stream)));
+}
+
+int qvggt_rotate_smooth_quant_static(const void *X, int x_dtype, int M, int K, const int8_t *signs, const float *inv_smooth,
+                                     const float *x_step, int per_token, uint8_t *Xq, float *x_scale, void *stream)
+{
+    if (!valid_dtype(x_dtype)) return QVGGT_ERR_DTYPE;
+    if (M < 0 || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (per_token != 0 && per_token != 1) return QVGGT_ERR_ARG;
+    if (M == 0) return QVGGT_OK;
+    if (!X || !Xq || !x_scale || !x_step) return QVGGT_ERR_NULL;
+    if (!aligned16(X) || !aligned16(Xq) || !aligned16(x_scale) || !aligned16(inv_smooth) || !aligned16(signs) ||
+        (reinterpret_cast<uintptr_t>(x_step) & 3u) != 0)
+        return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_rotate_smooth_quant(X, x_dtype == QVGGT_F32, M, K, signs, inv_smooth, 0, Xq, x_scale,
+                                                     x_step, per_token, static_cast<hipStream_t>(stream)));
 }
 
 int qvggt_w4a4_gemm(const uint8_t *Xq, const float *x_scale, const uint8_t *Wq, const float *w_scale, const void *bias,
@@ -130,7 +146,7 @@ int qvggt_linear(const void *X, int x_dtype, int M, int N, int K, const int8_t *
     uint8_t *Xq = static_cast<uint8_t *>(workspace);
     float *x_scale = reinterpret_cast<float *>(Xq + round_up((size_t)M * (size_t)(K / 2), 256));
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = qvggt::run_rotate_smooth_quant(X, x_dtype == QVGGT_F32, M, K, signs, inv_smooth, 0, Xq, x_scale, s);
+    hipError_t e = qvggt::run_rotate_smooth_quant(X, x_dtype == QVGGT_F32, M, K, signs, inv_smooth, 0, Xq, x_scale, nullptr, 0, s);
     if (e != hipSuccess) return QVGGT_ERR_HIP;
     return hip_status(qvggt::run_w4a4_gemm(Xq, x_scale, Wq, w_scale, bias, M, N, K, Y, nullptr, s));
 }

@@ -99,7 +99,8 @@ __global__ __launch_bounds__(256) void rotate_rows_kernel(const void *__restrict
                                                           const float *__restrict__ mul, int mul_mode,
                                                           uint8_t *__restrict__ packed,
                                                           float *__restrict__ scale,
-                                                          unsigned int *__restrict__ col_absmax_bits)
+                                                          unsigned int *__restrict__ col_absmax_bits,
+                                                          const float *__restrict__ step, int step_stride)
 {
     constexpr int V = RowMap<K>::V, C = RowMap<K>::C, R = RowMap<K>::R;
     constexpr bool kPermuted = (K == 1024 || K == 2048 || K == 4096) && MODE == kQuantize;
@@ -144,9 +145,17 @@ __global__ __launch_bounds__(256) void rotate_rows_kernel(const void *__restrict
                 for (int i = 0; i < V; ++i)
                     atomicMax(&col_absmax_bits[c * 64 * V + lane * V + i], __float_as_uint(fabsf(x[c * V + i])));
         } else {
-            amax = wave_max(amax);
-            const float inv = amax > 0.0f ? 7.0f / amax : 0.0f;
-            if (lane == 0) scale[row] = amax / 7.0f;
+            // dynamic: the step comes from the row's absmax; static: it is given (per token or one for the tensor)
+            float inv, delta;
+            if (step != nullptr) {
+                delta = step[(size_t)row * step_stride];
+                inv = delta > 0.0f ? 1.0f / delta : 0.0f;
+            } else {
+                amax = wave_max(amax);
+                delta = amax / 7.0f;
+                inv = amax > 0.0f ? 7.0f / amax : 0.0f;
+            }
+            if (lane == 0) scale[row] = delta;
             uint8_t *out = packed + (size_t)row * (K / 2);
             if constexpr (K == 1024 || K == 2048 || K == 4096) {
                 // permuted layout: scatter the codes as bytes into the wave's LDS row at their positions,
@@ -249,7 +258,7 @@ __global__ void unpack_int4_kernel(const uint8_t *__restrict__ packed, size_t ro
 template <int MODE>
 static hipError_t launch_rotate_rows(const void *X, bool f32, int rows, int K, const int8_t *signs,
                                      const float *mul, int mul_mode, uint8_t *packed, float *scale,
-                                     unsigned int *colmax, hipStream_t stream)
+                                     unsigned int *colmax, const float *step, int step_stride, hipStream_t stream)
 {
     if (rows <= 0) return hipSuccess;
     const int waves_per_block = 4;
@@ -258,8 +267,8 @@ static hipError_t launch_rotate_rows(const void *X, bool f32, int rows, int K, c
     if (blocks > max_blocks) blocks = max_blocks;
 #define QVGGT_LAUNCH(KK)                                                                                     \
     case KK:                                                                                                 \
-        if (f32) rotate_rows_kernel<KK, true, MODE><<<blocks, 256, 0, stream>>>(X, rows, signs, mul, mul_mode, packed, scale, colmax); \
-        else rotate_rows_kernel<KK, false, MODE><<<blocks, 256, 0, stream>>>(X, rows, signs, mul, mul_mode, packed, scale, colmax);    \
+        if (f32) rotate_rows_kernel<KK, true, MODE><<<blocks, 256, 0, stream>>>(X, rows, signs, mul, mul_mode, packed, scale, colmax, step, step_stride); \
+        else rotate_rows_kernel<KK, false, MODE><<<blocks, 256, 0, stream>>>(X, rows, signs, mul, mul_mode, packed, scale, colmax, step, step_stride);    \
         break;
     switch (K) {
         QVGGT_LAUNCH(128)
@@ -276,16 +285,16 @@ static hipError_t launch_rotate_rows(const void *X, bool f32, int rows, int K, c
 }
 
 hipError_t run_rotate_quant_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, int mul_mode,
-                                 uint8_t *packed, float *scale, hipStream_t stream);
+                                 uint8_t *packed, float *scale, const float *step, int step_stride, hipStream_t stream);
 
 hipError_t run_rotate_smooth_quant(const void *X, bool f32, int rows, int K, const int8_t *signs,
                                    const float *mul, int mul_mode, uint8_t *packed, float *scale,
-                                   hipStream_t stream)
+                                   const float *step, int step_stride, hipStream_t stream)
 {
     // bf16 rows of the sizes VGGT-1B uses go to the matrix-core kernel; everything else to the generic one
     if (!f32 && (K == 1024 || K == 2048 || K == 4096))
-        return run_rotate_quant_mfma(X, rows, K, signs, mul, mul_mode, packed, scale, stream);
-    return launch_rotate_rows<kQuantize>(X, f32, rows, K, signs, mul, mul_mode, packed, scale, nullptr, stream);
+        return run_rotate_quant_mfma(X, rows, K, signs, mul, mul_mode, packed, scale, step, step_stride, stream);
+    return launch_rotate_rows<kQuantize>(X, f32, rows, K, signs, mul, mul_mode, packed, scale, nullptr, step, step_stride, stream);
 }
 
 hipError_t run_rotated_col_absmax(const void *X, bool f32, int rows, int K, const int8_t *signs,
@@ -295,7 +304,7 @@ hipError_t run_rotated_col_absmax(const void *X, bool f32, int rows, int K, cons
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return launch_rotate_rows<kColAbsMax>(X, f32, rows, K, signs, nullptr, 0, nullptr, nullptr,
-                                          reinterpret_cast<unsigned int *>(absmax), stream);
+                                          reinterpret_cast<unsigned int *>(absmax), nullptr, 0, stream);
 }
 
 hipError_t run_smooth_factor(float *buf, const float *act_absmax, int K, float alpha, hipStream_t stream)

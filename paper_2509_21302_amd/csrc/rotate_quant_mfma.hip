@@ -67,12 +67,13 @@ __host__ __device__ constexpr int row_of_seg_hi(int seg_hi /* seg >> 2 */)
 }
 }  // namespace rq
 
-template <int K, int PF, int OCC>
+template <int K, int PF, int OCC, bool STATIC>
 __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint16_t *__restrict__ X, int rows,
                                                                    const int8_t *__restrict__ signs,
                                                                    const float *__restrict__ mul, int mul_mode,
                                                                    uint8_t *__restrict__ packed,
-                                                                   float *__restrict__ scale)
+                                                                   float *__restrict__ scale,
+                                                                   const float *__restrict__ step, int step_stride)
 {
     using C = rq::Cfg<K>;
     constexpr int REM = C::REM, TOK = C::TOK;
@@ -230,7 +231,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
             }
         }
 
-        // scale, absmax per token
+        // scale, absmax per token (STATIC: the quantization step is given, no absmax)
         float amax[C::TOK_PER_LANE];
 #pragma unroll
         for (int t = 0; t < C::TOK_PER_LANE; ++t) amax[t] = 0.0f;
@@ -240,12 +241,14 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
             for (int r = 0; r < 16; ++r) {
                 const int h = r % C::HB_PER_LANE, t = r / C::HB_PER_LANE;
                 acc[nt][r] *= cm[h][nt];
-                amax[t] = fmaxf(amax[t], fabsf(acc[nt][r]));
+                if constexpr (!STATIC) amax[t] = fmaxf(amax[t], fabsf(acc[nt][r]));
             }
+        if constexpr (!STATIC) {
 #pragma unroll
-        for (int t = 0; t < C::TOK_PER_LANE; ++t) {
+            for (int t = 0; t < C::TOK_PER_LANE; ++t) {
 #pragma unroll
-            for (int m = 1; m < (REM == 5 ? 64 : 32); m <<= 1) amax[t] = fmaxf(amax[t], __shfl_xor(amax[t], m));
+                for (int m = 1; m < (REM == 5 ? 64 : 32); m <<= 1) amax[t] = fmaxf(amax[t], __shfl_xor(amax[t], m));
+            }
         }
 
         // quantize, pack, store
@@ -254,7 +257,14 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
             // token of this lane: REM 3: 2*t + g (m bit 4 = register bit 3, m bit 2 = lane half); REM 4: g; REM 5: 0
             const int tk = (REM == 3) ? (2 * t + g) : (REM == 4 ? g : 0);
             const int row = tile * TOK + tk;
-            const float inv = amax[t] > 0.0f ? 7.0f / amax[t] : 0.0f;
+            float inv, delta;
+            if constexpr (STATIC) {
+                delta = step[(size_t)min(row, rows - 1) * step_stride];
+                inv = delta > 0.0f ? 1.0f / delta : 0.0f;
+            } else {
+                delta = amax[t] / 7.0f;
+                inv = amax[t] > 0.0f ? 7.0f / amax[t] : 0.0f;
+            }
             uint32_t words[C::NL / 8];
 #pragma unroll
             for (int d = 0; d < C::NL / 8; ++d) {
@@ -263,7 +273,12 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
 #pragma unroll
                 for (int i = 7; i >= 0; --i) {
                     const int nt = i & 3, h = 2 * d + (i >> 2);
-                    const float f = fmaf(acc[nt][t * C::HB_PER_LANE + h], inv, rq::MAGIC);
+                    float f;
+                    if constexpr (STATIC) {     // a given step does not bound the ratio: clamp to the code range (ties to even below)
+                        f = __builtin_amdgcn_fmed3f(acc[nt][t * C::HB_PER_LANE + h] * inv, -8.0f, 7.0f) + rq::MAGIC;
+                    } else {
+                        f = fmaf(acc[nt][t * C::HB_PER_LANE + h], inv, rq::MAGIC);
+                    }
                     wv = (wv << 4) + __float_as_uint(f);
                 }
                 // remove the eight copies of the magic exponent pattern, then offset-binary -> two's complement
@@ -275,14 +290,14 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
 #pragma unroll
                 for (int d4 = 0; d4 < C::NL / 32; ++d4)
                     *reinterpret_cast<uint4 *>(out + 16 * d4) = make_uint4(words[4 * d4], words[4 * d4 + 1], words[4 * d4 + 2], words[4 * d4 + 3]);
-                if (c == 0 && (REM != 5 || g == 0)) scale[row] = amax[t] / 7.0f;
+                if (c == 0 && (REM != 5 || g == 0)) scale[row] = delta;
             }
         }
     }
 }
 
 hipError_t run_rotate_quant_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, int mul_mode,
-                                 uint8_t *packed, float *scale, hipStream_t stream)
+                                 uint8_t *packed, float *scale, const float *step, int step_stride, hipStream_t stream)
 {
     if (rows <= 0) return hipSuccess;
     const uint16_t *x = reinterpret_cast<const uint16_t *>(X);
@@ -291,7 +306,11 @@ hipError_t run_rotate_quant_mfma(const void *X, int rows, int K, const int8_t *s
     int blocks = (ntiles + rq::WAVES_PER_BLOCK - 1) / rq::WAVES_PER_BLOCK;
     const int max_blocks = 256 * 2;   // two resident blocks of four waves on each of the 256 compute units
     if (blocks > max_blocks) blocks = max_blocks;
-#define RQ(KK, PF, OCC) rotate_quant_mfma_kernel<KK, PF, OCC><<<blocks, 256, 0, stream>>>(x, rows, signs, mul, mul_mode, packed, scale)
+#define RQ(KK, PF, OCC)                                                                                                                      \
+    do {                                                                                                                                     \
+        if (step != nullptr) rotate_quant_mfma_kernel<KK, PF, OCC, true><<<blocks, 256, 0, stream>>>(x, rows, signs, mul, mul_mode, packed, scale, step, step_stride); \
+        else rotate_quant_mfma_kernel<KK, PF, OCC, false><<<blocks, 256, 0, stream>>>(x, rows, signs, mul, mul_mode, packed, scale, nullptr, 0);                        \
+    } while (0)
     switch (K) {
         case 1024: RQ(1024, 1, 2); break;
         case 2048: RQ(2048, 1, 2); break;

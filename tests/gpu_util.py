@@ -46,6 +46,14 @@ def gpu_rsq(Xd, signs_d, inv_d):
     return Xq, sx
 
 
+def gpu_rsq_static(Xd, signs_d, inv_d, step_d, per_token):
+    M, K = Xd.shape
+    Xq = torch.empty(M, K // 2, dtype=torch.uint8, device=DEV)
+    sx = torch.empty(M, dtype=torch.float32, device=DEV)
+    q.qvggt_rotate_smooth_quant_static(Xd, signs_d, inv_d, step_d, per_token, Xq, sx)
+    return Xq, sx
+
+
 def gpu_unpack(packed, K):
     rows = packed.shape[0]
     codes = torch.empty(rows, K, dtype=torch.int8, device=DEV)

@@ -74,6 +74,16 @@ def test_argument_validation_needs_no_gpu():
     # alpha
     for bad in (-0.1, 1.5, float("nan"), float("inf")):
         assert lib.qvggt_prep_weights(P, 0, 32, 1024, None, None, C.c_float(bad), P, P, P, None) == ARG
+    # static-step variant: same checks, plus the step pointer and the granularity flag
+    st = lib.qvggt_rotate_smooth_quant_static
+    assert st(P, 0, 4, 1000, None, None, P, 1, P, P, None) == SHAPE
+    assert st(P, 9, 4, 1024, None, None, P, 1, P, P, None) == DTYPE
+    assert st(P, 0, 4, 1024, None, None, None, 1, P, P, None) == NULL
+    assert st(P, 0, 4, 1024, None, None, P, 0, None, P, None) == NULL
+    assert st(P, 0, 4, 1024, None, None, P + 2, 0, P, P, None) == ALIGN
+    for bad in (-1, 2, 7):
+        assert st(P, 0, 4, 1024, None, None, P, bad, P, P, None) == ARG
+    assert st(None, 0, 0, 1024, None, None, None, 1, None, None, None) == OK
     # workspace
     need = q.qvggt_workspace_bytes(100, 32, 1024)
     assert lib.qvggt_linear(P, 0, 100, 32, 1024, None, None, P, P, None, P, P, need - 1, None) == WORKSPACE

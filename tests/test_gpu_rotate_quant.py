@@ -34,6 +34,51 @@ def test_rotate_quant_all_sizes(K, dtype):
     G.check_scales(sx.cpu().numpy(), dx, f"K={K}")
 
 
+@pytest.mark.parametrize("K", [128, 1024, 4096])
+@pytest.mark.parametrize("per_token", [1, 0])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_rotate_quant_static_step(K, per_token, dtype):
+    """A calibrated step instead of the row's own absmax: token-wise (one per row) or tensor-wise (one value).
+    The steps are drawn below each row's dynamic step so that part of every row saturates at -8 / 7."""
+    rows = 37 if K >= 2048 else 203
+    X = _heavy(rows, K, 300 + K, dtype)
+    rng = np.random.default_rng(K + per_token)
+    signs = (rng.integers(0, 2, K) * 2 - 1).astype(np.int8)
+    c_hat = np.exp(rng.uniform(-1, 1, K))
+    inv = (1.0 / (np.sqrt(K) * c_hat)).astype(np.float32)
+    dyn, _, Z = oracle.rotate_smooth_quant(X, 1.0 / (inv.astype(np.float64) * np.sqrt(K)), pre_signs=signs)
+    if per_token:
+        step = (dyn * rng.uniform(0.2, 1.5, rows)).astype(np.float32)
+    else:
+        step = np.array([np.median(dyn) * 0.5], dtype=np.float32)
+    want = oracle.quantize_rows_static(Z, np.broadcast_to(step.astype(np.float64), (rows,)), 4)
+    assert (want == 7).any() and (want == -8).any()          # the clamp is exercised
+    Xq, sx = G.gpu_rsq_static(G.to_dev(X), G.to_dev(signs), G.to_dev(inv), G.to_dev(step), per_token)
+    G.check_codes(G.gpu_unpack(Xq, K), want, f"K={K} per_token={per_token}")
+    assert np.array_equal(sx.cpu().numpy(), np.broadcast_to(step, (rows,)))
+
+
+def test_rotate_quant_static_step_feeds_the_gemm():
+    """Codes and echoed steps of the static variant are valid inputs of the integer GEMM."""
+    spec = synth.layer_spec(2)
+    K, N, rows = 1024, 256, 300
+    rng = np.random.default_rng(11)
+    X = _heavy(rows, K, 12)
+    W = rng.standard_normal((N, K)).astype(np.float32) * 0.05
+    signs = synth.make_signs(spec)[:K]
+    prep_o = oracle.prepare_weights(W, None, pre_signs=signs)
+    _, _, Z = oracle.rotate_smooth_quant(X, prep_o.c_hat, pre_signs=signs)
+    step = np.array([np.percentile(np.abs(Z), 99.9) / 7.0], dtype=np.float32)
+    qx = oracle.quantize_rows_static(Z, np.full(rows, float(step[0])), 4)
+    acc = oracle.int_gemm(qx, prep_o.qw)
+    want = oracle.dequant_bias(acc, np.full(rows, float(step[0])), prep_o.dw, None)
+    prep = G.gpu_prep(W, None, signs)
+    Xq, sx = G.gpu_rsq_static(G.to_dev(X), prep["signs"], prep["inv"], G.to_dev(step), 0)
+    Y = torch.empty(rows, N, dtype=torch.bfloat16, device=G.DEV)
+    G.q.qvggt_w4a4_gemm(Xq, sx, prep["Wq"], prep["sw"], None, rows, N, K, Y)
+    assert G.rel_fro(G.bf16_bits(Y), want) <= G.Y_REL_FRO
+
+
 def test_rotate_quant_optional_arguments():
     K, rows = 1024, 64
     X = _heavy(rows, K, 7)

@@ -1,12 +1,13 @@
 """Benchmark of the W4A4 DSFQ linear path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 5] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 5] [--bits 4] [--no-cpu-baseline]
 
 A step is one pass of the whole online path (rotate + smooth + per-token quantize, int4 GEMM,
 dequant + bias epilogue: qvggt_linear) over every layer of the chosen synthetic config, inputs
 resident in HBM.  Prints one JSON line.  The default workload is the benchmark's configs[4]
 (fc1 and fc2 of the VGGT-1B MLP at 100 frames), the largest single-GPU configuration and the
-one the throughput targets are stated on.
+one the throughput targets are stated on.  --bits 8 / 6 time the same layers in the 8-bit / 6-bit setting (int8
+codes); the default 4-bit run also reports the 8-bit setting as a side measurement ("w8a8").
 """
 import argparse
 import json
@@ -29,6 +30,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=5, choices=[2, 3, 4, 5])
+    ap.add_argument("--bits", type=int, default=4, choices=[4, 6, 8], help="quantization setting timed as the headline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=16384, help="rows per layer the oracle is timed on")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -66,22 +68,52 @@ def main():
         signs = to_dev(synth.make_signs(s))
         a = torch.empty(s.K, dtype=torch.float32, device=dev)
         q.qvggt_rotated_col_absmax(to_dev(synth.make_calibration(s)), signs, a)
-        Wq = torch.empty(s.N, s.K // 2, dtype=torch.uint8, device=dev)
-        sw = torch.empty(s.N, dtype=torch.float32, device=dev)
-        inv = torch.empty(s.K, dtype=torch.float32, device=dev)
-        q.qvggt_prep_weights(to_dev(synth.make_weights(s)), a, signs, 0.5, Wq, sw, inv)
+        Wd = to_dev(synth.make_weights(s))
         X = to_dev(synth.make_activation_frames(s, workers=16))
-        layers.append(dict(
-            spec=s, signs=signs, Wq=Wq, sw=sw, inv=inv, bias=to_dev(synth.make_bias(s)), X=X,
-            Y=torch.empty(s.M, s.N, dtype=torch.bfloat16, device=dev),
-            ws=torch.empty(q.qvggt_workspace_bytes(s.M, s.N, s.K), dtype=torch.uint8, device=dev),
-            Xq=torch.empty(s.M, s.K // 2, dtype=torch.uint8, device=dev),
-            sx=torch.empty(s.M, dtype=torch.float32, device=dev)))
+        L = dict(spec=s, signs=signs, bias=to_dev(synth.make_bias(s)), X=X,
+                 Y=torch.empty(s.M, s.N, dtype=torch.bfloat16, device=dev),
+                 ws=torch.empty(q.qvggt_workspace_bytes_i8(s.M, s.N, s.K), dtype=torch.uint8, device=dev),
+                 Xq=torch.empty(s.M, s.K, dtype=torch.uint8, device=dev),      # sized for int8 codes; the 4-bit path uses half
+                 sx=torch.empty(s.M, dtype=torch.float32, device=dev), prep={})
+        L["Xq4"] = L["Xq"].view(-1)[: s.M * s.K // 2].view(s.M, s.K // 2)
+        L["Xq8"] = L["Xq"].view(torch.int8)
+        for bits in sorted({args.bits, 4, 8}):
+            sw = torch.empty(s.N, dtype=torch.float32, device=dev)
+            inv = torch.empty(s.K, dtype=torch.float32, device=dev)
+            if bits == 4:
+                Wq = torch.empty(s.N, s.K // 2, dtype=torch.uint8, device=dev)
+                q.qvggt_prep_weights(Wd, a, signs, 0.5, Wq, sw, inv)
+            else:
+                Wq = torch.empty(s.N, s.K, dtype=torch.int8, device=dev)
+                q.qvggt_prep_weights_i8(Wd, a, signs, 0.5, bits, Wq, sw, inv)
+            L["prep"][bits] = dict(Wq=Wq, sw=sw, inv=inv)
+        layers.append(L)
     torch.cuda.synchronize()
 
-    def step():
+    def linear(L, bits):
+        P = L["prep"][bits]
+        if bits == 4:
+            q.qvggt_linear(L["X"], L["signs"], P["inv"], P["Wq"], P["sw"], L["bias"], L["Y"], L["ws"])
+        else:
+            q.qvggt_linear_i8(L["X"], L["signs"], P["inv"], bits, P["Wq"], P["sw"], L["bias"], L["Y"], L["ws"])
+
+    def rotate_quant(L, bits):
+        P, s = L["prep"][bits], L["spec"]
+        if bits == 4:
+            q.qvggt_rotate_smooth_quant(L["X"], L["signs"], P["inv"], L["Xq4"], L["sx"])
+        else:
+            q.qvggt_rotate_smooth_quant_i8(L["X"], L["signs"], P["inv"], bits, L["Xq8"], L["sx"])
+
+    def gemm(L, bits):
+        P, s = L["prep"][bits], L["spec"]
+        if bits == 4:
+            q.qvggt_w4a4_gemm(L["Xq4"], L["sx"], P["Wq"], P["sw"], L["bias"], s.M, s.N, s.K, L["Y"], None)
+        else:
+            q.qvggt_i8_gemm(L["Xq8"], L["sx"], P["Wq"], P["sw"], L["bias"], s.M, s.N, s.K, L["Y"], None)
+
+    def step(bits=args.bits):
         for L in layers:
-            q.qvggt_linear(L["X"], L["signs"], L["inv"], L["Wq"], L["sw"], L["bias"], L["Y"], L["ws"])
+            linear(L, bits)
 
     # ------------------------------------------------------------------ timed region: whole path
     for _ in range(args.warmup):
@@ -98,39 +130,60 @@ def main():
 
     # ------------------------------------------------------------------ per-kernel durations (HIP events on the launch stream)
     # same kernels, same arguments, launched through the two single-kernel entry points so that events can sit between them
-    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-           for _ in layers] for _ in range(args.steps)]
-    for k in range(args.steps):
-        for L, (e0, e1, e2) in zip(layers, ev[k]):
+    def per_kernel(bits, steps):
+        ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in layers] for _ in range(steps)]
+        for k in range(steps):
+            for L, (e0, e1, e2) in zip(layers, ev[k]):
+                e0.record()
+                rotate_quant(L, bits)
+                e1.record()
+                gemm(L, bits)
+                e2.record()
+        torch.cuda.synchronize()
+        per_layer = {}
+        rq_ms_all, gemm_ms_all, rq_bytes_all, gemm_ops_all = 0.0, 0.0, 0.0, 0.0
+        for i, L in enumerate(layers):
             s = L["spec"]
-            e0.record()
-            q.qvggt_rotate_smooth_quant(L["X"], L["signs"], L["inv"], L["Xq"], L["sx"])
-            e1.record()
-            q.qvggt_w4a4_gemm(L["Xq"], L["sx"], L["Wq"], L["sw"], L["bias"], s.M, s.N, s.K, L["Y"], None)
-            e2.record()
-    torch.cuda.synchronize()
-    per_layer = {}
-    rq_ms_all, gemm_ms_all, rq_bytes_all, gemm_ops_all = 0.0, 0.0, 0.0, 0.0
-    for i, L in enumerate(layers):
-        s = L["spec"]
-        rq = float(np.mean([ev[k][i][0].elapsed_time(ev[k][i][1]) for k in range(args.steps)]))
-        gm = float(np.mean([ev[k][i][1].elapsed_time(ev[k][i][2]) for k in range(args.steps)]))
-        x_bytes = 2 if s.x_dtype == "bf16" else 4
-        rq_bytes = s.M * (x_bytes * s.K + s.K / 2 + 4)          # X in, codes out, scale out
-        gemm_ops = 2.0 * s.M * s.N * s.K
-        per_layer[s.name] = dict(M=s.M, K=s.K, N=s.N, rotate_quant_ms=rq, rotate_quant_GBps=rq_bytes / rq / 1e6,
-                                 gemm_ms=gm, gemm_TOPS=gemm_ops / gm / 1e9)
-        rq_ms_all += rq; gemm_ms_all += gm; rq_bytes_all += rq_bytes; gemm_ops_all += gemm_ops
+            rq = float(np.mean([ev[k][i][0].elapsed_time(ev[k][i][1]) for k in range(steps)]))
+            gm = float(np.mean([ev[k][i][1].elapsed_time(ev[k][i][2]) for k in range(steps)]))
+            x_bytes = 2 if s.x_dtype == "bf16" else 4
+            rq_bytes = s.M * (x_bytes * s.K + s.K * (0.5 if bits == 4 else 1.0) + 4)          # X in, codes out, scale out
+            gemm_ops = 2.0 * s.M * s.N * s.K
+            per_layer[s.name] = dict(M=s.M, K=s.K, N=s.N, rotate_quant_ms=rq, rotate_quant_GBps=rq_bytes / rq / 1e6,
+                                     gemm_ms=gm, gemm_TOPS=gemm_ops / gm / 1e9)
+            rq_ms_all += rq; gemm_ms_all += gm; rq_bytes_all += rq_bytes; gemm_ops_all += gemm_ops
+        return per_layer, rq_ms_all, gemm_ms_all, rq_bytes_all, gemm_ops_all
+
+    per_layer, rq_ms_all, gemm_ms_all, rq_bytes_all, gemm_ops_all = per_kernel(args.bits, args.steps)
     n_layers = len(layers)
     gemm_tops = gemm_ops_all / gemm_ms_all / 1e9
     rq_gbps = rq_bytes_all / rq_ms_all / 1e6
+
+    # side measurement: the 8-bit setting on the same layers (whole path, then per kernel), outside the headline's timed region
+    side = None
+    if args.bits == 4:
+        n = max(3, args.steps // 4)
+        for _ in range(2):
+            step(8)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            step(8)
+        torch.cuda.synchronize()
+        ms8 = (time.perf_counter() - t0) * 1e3 / n
+        pl8, rq8, gm8, rqb8, ops8 = per_kernel(8, n)
+        side = dict(steps=n, ms_per_step=ms8, value_TOPS=ops_per_step / (ms8 * 1e-3) / 1e12, gemm_TOPS=ops8 / gm8 / 1e9,
+                    gemm_frac_int8_peak=ops8 / gm8 / 1e9 / INT8_PEAK_TOPS, rotate_quant_GBps=rqb8 / rq8 / 1e6,
+                    rotate_quant_frac_hbm_peak=rqb8 / rq8 / 1e6 / HBM_PEAK_GBS, per_layer=pl8)
     # HBM bytes per launch measured with rocprofv3 counters (see profiles/); None if that file is absent
     traffic, traffic_rq = None, None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         try:
             t = json.load(open(tpath)).get(f"config{args.config}", {})
-            traffic, traffic_rq = t.get("w4a4_gemm_bytes_per_launch"), t.get("rotate_quant_bytes_per_launch")
+            if args.bits == 4:
+                traffic, traffic_rq = t.get("w4a4_gemm_bytes_per_launch"), t.get("rotate_quant_bytes_per_launch")
         except Exception:
             traffic, traffic_rq = None, None
     roofline = dict(kernel="w4a4_gemm_kernel", bound="mfma", achieved=gemm_tops, peak=INT8_PEAK_TOPS, unit="TOP/s",
@@ -159,11 +212,11 @@ def main():
             s = L["spec"]
             sg = synth.make_signs(s)
             a = oracle.rotated_col_absmax(synth.make_calibration(s), pre_signs=sg)
-            preps.append((sg, oracle.prepare_weights(synth.make_weights(s), a, pre_signs=sg), synth.make_bias(s),
+            preps.append((sg, oracle.prepare_weights(synth.make_weights(s), a, pre_signs=sg, bits=args.bits), synth.make_bias(s),
                           synth.make_activation_rows(s, list(range(rows)))))
         t0 = time.perf_counter()
         for sg, prep, bias, Xs in preps:
-            oracle.linear(Xs, prep, bias=bias, pre_signs=sg)
+            oracle.linear(Xs, prep, bias=bias, pre_signs=sg, bits=args.bits)
         cpu_s = time.perf_counter() - t0
         cpu_ops = sum(2.0 * rows * L["spec"].N * L["spec"].K for L in layers)
         cpu = dict(value=cpu_ops / cpu_s / 1e12, unit="TOPS", cores=int(os.environ.get("OMP_NUM_THREADS", os.cpu_count())),
@@ -173,9 +226,9 @@ def main():
 
     s0 = layers[0]["spec"]
     out = {
-        "metric": METRIC, "value": value, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "metric": METRIC if args.bits == 4 else METRIC.replace("W4A4", f"W{args.bits}A{args.bits}"), "value": value, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int4 (int8 MFMA, int32 accumulate)", "data": "synthetic",
+        "dtype": ("int4" if args.bits == 4 else f"int{args.bits} in int8") + " (int8 MFMA, int32 accumulate)", "data": "synthetic",
         "config": {"workload": f"BASELINE configs[{args.config - 1}]: " + ", ".join(
             f"{L['spec'].name} {L['spec'].M}x{L['spec'].K}->{L['spec'].N}" for L in layers),
             "tokens": s0.M, "frames": s0.frames, "layers": [L["spec"].name for L in layers], "parallelism": "1 GPU"},
@@ -183,6 +236,8 @@ def main():
         "rotate_quant_GBps": rq_gbps, "rotate_quant_frac_hbm_peak": rq_gbps / HBM_PEAK_GBS,
         "per_layer": per_layer, "roofline": roofline, "roofline_rotate_quant": roofline_rq, "cpu_baseline": cpu,
     }
+    if side is not None:
+        out["w8a8"] = side
     print(json.dumps(out))
 
 

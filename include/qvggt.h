@@ -47,7 +47,7 @@ typedef enum {
     QVGGT_ERR_ALIGN = 3,     /* a pointer is not 16-byte aligned */
     QVGGT_ERR_DTYPE = 4,     /* dtype is neither QVGGT_BF16 nor QVGGT_F32 */
     QVGGT_ERR_WORKSPACE = 5, /* workspace smaller than qvggt_workspace_bytes() */
-    QVGGT_ERR_ARG = 6,       /* alpha outside [0, 1] or not finite; a flag outside its values */
+    QVGGT_ERR_ARG = 6,       /* alpha outside [0, 1] or not finite; a flag outside its values; bits outside 5..8 */
     QVGGT_ERR_HIP = 7        /* a kernel launch failed (hipGetLastError) */
 } qvggt_status;
 
@@ -124,6 +124,35 @@ int qvggt_rotate_smooth_quant_static(const void *X, int x_dtype, int M, int K, c
  */
 int qvggt_w4a4_gemm(const uint8_t *Xq, const float *x_scale, const uint8_t *Wq, const float *w_scale,
                     const void *bias, int M, int N, int K, void *Y, int32_t *acc_debug, void *stream);
+
+/*
+ * The 8-bit and 6-bit settings of the same layer (Sec. 4.1 bit settings and the pose / point-map tables at 8/8;
+ * appendix "More experiments", the 6/6 rows).  Everything is as in the 4-bit entry points above except the
+ * quantizer's range and the storage of the codes:
+ *     qmax = 2^(bits-1) - 1;   scale = absmax / qmax;   code = clamp(rne(v / scale), -qmax - 1, qmax)
+ * with bits in 5..8 (else QVGGT_ERR_ARG), and codes stored one per byte as int8: Xq int8 [M, K], Wq int8 [N, K].
+ * The position of a code inside its row is again the library's fixed permutation (the same for Xq and Wq);
+ * qvggt_layout_int8 converts to and from natural order.  Sums stay in int32: |acc| <= 128 * 128 * 8192 = 2^27.
+ *
+ * qvggt_prep_weights_i8:         offline half, as qvggt_prep_weights.
+ * qvggt_rotate_smooth_quant_i8:  online kernel 1, per token, dynamic, as qvggt_rotate_smooth_quant.
+ * qvggt_i8_gemm:                 online kernel 2, as qvggt_w4a4_gemm (acc_debug receives the exact sums).
+ * qvggt_linear_i8:               both on one stream; workspace of qvggt_workspace_bytes_i8(M, N, K) bytes.
+ * qvggt_layout_int8:             src int8 [rows, K] -> dst int8 [rows, K] (distinct buffers); to_library = 1: natural
+ *                                order -> library order, 0: the inverse; other values are QVGGT_ERR_ARG.
+ */
+int qvggt_prep_weights_i8(const void *W, int w_dtype, int N, int K, const float *act_absmax_rot,
+                          const int8_t *signs, float alpha, int bits, int8_t *Wq, float *w_scale,
+                          float *inv_smooth, void *stream);
+int qvggt_rotate_smooth_quant_i8(const void *X, int x_dtype, int M, int K, const int8_t *signs,
+                                 const float *inv_smooth, int bits, int8_t *Xq, float *x_scale, void *stream);
+int qvggt_i8_gemm(const int8_t *Xq, const float *x_scale, const int8_t *Wq, const float *w_scale,
+                  const void *bias, int M, int N, int K, void *Y, int32_t *acc_debug, void *stream);
+int qvggt_linear_i8(const void *X, int x_dtype, int M, int N, int K, const int8_t *signs,
+                    const float *inv_smooth, int bits, const int8_t *Wq, const float *w_scale, const void *bias,
+                    void *Y, void *workspace, size_t workspace_bytes, void *stream);
+size_t qvggt_workspace_bytes_i8(int M, int N, int K);
+int qvggt_layout_int8(const int8_t *src, int rows, int K, int8_t *dst, int to_library, void *stream);
 
 /*
  * Whole online path: qvggt_rotate_smooth_quant into the workspace, then qvggt_w4a4_gemm.

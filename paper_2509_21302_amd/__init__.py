@@ -18,4 +18,10 @@ from .binding import (  # noqa: F401
     qvggt_workspace_bytes,
     qvggt_pack_int4,
     qvggt_unpack_int4,
+    qvggt_prep_weights_i8,
+    qvggt_rotate_smooth_quant_i8,
+    qvggt_i8_gemm,
+    qvggt_linear_i8,
+    qvggt_workspace_bytes_i8,
+    qvggt_layout_int8,
 )

@@ -18,6 +18,8 @@ EXPORTS = [
     "qvggt_status_string", "qvggt_rotated_col_absmax", "qvggt_prep_weights", "qvggt_rotate_smooth_quant",
     "qvggt_rotate_smooth_quant_static",
     "qvggt_w4a4_gemm", "qvggt_linear", "qvggt_workspace_bytes", "qvggt_pack_int4", "qvggt_unpack_int4",
+    "qvggt_prep_weights_i8", "qvggt_rotate_smooth_quant_i8", "qvggt_i8_gemm", "qvggt_linear_i8",
+    "qvggt_workspace_bytes_i8", "qvggt_layout_int8",
 ]
 
 
@@ -58,6 +60,18 @@ def load_library() -> C.CDLL:
     lib.qvggt_w4a4_gemm.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp, vp, vp]
     lib.qvggt_linear.restype = i
     lib.qvggt_linear.argtypes = [vp, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.qvggt_prep_weights_i8.restype = i
+    lib.qvggt_prep_weights_i8.argtypes = [vp, i, i, i, vp, vp, f, i, vp, vp, vp, vp]
+    lib.qvggt_rotate_smooth_quant_i8.restype = i
+    lib.qvggt_rotate_smooth_quant_i8.argtypes = [vp, i, i, i, vp, vp, i, vp, vp, vp]
+    lib.qvggt_i8_gemm.restype = i
+    lib.qvggt_i8_gemm.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp, vp, vp]
+    lib.qvggt_linear_i8.restype = i
+    lib.qvggt_linear_i8.argtypes = [vp, i, i, i, i, vp, vp, i, vp, vp, vp, vp, vp, sz, vp]
+    lib.qvggt_workspace_bytes_i8.restype = sz
+    lib.qvggt_workspace_bytes_i8.argtypes = [i, i, i]
+    lib.qvggt_layout_int8.restype = i
+    lib.qvggt_layout_int8.argtypes = [vp, i, i, vp, i, vp]
     lib.qvggt_workspace_bytes.restype = sz
     lib.qvggt_workspace_bytes.argtypes = [i, i, i]
     lib.qvggt_pack_int4.restype = i
@@ -158,3 +172,42 @@ def qvggt_pack_int4(codes, packed, stream=None):
 def qvggt_unpack_int4(packed, codes, stream=None):
     rows, K = codes.shape
     _check(load_library().qvggt_unpack_int4(_ptr(packed), rows, K, _ptr(codes), _stream(stream)), "qvggt_unpack_int4")
+
+
+# ---- the 8-bit / 6-bit settings: int8 codes
+def qvggt_prep_weights_i8(W, act_absmax_rot, signs, alpha, bits, Wq, w_scale, inv_smooth, stream=None):
+    N, K = W.shape
+    _check(load_library().qvggt_prep_weights_i8(_ptr(W), _dtype_code(W), N, K, _ptr(act_absmax_rot), _ptr(signs),
+                                                float(alpha), int(bits), _ptr(Wq), _ptr(w_scale), _ptr(inv_smooth),
+                                                _stream(stream)), "qvggt_prep_weights_i8")
+
+
+def qvggt_rotate_smooth_quant_i8(X, signs, inv_smooth, bits, Xq, x_scale, stream=None):
+    M, K = X.shape
+    _check(load_library().qvggt_rotate_smooth_quant_i8(_ptr(X), _dtype_code(X), M, K, _ptr(signs), _ptr(inv_smooth),
+                                                       int(bits), _ptr(Xq), _ptr(x_scale), _stream(stream)),
+           "qvggt_rotate_smooth_quant_i8")
+
+
+def qvggt_i8_gemm(Xq, x_scale, Wq, w_scale, bias, M, N, K, Y, acc_debug=None, stream=None):
+    _check(load_library().qvggt_i8_gemm(_ptr(Xq), _ptr(x_scale), _ptr(Wq), _ptr(w_scale), _ptr(bias), M, N, K,
+                                        _ptr(Y), _ptr(acc_debug), _stream(stream)), "qvggt_i8_gemm")
+
+
+def qvggt_workspace_bytes_i8(M: int, N: int, K: int) -> int:
+    return int(load_library().qvggt_workspace_bytes_i8(M, N, K))
+
+
+def qvggt_linear_i8(X, signs, inv_smooth, bits, Wq, w_scale, bias, Y, workspace, stream=None):
+    M, K = X.shape
+    N = Y.shape[1]
+    _check(load_library().qvggt_linear_i8(_ptr(X), _dtype_code(X), M, N, K, _ptr(signs), _ptr(inv_smooth), int(bits),
+                                          _ptr(Wq), _ptr(w_scale), _ptr(bias), _ptr(Y), _ptr(workspace),
+                                          workspace.numel() * workspace.element_size(), _stream(stream)),
+           "qvggt_linear_i8")
+
+
+def qvggt_layout_int8(src, dst, to_library, stream=None):
+    rows, K = src.shape
+    _check(load_library().qvggt_layout_int8(_ptr(src), rows, K, _ptr(dst), int(to_library), _stream(stream)),
+           "qvggt_layout_int8")

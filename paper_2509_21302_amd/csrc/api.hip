@@ -8,15 +8,18 @@
 namespace qvggt {
 hipError_t run_rotate_smooth_quant(const void *X, bool f32, int rows, int K, const int8_t *signs, const float *mul,
                                    int mul_mode, uint8_t *packed, float *scale, const float *step, int step_stride,
-                                   hipStream_t stream);
+                                   int bits, hipStream_t stream);
 hipError_t run_rotated_col_absmax(const void *X, bool f32, int rows, int K, const int8_t *signs, float *absmax,
                                   hipStream_t stream);
 hipError_t run_smooth_factor(float *buf, const float *act_absmax, int K, float alpha, hipStream_t stream);
 hipError_t run_fill_f32(float *p, int n, float v, hipStream_t stream);
 hipError_t run_pack_int4(const int8_t *codes, int rows, int K, uint8_t *packed, hipStream_t stream);
 hipError_t run_unpack_int4(const uint8_t *packed, int rows, int K, int8_t *codes, hipStream_t stream);
+hipError_t run_layout_int8(const int8_t *src, int rows, int K, int8_t *dst, int to_library, hipStream_t stream);
 hipError_t run_w4a4_gemm(const uint8_t *Xq, const float *sx, const uint8_t *Wq, const float *sw, const void *bias,
                          int M, int N, int K, void *Y, int32_t *acc_debug, hipStream_t stream);
+hipError_t run_i8_gemm(const int8_t *Xq, const float *sx, const int8_t *Wq, const float *sw, const void *bias, int M, int N,
+                       int K, void *Y, int32_t *acc_debug, hipStream_t stream);
 }  // namespace qvggt
 
 namespace {
@@ -27,39 +30,11 @@ bool valid_dtype(int d) { return d == QVGGT_BF16 || d == QVGGT_F32; }
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 int hip_status(hipError_t e) { return e == hipSuccess ? QVGGT_OK : QVGGT_ERR_HIP; }
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+bool valid_wide_bits(int bits) { return bits >= 5 && bits <= 8; }
 
-}  // namespace
-
-extern "C" {
-
-const char *qvggt_status_string(int status)
-{
-    switch (status) {
-        case QVGGT_OK: return "QVGGT_OK";
-        case QVGGT_ERR_NULL: return "QVGGT_ERR_NULL: a required pointer is NULL";
-        case QVGGT_ERR_SHAPE: return "QVGGT_ERR_SHAPE: unsupported M, N or K";
-        case QVGGT_ERR_ALIGN: return "QVGGT_ERR_ALIGN: pointer not 16-byte aligned";
-        case QVGGT_ERR_DTYPE: return "QVGGT_ERR_DTYPE: dtype must be QVGGT_BF16 or QVGGT_F32";
-        case QVGGT_ERR_WORKSPACE: return "QVGGT_ERR_WORKSPACE: workspace too small";
-        case QVGGT_ERR_ARG: return "QVGGT_ERR_ARG: alpha must be a finite value in [0, 1]; per_token must be 0 or 1";
-        case QVGGT_ERR_HIP: return "QVGGT_ERR_HIP: kernel launch failed";
-        default: return "unknown qvggt status";
-    }
-}
-
-int qvggt_rotated_col_absmax(const void *X_cal, int x_dtype, int M, int K, const int8_t *signs, float *absmax_rot,
-                             void *stream)
-{
-    if (!valid_dtype(x_dtype)) return QVGGT_ERR_DTYPE;
-    if (M < 0 || !valid_k(K)) return QVGGT_ERR_SHAPE;
-    if (!absmax_rot || (M > 0 && !X_cal)) return QVGGT_ERR_NULL;
-    if (!aligned16(X_cal) || !aligned16(absmax_rot) || !aligned16(signs)) return QVGGT_ERR_ALIGN;
-    return hip_status(qvggt::run_rotated_col_absmax(X_cal, x_dtype == QVGGT_F32, M, K, signs, absmax_rot,
-                                                    static_cast<hipStream_t>(stream)));
-}
-
-int qvggt_prep_weights(const void *W, int w_dtype, int N, int K, const float *act_absmax_rot, const int8_t *signs,
-                       float alpha, uint8_t *Wq, float *w_scale, float *inv_smooth, void *stream)
+// offline half for either code width: bits == 4 writes packed nibbles, 5..8 int8 codes
+int prep_weights(const void *W, int w_dtype, int N, int K, const float *act_absmax_rot, const int8_t *signs, float alpha,
+                 int bits, void *Wq, float *w_scale, float *inv_smooth, void *stream)
 {
     if (!valid_dtype(w_dtype)) return QVGGT_ERR_DTYPE;
     if (!valid_n(N) || !valid_k(K)) return QVGGT_ERR_SHAPE;
@@ -81,7 +56,51 @@ int qvggt_prep_weights(const void *W, int w_dtype, int N, int K, const float *ac
     }
     if (e != hipSuccess) return QVGGT_ERR_HIP;
     // rows of W go through the same rotate / scale / quantize kernel, with c_j / sqrt(K) as the multiplier
-    return hip_status(qvggt::run_rotate_smooth_quant(W, f32, N, K, signs, inv_smooth, 1, Wq, w_scale, nullptr, 0, s));
+    return hip_status(qvggt::run_rotate_smooth_quant(W, f32, N, K, signs, inv_smooth, 1, static_cast<uint8_t *>(Wq), w_scale,
+                                                     nullptr, 0, bits, s));
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *qvggt_status_string(int status)
+{
+    switch (status) {
+        case QVGGT_OK: return "QVGGT_OK";
+        case QVGGT_ERR_NULL: return "QVGGT_ERR_NULL: a required pointer is NULL";
+        case QVGGT_ERR_SHAPE: return "QVGGT_ERR_SHAPE: unsupported M, N or K";
+        case QVGGT_ERR_ALIGN: return "QVGGT_ERR_ALIGN: pointer not 16-byte aligned";
+        case QVGGT_ERR_DTYPE: return "QVGGT_ERR_DTYPE: dtype must be QVGGT_BF16 or QVGGT_F32";
+        case QVGGT_ERR_WORKSPACE: return "QVGGT_ERR_WORKSPACE: workspace too small";
+        case QVGGT_ERR_ARG: return "QVGGT_ERR_ARG: alpha must be a finite value in [0, 1]; flags 0 or 1; bits of the int8 path in 5..8";
+        case QVGGT_ERR_HIP: return "QVGGT_ERR_HIP: kernel launch failed";
+        default: return "unknown qvggt status";
+    }
+}
+
+int qvggt_rotated_col_absmax(const void *X_cal, int x_dtype, int M, int K, const int8_t *signs, float *absmax_rot,
+                             void *stream)
+{
+    if (!valid_dtype(x_dtype)) return QVGGT_ERR_DTYPE;
+    if (M < 0 || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (!absmax_rot || (M > 0 && !X_cal)) return QVGGT_ERR_NULL;
+    if (!aligned16(X_cal) || !aligned16(absmax_rot) || !aligned16(signs)) return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_rotated_col_absmax(X_cal, x_dtype == QVGGT_F32, M, K, signs, absmax_rot,
+                                                    static_cast<hipStream_t>(stream)));
+}
+
+int qvggt_prep_weights(const void *W, int w_dtype, int N, int K, const float *act_absmax_rot, const int8_t *signs,
+                       float alpha, uint8_t *Wq, float *w_scale, float *inv_smooth, void *stream)
+{
+    return prep_weights(W, w_dtype, N, K, act_absmax_rot, signs, alpha, 4, Wq, w_scale, inv_smooth, stream);
+}
+
+int qvggt_prep_weights_i8(const void *W, int w_dtype, int N, int K, const float *act_absmax_rot, const int8_t *signs,
+                          float alpha, int bits, int8_t *Wq, float *w_scale, float *inv_smooth, void *stream)
+{
+    if (!valid_wide_bits(bits)) return QVGGT_ERR_ARG;
+    return prep_weights(W, w_dtype, N, K, act_absmax_rot, signs, alpha, bits, Wq, w_scale, inv_smooth, stream);
 }
 
 int qvggt_rotate_smooth_quant(const void *X, int x_dtype, int M, int K, const int8_t *signs, const float *inv_smooth,
@@ -94,7 +113,22 @@ int qvggt_rotate_smooth_quant(const void *X, int x_dtype, int M, int K, const in
     if (!aligned16(X) || !aligned16(Xq) || !aligned16(x_scale) || !aligned16(inv_smooth) || !aligned16(signs))
         return QVGGT_ERR_ALIGN;
     return hip_status(qvggt::run_rotate_smooth_quant(X, x_dtype == QVGGT_F32, M, K, signs, inv_smooth, 0, Xq, x_scale,
-                                                     nullptr, 0, static_cast<hipStream_t>(stream)));
+                                                     nullptr, 0, 4, static_cast<hipStream_t>(stream)));
+}
+
+int qvggt_rotate_smooth_quant_i8(const void *X, int x_dtype, int M, int K, const int8_t *signs, const float *inv_smooth,
+                                 int bits, int8_t *Xq, float *x_scale, void *stream)
+{
+    if (!valid_dtype(x_dtype)) return QVGGT_ERR_DTYPE;
+    if (M < 0 || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (!valid_wide_bits(bits)) return QVGGT_ERR_ARG;
+    if (M == 0) return QVGGT_OK;
+    if (!X || !Xq || !x_scale) return QVGGT_ERR_NULL;
+    if (!aligned16(X) || !aligned16(Xq) || !aligned16(x_scale) || !aligned16(inv_smooth) || !aligned16(signs))
+        return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_rotate_smooth_quant(X, x_dtype == QVGGT_F32, M, K, signs, inv_smooth, 0,
+                                                     reinterpret_cast<uint8_t *>(Xq), x_scale, nullptr, 0, bits,
+                                                     static_cast<hipStream_t>(stream)));
 }
 
 int qvggt_rotate_smooth_quant_static(const void *X, int x_dtype, int M, int K, const int8_t *signs, const float *inv_smooth,
@@ -109,7 +143,7 @@ int qvggt_rotate_smooth_quant_static(const void *X, int x_dtype, int M, int K, c
         (reinterpret_cast<uintptr_t>(x_step) & 3u) != 0)
         return QVGGT_ERR_ALIGN;
     return hip_status(qvggt::run_rotate_smooth_quant(X, x_dtype == QVGGT_F32, M, K, signs, inv_smooth, 0, Xq, x_scale,
-                                                     x_step, per_token, static_cast<hipStream_t>(stream)));
+                                                     x_step, per_token, 4, static_cast<hipStream_t>(stream)));
 }
 
 int qvggt_w4a4_gemm(const uint8_t *Xq, const float *x_scale, const uint8_t *Wq, const float *w_scale, const void *bias,
@@ -123,6 +157,56 @@ int qvggt_w4a4_gemm(const uint8_t *Xq, const float *x_scale, const uint8_t *Wq, 
         return QVGGT_ERR_ALIGN;
     return hip_status(qvggt::run_w4a4_gemm(Xq, x_scale, Wq, w_scale, bias, M, N, K, Y, acc_debug,
                                            static_cast<hipStream_t>(stream)));
+}
+
+int qvggt_i8_gemm(const int8_t *Xq, const float *x_scale, const int8_t *Wq, const float *w_scale, const void *bias,
+                  int M, int N, int K, void *Y, int32_t *acc_debug, void *stream)
+{
+    if (M < 0 || !valid_n(N) || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (M == 0) return QVGGT_OK;
+    if (!Xq || !x_scale || !Wq || !w_scale || !Y) return QVGGT_ERR_NULL;
+    if (!aligned16(Xq) || !aligned16(x_scale) || !aligned16(Wq) || !aligned16(w_scale) || !aligned16(bias) ||
+        !aligned16(Y) || !aligned16(acc_debug))
+        return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_i8_gemm(Xq, x_scale, Wq, w_scale, bias, M, N, K, Y, acc_debug,
+                                         static_cast<hipStream_t>(stream)));
+}
+
+size_t qvggt_workspace_bytes_i8(int M, int N, int K)
+{
+    if (M < 0 || !valid_n(N) || !valid_k(K)) return 0;
+    return round_up((size_t)M * (size_t)K, 256) + round_up((size_t)M * sizeof(float), 256) + 256;
+}
+
+int qvggt_linear_i8(const void *X, int x_dtype, int M, int N, int K, const int8_t *signs, const float *inv_smooth, int bits,
+                    const int8_t *Wq, const float *w_scale, const void *bias, void *Y, void *workspace,
+                    size_t workspace_bytes, void *stream)
+{
+    if (!valid_dtype(x_dtype)) return QVGGT_ERR_DTYPE;
+    if (M < 0 || !valid_n(N) || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (!valid_wide_bits(bits)) return QVGGT_ERR_ARG;
+    if (M == 0) return QVGGT_OK;
+    if (!X || !Wq || !w_scale || !Y || !workspace) return QVGGT_ERR_NULL;
+    if (!aligned16(X) || !aligned16(Wq) || !aligned16(w_scale) || !aligned16(bias) || !aligned16(Y) ||
+        !aligned16(workspace) || !aligned16(inv_smooth) || !aligned16(signs))
+        return QVGGT_ERR_ALIGN;
+    if (workspace_bytes < qvggt_workspace_bytes_i8(M, N, K)) return QVGGT_ERR_WORKSPACE;
+    uint8_t *Xq = static_cast<uint8_t *>(workspace);
+    float *x_scale = reinterpret_cast<float *>(Xq + round_up((size_t)M * (size_t)K, 256));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = qvggt::run_rotate_smooth_quant(X, x_dtype == QVGGT_F32, M, K, signs, inv_smooth, 0, Xq, x_scale, nullptr, 0, bits, s);
+    if (e != hipSuccess) return QVGGT_ERR_HIP;
+    return hip_status(qvggt::run_i8_gemm(reinterpret_cast<const int8_t *>(Xq), x_scale, Wq, w_scale, bias, M, N, K, Y, nullptr, s));
+}
+
+int qvggt_layout_int8(const int8_t *src, int rows, int K, int8_t *dst, int to_library, void *stream)
+{
+    if (rows < 0 || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (to_library != 0 && to_library != 1) return QVGGT_ERR_ARG;
+    if (rows == 0) return QVGGT_OK;
+    if (!src || !dst) return QVGGT_ERR_NULL;
+    if (!aligned16(src) || !aligned16(dst)) return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_layout_int8(src, rows, K, dst, to_library, static_cast<hipStream_t>(stream)));
 }
 
 size_t qvggt_workspace_bytes(int M, int N, int K)
@@ -146,7 +230,7 @@ int qvggt_linear(const void *X, int x_dtype, int M, int N, int K, const int8_t *
     uint8_t *Xq = static_cast<uint8_t *>(workspace);
     float *x_scale = reinterpret_cast<float *>(Xq + round_up((size_t)M * (size_t)(K / 2), 256));
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = qvggt::run_rotate_smooth_quant(X, x_dtype == QVGGT_F32, M, K, signs, inv_smooth, 0, Xq, x_scale, nullptr, 0, s);
+    hipError_t e = qvggt::run_rotate_smooth_quant(X, x_dtype == QVGGT_F32, M, K, signs, inv_smooth, 0, Xq, x_scale, nullptr, 0, 4, s);
     if (e != hipSuccess) return QVGGT_ERR_HIP;
     return hip_status(qvggt::run_w4a4_gemm(Xq, x_scale, Wq, w_scale, bias, M, N, K, Y, nullptr, s));
 }

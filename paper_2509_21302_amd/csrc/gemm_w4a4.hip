@@ -122,8 +122,9 @@ __device__ inline void wait_vmcnt()
 
 }  // namespace
 
-template <int TM, int TN, int WM, int WN, int STAGES, int MINB, bool DEBUG>
-__global__ __launch_bounds__(WM * WN * 64, MINB) void w4a4_gemm_kernel(
+// CB: bits a stored code occupies: 4 (two codes per byte, expanded in registers) or 8 (int8 codes, fed to the MFMA as read)
+template <int TM, int TN, int WM, int WN, int STAGES, int MINB, int CB, bool DEBUG>
+__global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per_eu(WM * WN * MINB / 4, WM * WN * MINB / 4))) void w4a4_gemm_kernel(
     const uint8_t *__restrict__ Xq, const float *__restrict__ sx, const uint8_t *__restrict__ Wq,
     const float *__restrict__ sw, const uint16_t *__restrict__ bias, int M, int N, int K,
     uint16_t *__restrict__ Y, int32_t *__restrict__ acc_debug, int tiles_m, int tiles_n, long long *dbg_times)
@@ -139,7 +140,9 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void w4a4_gemm_kernel(
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
-    const int KB = K >> 1;             // packed bytes per row
+    static_assert(CB == 4 || CB == 8, "codes are stored in 4 or 8 bits");
+    constexpr int KSTEPS = (CB == 4) ? 4 : 2;                   // MFMA K-steps (32 codes each) in a K-tile of 64 bytes per row
+    const int KB = (CB == 4) ? (K >> 1) : K;                    // bytes per row of codes
     const int ktiles = KB / KT_BYTES;
     const int ntiles = tiles_m * tiles_n;
 
@@ -236,10 +239,10 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void w4a4_gemm_kernel(
         static_for<NM>([&](auto t_c) {
             constexpr int t = decltype(t_c)::value, j = t / TM, i = t % TM;
             acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(F[PAR][j], F[PAR][TN + i], FRESH ? zero : acc[j][i], 0, 0, 0);
-            // this K-tile's share of the global -> LDS transfers: transfer n goes out in slot (2n + 1) * 4 * NM / (2 * LPW) of the K-tile
+            // this K-tile's share of the global -> LDS transfers: transfer n goes out in slot (2n + 1) * KSTEPS * NM / (2 * LPW) of the K-tile
             static_for<LPW>([&](auto n_c) {
                 constexpr int n = decltype(n_c)::value;
-                if constexpr ((2 * n + 1) * 4 * NM / (2 * LPW) == STEP * NM + t) issue_transfer(n_c);
+                if constexpr ((2 * n + 1) * KSTEPS * NM / (2 * LPW) == STEP * NM + t) issue_transfer(n_c);
             });
 #pragma unroll
             for (int f = 0; f < NF; ++f) {
@@ -251,6 +254,31 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void w4a4_gemm_kernel(
                 if (PAR == 0) QVGGT_EXPAND_HALF(raw[h >> 1][2 + (h & 1)], F[1][h >> 1], 2 * (h & 1));
                 else QVGGT_EXPAND_HALF(raw[h >> 1][h & 1], F[0][h >> 1], 2 * (h & 1));
             }
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+    // One K-step on int8 codes: a lane's 16 bytes of a fragment are the MFMA operand as they are, so F[STEP] is filled
+    // straight from LDS.  While K-step STEP runs on F[STEP], the fragments of the next K-step (ring stage rd_stage, K-step
+    // rd_step of that K-tile) are read into F[STEP ^ 1], one every NM / NF slots, in the order the MFMAs will want them.
+    auto kstep8 = [&](auto step_c, auto fresh_c, int rd_stage, int rd_step) {
+        constexpr int STEP = decltype(step_c)::value;
+        constexpr bool FRESH = decltype(fresh_c)::value;
+        const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        static_for<NM>([&](auto t_c) {
+            constexpr int t = decltype(t_c)::value, j = t / TM, i = t % TM;
+            acc[j][i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(F[STEP][j], F[STEP][TN + i], FRESH ? zero : acc[j][i], 0, 0, 0);
+            static_for<LPW>([&](auto n_c) {
+                constexpr int n = decltype(n_c)::value;
+                if constexpr ((2 * n + 1) * KSTEPS * NM / (2 * LPW) == STEP * NM + t) issue_transfer(n_c);
+            });
+            static_for<NF>([&](auto o_c) {
+                constexpr int o = decltype(o_c)::value;                  // o-th read: W0, all X, then the other W
+                constexpr int f = (o == 0) ? 0 : (o <= TM ? TN + o - 1 : o - TM);
+                if constexpr (o * NM / NF == t) {
+                    const int off = ((f < TN) ? w_off : x_off) ^ (rd_step << 5);
+                    F[STEP ^ 1][f] = *reinterpret_cast<const v4i *>(smem + rd_stage * C::STAGE_BYTES + off + ((f < TN) ? f : f - TN) * 32 * KT_BYTES);
+                }
+            });
             __builtin_amdgcn_sched_barrier(0);
         });
     };
@@ -277,8 +305,12 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void w4a4_gemm_kernel(
     for (int f = 0; f < NF; ++f) read_frag(f, 0, 0);
 #pragma unroll
     for (int f = 0; f < NF; ++f) {
-        QVGGT_EXPAND_HALF(raw[f][0], F[0][f], 0);
-        QVGGT_EXPAND_HALF(raw[f][1], F[0][f], 2);
+        if constexpr (CB == 4) {
+            QVGGT_EXPAND_HALF(raw[f][0], F[0][f], 0);
+            QVGGT_EXPAND_HALF(raw[f][1], F[0][f], 2);
+        } else {
+            F[0][f] = raw[f];
+        }
     }
 
     const int c = lane & 31, g = lane >> 5;
@@ -308,10 +340,15 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void w4a4_gemm_kernel(
                 issue_scales(tnext, sb ^ 1);
             }
             const int ns = (cs + 1 == STAGES) ? 0 : cs + 1;
-            kstep(I0{}, fresh_c, cs, 1);
-            kstep(I1{}, BF{}, cs, 1);
-            kstep(I2{}, BF{}, ns, 0);
-            kstep(I3{}, BF{}, ns, 0);
+            if constexpr (CB == 4) {
+                kstep(I0{}, fresh_c, cs, 1);
+                kstep(I1{}, BF{}, cs, 1);
+                kstep(I2{}, BF{}, ns, 0);
+                kstep(I3{}, BF{}, ns, 0);
+            } else {
+                kstep8(I0{}, fresh_c, cs, 1);
+                kstep8(I1{}, BF{}, ns, 0);
+            }
             advance_cursor();
             cs = ns;
         };
@@ -336,7 +373,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void w4a4_gemm_kernel(
         const int cols_left = N - col0;                      // channels of this wave's columns that exist (a multiple of 16)
         float sxm[TM];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) sxm[i] = scx[(wm * TM + i) * 32 + c] * (1.0f / 256.0f);
+        for (int i = 0; i < TM; ++i) sxm[i] = scx[(wm * TM + i) * 32 + c] * (CB == 4 ? 1.0f / 256.0f : 1.0f);
         {
             // A wave-private LDS tile [32 tokens][64 channels] turns the lane-per-token layout into rows, so
             // that a store instruction writes whole 128-byte lines (8 lanes x 16 bytes per token).  Whole lines can be
@@ -374,7 +411,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void w4a4_gemm_kernel(
                             if constexpr (DEBUG) {
                                 const int m = row0 + i * 32 + c, n = col0 + (2 * jp + jj) * 32 + 8 * q + 4 * g;
                                 if (m < M && n < N)
-                                    *reinterpret_cast<int4 *>(acc_debug + (size_t)m * N + n) = make_int4(a0 >> 8, a1 >> 8, a2 >> 8, a3 >> 8);
+                                    *reinterpret_cast<int4 *>(acc_debug + (size_t)m * N + n) = make_int4(a0 >> (16 - 2 * CB), a1 >> (16 - 2 * CB), a2 >> (16 - 2 * CB), a3 >> (16 - 2 * CB));
                             }
                         }
                     __builtin_amdgcn_sched_barrier(0);
@@ -403,7 +440,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) void w4a4_gemm_kernel(
     wait_vmcnt<0>();        // transfers issued past the last tile must not outlive the block's LDS allocation
 }
 
-template <int TM, int TN, int WM, int WN, int STAGES, int MINB>
+template <int TM, int TN, int WM, int WN, int STAGES, int MINB, int CB>
 static hipError_t launch_gemm(const uint8_t *Xq, const float *sx, const uint8_t *Wq, const float *sw, const void *bias,
                               int M, int N, int K, void *Y, int32_t *acc_debug, hipStream_t stream)
 {
@@ -418,7 +455,7 @@ static hipError_t launch_gemm(const uint8_t *Xq, const float *sx, const uint8_t 
 #endif
     // the variant that also writes the raw accumulators is a separate instantiation: the production kernel carries none of it
     const bool debug = acc_debug != nullptr;
-    auto kern = debug ? w4a4_gemm_kernel<TM, TN, WM, WN, STAGES, MINB, true> : w4a4_gemm_kernel<TM, TN, WM, WN, STAGES, MINB, false>;
+    auto kern = debug ? w4a4_gemm_kernel<TM, TN, WM, WN, STAGES, MINB, CB, true> : w4a4_gemm_kernel<TM, TN, WM, WN, STAGES, MINB, CB, false>;
     static bool attr_set[2] = {false, false};
     if (!attr_set[debug]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
@@ -444,16 +481,29 @@ hipError_t run_w4a4_gemm(const uint8_t *Xq, const float *sx, const uint8_t *Wq, 
     const char *ev = getenv("QVGGT_GEMM_VARIANT");
     const int variant = ev ? atoi(ev) : 0;
     switch (variant) {
-        case 1: GOP(4, 4, 2, 2, 4, 1);
-        case 2: GOP(4, 4, 2, 2, 3, 1);
-        case 3: GOP(2, 2, 2, 2, 3, 2);
+        case 1: GOP(4, 4, 2, 2, 4, 1, 4);
+        case 2: GOP(4, 4, 2, 2, 3, 1, 4);
+        case 3: GOP(2, 2, 2, 2, 3, 2, 4);
         default: break;
     }
 #endif
     const long long big_tiles = (long long)((M + 255) / 256) * ((N + 255) / 256);
     // 256 tokens x 256 channels per block, four waves of 128 x 128 (one per SIMD); small problems take 128 x 128 blocks
-    if (big_tiles >= 256) GOP(4, 4, 2, 2, 4, 1);
-    GOP(2, 2, 2, 2, 3, 2);
+    if (big_tiles >= 256) GOP(4, 4, 2, 2, 4, 1, 4);
+    GOP(2, 2, 2, 2, 3, 2, 4);
+}
+
+// The same kernel on int8 codes (8- and 6-bit settings): rows of K bytes, no expansion, two K-steps per K-tile.
+hipError_t run_i8_gemm(const int8_t *Xq, const float *sx, const int8_t *Wq, const float *sw, const void *bias, int M, int N,
+                       int K, void *Y, int32_t *acc_debug, hipStream_t stream)
+{
+    if (M <= 0) return hipSuccess;
+    const uint8_t *xq = reinterpret_cast<const uint8_t *>(Xq), *wq = reinterpret_cast<const uint8_t *>(Wq);
+#undef GOP
+#define GOP(...) return launch_gemm<__VA_ARGS__>(xq, sx, wq, sw, bias, M, N, K, Y, acc_debug, stream)
+    const long long big_tiles = (long long)((M + 255) / 256) * ((N + 255) / 256);
+    if (big_tiles >= 256) GOP(4, 4, 2, 2, 4, 1, 8);
+    GOP(2, 2, 2, 2, 3, 2, 8);
 #undef GOP
 }
 

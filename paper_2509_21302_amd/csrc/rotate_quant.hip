@@ -1,6 +1,7 @@
 // Online kernel 1 and its offline twins: randomised Walsh-Hadamard rotation of rows,
-// per-channel multiply, then either per-row 4-bit quantization (activations per token,
-// weights per output channel) or a per-channel absmax (smoothing statistics).
+// per-channel multiply, then either per-row quantization (activations per token, weights
+// per output channel; 4-bit codes packed two per byte, or wider codes as int8) or a
+// per-channel absmax (smoothing statistics).
 //
 // One wavefront owns one row at a time.  A row of K values lives in K/64 registers per
 // lane; element e = c*(64*V) + lane*V + i sits in register c*V + i, where V = min(8, K/64)
@@ -93,14 +94,15 @@ enum RowMode { kQuantize = 0, kColAbsMax = 1 };
 
 // mul_mode 0: mul[j] used as given (inv_smooth, or 1/sqrt(K) when mul == nullptr)
 // mul_mode 1: 1 / (K * mul[j])   (weights: c_j / sqrt(K) recovered from inv_smooth)
-template <int K, bool F32, int MODE>
+// CB: bits a stored code occupies (4: two per byte; 8: one int8 each).  qmax: largest code, 2^(bits-1) - 1.
+template <int K, bool F32, int MODE, int CB>
 __global__ __launch_bounds__(256) void rotate_rows_kernel(const void *__restrict__ X, int rows,
                                                           const int8_t *__restrict__ signs,
                                                           const float *__restrict__ mul, int mul_mode,
                                                           uint8_t *__restrict__ packed,
                                                           float *__restrict__ scale,
                                                           unsigned int *__restrict__ col_absmax_bits,
-                                                          const float *__restrict__ step, int step_stride)
+                                                          const float *__restrict__ step, int step_stride, float qmax)
 {
     constexpr int V = RowMap<K>::V, C = RowMap<K>::C, R = RowMap<K>::R;
     constexpr bool kPermuted = (K == 1024 || K == 2048 || K == 4096) && MODE == kQuantize;
@@ -152,11 +154,12 @@ __global__ __launch_bounds__(256) void rotate_rows_kernel(const void *__restrict
                 inv = delta > 0.0f ? 1.0f / delta : 0.0f;
             } else {
                 amax = wave_max(amax);
-                delta = amax / 7.0f;
-                inv = amax > 0.0f ? 7.0f / amax : 0.0f;
+                delta = amax / qmax;
+                inv = amax > 0.0f ? qmax / amax : 0.0f;
             }
             if (lane == 0) scale[row] = delta;
-            uint8_t *out = packed + (size_t)row * (K / 2);
+            const int q_hi = (int)qmax, q_lo = -q_hi - 1;
+            uint8_t *out = packed + (size_t)row * (K * CB / 8);
             if constexpr (K == 1024 || K == 2048 || K == 4096) {
                 // permuted layout: scatter the codes as bytes into the wave's LDS row at their positions,
                 // then every lane packs K/64 consecutive positions
@@ -166,35 +169,42 @@ __global__ __launch_bounds__(256) void rotate_rows_kernel(const void *__restrict
 #pragma unroll
                     for (int i = 0; i < V; ++i) {
                         int q = (int)__builtin_rintf(x[c * V + i] * inv);
-                        q = min(7, max(-8, q));
-                        stage[code_position(c * 64 * V + lane * V + i, K)] = (uint8_t)(q & 0xF);
+                        q = min(q_hi, max(q_lo, q));
+                        stage[code_position(c * 64 * V + lane * V + i, K)] = (uint8_t)(CB == 4 ? (q & 0xF) : q);
                     }
                 __builtin_amdgcn_wave_barrier();
                 constexpr int PER_LANE = K / 64;      // positions per lane, a multiple of 16
+                if constexpr (CB == 8) {
 #pragma unroll
-                for (int b = 0; b < PER_LANE / 8; ++b) {
-                    const uint2 v = *reinterpret_cast<const uint2 *>(stage + lane * PER_LANE + 8 * b);
-                    // bytes hold one code each (low nibble): squeeze 8 bytes into 8 nibbles
-                    uint32_t lo = v.x, hi = v.y;
-                    lo = (lo | (lo >> 4)) & 0x00FF00FFu; lo = (lo | (lo >> 8)) & 0x0000FFFFu;
-                    hi = (hi | (hi >> 4)) & 0x00FF00FFu; hi = (hi | (hi >> 8)) & 0x0000FFFFu;
-                    *reinterpret_cast<uint32_t *>(out + lane * (PER_LANE / 2) + 4 * b) = lo | (hi << 16);
+                    for (int b = 0; b < PER_LANE / 16; ++b)
+                        *reinterpret_cast<uint4 *>(out + lane * PER_LANE + 16 * b) = *reinterpret_cast<const uint4 *>(stage + lane * PER_LANE + 16 * b);
+                } else {
+#pragma unroll
+                    for (int b = 0; b < PER_LANE / 8; ++b) {
+                        const uint2 v = *reinterpret_cast<const uint2 *>(stage + lane * PER_LANE + 8 * b);
+                        // bytes hold one code each (low nibble): squeeze 8 bytes into 8 nibbles
+                        uint32_t lo = v.x, hi = v.y;
+                        lo = (lo | (lo >> 4)) & 0x00FF00FFu; lo = (lo | (lo >> 8)) & 0x0000FFFFu;
+                        hi = (hi | (hi >> 4)) & 0x00FF00FFu; hi = (hi | (hi >> 8)) & 0x0000FFFFu;
+                        *reinterpret_cast<uint32_t *>(out + lane * (PER_LANE / 2) + 4 * b) = lo | (hi << 16);
+                    }
                 }
                 __builtin_amdgcn_wave_barrier();
             } else {
 #pragma unroll
             for (int c = 0; c < C; ++c) {
-                uint32_t word = 0;
+                uint64_t word = 0;
 #pragma unroll
                 for (int i = 0; i < V; ++i) {
                     int q = (int)__builtin_rintf(x[c * V + i] * inv);
-                    q = min(7, max(-8, q));
-                    word |= (uint32_t)(q & 0xF) << (4 * i);
+                    q = min(q_hi, max(q_lo, q));
+                    word |= (uint64_t)(q & ((1 << CB) - 1)) << (CB * i);
                 }
-                // natural order: element e -> nibble e; a lane's V codes are V/2 consecutive bytes
-                const int byte0 = (c * 64 * V + lane * V) / 2;
-                if constexpr (V == 8) *reinterpret_cast<uint32_t *>(out + byte0) = word;
-                else if constexpr (V == 4) *reinterpret_cast<uint16_t *>(out + byte0) = (uint16_t)word;
+                // natural order: element e -> code slot e; a lane's V codes are V * CB / 8 consecutive bytes
+                const int byte0 = (c * 64 * V + lane * V) * CB / 8;
+                if constexpr (V * CB == 64) *reinterpret_cast<uint2 *>(out + byte0) = make_uint2((uint32_t)word, (uint32_t)(word >> 32));
+                else if constexpr (V * CB == 32) *reinterpret_cast<uint32_t *>(out + byte0) = (uint32_t)word;
+                else if constexpr (V * CB == 16) *reinterpret_cast<uint16_t *>(out + byte0) = (uint16_t)word;
                 else out[byte0] = (uint8_t)word;
             }
             }
@@ -252,13 +262,23 @@ __global__ void unpack_int4_kernel(const uint8_t *__restrict__ packed, size_t ro
     codes[idx] = (int8_t)(nib >= 8 ? nib - 16 : nib);
 }
 
+// int8 codes: natural order <-> the library's position order (the same map as for packed rows, one byte per position)
+__global__ void layout_int8_kernel(const int8_t *__restrict__ src, size_t rows, int K, int8_t *__restrict__ dst, int to_library)
+{
+    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // one output byte each
+    if (idx >= rows * (size_t)K) return;
+    size_t row = idx / K;
+    int o = (int)(idx % K);
+    dst[idx] = src[row * K + (to_library ? code_element(o, K) : code_position(o, K))];
+}
+
 // ---------------------------------------------------------------------------------------
 // host-side launchers (called from api.hip)
 
-template <int MODE>
+template <int MODE, int CB>
 static hipError_t launch_rotate_rows(const void *X, bool f32, int rows, int K, const int8_t *signs,
                                      const float *mul, int mul_mode, uint8_t *packed, float *scale,
-                                     unsigned int *colmax, const float *step, int step_stride, hipStream_t stream)
+                                     unsigned int *colmax, const float *step, int step_stride, float qmax, hipStream_t stream)
 {
     if (rows <= 0) return hipSuccess;
     const int waves_per_block = 4;
@@ -267,8 +287,8 @@ static hipError_t launch_rotate_rows(const void *X, bool f32, int rows, int K, c
     if (blocks > max_blocks) blocks = max_blocks;
 #define QVGGT_LAUNCH(KK)                                                                                     \
     case KK:                                                                                                 \
-        if (f32) rotate_rows_kernel<KK, true, MODE><<<blocks, 256, 0, stream>>>(X, rows, signs, mul, mul_mode, packed, scale, colmax, step, step_stride); \
-        else rotate_rows_kernel<KK, false, MODE><<<blocks, 256, 0, stream>>>(X, rows, signs, mul, mul_mode, packed, scale, colmax, step, step_stride);    \
+        if (f32) rotate_rows_kernel<KK, true, MODE, CB><<<blocks, 256, 0, stream>>>(X, rows, signs, mul, mul_mode, packed, scale, colmax, step, step_stride, qmax); \
+        else rotate_rows_kernel<KK, false, MODE, CB><<<blocks, 256, 0, stream>>>(X, rows, signs, mul, mul_mode, packed, scale, colmax, step, step_stride, qmax);    \
         break;
     switch (K) {
         QVGGT_LAUNCH(128)
@@ -285,16 +305,21 @@ static hipError_t launch_rotate_rows(const void *X, bool f32, int rows, int K, c
 }
 
 hipError_t run_rotate_quant_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, int mul_mode,
-                                 uint8_t *packed, float *scale, const float *step, int step_stride, hipStream_t stream);
+                                 uint8_t *packed, float *scale, const float *step, int step_stride, int bits,
+                                 hipStream_t stream);
 
+// bits: 4 (packed nibbles) or 5..8 (int8 codes in [-2^(bits-1), 2^(bits-1) - 1])
 hipError_t run_rotate_smooth_quant(const void *X, bool f32, int rows, int K, const int8_t *signs,
                                    const float *mul, int mul_mode, uint8_t *packed, float *scale,
-                                   const float *step, int step_stride, hipStream_t stream)
+                                   const float *step, int step_stride, int bits, hipStream_t stream)
 {
+    const float qmax = (float)((1 << (bits - 1)) - 1);
     // bf16 rows of the sizes VGGT-1B uses go to the matrix-core kernel; everything else to the generic one
     if (!f32 && (K == 1024 || K == 2048 || K == 4096))
-        return run_rotate_quant_mfma(X, rows, K, signs, mul, mul_mode, packed, scale, step, step_stride, stream);
-    return launch_rotate_rows<kQuantize>(X, f32, rows, K, signs, mul, mul_mode, packed, scale, nullptr, step, step_stride, stream);
+        return run_rotate_quant_mfma(X, rows, K, signs, mul, mul_mode, packed, scale, step, step_stride, bits, stream);
+    if (bits == 4)
+        return launch_rotate_rows<kQuantize, 4>(X, f32, rows, K, signs, mul, mul_mode, packed, scale, nullptr, step, step_stride, qmax, stream);
+    return launch_rotate_rows<kQuantize, 8>(X, f32, rows, K, signs, mul, mul_mode, packed, scale, nullptr, step, step_stride, qmax, stream);
 }
 
 hipError_t run_rotated_col_absmax(const void *X, bool f32, int rows, int K, const int8_t *signs,
@@ -303,8 +328,8 @@ hipError_t run_rotated_col_absmax(const void *X, bool f32, int rows, int K, cons
     fill_u32_kernel<<<(K + 255) / 256, 256, 0, stream>>>(reinterpret_cast<unsigned int *>(absmax), K, 0u);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return launch_rotate_rows<kColAbsMax>(X, f32, rows, K, signs, nullptr, 0, nullptr, nullptr,
-                                          reinterpret_cast<unsigned int *>(absmax), nullptr, 0, stream);
+    return launch_rotate_rows<kColAbsMax, 4>(X, f32, rows, K, signs, nullptr, 0, nullptr, nullptr,
+                                             reinterpret_cast<unsigned int *>(absmax), nullptr, 0, 7.0f, stream);
 }
 
 hipError_t run_smooth_factor(float *buf, const float *act_absmax, int K, float alpha, hipStream_t stream)
@@ -324,6 +349,14 @@ hipError_t run_pack_int4(const int8_t *codes, int rows, int K, uint8_t *packed, 
     size_t n = (size_t)rows * (K / 2);
     if (n == 0) return hipSuccess;
     pack_int4_kernel<<<(unsigned)((n + 255) / 256), 256, 0, stream>>>(codes, (size_t)rows, K, packed);
+    return hipGetLastError();
+}
+
+hipError_t run_layout_int8(const int8_t *src, int rows, int K, int8_t *dst, int to_library, hipStream_t stream)
+{
+    size_t n = (size_t)rows * K;
+    if (n == 0) return hipSuccess;
+    layout_int8_kernel<<<(unsigned)((n + 255) / 256), 256, 0, stream>>>(src, (size_t)rows, K, dst, to_library);
     return hipGetLastError();
 }
 

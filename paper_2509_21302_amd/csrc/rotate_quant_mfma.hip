@@ -36,6 +36,7 @@ constexpr int LDS_PITCH = 272;                 // bytes per 128-value bf16 segme
 constexpr int LDS_PER_WAVE = 32 * LDS_PITCH;   // 8704
 constexpr int WAVES_PER_BLOCK = 4;
 constexpr float MAGIC = 12582912.0f + 8.0f;    // 1.5 * 2^23 + 8: adding it leaves (code + 8) in the low mantissa bits
+constexpr float MAGIC8 = 12582912.0f + 128.0f; // the same for int8 codes: (code + 128) in the low byte
 
 template <int K>
 struct Cfg {
@@ -67,13 +68,15 @@ __host__ __device__ constexpr int row_of_seg_hi(int seg_hi /* seg >> 2 */)
 }
 }  // namespace rq
 
-template <int K, int PF, int OCC, bool STATIC>
+// CB: bits a stored code occupies: 4 (packed nibbles, codes in [-8, 7]) or 8 (int8, codes in [-qmax - 1, qmax])
+template <int K, int PF, int OCC, bool STATIC, int CB>
 __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint16_t *__restrict__ X, int rows,
                                                                    const int8_t *__restrict__ signs,
                                                                    const float *__restrict__ mul, int mul_mode,
                                                                    uint8_t *__restrict__ packed,
                                                                    float *__restrict__ scale,
-                                                                   const float *__restrict__ step, int step_stride)
+                                                                   const float *__restrict__ step, int step_stride,
+                                                                   float qmax8)
 {
     using C = rq::Cfg<K>;
     constexpr int REM = C::REM, TOK = C::TOK;
@@ -262,8 +265,34 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
                 delta = step[(size_t)min(row, rows - 1) * step_stride];
                 inv = delta > 0.0f ? 1.0f / delta : 0.0f;
             } else {
-                delta = amax[t] / 7.0f;
-                inv = amax[t] > 0.0f ? 7.0f / amax[t] : 0.0f;
+                const float qmax = (CB == 4) ? 7.0f : qmax8;
+                delta = amax[t] / qmax;
+                inv = amax[t] > 0.0f ? qmax / amax[t] : 0.0f;
+            }
+            if constexpr (CB == 8) {
+                // four codes per word: byte i of word d is local index 4*d + i = nt + 4*h  ->  nt = i, h = d
+                uint32_t words[C::NL / 4];
+#pragma unroll
+                for (int d = 0; d < C::NL / 4; ++d) {
+                    uint32_t wv = 0;
+#pragma unroll
+                    for (int i = 3; i >= 0; --i) {
+                        float f;
+                        if constexpr (STATIC) f = __builtin_amdgcn_fmed3f(acc[i][t * C::HB_PER_LANE + d] * inv, -qmax8 - 1.0f, qmax8) + rq::MAGIC8;
+                        else f = fmaf(acc[i][t * C::HB_PER_LANE + d], inv, rq::MAGIC8);
+                        wv = (wv << 8) + __float_as_uint(f);
+                    }
+                    constexpr uint32_t BIAS8 = (uint32_t)(0x4B400000ull * 0x01010101ull);
+                    words[d] = (wv - BIAS8) ^ 0x80808080u;
+                }
+                if (row < rows) {
+                    uint8_t *out = packed + (size_t)row * K + (size_t)c * (K / 32) + (REM == 5 ? g * 64 : 0);
+#pragma unroll
+                    for (int d4 = 0; d4 < C::NL / 16; ++d4)
+                        *reinterpret_cast<uint4 *>(out + 16 * d4) = make_uint4(words[4 * d4], words[4 * d4 + 1], words[4 * d4 + 2], words[4 * d4 + 3]);
+                    if (c == 0 && (REM != 5 || g == 0)) scale[row] = delta;
+                }
+                continue;
             }
             uint32_t words[C::NL / 8];
 #pragma unroll
@@ -297,7 +326,8 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
 }
 
 hipError_t run_rotate_quant_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, int mul_mode,
-                                 uint8_t *packed, float *scale, const float *step, int step_stride, hipStream_t stream)
+                                 uint8_t *packed, float *scale, const float *step, int step_stride, int bits,
+                                 hipStream_t stream)
 {
     if (rows <= 0) return hipSuccess;
     const uint16_t *x = reinterpret_cast<const uint16_t *>(X);
@@ -306,10 +336,17 @@ hipError_t run_rotate_quant_mfma(const void *X, int rows, int K, const int8_t *s
     int blocks = (ntiles + rq::WAVES_PER_BLOCK - 1) / rq::WAVES_PER_BLOCK;
     const int max_blocks = 256 * 2;   // two resident blocks of four waves on each of the 256 compute units
     if (blocks > max_blocks) blocks = max_blocks;
-#define RQ(KK, PF, OCC)                                                                                                                      \
-    do {                                                                                                                                     \
-        if (step != nullptr) rotate_quant_mfma_kernel<KK, PF, OCC, true><<<blocks, 256, 0, stream>>>(x, rows, signs, mul, mul_mode, packed, scale, step, step_stride); \
-        else rotate_quant_mfma_kernel<KK, PF, OCC, false><<<blocks, 256, 0, stream>>>(x, rows, signs, mul, mul_mode, packed, scale, nullptr, 0);                        \
+    const float qmax8 = (float)((1 << (bits - 1)) - 1);
+#define RQ1(KK, PF, OCC, ST, CB) rotate_quant_mfma_kernel<KK, PF, OCC, ST, CB><<<blocks, 256, 0, stream>>>(x, rows, signs, mul, mul_mode, packed, scale, step, step_stride, qmax8)
+#define RQ(KK, PF, OCC)                                      \
+    do {                                                     \
+        if (bits == 4) {                                     \
+            if (step != nullptr) RQ1(KK, PF, OCC, true, 4);  \
+            else RQ1(KK, PF, OCC, false, 4);                 \
+        } else {                                             \
+            if (step != nullptr) RQ1(KK, PF, OCC, true, 8);  \
+            else RQ1(KK, PF, OCC, false, 8);                 \
+        }                                                    \
     } while (0)
     switch (K) {
         case 1024: RQ(1024, 1, 2); break;

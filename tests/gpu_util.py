@@ -78,6 +78,46 @@ def gpu_linear(Xd, prep, bias_d):
     return Y
 
 
+# ---- the 8-bit / 6-bit settings (int8 codes)
+def gpu_layout_int8(codes, to_library):
+    """numpy or device int8 [rows, K] -> device int8 [rows, K] in the other order"""
+    c = codes if torch.is_tensor(codes) else torch.from_numpy(np.ascontiguousarray(codes, dtype=np.int8)).to(DEV)
+    out = torch.empty_like(c)
+    q.qvggt_layout_int8(c, out, to_library)
+    return out
+
+
+def gpu_prep_i8(W, X_cal, signs, bits, alpha=0.5):
+    Wd, sd = to_dev(W), to_dev(signs)
+    N, K = Wd.shape
+    a = None
+    if X_cal is not None:
+        a = torch.empty(K, dtype=torch.float32, device=DEV)
+        q.qvggt_rotated_col_absmax(to_dev(X_cal), sd, a)
+    Wq = torch.empty(N, K, dtype=torch.int8, device=DEV)
+    sw = torch.empty(N, dtype=torch.float32, device=DEV)
+    inv = torch.empty(K, dtype=torch.float32, device=DEV)
+    q.qvggt_prep_weights_i8(Wd, a, sd, alpha, bits, Wq, sw, inv)
+    return dict(Wq=Wq, sw=sw, inv=inv, signs=sd, a=a, N=N, K=K, bits=bits)
+
+
+def gpu_rsq_i8(Xd, signs_d, inv_d, bits):
+    M, K = Xd.shape
+    Xq = torch.empty(M, K, dtype=torch.int8, device=DEV)
+    sx = torch.empty(M, dtype=torch.float32, device=DEV)
+    q.qvggt_rotate_smooth_quant_i8(Xd, signs_d, inv_d, bits, Xq, sx)
+    return Xq, sx
+
+
+def gpu_linear_i8(Xd, prep, bias_d):
+    M, K = Xd.shape
+    N = prep["N"]
+    Y = torch.empty(M, N, dtype=torch.bfloat16, device=DEV)
+    ws = torch.empty(q.qvggt_workspace_bytes_i8(M, N, K), dtype=torch.uint8, device=DEV)
+    q.qvggt_linear_i8(Xd, prep["signs"], prep["inv"], prep["bits"], prep["Wq"], prep["sw"], bias_d, Y, ws)
+    return Y
+
+
 # ---- the acceptance criteria of the quantized path -----------------------------------------
 CODE_MISMATCH_FRACTION = 1e-4     # activation codes may differ by one step on at most 0.01 % of elements
 SCALE_RTOL = 1e-5                 # fp32 butterflies and scaling against the fp64 oracle

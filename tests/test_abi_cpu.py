@@ -24,6 +24,9 @@ def test_library_exports_every_declared_symbol():
     for name in declared:
         assert hasattr(lib, name), f"{name} declared in qvggt.h but not exported"
     assert sorted(q.EXPORTS) == declared
+    # every entry point has its C signature registered with ctypes: without it a 64-bit pointer would be passed as a C int
+    for name in declared:
+        assert getattr(lib, name).argtypes is not None, f"{name}: no argtypes in the binding"
 
 
 def test_status_strings():
@@ -84,6 +87,27 @@ def test_argument_validation_needs_no_gpu():
     for bad in (-1, 2, 7):
         assert st(P, 0, 4, 1024, None, None, P, bad, P, P, None) == ARG
     assert st(None, 0, 0, 1024, None, None, None, 1, None, None, None) == OK
+    # 8-bit / 6-bit entry points: the same checks, and the bit-width
+    for bad in (4, 9, 0, -8):
+        assert lib.qvggt_rotate_smooth_quant_i8(P, 0, 4, 1024, None, None, bad, P, P, None) == ARG
+        assert lib.qvggt_prep_weights_i8(P, 0, 32, 1024, None, None, C.c_float(0.5), bad, P, P, P, None) == ARG
+        assert lib.qvggt_linear_i8(P, 0, 4, 32, 1024, None, None, bad, P, P, None, P, P, 1 << 20, None) == ARG
+    assert lib.qvggt_rotate_smooth_quant_i8(P, 0, 4, 1000, None, None, 8, P, P, None) == SHAPE
+    assert lib.qvggt_rotate_smooth_quant_i8(P, 3, 4, 1024, None, None, 8, P, P, None) == DTYPE
+    assert lib.qvggt_rotate_smooth_quant_i8(P, 0, 4, 1024, None, None, 6, None, P, None) == NULL
+    assert lib.qvggt_prep_weights_i8(P, 0, 24, 1024, None, None, C.c_float(0.5), 8, P, P, P, None) == SHAPE
+    assert lib.qvggt_prep_weights_i8(P, 0, 32, 1024, None, None, C.c_float(2.0), 8, P, P, P, None) == ARG
+    assert lib.qvggt_i8_gemm(P, P, P, P, None, 4, 100, 1024, P, None, None) == SHAPE
+    assert lib.qvggt_i8_gemm(P, P, None, P, None, 4, 32, 1024, P, None, None) == NULL
+    assert lib.qvggt_i8_gemm(P, P, P, P, P + 4, 4, 32, 1024, P, None, None) == ALIGN
+    assert lib.qvggt_i8_gemm(None, None, None, None, None, 0, 32, 1024, None, None, None) == OK
+    need8 = q.qvggt_workspace_bytes_i8(100, 32, 1024)
+    assert need8 >= 100 * 1024 + 100 * 4 and q.qvggt_workspace_bytes_i8(10, 30, 1024) == 0
+    assert lib.qvggt_linear_i8(P, 0, 100, 32, 1024, None, None, 8, P, P, None, P, P, need8 - 1, None) == WORKSPACE
+    assert lib.qvggt_layout_int8(P, 4, 1000, P, 1, None) == SHAPE
+    assert lib.qvggt_layout_int8(P, 4, 1024, P, 2, None) == ARG
+    assert lib.qvggt_layout_int8(P, 4, 1024, None, 1, None) == NULL
+    assert lib.qvggt_layout_int8(None, 0, 1024, None, 0, None) == OK
     # workspace
     need = q.qvggt_workspace_bytes(100, 32, 1024)
     assert lib.qvggt_linear(P, 0, 100, 32, 1024, None, None, P, P, None, P, P, need - 1, None) == WORKSPACE

@@ -105,6 +105,44 @@ def test_quantizer_properties():
     assert np.allclose(d8, np.abs(A).max(axis=1) / 127.0) and q8.max() == 127 or q8.min() == -127
 
 
+@pytest.mark.parametrize("bits", [4, 5, 6, 8])
+def test_quantizer_other_bit_widths(bits):
+    """The 8-bit and 6-bit settings use the same quantizer with qmax = 2^(bits-1) - 1: closed forms, the error bound,
+    and a brute-force re-derivation with Python's own round-half-even on every element."""
+    qmax = 2 ** (bits - 1) - 1
+    rng = np.random.default_rng(bits)
+    A = rng.standard_t(3, (20, 96)) * 2.3
+    A[4] = 0.0
+    d, q = oracle.quantize_rows(A, bits)
+    amax = np.abs(A).max(axis=1)
+    assert np.array_equal(d, amax / qmax)
+    assert q.min() >= -qmax and q.max() <= qmax and not q[4].any() and d[4] == 0.0
+    live = amax > 0
+    assert np.array_equal(np.abs(q[np.arange(20), np.abs(A).argmax(axis=1)])[live], np.full(live.sum(), qmax))
+    assert np.all(np.abs(A - d[:, None] * q) <= d[:, None] / 2 * (1 + 1e-12))
+    for r in range(20):
+        if d[r] > 0:
+            assert q[r].tolist() == [max(-qmax - 1, min(qmax, round(float(v) / float(d[r])))) for v in A[r]]
+    # ties go to the even code, the clamp is at -qmax - 1 and qmax
+    T = np.array([[0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 1e9, -1e9]])
+    assert oracle.quantize_rows_static(T, np.array([1.0]), bits)[0].tolist() == [0, 2, 2, 0, -2, -2, qmax, -qmax - 1]
+
+
+def test_more_bits_means_a_smaller_error_by_the_ratio_of_the_steps():
+    rng = np.random.default_rng(12)
+    X = rng.standard_normal((64, 256))
+    W = rng.standard_normal((48, 256)) * 0.05
+    exact = X @ W.T
+    err = {}
+    for bits in (4, 6, 8):
+        prep = oracle.prepare_weights(W, None, bits=bits)
+        y = oracle.linear(X, prep, bits=bits).y
+        err[bits] = np.linalg.norm(y - exact) / np.linalg.norm(exact)
+    # uniform rounding noise scales with the step: 7/31 and 31/127 between the settings, within a factor 1.5
+    assert 0.5 * 7 / 31 < err[6] / err[4] < 1.5 * 7 / 31
+    assert 0.5 * 31 / 127 < err[8] / err[6] < 1.5 * 31 / 127
+
+
 def test_quantizer_clamp_is_live_with_a_static_step():
     A = np.array([[-100.0, -7.6, 7.4, 7.6, 100.0, -8.5]])
     q = oracle.quantize_rows_static(A, np.array([1.0]), 4)

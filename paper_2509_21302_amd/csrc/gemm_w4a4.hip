@@ -415,7 +415,9 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
                             }
                         }
                     __builtin_amdgcn_sched_barrier(0);
-                    // the staging tile is private to the wave and LDS operations of a wave execute in order: no barrier needed
+                    // the staging tile is private to the wave and LDS operations of a wave execute in order: no barrier instruction is
+                    // needed, only the compiler has to be told that other lanes' writes are read next
+                    lanes_exchange_fence();
 #pragma unroll
                     for (int it = 0; it < 4; ++it) {
                         const v4i v = *reinterpret_cast<const v4i *>(ep + (it * 8 + rd_row) * C::EP_PITCH + rd_col * 16);

@@ -49,6 +49,16 @@ __device__ inline uint32_t pack_bf16x2(float lo, float hi)
     return *reinterpret_cast<uint32_t *>(&p);
 }
 
+// Lanes of one wave hand data to each other through a wave-private LDS area.  LDS operations of a wave execute in order, so
+// no instruction has to separate the writes from the reads; the compiler, however, must be told that a lane is about to
+// read what other lanes wrote (it may otherwise treat such a read as a repeat of an earlier one).
+__device__ inline void lanes_exchange_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 __device__ inline float wave_max(float v)
 {
 #pragma unroll

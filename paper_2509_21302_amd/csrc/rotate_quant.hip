@@ -172,7 +172,7 @@ __global__ __launch_bounds__(256) void rotate_rows_kernel(const void *__restrict
                         q = min(q_hi, max(q_lo, q));
                         stage[code_position(c * 64 * V + lane * V + i, K)] = (uint8_t)(CB == 4 ? (q & 0xF) : q);
                     }
-                __builtin_amdgcn_wave_barrier();
+                lanes_exchange_fence();
                 constexpr int PER_LANE = K / 64;      // positions per lane, a multiple of 16
                 if constexpr (CB == 8) {
 #pragma unroll
@@ -189,7 +189,7 @@ __global__ __launch_bounds__(256) void rotate_rows_kernel(const void *__restrict
                         *reinterpret_cast<uint32_t *>(out + lane * (PER_LANE / 2) + 4 * b) = lo | (hi << 16);
                     }
                 }
-                __builtin_amdgcn_wave_barrier();
+                lanes_exchange_fence();
             } else {
 #pragma unroll
             for (int c = 0; c < C; ++c) {

@@ -179,6 +179,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
             const int row_hi = rq::row_of_seg_hi<K>(j);
             *reinterpret_cast<uint4 *>(lds + row_hi * rq::LDS_PITCH + wr_base) = v;
         }
+        lanes_exchange_fence();     // the MFMA operand reads below take what other lanes staged
         // shift the prefetch queue and issue the loads of the tile PF steps ahead
 #pragma unroll
         for (int p = 0; p + 1 < PF; ++p)

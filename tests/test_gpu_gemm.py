@@ -88,3 +88,35 @@ def test_identity_like_weights_reproduce_codes():
     qw = np.eye(K, dtype=np.int8)
     acc, _ = _run(qx, qw, np.ones(M), np.ones(K), None)
     assert np.array_equal(acc, qx.astype(np.int32))
+
+
+def test_shape_sweep_both_code_widths():
+    """Seeded sweep over ragged shapes (M not a multiple of any tile, N any multiple of 16, every supported K) for the
+    4-bit and the 8-bit kernel: accumulators bit-exact, output within one bf16 ulp of the oracle's epilogue."""
+    import paper_2509_21302_amd as q
+    from synth import f32_to_bf16_bits
+    rng = np.random.default_rng(2024)
+    Ks = [128, 256, 512, 1024, 2048, 4096, 8192]
+    for case in range(36):
+        K = Ks[case % len(Ks)]
+        M = int(rng.integers(1, 700)) if K <= 2048 else int(rng.integers(1, 300))
+        N = 16 * int(rng.integers(1, 66 if K <= 2048 else 20))
+        wide = case % 2 == 1
+        lim = 128 if wide else 8
+        qx = rng.integers(-lim, lim, (M, K)).astype(np.int8)
+        qw = rng.integers(-lim, lim, (N, K)).astype(np.int8)
+        dx = np.exp(rng.uniform(-3, 1, M)).astype(np.float32)
+        dw = np.exp(rng.uniform(-8, -4, N)).astype(np.float32)
+        bias_bits = f32_to_bf16_bits((rng.standard_normal(N) * 0.02).astype(np.float32)) if case % 3 else None
+        Y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=G.DEV)
+        acc = torch.full((M, N), 12345, dtype=torch.int32, device=G.DEV)
+        if wide:
+            q.qvggt_i8_gemm(G.gpu_layout_int8(qx, 1), G.to_dev(dx), G.gpu_layout_int8(qw, 1), G.to_dev(dw), G.to_dev(bias_bits), M, N, K, Y, acc)
+        else:
+            q.qvggt_w4a4_gemm(G.gpu_pack(qx), G.to_dev(dx), G.gpu_pack(qw), G.to_dev(dw), G.to_dev(bias_bits), M, N, K, Y, acc)
+        want = oracle.int_gemm(qx, qw)
+        what = f"case {case}: M={M} N={N} K={K} wide={wide}"
+        assert np.array_equal(acc.cpu().numpy(), want), what
+        Yo = oracle.dequant_bias(want, dx, dw, None if bias_bits is None else oracle.to_f64(bias_bits))
+        ulp_off = np.abs(G.bf16_bits(Y).astype(np.int32) - Yo.astype(np.int32))
+        assert ulp_off.max() <= 1 and (ulp_off != 0).mean() < 5e-3, what

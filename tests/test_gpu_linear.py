@@ -134,3 +134,36 @@ def test_linear_matches_its_two_kernels():
     Y2 = torch.empty_like(Y1)
     q.qvggt_w4a4_gemm(Xq, sx, prep["Wq"], prep["sw"], bias, s.M, s.N, s.K, Y2, None)
     assert torch.equal(Y1, Y2)
+
+
+def test_linear_under_hip_graph_capture():
+    """The entry points only enqueue kernels on the given stream and allocate nothing, so a captured qvggt_linear must
+    replay correctly: three replays with fresh inputs written into the captured buffers, each against the eager result."""
+    s = synth.layer_spec(2)
+    prep = _gpu_prep(s)
+    bias = G.to_dev(synth.make_bias(s))
+    X0 = G.to_dev(synth.make_activation_frames(s))
+    import paper_2509_21302_amd as q
+    Xbuf = X0.clone()
+    Y = torch.empty(s.M, s.N, dtype=torch.bfloat16, device=G.DEV)
+    ws = torch.empty(q.qvggt_workspace_bytes(s.M, s.N, s.K), dtype=torch.uint8, device=G.DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                       # warm-up outside capture: first-call kernel attributes are set here
+        q.qvggt_linear(Xbuf, prep["signs"], prep["inv"], prep["Wq"], prep["sw"], bias, Y, ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        q.qvggt_linear(Xbuf, prep["signs"], prep["inv"], prep["Wq"], prep["sw"], bias, Y, ws)
+    gen = torch.Generator(device=G.DEV).manual_seed(3)
+    for rep in range(3):
+        Xnew = (X0.float() * (0.5 + rep) + torch.randn(X0.shape, device=G.DEV, generator=gen) * 0.1 * rep).to(torch.bfloat16)
+        Xbuf.copy_(Xnew)
+        Y.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = Y.clone()
+        want = G.gpu_linear(Xnew, prep, bias)           # eager, own buffers
+        torch.cuda.synchronize()
+        assert torch.equal(got, want), f"replay {rep}"

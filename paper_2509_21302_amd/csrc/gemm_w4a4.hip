@@ -92,16 +92,18 @@ __device__ inline void dma4(const void *src, uint32_t lds_base)
     asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" ::"v"(src), "s"(lds_base) : "memory", "m0");
 }
 // The instruction offset of such a transfer moves the LDS address and the global address alike: with one base in M0,
-// transfers to different places of a stage differ only in OFF (the global pointer is pre-compensated by -OFF).
+// transfers to different places of a stage differ only in OFF (the lane's global offset is pre-compensated by -OFF).
+// The global address is a wave-uniform 64-bit base (scalar registers) plus a 32-bit offset per lane: moving along K only
+// touches the scalar base, no vector ALU work.
 template <int OFF>
-__device__ inline void dma16_set_base(const void *src, uint32_t lds_base)
+__device__ inline void dma16_set_base(uint32_t lane_off, const void *base, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off offset:%2" ::"v"(src), "s"(lds_base), "n"(OFF) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1 offset:%3" ::"v"(lane_off), "s"(base), "s"(lds_base), "n"(OFF) : "memory", "m0");
 }
 template <int OFF>
-__device__ inline void dma16_same_base(const void *src)
+__device__ inline void dma16_same_base(uint32_t lane_off, const void *base)
 {
-    asm volatile("global_load_lds_dwordx4 %0, off offset:%1" ::"v"(src), "n"(OFF) : "memory");
+    asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" ::"v"(lane_off), "s"(base), "n"(OFF) : "memory");
 }
 template <class F, int... Is>
 __device__ inline void static_for_impl(F &&f, std::integer_sequence<int, Is...>)
@@ -159,16 +161,22 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
     // slot l % 4 of that row; it fetches the chunk that the swizzle puts there.
     const int t_row = lane >> 2;
     const int t_chunk = (lane & 3) ^ ((t_row >> 2) & 3);
-    const uint8_t *gp[LPW];
+    // A wave's LPW groups lie in one operand (X rows come first in a stage), so all its transfers share one base.
+    static_assert((C::BM / 16) % LPW == 0, "a wave's 16-row groups must not straddle the two operands");
+    constexpr uint32_t BASE_SHIFT = 4096;                       // keeps the pre-compensated lane offsets non-negative
+    const bool loads_x = wave * LPW * 16 < C::BM;
+    uint32_t lane_off[LPW];
+    const uint8_t *tile_base;                                   // wave-uniform: row 0 of the operand's tile, minus BASE_SHIFT
     int ld_tile = first_tile, ld_kt = 0, ld_stage = 0;
     auto set_tile_pointers = [&](int t) {
         const int tm = t / tiles_n, tn = t % tiles_n;
+        const int row0 = loads_x ? tm * C::BM : tn * C::BN;     // first row of the tile in its operand
+        const int last = (loads_x ? M : N) - 1 - row0;          // last existing row, relative to row0 (>= 0)
+        tile_base = (loads_x ? Xq : Wq) + (size_t)row0 * KB - BASE_SHIFT;
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
-            const int r = (wave * LPW + i) * 16 + t_row;        // row inside the stage: LPW consecutive 16-row groups per wave
-            const uint8_t *base = (r < C::BM) ? Xq + (size_t)min(tm * C::BM + r, M - 1) * KB
-                                              : Wq + (size_t)min(tn * C::BN + r - C::BM, N - 1) * KB;
-            gp[i] = base + t_chunk * 16 - (i * 1024 - DMA_SHIFT);   // minus the instruction offset of transfer i
+            const int r = (wave * LPW + i) * 16 + t_row - (loads_x ? 0 : C::BM);   // row inside the operand's tile
+            lane_off[i] = (uint32_t)min(r, last) * (uint32_t)KB + t_chunk * 16 + BASE_SHIFT - (i * 1024 - DMA_SHIFT);
         }
     };
     // The K-tile under the load cursor goes to ring stage ld_stage, one transfer instruction at a time (a wave that issues
@@ -176,10 +184,10 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
     // output tiles (past this block's last tile it re-reads that tile: never used, keeps the transfers in flight uniform).
     auto issue_transfer = [&](auto i_c) {
         constexpr int i = decltype(i_c)::value;
-        const uint8_t *src = gp[i] + ld_kt * KT_BYTES;
+        const uint8_t *base = tile_base + ld_kt * KT_BYTES;
         // the wave's LPW KiB of a stage are contiguous; M0 (set by the first transfer of a K-tile) points DMA_SHIFT into them
-        if constexpr (i == 0) dma16_set_base<i * 1024 - DMA_SHIFT>(src, lds0 + ld_stage * C::STAGE_BYTES + wave * LPW * 1024 + DMA_SHIFT);
-        else dma16_same_base<i * 1024 - DMA_SHIFT>(src);
+        if constexpr (i == 0) dma16_set_base<i * 1024 - DMA_SHIFT>(lane_off[i], base, lds0 + ld_stage * C::STAGE_BYTES + wave * LPW * 1024 + DMA_SHIFT);
+        else dma16_same_base<i * 1024 - DMA_SHIFT>(lane_off[i], base);
     };
     auto advance_cursor = [&]() {
         ld_stage = (ld_stage + 1 == STAGES) ? 0 : ld_stage + 1;

@@ -404,6 +404,13 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
                 uint16_t *yp = Y + (size_t)(row0 + rd_row) * N + col0 + jp * 64 + rd_col * 8;
 #pragma unroll
                 for (int i = 0; i < TM; ++i) {
+                    // the token's scale folded into the channel scales once per piece: one multiply per channel instead of one per value
+                    float4 sc[2][4];
+#pragma unroll
+                    for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            sc[jj][q] = make_float4(swq[jj][q].x * sxm[i], swq[jj][q].y * sxm[i], swq[jj][q].z * sxm[i], swq[jj][q].w * sxm[i]);
 #pragma unroll
                     for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
@@ -413,8 +420,8 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
                             asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a1) : "a"(acc[2 * jp + jj][i][4 * q + 1]));
                             asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a2) : "a"(acc[2 * jp + jj][i][4 * q + 2]));
                             asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a3) : "a"(acc[2 * jp + jj][i][4 * q + 3]));
-                            const float y0 = fmaf((float)a0 * sxm[i], swq[jj][q].x, bq[jj][q].x), y1 = fmaf((float)a1 * sxm[i], swq[jj][q].y, bq[jj][q].y);
-                            const float y2 = fmaf((float)a2 * sxm[i], swq[jj][q].z, bq[jj][q].z), y3 = fmaf((float)a3 * sxm[i], swq[jj][q].w, bq[jj][q].w);
+                            const float y0 = fmaf((float)a0, sc[jj][q].x, bq[jj][q].x), y1 = fmaf((float)a1, sc[jj][q].y, bq[jj][q].y);
+                            const float y2 = fmaf((float)a2, sc[jj][q].z, bq[jj][q].z), y3 = fmaf((float)a3, sc[jj][q].w, bq[jj][q].w);
                             *reinterpret_cast<uint2 *>(ep + c * C::EP_PITCH + (jj * 32 + 8 * q + 4 * g) * 2) = make_uint2(pack_bf16x2(y0, y1), pack_bf16x2(y2, y3));
                             if constexpr (DEBUG) {
                                 const int m = row0 + i * 32 + c, n = col0 + (2 * jp + jj) * 32 + 8 * q + 4 * g;

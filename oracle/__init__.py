@@ -5,3 +5,4 @@ See dsfq_oracle.c for the definitions and citations; this module only marshals
 numpy arrays to that C code and strings its steps together in the paper's order.
 """
 from .dsfq import *  # noqa: F401,F403
+from . import nfds  # noqa: F401,E402  (calibration-set arithmetic of Sec. 3.3)

@@ -193,6 +193,38 @@ def main():
                        frac=rq_gbps / HBM_PEAK_GBS, traffic=traffic_rq,
                        bytes_per_launch=rq_bytes_all / n_layers, avg_launch_ms=rq_ms_all / n_layers)
 
+    # side measurement: the two HBM-bound reductions of the calibration-set arithmetic (Sec. 3.3) on the first layer's input,
+    # taken as one sample of `frames` frames: per-frame mean / variance, and the cosine of every frame with frame 0
+    nfds = None
+    if args.bits == 4:
+        L0 = layers[0]
+        s0_ = L0["spec"]
+        fe = s0_.rows_per_frame * s0_.K
+        Xf = L0["X"][: s0_.frames * s0_.rows_per_frame].view(s0_.frames, fe)
+        code = q.QVGGT_BF16 if Xf.dtype == torch.bfloat16 else q.QVGGT_F32
+        ws = torch.empty(q.qvggt_nfds_workspace_bytes(s0_.frames, fe, code), dtype=torch.uint8, device=dev)
+        mean = torch.empty(s0_.frames, dtype=torch.float32, device=dev)
+        var = torch.empty(s0_.frames, dtype=torch.float32, device=dev)
+        corr = torch.empty(1, s0_.frames - 1, dtype=torch.float32, device=dev)
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        reps = 5
+        for it in range(reps + 1):
+            if it == 1:
+                e[0].record()
+            q.qvggt_nfds_moments(Xf, mean, var, ws)
+        e[1].record()
+        for it in range(reps):
+            q.qvggt_nfds_frame_correlation(Xf.view(1, s0_.frames, fe), corr, ws)
+        e[2].record()
+        torch.cuda.synchronize()
+        nbytes = Xf.numel() * Xf.element_size()
+        t_m, t_c = e[0].elapsed_time(e[1]) / reps, e[1].elapsed_time(e[2]) / reps
+        nfds = dict(tensor=f"{s0_.frames} frames x {s0_.rows_per_frame} tokens x {s0_.K} ({Xf.dtype})".replace("torch.", ""),
+                    moments_ms=t_m, moments_GBps=nbytes / t_m / 1e6, moments_frac_hbm_peak=nbytes / t_m / 1e6 / HBM_PEAK_GBS,
+                    frame_correlation_ms=t_c, frame_correlation_GBps=nbytes / t_c / 1e6,
+                    frame_correlation_frac_hbm_peak=nbytes / t_c / 1e6 / HBM_PEAK_GBS)
+        del ws
+
     if args.calibrate_copy:
         # 1 GiB read + 1 GiB written by an elementwise kernel: what the HBM byte counters report for it fixes their scale
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
@@ -238,6 +270,8 @@ def main():
     }
     if side is not None:
         out["w8a8"] = side
+    if nfds is not None:
+        out["nfds_reductions"] = nfds
     print(json.dumps(out))
 
 

@@ -47,7 +47,7 @@ typedef enum {
     QVGGT_ERR_ALIGN = 3,     /* a pointer is not 16-byte aligned */
     QVGGT_ERR_DTYPE = 4,     /* dtype is neither QVGGT_BF16 nor QVGGT_F32 */
     QVGGT_ERR_WORKSPACE = 5, /* workspace smaller than qvggt_workspace_bytes() */
-    QVGGT_ERR_ARG = 6,       /* alpha outside [0, 1] or not finite; a flag outside its values; bits outside 5..8 */
+    QVGGT_ERR_ARG = 6,       /* a scalar argument outside its documented range (alpha, p, eps, flags, bits) */
     QVGGT_ERR_HIP = 7        /* a kernel launch failed (hipGetLastError) */
 } qvggt_status;
 
@@ -174,6 +174,41 @@ size_t qvggt_workspace_bytes(int M, int N, int K);
  */
 int qvggt_pack_int4(const int8_t *codes, int rows, int K, uint8_t *packed, void *stream);
 int qvggt_unpack_int4(const uint8_t *packed, int rows, int K, int8_t *codes, void *stream);
+
+/*
+ * Arithmetic of the calibration-set construction (Sec. 3.3, Noise-Filtered Diverse Sampling).  Offline, outside the
+ * inference path; the two calls that read whole activation tensors are HBM-bound reductions, the others handle a pool
+ * of a few hundred samples.  Double arithmetic inside, float results.  Choosing the final samples inside each cluster
+ * (the uniform draw of Eq. "cluster") is left to the caller.
+ *
+ * qvggt_nfds_moments (first equation of the noise filter): mean[r] and var[r] (population variance) over the `count`
+ *   elements of row r of A [rows, count] (bf16 or f32), one row per (sample, layer) activation.  A row must be a whole
+ *   number of 16-byte vectors (count a multiple of 8 for bf16, of 4 for f32).  workspace: device buffer of at least
+ *   qvggt_nfds_workspace_bytes(rows, count, dtype) bytes (partial sums; contents undefined afterwards).
+ * qvggt_nfds_frame_correlation (frame-aware correlation vector): A [samples, frames, frame_elems] holds the feature of
+ *   each sample frame after frame (frame_elems = tokens per frame x channels); corr [samples, frames - 1] receives the
+ *   cosine between frame 0 and frame t, t = 1 .. frames - 1.  workspace as above with rows = samples * frames,
+ *   count = frame_elems.  A frame of zeros gives NaN, as the definition does.
+ * qvggt_nfds_scores (noise score): m, s f32 [D, L] per-sample per-layer moments -> score f32 [D]; the z-scores use the
+ *   pool's mean and standard deviation per layer with eps (>= 0) under the root.  D <= 65536, L <= 2048.
+ * qvggt_nfds_keep_lowest (Eq. "filter"): keep[i] = 1 for the floor(p * D) samples of lowest score (the percentile
+ *   threshold T), else 0; equal scores are ordered by index.  p in [0, 1].
+ * qvggt_nfds_kmeans_step (Eq. "cluster"): one Lloyd iteration on c f32 [n, dim] with K centres: labels[i] = index of the
+ *   nearest centre of centres_in [K, dim] (squared Euclidean distance, the lower index on a tie), centres_out[k] = mean
+ *   of the points labelled k (a centre without points is copied).  The caller iterates and supplies the initial centres.
+ *   n <= 65536, dim <= 4096, K <= 256; centres_in and centres_out must differ.
+ * Errors: QVGGT_ERR_SHAPE for sizes outside these limits, QVGGT_ERR_ARG for eps / p out of range or aliased centres,
+ * otherwise as for the other calls (f32 arrays here only need 4-byte alignment; A and workspace 16 bytes).
+ */
+size_t qvggt_nfds_workspace_bytes(int rows, long long count, int dtype);
+int qvggt_nfds_moments(const void *A, int dtype, int rows, long long count, float *mean, float *var, void *workspace,
+                       size_t workspace_bytes, void *stream);
+int qvggt_nfds_frame_correlation(const void *A, int dtype, int samples, int frames, long long frame_elems, float *corr,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+int qvggt_nfds_scores(const float *m, const float *s, int D, int L, double eps, float *score, void *stream);
+int qvggt_nfds_keep_lowest(const float *score, int D, double p, uint8_t *keep, void *stream);
+int qvggt_nfds_kmeans_step(const float *c, int n, int dim, int K, const float *centres_in, float *centres_out,
+                           int32_t *labels, void *stream);
 
 #ifdef __cplusplus
 }

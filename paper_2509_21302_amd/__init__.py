@@ -24,4 +24,12 @@ from .binding import (  # noqa: F401
     qvggt_linear_i8,
     qvggt_workspace_bytes_i8,
     qvggt_layout_int8,
+    qvggt_nfds_workspace_bytes,
+    qvggt_nfds_moments,
+    qvggt_nfds_frame_correlation,
+    qvggt_nfds_scores,
+    qvggt_nfds_keep_lowest,
+    qvggt_nfds_kmeans_step,
+    QVGGT_BF16,
+    QVGGT_F32,
 )

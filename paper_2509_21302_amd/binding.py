@@ -20,6 +20,8 @@ EXPORTS = [
     "qvggt_w4a4_gemm", "qvggt_linear", "qvggt_workspace_bytes", "qvggt_pack_int4", "qvggt_unpack_int4",
     "qvggt_prep_weights_i8", "qvggt_rotate_smooth_quant_i8", "qvggt_i8_gemm", "qvggt_linear_i8",
     "qvggt_workspace_bytes_i8", "qvggt_layout_int8",
+    "qvggt_nfds_workspace_bytes", "qvggt_nfds_moments", "qvggt_nfds_frame_correlation", "qvggt_nfds_scores",
+    "qvggt_nfds_keep_lowest", "qvggt_nfds_kmeans_step",
 ]
 
 
@@ -72,6 +74,19 @@ def load_library() -> C.CDLL:
     lib.qvggt_workspace_bytes_i8.argtypes = [i, i, i]
     lib.qvggt_layout_int8.restype = i
     lib.qvggt_layout_int8.argtypes = [vp, i, i, vp, i, vp]
+    ll, dbl = C.c_longlong, C.c_double
+    lib.qvggt_nfds_workspace_bytes.restype = sz
+    lib.qvggt_nfds_workspace_bytes.argtypes = [i, ll, i]
+    lib.qvggt_nfds_moments.restype = i
+    lib.qvggt_nfds_moments.argtypes = [vp, i, i, ll, vp, vp, vp, sz, vp]
+    lib.qvggt_nfds_frame_correlation.restype = i
+    lib.qvggt_nfds_frame_correlation.argtypes = [vp, i, i, i, ll, vp, vp, sz, vp]
+    lib.qvggt_nfds_scores.restype = i
+    lib.qvggt_nfds_scores.argtypes = [vp, vp, i, i, dbl, vp, vp]
+    lib.qvggt_nfds_keep_lowest.restype = i
+    lib.qvggt_nfds_keep_lowest.argtypes = [vp, i, dbl, vp, vp]
+    lib.qvggt_nfds_kmeans_step.restype = i
+    lib.qvggt_nfds_kmeans_step.argtypes = [vp, i, i, i, vp, vp, vp, vp]
     lib.qvggt_workspace_bytes.restype = sz
     lib.qvggt_workspace_bytes.argtypes = [i, i, i]
     lib.qvggt_pack_int4.restype = i
@@ -211,3 +226,37 @@ def qvggt_layout_int8(src, dst, to_library, stream=None):
     rows, K = src.shape
     _check(load_library().qvggt_layout_int8(_ptr(src), rows, K, _ptr(dst), int(to_library), _stream(stream)),
            "qvggt_layout_int8")
+
+
+# ---- calibration-set arithmetic (Sec. 3.3)
+def qvggt_nfds_workspace_bytes(rows: int, count: int, dtype_code: int) -> int:
+    return int(load_library().qvggt_nfds_workspace_bytes(rows, count, dtype_code))
+
+
+def qvggt_nfds_moments(A, mean, var, workspace, stream=None):
+    rows, count = A.shape
+    _check(load_library().qvggt_nfds_moments(_ptr(A), _dtype_code(A), rows, count, _ptr(mean), _ptr(var), _ptr(workspace),
+                                             workspace.numel() * workspace.element_size(), _stream(stream)), "qvggt_nfds_moments")
+
+
+def qvggt_nfds_frame_correlation(A, corr, workspace, stream=None):
+    samples, frames, frame_elems = A.shape
+    _check(load_library().qvggt_nfds_frame_correlation(_ptr(A), _dtype_code(A), samples, frames, frame_elems, _ptr(corr),
+                                                       _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                                       _stream(stream)), "qvggt_nfds_frame_correlation")
+
+
+def qvggt_nfds_scores(m, s, eps, score, stream=None):
+    D, L = m.shape
+    _check(load_library().qvggt_nfds_scores(_ptr(m), _ptr(s), D, L, float(eps), _ptr(score), _stream(stream)), "qvggt_nfds_scores")
+
+
+def qvggt_nfds_keep_lowest(score, p, keep, stream=None):
+    _check(load_library().qvggt_nfds_keep_lowest(_ptr(score), score.numel(), float(p), _ptr(keep), _stream(stream)),
+           "qvggt_nfds_keep_lowest")
+
+
+def qvggt_nfds_kmeans_step(c, centres_in, centres_out, labels, stream=None):
+    n, dim = c.shape
+    _check(load_library().qvggt_nfds_kmeans_step(_ptr(c), n, dim, centres_in.shape[0], _ptr(centres_in), _ptr(centres_out),
+                                                 _ptr(labels), _stream(stream)), "qvggt_nfds_kmeans_step")

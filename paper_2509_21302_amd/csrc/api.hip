@@ -20,6 +20,15 @@ hipError_t run_w4a4_gemm(const uint8_t *Xq, const float *sx, const uint8_t *Wq, 
                          int M, int N, int K, void *Y, int32_t *acc_debug, hipStream_t stream);
 hipError_t run_i8_gemm(const int8_t *Xq, const float *sx, const int8_t *Wq, const float *sw, const void *bias, int M, int N,
                        int K, void *Y, int32_t *acc_debug, hipStream_t stream);
+size_t nfds_workspace_bytes(int rows, long long count, bool f32);
+hipError_t run_nfds_moments(const void *A, bool f32, int rows, long long count, float *mean, float *var, double *ws,
+                            hipStream_t stream);
+hipError_t run_nfds_frame_correlation(const void *A, bool f32, int samples, int f, long long dhat, float *c, double *ws,
+                                      hipStream_t stream);
+hipError_t run_nfds_scores(const float *m, const float *s, int D, int L, double eps, float *score, hipStream_t stream);
+hipError_t run_nfds_keep_lowest(const float *score, int D, int n_keep, uint8_t *keep, hipStream_t stream);
+hipError_t run_nfds_kmeans_step(const float *c, int n, int dim, int K, const float *cin, float *cout, int32_t *labels,
+                                hipStream_t stream);
 }  // namespace qvggt
 
 namespace {
@@ -73,7 +82,7 @@ const char *qvggt_status_string(int status)
         case QVGGT_ERR_ALIGN: return "QVGGT_ERR_ALIGN: pointer not 16-byte aligned";
         case QVGGT_ERR_DTYPE: return "QVGGT_ERR_DTYPE: dtype must be QVGGT_BF16 or QVGGT_F32";
         case QVGGT_ERR_WORKSPACE: return "QVGGT_ERR_WORKSPACE: workspace too small";
-        case QVGGT_ERR_ARG: return "QVGGT_ERR_ARG: alpha must be a finite value in [0, 1]; flags 0 or 1; bits of the int8 path in 5..8";
+        case QVGGT_ERR_ARG: return "QVGGT_ERR_ARG: a scalar argument is outside its documented range (alpha, p in [0, 1]; flags 0 or 1; bits in 5..8; eps >= 0)";
         case QVGGT_ERR_HIP: return "QVGGT_ERR_HIP: kernel launch failed";
         default: return "unknown qvggt status";
     }
@@ -251,6 +260,77 @@ int qvggt_unpack_int4(const uint8_t *packed, int rows, int K, int8_t *codes, voi
     if (!codes || !packed) return QVGGT_ERR_NULL;
     if (!aligned16(codes) || !aligned16(packed)) return QVGGT_ERR_ALIGN;
     return hip_status(qvggt::run_unpack_int4(packed, rows, K, codes, static_cast<hipStream_t>(stream)));
+}
+
+// ---- calibration-set arithmetic (Sec. 3.3)
+namespace {
+// a row of `count` elements must be a whole number of 16-byte vectors, and the totals must stay addressable
+bool valid_row(long long count, int dtype) { return count > 0 && (count * (dtype == QVGGT_F32 ? 4 : 2)) % 16 == 0 && count <= (1LL << 40); }
+}  // namespace
+
+size_t qvggt_nfds_workspace_bytes(int rows, long long count, int dtype)
+{
+    if (rows < 0 || rows > (1 << 22) || !valid_dtype(dtype) || !valid_row(count, dtype)) return 0;
+    return round_up(qvggt::nfds_workspace_bytes(rows, count, dtype == QVGGT_F32), 256) + 256;
+}
+
+int qvggt_nfds_moments(const void *A, int dtype, int rows, long long count, float *mean, float *var, void *workspace,
+                       size_t workspace_bytes, void *stream)
+{
+    if (!valid_dtype(dtype)) return QVGGT_ERR_DTYPE;
+    if (rows < 0 || rows > (1 << 22) || !valid_row(count, dtype)) return QVGGT_ERR_SHAPE;
+    if (rows == 0) return QVGGT_OK;
+    if (!A || !mean || !var || !workspace) return QVGGT_ERR_NULL;
+    if (!aligned16(A) || !aligned16(workspace) || (reinterpret_cast<uintptr_t>(mean) & 3u) || (reinterpret_cast<uintptr_t>(var) & 3u))
+        return QVGGT_ERR_ALIGN;
+    if (workspace_bytes < qvggt_nfds_workspace_bytes(rows, count, dtype)) return QVGGT_ERR_WORKSPACE;
+    return hip_status(qvggt::run_nfds_moments(A, dtype == QVGGT_F32, rows, count, mean, var, static_cast<double *>(workspace),
+                                              static_cast<hipStream_t>(stream)));
+}
+
+int qvggt_nfds_frame_correlation(const void *A, int dtype, int samples, int frames, long long frame_elems, float *corr,
+                                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!valid_dtype(dtype)) return QVGGT_ERR_DTYPE;
+    if (samples < 0 || frames < 2 || frames > 4096 || (long long)samples * frames > (1 << 22) || !valid_row(frame_elems, dtype))
+        return QVGGT_ERR_SHAPE;
+    if (samples == 0) return QVGGT_OK;
+    if (!A || !corr || !workspace) return QVGGT_ERR_NULL;
+    if (!aligned16(A) || !aligned16(workspace) || (reinterpret_cast<uintptr_t>(corr) & 3u)) return QVGGT_ERR_ALIGN;
+    if (workspace_bytes < qvggt_nfds_workspace_bytes(samples * frames, frame_elems, dtype)) return QVGGT_ERR_WORKSPACE;
+    return hip_status(qvggt::run_nfds_frame_correlation(A, dtype == QVGGT_F32, samples, frames, frame_elems, corr,
+                                                        static_cast<double *>(workspace), static_cast<hipStream_t>(stream)));
+}
+
+int qvggt_nfds_scores(const float *m, const float *s, int D, int L, double eps, float *score, void *stream)
+{
+    if (D < 1 || D > 65536 || L < 1 || L > 2048) return QVGGT_ERR_SHAPE;
+    if (!(eps >= 0.0) || !std::isfinite(eps)) return QVGGT_ERR_ARG;
+    if (!m || !s || !score) return QVGGT_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(m) & 3u) || (reinterpret_cast<uintptr_t>(s) & 3u) || (reinterpret_cast<uintptr_t>(score) & 3u))
+        return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_nfds_scores(m, s, D, L, eps, score, static_cast<hipStream_t>(stream)));
+}
+
+int qvggt_nfds_keep_lowest(const float *score, int D, double p, uint8_t *keep, void *stream)
+{
+    if (D < 1 || D > 65536) return QVGGT_ERR_SHAPE;
+    if (!(p >= 0.0 && p <= 1.0)) return QVGGT_ERR_ARG;
+    if (!score || !keep) return QVGGT_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(score) & 3u) return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_nfds_keep_lowest(score, D, (int)std::floor(p * (double)D), keep, static_cast<hipStream_t>(stream)));
+}
+
+int qvggt_nfds_kmeans_step(const float *c, int n, int dim, int K, const float *centres_in, float *centres_out,
+                           int32_t *labels, void *stream)
+{
+    if (n < 1 || n > 65536 || dim < 1 || dim > 4096 || K < 1 || K > 256) return QVGGT_ERR_SHAPE;
+    if (!c || !centres_in || !centres_out || !labels) return QVGGT_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(c) & 3u) || (reinterpret_cast<uintptr_t>(centres_in) & 3u) ||
+        (reinterpret_cast<uintptr_t>(centres_out) & 3u) || (reinterpret_cast<uintptr_t>(labels) & 3u))
+        return QVGGT_ERR_ALIGN;
+    if (centres_in == centres_out) return QVGGT_ERR_ARG;
+    return hip_status(qvggt::run_nfds_kmeans_step(c, n, dim, K, centres_in, centres_out, labels, static_cast<hipStream_t>(stream)));
 }
 
 }  // extern "C"

@@ -123,3 +123,32 @@ def test_binding_rejects_host_tensors():
     x = torch.zeros(4, 1024, dtype=torch.bfloat16)
     with pytest.raises(ValueError):
         q.qvggt_rotate_smooth_quant(x, None, None, torch.zeros(4, 512, dtype=torch.uint8), torch.zeros(4))
+
+
+def test_nfds_argument_validation_needs_no_gpu():
+    lib = q.load_library()
+    dbl = C.c_double
+    assert q.qvggt_nfds_workspace_bytes(8, 1 << 20, 0) > 0
+    assert q.qvggt_nfds_workspace_bytes(8, 1001, 0) == 0            # a row must be whole 16-byte vectors
+    assert q.qvggt_nfds_workspace_bytes(8, 1 << 20, 5) == 0
+    need = q.qvggt_nfds_workspace_bytes(8, 1 << 20, 0)
+    assert lib.qvggt_nfds_moments(P, 0, 8, 1001, P, P, P, need, None) == SHAPE
+    assert lib.qvggt_nfds_moments(P, 7, 8, 1024, P, P, P, need, None) == DTYPE
+    assert lib.qvggt_nfds_moments(None, 0, 8, 1024, P, P, P, need, None) == NULL
+    assert lib.qvggt_nfds_moments(P + 4, 0, 8, 1024, P, P, P, need, None) == ALIGN
+    assert lib.qvggt_nfds_moments(P, 0, 8, 1 << 20, P, P, P, need - 1, None) == WORKSPACE
+    assert lib.qvggt_nfds_moments(None, 0, 0, 1024, None, None, None, 0, None) == OK
+    assert lib.qvggt_nfds_frame_correlation(P, 0, 2, 1, 1024, P, P, need, None) == SHAPE     # needs at least two frames
+    assert lib.qvggt_nfds_frame_correlation(P, 0, 2, 4, 1024, None, P, need, None) == NULL
+    assert lib.qvggt_nfds_frame_correlation(P, 0, 2, 4, 1 << 20, P, P, 16, None) == WORKSPACE
+    assert lib.qvggt_nfds_scores(P, P, 0, 4, dbl(1e-6), P, None) == SHAPE
+    assert lib.qvggt_nfds_scores(P, P, 10, 4000, dbl(1e-6), P, None) == SHAPE
+    assert lib.qvggt_nfds_scores(P, P, 10, 4, dbl(-1.0), P, None) == ARG
+    assert lib.qvggt_nfds_scores(P, None, 10, 4, dbl(0.0), P, None) == NULL
+    assert lib.qvggt_nfds_keep_lowest(P, 10, dbl(1.5), P, None) == ARG
+    assert lib.qvggt_nfds_keep_lowest(P, 0, dbl(0.5), P, None) == SHAPE
+    assert lib.qvggt_nfds_keep_lowest(P, 10, dbl(0.5), None, None) == NULL
+    assert lib.qvggt_nfds_kmeans_step(P, 10, 3, 0, P, P + 64, P, None) == SHAPE
+    assert lib.qvggt_nfds_kmeans_step(P, 10, 3, 2, P, P, P, None) == ARG                     # in-place centres
+    assert lib.qvggt_nfds_kmeans_step(P, 10, 3, 2, P, P + 64, None, None) == NULL
+    assert lib.qvggt_nfds_kmeans_step(P + 2, 10, 3, 2, P, P + 64, P, None) == ALIGN

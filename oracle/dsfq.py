@@ -86,6 +86,20 @@ def hadamard(K: int, form: str = "recursive") -> np.ndarray:
     return H
 
 
+def hadamard_paley(m: int) -> np.ndarray:
+    """Unnormalised m x m Hadamard matrix of Paley's construction, m in {12, 20, 28}."""
+    H = np.empty((m, m), dtype=np.int8)
+    _chk(_lib.orc_hadamard_paley(C.c_int(m), _ptr(H, _i8p)), "hadamard_paley")
+    return H
+
+
+def hadamard_general(K: int) -> np.ndarray:
+    """Unnormalised K x K matrix H_{2^n} (x) H_m for K = 2^n m, m in {1, 12, 20, 28} (Sec. 3.2)."""
+    H = np.empty((K, K), dtype=np.int8)
+    _chk(_lib.orc_hadamard_general(C.c_int(K), _ptr(H, _i8p)), "hadamard_general")
+    return H
+
+
 def rotate(X, pre_signs=None, post_signs=None) -> np.ndarray:
     """X . H with H = diag(pre) . Hhat . diag(post), Hhat the orthonormal Hadamard."""
     X = _f64(X)

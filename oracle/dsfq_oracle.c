@@ -76,6 +76,98 @@ int orc_hadamard_popcount(int K, int8_t *H)
     return ORC_OK;
 }
 
+/* ---------------------------------------------------------------- sizes that are not powers of two
+ * Sec. 3.2: for d = 2^n m the matrix is H_{2^n} (x) H_m.  The paper does not say which H_m; taken here (the usual
+ * choice for m = 12, 20, 28) are Paley's constructions from the quadratic character chi of GF(q):
+ *   type I  (q = 3 mod 4, m = q + 1: 12 from q = 11, 20 from q = 19):  H = I + S,
+ *           S = [[0, 1 .. 1], [-1 .., Q]],  Q[i][j] = chi(i - j)   (S is skew, S S^T = q I);
+ *   type II (q = 1 mod 4, m = 2 (q + 1): 28 from q = 13):  C = [[0, 1 .. 1], [1 .., Q]] (symmetric, C C^T = q I);
+ *           every 0 of C becomes [[1, -1], [-1, -1]], every +-1 becomes +-[[1, 1], [1, -1]].
+ * chi(x) = 0 for x = 0, 1 if x is a non-zero square mod q, -1 otherwise, by Euler's criterion x^((q-1)/2) mod q.
+ */
+static int chi_mod(int x, int q)
+{
+    x %= q;
+    if (x < 0) x += q;
+    if (x == 0) return 0;
+    long long r = 1, b = x;
+    for (int e = (q - 1) / 2; e > 0; e >>= 1) {
+        if (e & 1) r = r * b % q;
+        b = b * b % q;
+    }
+    return r == 1 ? 1 : -1;
+}
+
+int orc_hadamard_paley(int m, int8_t *H)
+{
+    if (!H) return ORC_ERR_ARG;
+    if (m == 12 || m == 20) {
+        const int q = m - 1;
+        for (int i = 0; i < m; ++i)
+            for (int j = 0; j < m; ++j) {
+                int s;
+                if (i == 0) s = (j == 0) ? 0 : 1;
+                else if (j == 0) s = -1;
+                else s = chi_mod((i - 1) - (j - 1), q);
+                H[i * m + j] = (int8_t)(s + (i == j ? 1 : 0));
+            }
+        return ORC_OK;
+    }
+    if (m == 28) {
+        const int q = 13, n = 14;
+        for (int i = 0; i < n; ++i)
+            for (int j = 0; j < n; ++j) {
+                int c;
+                if (i == 0 && j == 0) c = 0;
+                else if (i == 0 || j == 0) c = 1;
+                else c = chi_mod((i - 1) - (j - 1), q);
+                /* 2 x 2 block of entry (i, j) */
+                int b00, b01, b10, b11;
+                if (c == 0) { b00 = 1; b01 = -1; b10 = -1; b11 = -1; }
+                else { b00 = c; b01 = c; b10 = c; b11 = -c; }
+                H[(2 * i) * m + 2 * j] = (int8_t)b00;
+                H[(2 * i) * m + 2 * j + 1] = (int8_t)b01;
+                H[(2 * i + 1) * m + 2 * j] = (int8_t)b10;
+                H[(2 * i + 1) * m + 2 * j + 1] = (int8_t)b11;
+            }
+        return ORC_OK;
+    }
+    return ORC_ERR_ARG;
+}
+
+/* K = 2^n m with m in {1, 12, 20, 28}: returns m (0 if K has no such form); K is a power of two when m == 1 */
+static int paley_factor(int K)
+{
+    if (K < 1) return 0;
+    if (is_pow2(K)) return 1;
+    int odd = K;
+    while ((odd & 1) == 0) odd >>= 1;
+    if (odd != 3 && odd != 5 && odd != 7) return 0;
+    const int m = 4 * odd;
+    return (K % m == 0 && is_pow2(K / m)) ? m : 0;
+}
+
+/* Unnormalised K x K matrix H_{2^n} (x) H_m, index e = a m + b (a the 2^n part): H[e][e'] = H2n[a][a'] Hm[b][b']. */
+int orc_hadamard_general(int K, int8_t *H)
+{
+    const int m = paley_factor(K);
+    if (m == 0 || !H) return ORC_ERR_ARG;
+    if (m == 1) return orc_hadamard_recursive(K, H);
+    const int n2 = K / m;
+    int8_t *A = (int8_t *)malloc((size_t)n2 * n2), *B = (int8_t *)malloc((size_t)m * m);
+    if (!A || !B) { free(A); free(B); return ORC_ERR_ALLOC; }
+    orc_hadamard_recursive(n2, A);
+    orc_hadamard_paley(m, B);
+    for (int a = 0; a < n2; ++a)
+        for (int b = 0; b < m; ++b)
+            for (int a2 = 0; a2 < n2; ++a2)
+                for (int b2 = 0; b2 < m; ++b2)
+                    H[(size_t)(a * m + b) * K + (a2 * m + b2)] = (int8_t)(A[a * n2 + a2] * B[b * m + b2]);
+    free(A);
+    free(B);
+    return ORC_OK;
+}
+
 /* ---------------------------------------------------------------- rotation
  * Xr = X . H with the randomised orthonormal Hadamard.  Two sign conventions
  * are supported because the paper's text and the works it follows differ:
@@ -85,10 +177,10 @@ int orc_hadamard_popcount(int K, int8_t *H)
  */
 int orc_rotate(const double *X, int rows, int K, const int8_t *pre, const int8_t *post, double *Xr)
 {
-    if (!X || !Xr || rows < 0 || !is_pow2(K)) return ORC_ERR_ARG;
+    if (!X || !Xr || rows < 0 || paley_factor(K) == 0) return ORC_ERR_ARG;
     int8_t *H = (int8_t *)malloc((size_t)K * K);
     if (!H) return ORC_ERR_ALLOC;
-    orc_hadamard_recursive(K, H);
+    orc_hadamard_general(K, H);
     const double norm = sqrt((double)K);
 #pragma omp parallel for schedule(static)
     for (int t = 0; t < rows; ++t) {

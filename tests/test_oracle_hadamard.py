@@ -97,3 +97,78 @@ def test_norm_preserved_and_one_hot_dispersed():
     y = oracle.rotate(e)
     assert np.allclose(np.abs(y), 3.0 / np.sqrt(K), rtol=1e-14)       # an outlier spreads evenly
     assert np.array_equal(np.sign(y[0]).astype(np.int8), oracle.hadamard(K)[37])
+
+
+# ----------------------------------------------------------------- sizes 2^n m (Sec. 3.2: H_d = H_{2^n} (x) H_m)
+@pytest.mark.parametrize("m", [12, 20, 28])
+def test_paley_matrices_are_hadamard(m):
+    H = oracle.hadamard_paley(m).astype(np.int64)
+    assert set(np.unique(H)) == {-1, 1}
+    assert np.array_equal(H @ H.T, m * np.eye(m, dtype=np.int64))
+    assert np.array_equal(H.T @ H, m * np.eye(m, dtype=np.int64))
+    # any two distinct rows agree in exactly m / 2 places
+    for i in range(m):
+        for j in range(i + 1, m):
+            assert int((H[i] == H[j]).sum()) == m // 2
+
+
+def test_paley_type_one_structure_from_brute_force_squares():
+    """q = 11, 19: H - I is skew with the quadratic character of GF(q) in its core, the squares found by enumeration."""
+    for m in (12, 20):
+        q = m - 1
+        squares = {(k * k) % q for k in range(1, q)}
+        H = oracle.hadamard_paley(m).astype(int)
+        S = H - np.eye(m, dtype=int)
+        assert np.array_equal(S, -S.T)
+        assert S[0, 1:].tolist() == [1] * q and S[1:, 0].tolist() == [-1] * q
+        for i in range(q):
+            for j in range(q):
+                want = 0 if i == j else (1 if (i - j) % q in squares else -1)
+                assert S[1 + i, 1 + j] == want
+
+
+def test_paley_type_two_structure_from_brute_force_squares():
+    q = 13
+    squares = {(k * k) % q for k in range(1, q)}
+    H = oracle.hadamard_paley(28).astype(int)
+    assert np.array_equal(H, H.T)                               # q = 1 mod 4: symmetric
+    for i in range(14):
+        for j in range(14):
+            blk = H[2 * i:2 * i + 2, 2 * j:2 * j + 2]
+            if i == j:
+                assert blk.tolist() == [[1, -1], [-1, -1]]
+            else:
+                c = 1 if (i == 0 or j == 0 or ((i - 1) - (j - 1)) % q in squares) else -1
+                assert blk.tolist() == [[c, c], [c, -c]]
+
+
+@pytest.mark.parametrize("K", [768, 1280, 1792, 1536])
+def test_general_size_is_the_kronecker_product(K):
+    m = {3: 12, 5: 20, 7: 28}[K // (K & -K)]
+    n2 = K // m
+    H = oracle.hadamard_general(K)
+    assert np.array_equal(H, np.kron(oracle.hadamard(n2), oracle.hadamard_paley(m)))
+    Hl = H.astype(np.int64)
+    assert np.array_equal(Hl @ Hl.T, K * np.eye(K, dtype=np.int64))
+
+
+@pytest.mark.parametrize("K", [768, 2560])
+def test_rotation_general_size_is_orthonormal_and_dense(K):
+    rng = np.random.default_rng(K)
+    X = rng.standard_normal((6, K))
+    W = rng.standard_normal((5, K))
+    signs = (rng.integers(0, 2, K) * 2 - 1).astype(np.int8)
+    Xr, Wr = oracle.rotate(X, pre_signs=signs), oracle.rotate(W, pre_signs=signs)
+    assert np.allclose(Xr @ Wr.T, X @ W.T, rtol=0, atol=1e-10 * np.abs(X @ W.T).max())
+    assert np.allclose((Xr ** 2).sum(axis=1), (X ** 2).sum(axis=1), rtol=1e-12)
+    dense = (X * signs) @ oracle.hadamard_general(K).astype(np.float64) / np.sqrt(K)
+    assert np.allclose(Xr, dense, rtol=0, atol=1e-12 * np.abs(dense).max())
+    # one-hot input: the row of the matrix, all entries +-1 / sqrt(K)
+    e = np.zeros((1, K)); e[0, 5] = 1.0
+    assert np.allclose(np.abs(oracle.rotate(e)), 1.0 / np.sqrt(K), rtol=1e-14)
+
+
+def test_sizes_without_a_construction_are_refused():
+    for K in (1000, 1408, 2304, 96 * 11):
+        with pytest.raises(oracle.OracleError):
+            oracle.rotate(np.zeros((1, K)))

@@ -18,7 +18,9 @@
  *   - Every call only enqueues kernels on `stream` (a hipStream_t passed as void*; NULL is
  *     the default stream) and returns; buffers must stay valid until the stream has run.
  *   - Matrices are dense row-major.  bf16 values are IEEE bfloat16 bit patterns (uint16).
- *   - K (input features, the Hadamard size) must be a power of two in [128, 8192];
+ *   - K (input features, the Hadamard size) must be a power of two in [128, 8192], or one of the sizes
+ *     2^n * m with a Paley matrix as the m-point factor (Sec. 3.2, H_d = H_{2^n} (x) H_m): m = 12: 768, 1536, 3072, 6144;
+ *     m = 20: 1280, 2560, 5120; m = 28: 1792, 3584 (type I from GF(11), GF(19), type II from GF(13));
  *     N (output features) a multiple of 16; M (tokens) any value >= 0 (M == 0 is a no-op).
  *     All device pointers must be 16-byte aligned.  Inputs must be finite.
  *   - Return value: QVGGT_OK or an error code; arguments are validated on the host
@@ -43,7 +45,7 @@ extern "C" {
 typedef enum {
     QVGGT_OK = 0,
     QVGGT_ERR_NULL = 1,      /* a required pointer is NULL */
-    QVGGT_ERR_SHAPE = 2,     /* M < 0, N < 16 or not a multiple of 16, K not a power of two in [128, 8192] */
+    QVGGT_ERR_SHAPE = 2,     /* M < 0, N < 16 or not a multiple of 16, K not one of the supported sizes */
     QVGGT_ERR_ALIGN = 3,     /* a pointer is not 16-byte aligned */
     QVGGT_ERR_DTYPE = 4,     /* dtype is neither QVGGT_BF16 nor QVGGT_F32 */
     QVGGT_ERR_WORKSPACE = 5, /* workspace smaller than qvggt_workspace_bytes() */

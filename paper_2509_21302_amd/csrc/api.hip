@@ -15,6 +15,7 @@ hipError_t run_smooth_factor(float *buf, const float *act_absmax, int K, float a
 hipError_t run_fill_f32(float *p, int n, float v, hipStream_t stream);
 hipError_t run_pack_int4(const int8_t *codes, int rows, int K, uint8_t *packed, hipStream_t stream);
 hipError_t run_unpack_int4(const uint8_t *packed, int rows, int K, int8_t *codes, hipStream_t stream);
+bool general_size_supported(int K);
 hipError_t run_layout_int8(const int8_t *src, int rows, int K, int8_t *dst, int to_library, hipStream_t stream);
 hipError_t run_w4a4_gemm(const uint8_t *Xq, const float *sx, const uint8_t *Wq, const float *sw, const void *bias,
                          int M, int N, int K, void *Y, int32_t *acc_debug, hipStream_t stream);
@@ -33,7 +34,8 @@ hipError_t run_nfds_kmeans_step(const float *c, int n, int dim, int K, const flo
 
 namespace {
 
-bool valid_k(int K) { return K >= qvggt::kMinK && K <= qvggt::kMaxK && (K & (K - 1)) == 0; }
+// a power of two in [128, 8192], or one of the sizes 2^n * m (m = 12, 20, 28) the general rotation kernel is built for
+bool valid_k(int K) { return (K >= qvggt::kMinK && K <= qvggt::kMaxK && (K & (K - 1)) == 0) || qvggt::general_size_supported(K); }
 bool valid_n(int N) { return N >= 16 && (N % 16) == 0; }
 bool valid_dtype(int d) { return d == QVGGT_BF16 || d == QVGGT_F32; }
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }

@@ -275,6 +275,12 @@ __global__ void layout_int8_kernel(const int8_t *__restrict__ src, size_t rows, 
 // ---------------------------------------------------------------------------------------
 // host-side launchers (called from api.hip)
 
+// sizes 2^n * m (m = 12, 20, 28): rotate_quant_general.hip
+bool general_size_supported(int K);
+hipError_t run_rotate_rows_general(const void *X, bool f32, int rows, int K, const int8_t *signs, const float *mul, int mul_mode,
+                                   uint8_t *packed, float *scale, unsigned int *colmax, const float *step, int step_stride,
+                                   int bits, hipStream_t stream);
+
 template <int MODE, int CB>
 static hipError_t launch_rotate_rows(const void *X, bool f32, int rows, int K, const int8_t *signs,
                                      const float *mul, int mul_mode, uint8_t *packed, float *scale,
@@ -313,6 +319,8 @@ hipError_t run_rotate_smooth_quant(const void *X, bool f32, int rows, int K, con
                                    const float *mul, int mul_mode, uint8_t *packed, float *scale,
                                    const float *step, int step_stride, int bits, hipStream_t stream)
 {
+    if (general_size_supported(K))
+        return run_rotate_rows_general(X, f32, rows, K, signs, mul, mul_mode, packed, scale, nullptr, step, step_stride, bits, stream);
     const float qmax = (float)((1 << (bits - 1)) - 1);
     // bf16 rows of the sizes VGGT-1B uses go to the matrix-core kernel; everything else to the generic one
     if (!f32 && (K == 1024 || K == 2048 || K == 4096))
@@ -328,6 +336,9 @@ hipError_t run_rotated_col_absmax(const void *X, bool f32, int rows, int K, cons
     fill_u32_kernel<<<(K + 255) / 256, 256, 0, stream>>>(reinterpret_cast<unsigned int *>(absmax), K, 0u);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (general_size_supported(K))
+        return run_rotate_rows_general(X, f32, rows, K, signs, nullptr, 0, nullptr, nullptr, reinterpret_cast<unsigned int *>(absmax),
+                                       nullptr, 0, 4, stream);
     return launch_rotate_rows<kColAbsMax, 4>(X, f32, rows, K, signs, nullptr, 0, nullptr, nullptr,
                                              reinterpret_cast<unsigned int *>(absmax), nullptr, 0, 7.0f, stream);
 }

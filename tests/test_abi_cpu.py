@@ -41,6 +41,10 @@ def test_workspace_bytes():
     assert q.qvggt_workspace_bytes(0, 3072, 1024) > 0
     assert q.qvggt_workspace_bytes(10, 3072, 1000) == 0      # K not a power of two
     assert q.qvggt_workspace_bytes(10, 3070, 1024) == 0      # N not a multiple of 16
+    for K in (768, 1536, 3072, 6144, 1280, 2560, 5120, 1792, 3584):     # sizes 2^n * m with a Paley factor
+        assert q.qvggt_workspace_bytes(10, 32, K) > 0
+    for K in (1408, 2304, 7168, 384, 96):
+        assert q.qvggt_workspace_bytes(10, 32, K) == 0
     assert q.qvggt_workspace_bytes(-1, 3072, 1024) == 0
 
 

@@ -173,3 +173,51 @@ def test_run_to_run_bit_identity():
     signs = G.to_dev(synth.make_signs(s))
     a, b = G.gpu_rsq(X, signs, None), G.gpu_rsq(X, signs, None)
     assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+GENERAL_K = [768, 1536, 3072, 6144, 1280, 2560, 5120, 1792, 3584]       # 2^n * m, m = 12, 20, 28
+
+
+@pytest.mark.parametrize("K", GENERAL_K)
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_rotate_quant_sizes_with_a_paley_factor(K, dtype):
+    """H_K = H_{2^n} (x) H_m (Sec. 3.2): codes and scales against the oracle's dense product with the same matrix."""
+    rows = 41
+    X = _heavy(rows, K, 700 + K, dtype)
+    rng = np.random.default_rng(K)
+    signs = (rng.integers(0, 2, K) * 2 - 1).astype(np.int8)
+    c_hat = np.exp(rng.uniform(-1, 1, K))
+    inv = (1.0 / (np.sqrt(K) * c_hat)).astype(np.float32)
+    for bits in (4, 8):
+        dx, qx, _ = oracle.rotate_smooth_quant(X, 1.0 / (inv.astype(np.float64) * np.sqrt(K)), pre_signs=signs, bits=bits)
+        if bits == 4:
+            Xq, sx = G.gpu_rsq(G.to_dev(X), G.to_dev(signs), G.to_dev(inv))
+            codes = G.gpu_unpack(Xq, K)
+        else:
+            Xq, sx = G.gpu_rsq_i8(G.to_dev(X), G.to_dev(signs), G.to_dev(inv), bits)
+            codes = G.gpu_layout_int8(Xq, 0).cpu().numpy()
+        G.check_codes(codes, qx, f"K={K} bits={bits}")
+        G.check_scales(sx.cpu().numpy(), dx, f"K={K} bits={bits}")
+
+
+@pytest.mark.parametrize("K,N", [(768, 256), (2560, 144), (3584, 512)])
+def test_linear_end_to_end_with_a_paley_factor(K, N):
+    """Whole path (statistic, weight preparation, rotate-quantize, integer GEMM, epilogue) on a size 2^n * m."""
+    rng = np.random.default_rng(K + N)
+    M = 300
+    X = _heavy(M, K, K)
+    Xc = _heavy(64, K, K + 1)
+    W = (rng.standard_normal((N, K)) * 0.03).astype(np.float32)
+    bias = synth.f32_to_bf16_bits((rng.standard_normal(N) * 0.02).astype(np.float32))
+    signs = (rng.integers(0, 2, K) * 2 - 1).astype(np.int8)
+    a = oracle.rotated_col_absmax(Xc, pre_signs=signs)
+    po = oracle.prepare_weights(W, a, pre_signs=signs, alpha=0.5)
+    want = oracle.linear(X, po, bias=bias, pre_signs=signs)
+    pg = G.gpu_prep(W, Xc, signs, 0.5)
+    G.check_scales(pg["a"].cpu().numpy(), a)
+    G.check_codes(G.gpu_unpack(pg["Wq"], K), po.qw, f"weights K={K}")
+    Y = G.bf16_bits(G.gpu_linear(G.to_dev(X), pg, G.to_dev(bias)))
+    err = G.rel_fro(Y, want.Y)
+    assert err <= G.Y_REL_FRO, err
+    exact = oracle.to_f64(X) @ W.astype(np.float64).T + oracle.to_f64(bias)
+    assert np.linalg.norm(oracle.bf16_bits_to_f64(Y) - exact) / np.linalg.norm(exact) < 0.35

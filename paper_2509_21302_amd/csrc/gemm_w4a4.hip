@@ -433,12 +433,20 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
                     // the staging tile is private to the wave and LDS operations of a wave execute in order: no barrier instruction is
                     // needed, only the compiler has to be told that other lanes' writes are read next
                     lanes_exchange_fence();
+                    // all four row groups are read before the first store: one LDS round trip per piece instead of four.  A piece
+                    // that lies fully inside Y (the usual case, a wave-uniform test) stores without per-lane predicates.
+                    v4i rowv[4];
 #pragma unroll
-                    for (int it = 0; it < 4; ++it) {
-                        const v4i v = *reinterpret_cast<const v4i *>(ep + (it * 8 + rd_row) * C::EP_PITCH + rd_col * 16);
-                        if (col_ok && rd_row < rows_left - (i * 32 + it * 8)) __builtin_nontemporal_store(v, reinterpret_cast<v4i *>(yp));
-                        yp += (size_t)8 * N;
+                    for (int it = 0; it < 4; ++it) rowv[it] = *reinterpret_cast<const v4i *>(ep + (it * 8 + rd_row) * C::EP_PITCH + rd_col * 16);
+                    if (rows_left - i * 32 >= 32 && cols_left - jp * 64 >= 64) {
+#pragma unroll
+                        for (int it = 0; it < 4; ++it) __builtin_nontemporal_store(rowv[it], reinterpret_cast<v4i *>(yp + (size_t)it * 8 * N));
+                    } else {
+#pragma unroll
+                        for (int it = 0; it < 4; ++it)
+                            if (col_ok && rd_row < rows_left - (i * 32 + it * 8)) __builtin_nontemporal_store(rowv[it], reinterpret_cast<v4i *>(yp + (size_t)it * 8 * N));
                     }
+                    yp += (size_t)32 * N;
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }

@@ -32,6 +32,8 @@ def main():
     ap.add_argument("--config", type=int, default=5, choices=[2, 3, 4, 5])
     ap.add_argument("--bits", type=int, default=4, choices=[4, 6, 8], help="quantization setting timed as the headline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="skip the side measurements (8-bit setting, calibration reductions): what the profiles under profiles/ are taken with")
     ap.add_argument("--cpu-rows", type=int, default=16384, help="rows per layer the oracle is timed on")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain 1 GiB device copies (reference dispatches for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
@@ -77,7 +79,7 @@ def main():
                  sx=torch.empty(s.M, dtype=torch.float32, device=dev), prep={})
         L["Xq4"] = L["Xq"].view(-1)[: s.M * s.K // 2].view(s.M, s.K // 2)
         L["Xq8"] = L["Xq"].view(torch.int8)
-        for bits in sorted({args.bits, 4, 8}):
+        for bits in sorted({args.bits} if args.headline_only else {args.bits, 4, 8}):
             sw = torch.empty(s.N, dtype=torch.float32, device=dev)
             inv = torch.empty(s.K, dtype=torch.float32, device=dev)
             if bits == 4:
@@ -162,7 +164,7 @@ def main():
 
     # side measurement: the 8-bit setting on the same layers (whole path, then per kernel), outside the headline's timed region
     side = None
-    if args.bits == 4:
+    if args.bits == 4 and not args.headline_only:
         n = max(3, args.steps // 4)
         for _ in range(2):
             step(8)
@@ -196,7 +198,7 @@ def main():
     # side measurement: the two HBM-bound reductions of the calibration-set arithmetic (Sec. 3.3) on the first layer's input,
     # taken as one sample of `frames` frames: per-frame mean / variance, and the cosine of every frame with frame 0
     nfds = None
-    if args.bits == 4:
+    if args.bits == 4 and not args.headline_only:
         L0 = layers[0]
         s0_ = L0["spec"]
         fe = s0_.rows_per_frame * s0_.K

@@ -59,6 +59,35 @@ __device__ inline void lanes_exchange_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Maximum over groups of lanes without going through LDS: four DPP steps inside a row of 16 lanes (quad permutes, then
+// mirrors: after each step every lane of the group holds the group's maximum), then the gfx950 row swaps across rows.
+template <int CTRL>
+__device__ inline float dpp_max_step(float v)
+{
+    const int p = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false);
+    return fmaxf(v, __int_as_float(p));
+}
+__device__ inline float max_over_16_lanes(float v)
+{
+    v = dpp_max_step<0xB1>(v);     // quad_perm [1, 0, 3, 2]
+    v = dpp_max_step<0x4E>(v);     // quad_perm [2, 3, 0, 1]
+    v = dpp_max_step<0x141>(v);    // row_half_mirror
+    v = dpp_max_step<0x140>(v);    // row_mirror
+    return v;
+}
+__device__ inline float max_over_32_lanes(float v)   // lanes 0..31 and lanes 32..63 separately
+{
+    v = max_over_16_lanes(v);
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ inline float max_over_64_lanes(float v)
+{
+    v = max_over_32_lanes(v);
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 __device__ inline float wave_max(float v)
 {
 #pragma unroll

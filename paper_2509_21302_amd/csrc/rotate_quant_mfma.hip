@@ -253,8 +253,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
         if constexpr (!STATIC) {
 #pragma unroll
             for (int t = 0; t < C::TOK_PER_LANE; ++t) {
-#pragma unroll
-                for (int m = 1; m < (REM == 5 ? 64 : 32); m <<= 1) amax[t] = fmaxf(amax[t], __shfl_xor(amax[t], m));
+                amax[t] = (REM == 5) ? max_over_64_lanes(amax[t]) : max_over_32_lanes(amax[t]);
             }
         }
 

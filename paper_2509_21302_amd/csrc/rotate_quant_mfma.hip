@@ -85,7 +85,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
     constexpr int REM = C::REM, TOK = C::TOK;
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[rq::WAVES_PER_BLOCK * rq::LDS_PER_WAVE];
 
-    const int lane = threadIdx.x & 63, wave_in_block = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int c = lane & 31, g = lane >> 5;
     uint8_t *lds = lds_all + wave_in_block * rq::LDS_PER_WAVE;
     const int wave = blockIdx.x * rq::WAVES_PER_BLOCK + wave_in_block;
@@ -160,14 +160,23 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
         const v4u v = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(p));
         return make_uint4(v[0], v[1], v[2], v[3]);
     };
+    // a tile is 4096 consecutive values; when all its rows exist (a wave-uniform test, false at most for the last tile) the
+    // eight loads differ by constants only
+    auto load_tile = [&](int t, uint4 (&dst)[8]) {
+        if ((t + 1) * TOK <= rows) {
+            const uint4 *p = reinterpret_cast<const uint4 *>(X + (size_t)t * 4096) + lane;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) dst[j] = load16(p + 64 * j);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) dst[j] = load16(tile_ptr(t, j));
+        }
+    };
     uint4 G[PF][8];
     int tile = wave;
 #pragma unroll
     for (int p = 0; p < PF; ++p)
-        if (tile + p * nwaves < ntiles) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) G[p][j] = load16(tile_ptr(tile + p * nwaves, j));
-        }
+        if (tile + p * nwaves < ntiles) load_tile(tile + p * nwaves, G[p]);
     const int wr_base = ((lane >> 4) * rq::LDS_PITCH) + (lane & 15) * 16;
     const int rd_base = c * rq::LDS_PITCH + g * 16;
 
@@ -189,10 +198,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
 #pragma unroll
             for (int j = 0; j < 8; ++j) G[p][j] = G[p + 1][j];
         const int next = tile + PF * nwaves;
-        if (next < ntiles) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) G[PF - 1][j] = load16(tile_ptr(next, j));
-        }
+        if (next < ntiles) load_tile(next, G[PF - 1]);
 
         // R . H_128 on the matrix cores
         v16f acc[4];
@@ -268,9 +274,10 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
                 delta = step[(size_t)min(row, rows - 1) * step_stride];
                 inv = delta > 0.0f ? 1.0f / delta : 0.0f;
             } else {
+                // hardware reciprocal (1 ulp) instead of two IEEE divisions: |z| * inv <= qmax (1 + 2^-22) still rounds to qmax
                 const float qmax = (CB == 4) ? 7.0f : qmax8;
                 delta = amax[t] / qmax;
-                inv = amax[t] > 0.0f ? qmax / amax[t] : 0.0f;
+                inv = amax[t] > 0.0f ? qmax * __builtin_amdgcn_rcpf(amax[t]) : 0.0f;
             }
             if constexpr (CB == 8) {
                 // four codes per word: byte i of word d is local index 4*d + i = nt + 4*h  ->  nt = i, h = d

@@ -94,19 +94,27 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
 
     // ---- per-lane constants -------------------------------------------------------------------
     // sign masks for the packed bf16 pairs this lane loads: load j covers flat elements 512*j + 8*lane .. +8
+    // (the eight sign bytes of a load are fetched with one 8-byte load, all loads issued before the first use)
     uint32_t sgn[C::SIGN_CLASSES][4];
 #pragma unroll
     for (int q = 0; q < C::SIGN_CLASSES; ++q)
 #pragma unroll
-        for (int d = 0; d < 4; ++d) {
-            uint32_t msk = 0;
-            if (signs != nullptr) {
-                const int e = 512 * q + 8 * lane + 2 * d;
-                if (signs[e] < 0) msk |= 0x00008000u;
-                if (signs[e + 1] < 0) msk |= 0x80000000u;
+        for (int d = 0; d < 4; ++d) sgn[q][d] = 0;
+    if (signs != nullptr) {
+        uint2 sb[C::SIGN_CLASSES];
+#pragma unroll
+        for (int q = 0; q < C::SIGN_CLASSES; ++q) sb[q] = *reinterpret_cast<const uint2 *>(signs + 512 * q + 8 * lane);
+#pragma unroll
+        for (int q = 0; q < C::SIGN_CLASSES; ++q) {
+            // bit 7 of a sign byte (set for -1) moves to the sign bit of its bf16: even byte -> bit 15, odd byte -> bit 31
+            const uint32_t w[2] = {sb[q].x, sb[q].y};
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const uint32_t two = w[d >> 1] >> (16 * (d & 1));
+                sgn[q][d] = ((two & 0x80u) << 8) | ((two & 0x8000u) << 16);
             }
-            sgn[q][d] = msk;
         }
+    }
     // B operand: lane (n = c, k-half = g) holds H_128[k][n] for k = 16*ks + 8*g + i.  sign = parity(k & n):
     //   bits 0..3 of k (8*g + i) against c & 15 -> base pattern; bit 4 (ks & 1) against c bit 4; bits 5, 6 (ks >> 1) against nt.
     v8bf Bsel[2][2];
@@ -134,17 +142,28 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
     float cm[C::HB_PER_LANE][4];
     {
         const float rs = 1.0f / sqrtf((float)K);
+        if (mul != nullptr) {
+            // all loads first, then the arithmetic: the loads are in flight together
 #pragma unroll
-        for (int h = 0; h < C::HB_PER_LANE; ++h)
+            for (int h = 0; h < C::HB_PER_LANE; ++h)
 #pragma unroll
-            for (int nt = 0; nt < 4; ++nt) {
-                int hb = h;
-                if (REM == 5) hb = (h & 7) | (g << 3) | ((h >> 3) << 4);
-                const int e = 128 * hb + 32 * nt + c;
-                float m = rs;
-                if (mul != nullptr) m = mul_mode ? 1.0f / ((float)K * mul[e]) : mul[e];
-                cm[h][nt] = m;
+                for (int nt = 0; nt < 4; ++nt) {
+                    int hb = h;
+                    if (REM == 5) hb = (h & 7) | (g << 3) | ((h >> 3) << 4);
+                    cm[h][nt] = mul[128 * hb + 32 * nt + c];
+                }
+            if (mul_mode) {
+#pragma unroll
+                for (int h = 0; h < C::HB_PER_LANE; ++h)
+#pragma unroll
+                    for (int nt = 0; nt < 4; ++nt) cm[h][nt] = 1.0f / ((float)K * cm[h][nt]);
             }
+        } else {
+#pragma unroll
+            for (int h = 0; h < C::HB_PER_LANE; ++h)
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt) cm[h][nt] = rs;
+        }
     }
 
     // ---- tile loop ------------------------------------------------------------------------------

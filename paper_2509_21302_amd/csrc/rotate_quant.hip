@@ -117,16 +117,30 @@ __global__ __launch_bounds__(256) void rotate_rows_kernel(const void *__restrict
     for (int w = 0; w < (R + 31) / 32; ++w) neg[w] = 0;
     float cm[R];
     const float rs = 1.0f / sqrtf((float)K);
+    // loads first (all in flight together), arithmetic afterwards: the set-up is one memory round trip, not one per element
+    if (signs != nullptr) {
+        int8_t sb[R];
 #pragma unroll
-    for (int c = 0; c < C; ++c)
+        for (int c = 0; c < C; ++c)
 #pragma unroll
-        for (int i = 0; i < V; ++i) {
-            const int e = c * 64 * V + lane * V + i, r = c * V + i;
-            if (signs != nullptr && signs[e] < 0) neg[r >> 5] |= 1u << (r & 31);
-            float m = rs;
-            if (mul != nullptr) m = mul_mode ? 1.0f / ((float)K * mul[e]) : mul[e];
-            cm[r] = m;
+            for (int i = 0; i < V; ++i) sb[c * V + i] = signs[c * 64 * V + lane * V + i];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if (sb[r] < 0) neg[r >> 5] |= 1u << (r & 31);
+    }
+    if (mul != nullptr) {
+#pragma unroll
+        for (int c = 0; c < C; ++c)
+#pragma unroll
+            for (int i = 0; i < V; ++i) cm[c * V + i] = mul[c * 64 * V + lane * V + i];
+        if (mul_mode) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) cm[r] = 1.0f / ((float)K * cm[r]);
         }
+    } else {
+#pragma unroll
+        for (int r = 0; r < R; ++r) cm[r] = rs;
+    }
 
     for (int row = wave; row < rows; row += nwaves) {
         float x[R];

@@ -82,13 +82,25 @@ __global__ __launch_bounds__(256) void rotate_rows_general_kernel(const void *__
 #pragma unroll
     for (int w = 0; w < (R + 31) / 32; ++w) neg[w] = 0;
     const float rs = 1.0f / sqrtf((float)K);
+    // loads first (all in flight together), arithmetic afterwards
+    if (signs != nullptr) {
+        int8_t sb[R];
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int e = (lane + 64 * (r / MM)) * MM + (r % MM);
-        if (signs != nullptr && signs[e] < 0) neg[r >> 5] |= 1u << (r & 31);
-        float m = rs;
-        if (mul != nullptr) m = mul_mode ? 1.0f / ((float)K * mul[e]) : mul[e];
-        cm[r] = m;
+        for (int r = 0; r < R; ++r) sb[r] = signs[(lane + 64 * (r / MM)) * MM + (r % MM)];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if (sb[r] < 0) neg[r >> 5] |= 1u << (r & 31);
+    }
+    if (mul != nullptr) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) cm[r] = mul[(lane + 64 * (r / MM)) * MM + (r % MM)];
+        if (mul_mode) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) cm[r] = 1.0f / ((float)K * cm[r]);
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < R; ++r) cm[r] = rs;
     }
 
     for (int row = wave; row < rows; row += nwaves) {

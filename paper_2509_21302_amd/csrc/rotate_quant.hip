@@ -142,6 +142,9 @@ __global__ __launch_bounds__(256) void rotate_rows_kernel(const void *__restrict
         for (int r = 0; r < R; ++r) cm[r] = rs;
     }
 
+    float colmax[MODE == kColAbsMax ? R : 1];
+#pragma unroll
+    for (int r = 0; r < (MODE == kColAbsMax ? R : 1); ++r) colmax[r] = 0.0f;
     for (int row = wave; row < rows; row += nwaves) {
         float x[R];
         load_row<K, F32>(X, (size_t)row, lane, x);
@@ -154,12 +157,9 @@ __global__ __launch_bounds__(256) void rotate_rows_kernel(const void *__restrict
         for (int r = 0; r < R; ++r) { x[r] *= cm[r]; amax = fmaxf(amax, fabsf(x[r])); }
 
         if constexpr (MODE == kColAbsMax) {
-            // non-negative floats order like their bit patterns
+            // the wave keeps a running maximum over its rows; one atomic per column after the loop
 #pragma unroll
-            for (int c = 0; c < C; ++c)
-#pragma unroll
-                for (int i = 0; i < V; ++i)
-                    atomicMax(&col_absmax_bits[c * 64 * V + lane * V + i], __float_as_uint(fabsf(x[c * V + i])));
+            for (int r = 0; r < R; ++r) colmax[r] = fmaxf(colmax[r], fabsf(x[r]));
         } else {
             // dynamic: the step comes from the row's absmax; static: it is given (per token or one for the tensor)
             float inv, delta;
@@ -222,6 +222,16 @@ __global__ __launch_bounds__(256) void rotate_rows_kernel(const void *__restrict
                 else out[byte0] = (uint8_t)word;
             }
             }
+        }
+    }
+    if constexpr (MODE == kColAbsMax) {
+        if (wave < rows) {
+            // non-negative floats order like their bit patterns
+#pragma unroll
+            for (int c = 0; c < C; ++c)
+#pragma unroll
+                for (int i = 0; i < V; ++i)
+                    atomicMax(&col_absmax_bits[c * 64 * V + lane * V + i], __float_as_uint(colmax[c * V + i]));
         }
     }
 }
@@ -303,8 +313,12 @@ static hipError_t launch_rotate_rows(const void *X, bool f32, int rows, int K, c
     if (rows <= 0) return hipSuccess;
     const int waves_per_block = 4;
     int blocks = (rows + waves_per_block - 1) / waves_per_block;
-    const int max_blocks = 256 * 8;
+    // up to eight blocks per compute unit; the column statistic takes fewer waves for small inputs so that each folds several
+    // rows into its running maximum before touching the shared result
+    const int max_blocks = (MODE == kColAbsMax) ? 256 * 2 : 256 * 8;
+    if (MODE == kColAbsMax) blocks = (rows + 31) / 32;     // eight rows or more per wave: the atomics at the end are what costs
     if (blocks > max_blocks) blocks = max_blocks;
+    if (blocks < 1) blocks = 1;
 #define QVGGT_LAUNCH(KK)                                                                                     \
     case KK:                                                                                                 \
         if (f32) rotate_rows_kernel<KK, true, MODE, CB><<<blocks, 256, 0, stream>>>(X, rows, signs, mul, mul_mode, packed, scale, colmax, step, step_stride, qmax); \

@@ -8,6 +8,7 @@
 // kernels and VGGT-1B itself has no layer that needs it.
 #include "qvggt_common.h"
 
+#include <algorithm>
 #include <type_traits>
 #include <utility>
 
@@ -103,6 +104,9 @@ __global__ __launch_bounds__(256) void rotate_rows_general_kernel(const void *__
         for (int r = 0; r < R; ++r) cm[r] = rs;
     }
 
+    float colmax[MODE == gen::kColAbsMax ? R : 1];
+#pragma unroll
+    for (int r = 0; r < (MODE == gen::kColAbsMax ? R : 1); ++r) colmax[r] = 0.0f;
     for (int row = wave; row < rows; row += nwaves) {
         float x[R];
         // a lane's MM values of one a are contiguous: 8-byte (bf16) or 16-byte (f32) pieces of four values
@@ -170,10 +174,9 @@ __global__ __launch_bounds__(256) void rotate_rows_general_kernel(const void *__
         for (int r = 0; r < R; ++r) { x[r] *= cm[r]; amax = fmaxf(amax, fabsf(x[r])); }
 
         if constexpr (MODE == gen::kColAbsMax) {
-            // non-negative floats order like their bit patterns
+            // the wave keeps a running maximum over its rows; one atomic per column after the loop
 #pragma unroll
-            for (int r = 0; r < R; ++r)
-                atomicMax(&col_absmax_bits[(lane + 64 * (r / MM)) * MM + (r % MM)], __float_as_uint(fabsf(x[r])));
+            for (int r = 0; r < R; ++r) colmax[r] = fmaxf(colmax[r], fabsf(x[r]));
         } else {
             float inv, delta;
             if (step != nullptr) {
@@ -204,7 +207,16 @@ __global__ __launch_bounds__(256) void rotate_rows_general_kernel(const void *__
                 }
         }
     }
+    if constexpr (MODE == gen::kColAbsMax) {
+        if (wave < rows) {
+            // non-negative floats order like their bit patterns
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                atomicMax(&col_absmax_bits[(lane + 64 * (r / MM)) * MM + (r % MM)], __float_as_uint(colmax[r]));
+        }
+    }
 }
+
 
 // K = N2 * MM for the sizes this file instantiates
 bool general_size_supported(int K)
@@ -223,6 +235,7 @@ static hipError_t launch_general(const void *X, bool f32, int rows, const int8_t
     if (rows <= 0) return hipSuccess;
     int blocks = (rows + 3) / 4;
     if (blocks > 256 * 8) blocks = 256 * 8;
+    if (colmax != nullptr) blocks = std::max(1, std::min((rows + 31) / 32, 256 * 2));   // eight rows or more per wave for the statistic
     const float qmax = (float)((1 << (bits - 1)) - 1);
 #define QVGGT_GEN(F32_, MODE_, CB_) \
     rotate_rows_general_kernel<N2, MM, F32_, MODE_, CB_><<<blocks, 256, 0, stream>>>(X, rows, signs, mul, mul_mode, packed, scale, colmax, step, step_stride, qmax)

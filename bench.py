@@ -219,12 +219,24 @@ def main():
             q.qvggt_nfds_frame_correlation(Xf.view(1, s0_.frames, fe), corr, ws)
         e[2].record()
         torch.cuda.synchronize()
+        # the smoothing statistic at scale: max_t |X H|[t, j] over all tokens of the same tensor (Sec. 3.2, numerator of the factor)
+        astat = torch.empty(s0_.K, dtype=torch.float32, device=dev)
+        e2 = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        q.qvggt_rotated_col_absmax(L0["X"], L0["signs"], astat)
+        e2[0].record()
+        for it in range(reps):
+            q.qvggt_rotated_col_absmax(L0["X"], L0["signs"], astat)
+        e2[1].record()
+        torch.cuda.synchronize()
         nbytes = Xf.numel() * Xf.element_size()
+        t_a = e2[0].elapsed_time(e2[1]) / reps
         t_m, t_c = e[0].elapsed_time(e[1]) / reps, e[1].elapsed_time(e[2]) / reps
         nfds = dict(tensor=f"{s0_.frames} frames x {s0_.rows_per_frame} tokens x {s0_.K} ({Xf.dtype})".replace("torch.", ""),
                     moments_ms=t_m, moments_GBps=nbytes / t_m / 1e6, moments_frac_hbm_peak=nbytes / t_m / 1e6 / HBM_PEAK_GBS,
                     frame_correlation_ms=t_c, frame_correlation_GBps=nbytes / t_c / 1e6,
-                    frame_correlation_frac_hbm_peak=nbytes / t_c / 1e6 / HBM_PEAK_GBS)
+                    frame_correlation_frac_hbm_peak=nbytes / t_c / 1e6 / HBM_PEAK_GBS,
+                    rotated_col_absmax_ms=t_a, rotated_col_absmax_GBps=nbytes / t_a / 1e6,
+                    rotated_col_absmax_frac_hbm_peak=nbytes / t_a / 1e6 / HBM_PEAK_GBS)
         del ws
 
     if args.calibrate_copy:
@@ -273,7 +285,7 @@ def main():
     if side is not None:
         out["w8a8"] = side
     if nfds is not None:
-        out["nfds_reductions"] = nfds
+        out["calibration_reductions"] = nfds
     print(json.dumps(out))
 
 

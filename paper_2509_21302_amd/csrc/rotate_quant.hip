@@ -341,6 +341,8 @@ static hipError_t launch_rotate_rows(const void *X, bool f32, int rows, int K, c
 hipError_t run_rotate_quant_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, int mul_mode,
                                  uint8_t *packed, float *scale, const float *step, int step_stride, int bits,
                                  hipStream_t stream);
+hipError_t run_rotated_col_absmax_mfma(const void *X, int rows, int K, const int8_t *signs, unsigned int *absmax_bits,
+                                       hipStream_t stream);
 
 // bits: 4 (packed nibbles) or 5..8 (int8 codes in [-2^(bits-1), 2^(bits-1) - 1])
 hipError_t run_rotate_smooth_quant(const void *X, bool f32, int rows, int K, const int8_t *signs,
@@ -364,6 +366,8 @@ hipError_t run_rotated_col_absmax(const void *X, bool f32, int rows, int K, cons
     fill_u32_kernel<<<(K + 255) / 256, 256, 0, stream>>>(reinterpret_cast<unsigned int *>(absmax), K, 0u);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (!f32 && (K == 1024 || K == 2048 || K == 4096))
+        return run_rotated_col_absmax_mfma(X, rows, K, signs, reinterpret_cast<unsigned int *>(absmax), stream);
     if (general_size_supported(K))
         return run_rotate_rows_general(X, f32, rows, K, signs, nullptr, 0, nullptr, nullptr, reinterpret_cast<unsigned int *>(absmax),
                                        nullptr, 0, 4, stream);

@@ -71,7 +71,9 @@ __host__ __device__ constexpr int row_of_seg_hi(int seg_hi /* seg >> 2 */)
 }
 }  // namespace rq
 
-// CB: bits a stored code occupies: 4 (packed nibbles, codes in [-8, 7]) or 8 (int8, codes in [-qmax - 1, qmax])
+// CB: bits a stored code occupies: 4 (packed nibbles, codes in [-8, 7]) or 8 (int8, codes in [-qmax - 1, qmax]);
+// CB = 0 is the statistic mode: nothing is quantized or stored, the kernel leaves max_t |X H / sqrt(K)|[t, j] per column j
+// in col_absmax_bits (the numerator of the smoothing factor, Sec. 3.2), which must be zero on entry
 template <int K, int PF, int OCC, bool STATIC, int CB>
 __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint16_t *__restrict__ X, int rows,
                                                                    const int8_t *__restrict__ signs,
@@ -79,8 +81,9 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
                                                                    uint8_t *__restrict__ packed,
                                                                    float *__restrict__ scale,
                                                                    const float *__restrict__ step, int step_stride,
-                                                                   float qmax8)
+                                                                   float qmax8, unsigned int *__restrict__ col_absmax_bits)
 {
+    constexpr bool STAT = (CB == 0);
     using C = rq::Cfg<K>;
     constexpr int REM = C::REM, TOK = C::TOK;
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[rq::WAVES_PER_BLOCK * rq::LDS_PER_WAVE];
@@ -199,6 +202,12 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
     const int wr_base = ((lane >> 4) * rq::LDS_PITCH) + (lane & 15) * 16;
     const int rd_base = c * rq::LDS_PITCH + g * 16;
 
+    float cmax[STAT ? C::HB_PER_LANE : 1][4];     // statistic mode: running |.| maximum of the lane's columns over its tiles
+#pragma unroll
+    for (int h = 0; h < (STAT ? C::HB_PER_LANE : 1); ++h)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) cmax[h][nt] = 0.0f;
+
     for (; tile < ntiles; tile += nwaves) {
         // stage the tile: flip signs on the packed bf16, write each 16-byte chunk to its MFMA row
 #pragma unroll
@@ -263,6 +272,14 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
             }
         }
 
+        if constexpr (STAT) {
+            // rows past the end repeat the last row (see tile_ptr), which leaves a maximum unchanged
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) cmax[r % C::HB_PER_LANE][nt] = fmaxf(cmax[r % C::HB_PER_LANE][nt], fabsf(acc[nt][r]));
+            continue;
+        }
         // scale, absmax per token (STATIC: the quantization step is given, no absmax)
         float amax[C::TOK_PER_LANE];
 #pragma unroll
@@ -352,6 +369,26 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
             }
         }
     }
+    if constexpr (STAT) {
+        // the block's waves fold their maxima in LDS (non-negative floats order like their bit patterns), then every column
+        // costs one global atomic per block
+        unsigned int *blk = reinterpret_cast<unsigned int *>(lds_all);
+        static_assert(sizeof(lds_all) >= K * sizeof(unsigned int), "the staging area holds one value per column");
+        __syncthreads();
+        for (int j = threadIdx.x; j < K; j += 256) blk[j] = 0u;
+        __syncthreads();
+        const float rs = 1.0f / sqrtf((float)K);
+#pragma unroll
+        for (int h = 0; h < C::HB_PER_LANE; ++h)
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) {
+                int hb = h;
+                if (REM == 5) hb = (h & 7) | (g << 3) | ((h >> 3) << 4);
+                atomicMax(&blk[128 * hb + 32 * nt + c], __float_as_uint(cmax[h][nt] * rs));
+            }
+        __syncthreads();
+        for (int j = threadIdx.x; j < K; j += 256) atomicMax(&col_absmax_bits[j], blk[j]);
+    }
 }
 
 hipError_t run_rotate_quant_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, int mul_mode,
@@ -371,7 +408,7 @@ hipError_t run_rotate_quant_mfma(const void *X, int rows, int K, const int8_t *s
 #endif
     if (blocks > max_blocks) blocks = max_blocks;
     const float qmax8 = (float)((1 << (bits - 1)) - 1);
-#define RQ1(KK, PF, OCC, ST, CB) rotate_quant_mfma_kernel<KK, PF, OCC, ST, CB><<<blocks, 256, 0, stream>>>(x, rows, signs, mul, mul_mode, packed, scale, step, step_stride, qmax8)
+#define RQ1(KK, PF, OCC, ST, CB) rotate_quant_mfma_kernel<KK, PF, OCC, ST, CB><<<blocks, 256, 0, stream>>>(x, rows, signs, mul, mul_mode, packed, scale, step, step_stride, qmax8, nullptr)
 #define RQ(KK, PF, OCC)                                      \
     do {                                                     \
         if (bits == 4) {                                     \
@@ -388,6 +425,29 @@ hipError_t run_rotate_quant_mfma(const void *X, int rows, int K, const int8_t *s
         case 4096: RQ(4096, 1, 2); break;
         default: return hipErrorInvalidValue;
     }
+    return hipGetLastError();
+}
+
+// Column statistic max_t |X H|[t, j] of bf16 rows, K = 1024 / 2048 / 4096, with the same kernel in statistic mode.
+// absmax_bits (K values) must be zero on entry.
+hipError_t run_rotated_col_absmax_mfma(const void *X, int rows, int K, const int8_t *signs, unsigned int *absmax_bits,
+                                       hipStream_t stream)
+{
+    if (rows <= 0) return hipSuccess;
+    const uint16_t *x = reinterpret_cast<const uint16_t *>(X);
+    const int tok = 32 / (K / 128);
+    const int ntiles = (rows + tok - 1) / tok;
+    // sixteen tiles or more per wave where there are that many: every wave ends with atomics on all K columns
+    int blocks = (ntiles + 16 * rq::WAVES_PER_BLOCK - 1) / (16 * rq::WAVES_PER_BLOCK);
+    if (blocks > 256 * 2) blocks = 256 * 2;
+#define RQS(KK) rotate_quant_mfma_kernel<KK, 1, 2, false, 0><<<blocks, 256, 0, stream>>>(x, rows, signs, nullptr, 0, nullptr, nullptr, nullptr, 0, 0.0f, absmax_bits)
+    switch (K) {
+        case 1024: RQS(1024); break;
+        case 2048: RQS(2048); break;
+        case 4096: RQS(4096); break;
+        default: return hipErrorInvalidValue;
+    }
+#undef RQS
     return hipGetLastError();
 }
 

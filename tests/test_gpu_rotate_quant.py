@@ -221,3 +221,22 @@ def test_linear_end_to_end_with_a_paley_factor(K, N):
     assert err <= G.Y_REL_FRO, err
     exact = oracle.to_f64(X) @ W.astype(np.float64).T + oracle.to_f64(bias)
     assert np.linalg.norm(oracle.bf16_bits_to_f64(Y) - exact) / np.linalg.norm(exact) < 0.35
+
+
+@pytest.mark.parametrize("K", [256, 1024, 2048, 4096])
+@pytest.mark.parametrize("rows", [1, 37, 1374, 5003])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_rotated_col_absmax(K, rows, dtype):
+    """The smoothing statistic max_t |X H|[t, j] (Sec. 3.2): matrix-core kernel for bf16 at K = 1024 / 2048 / 4096, the generic
+    one otherwise; ragged row counts leave the last tile partial."""
+    import paper_2509_21302_amd as q
+    X = _heavy(rows, K, rows + K, dtype)
+    rng = np.random.default_rng(rows * K)
+    signs = (rng.integers(0, 2, K) * 2 - 1).astype(np.int8)
+    for sg in (signs, None):
+        a = torch.full((K,), -1.0, dtype=torch.float32, device=G.DEV)
+        q.qvggt_rotated_col_absmax(G.to_dev(X), G.to_dev(sg), a)
+        want = oracle.rotated_col_absmax(X, pre_signs=sg)
+        # a column's maximum can be a small number left by cancellation (one row: it is the rotated value itself), so the
+        # fp32 butterflies are held to the row's magnitude as well as to the value: |err| <= 1e-5 |want| + 2e-6 max|want|
+        assert np.allclose(a.cpu().numpy(), want, rtol=G.SCALE_RTOL, atol=2e-6 * want.max()), f"K={K} rows={rows}"

@@ -81,15 +81,17 @@ struct StreamCfg {
         (dst)[(k) + 1] = (int)((p_ << 4) & 0xF0F0F0F0u);               \
     } while (0)
 
+// M0 holds the LDS base of these transfers.  It is a register the compiler reserves for a few instructions of its own (none
+// of which this file uses) and never allocates, so it is neither listed as clobbered nor touched between the transfers.
 // 16 bytes per lane from global memory to LDS: lane l of the wave writes lds_base + 16 * l
 __device__ inline void dma16(const void *src, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_base) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_base) : "memory");
 }
 // 4 bytes per lane: lane l writes lds_base + 4 * l
 __device__ inline void dma4(const void *src, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" ::"v"(src), "s"(lds_base) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" ::"v"(src), "s"(lds_base) : "memory");
 }
 // The instruction offset of such a transfer moves the LDS address and the global address alike: with one base in M0,
 // transfers to different places of a stage differ only in OFF (the lane's global offset is pre-compensated by -OFF).
@@ -98,7 +100,7 @@ __device__ inline void dma4(const void *src, uint32_t lds_base)
 template <int OFF>
 __device__ inline void dma16_set_base(uint32_t lane_off, const void *base, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1 offset:%3" ::"v"(lane_off), "s"(base), "s"(lds_base), "n"(OFF) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1 offset:%3" ::"v"(lane_off), "s"(base), "s"(lds_base), "n"(OFF) : "memory");
 }
 template <int OFF>
 __device__ inline void dma16_same_base(uint32_t lane_off, const void *base)

@@ -40,6 +40,7 @@
 // work runs in the shadow of the matrix pipe.
 #include "qvggt_common.h"
 
+#include <algorithm>
 #include <cstdlib>
 #include <type_traits>
 #include <utility>
@@ -498,6 +499,42 @@ static hipError_t launch_gemm(const uint8_t *Xq, const float *sx, const uint8_t 
     return hipGetLastError();
 }
 
+// Which tile shape runs where.  The big configuration (256 x 256 per block, four waves of 128 x 128, one per SIMD) works in
+// rounds of 256 tiles, one per compute unit; a last round that is mostly empty costs as much as a full one.  So the token rows
+// that fill whole rounds go to the big kernel and the remaining rows, when they fit better there, to the small configuration
+// (128 x 128 per block, two blocks per compute unit) in a second launch on the same stream.  Rows are independent, the two
+// launches write disjoint rows of Y.
+template <int CB>
+static hipError_t gemm_by_rounds(const uint8_t *Xq, const float *sx, const uint8_t *Wq, const float *sw, const void *bias,
+                                 int M, int N, int K, void *Y, int32_t *acc_debug, hipStream_t stream)
+{
+    auto big = [&](int row0, int rows) {
+        return launch_gemm<4, 4, 2, 2, 4, 1, CB>(Xq + (size_t)row0 * (CB == 4 ? K / 2 : K), sx + row0, Wq, sw, bias, rows, N, K,
+                                                 static_cast<uint16_t *>(Y) + (size_t)row0 * N,
+                                                 acc_debug ? acc_debug + (size_t)row0 * N : nullptr, stream);
+    };
+    auto small = [&](int row0, int rows) {
+        return launch_gemm<2, 2, 2, 2, 3, 2, CB>(Xq + (size_t)row0 * (CB == 4 ? K / 2 : K), sx + row0, Wq, sw, bias, rows, N, K,
+                                                 static_cast<uint16_t *>(Y) + (size_t)row0 * N,
+                                                 acc_debug ? acc_debug + (size_t)row0 * N : nullptr, stream);
+    };
+    const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
+    const long long big_tiles = (long long)tiles_m * tiles_n;
+    if (big_tiles < 256) return small(0, M);
+    // whole tile rows that fit into the full rounds
+    const int main_tile_rows = (int)std::min<long long>(tiles_m, big_tiles / 256 * 256 / tiles_n);
+    const int rem_tile_rows = tiles_m - main_tile_rows;
+    if (rem_tile_rows == 0) return big(0, M);
+    const int rows_main = main_tile_rows * 256, rows_rem = M - rows_main;
+    const long long rem_big_rounds = ((long long)rem_tile_rows * tiles_n + 255) / 256;
+    const long long rem_small_rounds = ((long long)((rows_rem + 127) / 128) * ((N + 127) / 128) + 511) / 512;
+    // a round of small tiles takes about 0.5 - 0.7 of a round of big ones (measured at K = 1024 and 4096)
+    if (rem_small_rounds * 13 >= rem_big_rounds * 20) return big(0, M);
+    hipError_t e = big(0, rows_main);
+    if (e != hipSuccess) return e;
+    return small(rows_main, rows_rem);
+}
+
 hipError_t run_w4a4_gemm(const uint8_t *Xq, const float *sx, const uint8_t *Wq, const float *sw,
                          const void *bias, int M, int N, int K, void *Y, int32_t *acc_debug, hipStream_t stream)
 {
@@ -514,10 +551,7 @@ hipError_t run_w4a4_gemm(const uint8_t *Xq, const float *sx, const uint8_t *Wq, 
         default: break;
     }
 #endif
-    const long long big_tiles = (long long)((M + 255) / 256) * ((N + 255) / 256);
-    // 256 tokens x 256 channels per block, four waves of 128 x 128 (one per SIMD); small problems take 128 x 128 blocks
-    if (big_tiles >= 256) GOP(4, 4, 2, 2, 4, 1, 4);
-    GOP(2, 2, 2, 2, 3, 2, 4);
+    return gemm_by_rounds<4>(Xq, sx, Wq, sw, bias, M, N, K, Y, acc_debug, stream);
 }
 
 // The same kernel on int8 codes (8- and 6-bit settings): rows of K bytes, no expansion, two K-steps per K-tile.
@@ -527,11 +561,7 @@ hipError_t run_i8_gemm(const int8_t *Xq, const float *sx, const int8_t *Wq, cons
     if (M <= 0) return hipSuccess;
     const uint8_t *xq = reinterpret_cast<const uint8_t *>(Xq), *wq = reinterpret_cast<const uint8_t *>(Wq);
 #undef GOP
-#define GOP(...) return launch_gemm<__VA_ARGS__>(xq, sx, wq, sw, bias, M, N, K, Y, acc_debug, stream)
-    const long long big_tiles = (long long)((M + 255) / 256) * ((N + 255) / 256);
-    if (big_tiles >= 256) GOP(4, 4, 2, 2, 4, 1, 8);
-    GOP(2, 2, 2, 2, 3, 2, 8);
-#undef GOP
+    return gemm_by_rounds<8>(xq, sx, wq, sw, bias, M, N, K, Y, acc_debug, stream);
 }
 
 }  // namespace qvggt

@@ -120,3 +120,35 @@ def test_shape_sweep_both_code_widths():
         Yo = oracle.dequant_bias(want, dx, dw, None if bias_bits is None else oracle.to_f64(bias_bits))
         ulp_off = np.abs(G.bf16_bits(Y).astype(np.int32) - Yo.astype(np.int32))
         assert ulp_off.max() <= 1 and (ulp_off != 0).mean() < 5e-3, what
+
+
+@pytest.mark.parametrize("M,N,K,wide", [(66000, 512, 256, False), (33000, 1024, 512, True), (65700, 768, 128, False)])
+def test_rows_split_between_the_two_tile_shapes(M, N, K, wide):
+    """Shapes whose 256 x 256 tiles fill whole rounds of 256 plus a small remainder: the remainder rows go to the 128 x 128
+    configuration in a second launch.  Accumulators of rows on both sides of the seam, and the last rows, are bit-exact."""
+    import paper_2509_21302_amd as q
+    tiles_n = (N + 255) // 256
+    seam = ((M + 255) // 256 * tiles_n // 256 * 256 // tiles_n) * 256
+    assert 0 < seam < M
+    gen = torch.Generator(device="cpu").manual_seed(M)
+    lim = 128 if wide else 8
+    qx = torch.randint(-lim, lim, (M, K), generator=gen, dtype=torch.int8).numpy()
+    qw = torch.randint(-lim, lim, (N, K), generator=gen, dtype=torch.int8).numpy()
+    rng = np.random.default_rng(M)
+    dx = np.exp(rng.uniform(-3, 1, M)).astype(np.float32)
+    dw = np.exp(rng.uniform(-8, -4, N)).astype(np.float32)
+    Y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=G.DEV)
+    acc = torch.full((M, N), 12345, dtype=torch.int32, device=G.DEV)
+    if wide:
+        q.qvggt_i8_gemm(G.gpu_layout_int8(qx, 1), G.to_dev(dx), G.gpu_layout_int8(qw, 1), G.to_dev(dw), None, M, N, K, Y, acc)
+    else:
+        q.qvggt_w4a4_gemm(G.gpu_pack(qx), G.to_dev(dx), G.gpu_pack(qw), G.to_dev(dw), None, M, N, K, Y, acc)
+    rows = np.unique(np.concatenate([np.arange(0, 8), np.arange(seam - 300, min(seam + 300, M)), np.arange(M - 200, M),
+                                     rng.choice(M, 200, replace=False)]))
+    idx = torch.from_numpy(rows).to(G.DEV)
+    want = oracle.int_gemm(qx[rows], qw)
+    assert np.array_equal(acc[idx].cpu().numpy(), want)
+    Yo = oracle.dequant_bias(want, dx[rows], dw, None)
+    ulp_off = np.abs(G.bf16_bits(Y[idx]).astype(np.int32) - Yo.astype(np.int32))
+    assert ulp_off.max() <= 1 and (ulp_off != 0).mean() < 5e-3
+    assert not torch.isnan(Y.float()).any().item()                      # every row of Y was written by one of the launches

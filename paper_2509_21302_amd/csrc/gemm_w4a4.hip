@@ -520,7 +520,12 @@ static hipError_t gemm_by_rounds(const uint8_t *Xq, const float *sx, const uint8
     };
     const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
     const long long big_tiles = (long long)tiles_m * tiles_n;
-    if (big_tiles < 256) return small(0, M);
+    // a round of small tiles takes about 0.5 - 0.7 of a round of big ones (measured at K = 1024 and 4096): 13 / 20 below
+    if (big_tiles < 256) {
+        // less than one round of big tiles: small tiles unless they need a second round of their own
+        const long long small_rounds = ((long long)((M + 127) / 128) * ((N + 127) / 128) + 511) / 512;
+        return small_rounds * 13 < 20 ? small(0, M) : big(0, M);
+    }
     // whole tile rows that fit into the full rounds
     const int main_tile_rows = (int)std::min<long long>(tiles_m, big_tiles / 256 * 256 / tiles_n);
     const int rem_tile_rows = tiles_m - main_tile_rows;
@@ -528,7 +533,6 @@ static hipError_t gemm_by_rounds(const uint8_t *Xq, const float *sx, const uint8
     const int rows_main = main_tile_rows * 256, rows_rem = M - rows_main;
     const long long rem_big_rounds = ((long long)rem_tile_rows * tiles_n + 255) / 256;
     const long long rem_small_rounds = ((long long)((rows_rem + 127) / 128) * ((N + 127) / 128) + 511) / 512;
-    // a round of small tiles takes about 0.5 - 0.7 of a round of big ones (measured at K = 1024 and 4096)
     if (rem_small_rounds * 13 >= rem_big_rounds * 20) return big(0, M);
     hipError_t e = big(0, rows_main);
     if (e != hipSuccess) return e;

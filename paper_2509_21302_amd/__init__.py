@@ -33,3 +33,5 @@ from .binding import (  # noqa: F401
     QVGGT_BF16,
     QVGGT_F32,
 )
+
+from .module import DsfqLinear  # noqa: E402,F401

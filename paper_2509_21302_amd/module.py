@@ -1,0 +1,58 @@
+"""A small convenience object around the C ABI: one quantized linear layer, prepared once, applied many times.
+
+It only allocates device tensors with torch and calls the entry points of the same names; no arithmetic of the
+method happens here.  `bits` = 4 uses the packed 4-bit path, 5..8 the int8-code path (Sec. 4.1 settings, appendix).
+"""
+from __future__ import annotations
+
+from typing import Optional
+
+import torch
+
+from . import binding as q
+
+
+class DsfqLinear:
+    """Y = X W^T + b with W and X quantized as in Sec. 3.2 (rotation, smoothing, per-channel / per-token codes).
+
+    weight: [N, K] bf16 or f32 device tensor; bias: [N] bf16 device tensor or None; signs: int8 [K] of +-1 or None;
+    calibration: [M_cal, K] activations for the smoothing statistic, or None for rotation only (c = 1).
+    """
+
+    def __init__(self, weight: torch.Tensor, bias: Optional[torch.Tensor] = None, signs: Optional[torch.Tensor] = None,
+                 calibration: Optional[torch.Tensor] = None, alpha: float = 0.5, bits: int = 4):
+        if bits != 4 and not 5 <= bits <= 8:
+            raise ValueError("bits must be 4 or in 5..8")
+        self.N, self.K = weight.shape
+        self.bits, self.bias, self.signs = bits, bias, signs
+        dev = weight.device
+        absmax = None
+        if calibration is not None:
+            absmax = torch.empty(self.K, dtype=torch.float32, device=dev)
+            q.qvggt_rotated_col_absmax(calibration, signs, absmax)
+        self.w_scale = torch.empty(self.N, dtype=torch.float32, device=dev)
+        self.inv_smooth = torch.empty(self.K, dtype=torch.float32, device=dev)
+        if bits == 4:
+            self.Wq = torch.empty(self.N, self.K // 2, dtype=torch.uint8, device=dev)
+            q.qvggt_prep_weights(weight, absmax, signs, alpha, self.Wq, self.w_scale, self.inv_smooth)
+        else:
+            self.Wq = torch.empty(self.N, self.K, dtype=torch.int8, device=dev)
+            q.qvggt_prep_weights_i8(weight, absmax, signs, alpha, bits, self.Wq, self.w_scale, self.inv_smooth)
+        self._ws = None
+
+    def _workspace(self, M: int, dev) -> torch.Tensor:
+        need = q.qvggt_workspace_bytes(M, self.N, self.K) if self.bits == 4 else q.qvggt_workspace_bytes_i8(M, self.N, self.K)
+        if self._ws is None or self._ws.numel() < need or self._ws.device != dev:
+            self._ws = torch.empty(need, dtype=torch.uint8, device=dev)
+        return self._ws
+
+    def __call__(self, X: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """X: [M, K] bf16 or f32 on the GPU; returns bf16 [M, N] (written into `out` when given)."""
+        M = X.shape[0]
+        Y = out if out is not None else torch.empty(M, self.N, dtype=torch.bfloat16, device=X.device)
+        ws = self._workspace(M, X.device)
+        if self.bits == 4:
+            q.qvggt_linear(X, self.signs, self.inv_smooth, self.Wq, self.w_scale, self.bias, Y, ws)
+        else:
+            q.qvggt_linear_i8(X, self.signs, self.inv_smooth, self.bits, self.Wq, self.w_scale, self.bias, Y, ws)
+        return Y

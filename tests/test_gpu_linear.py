@@ -167,3 +167,23 @@ def test_linear_under_hip_graph_capture():
         want = G.gpu_linear(Xnew, prep, bias)           # eager, own buffers
         torch.cuda.synchronize()
         assert torch.equal(got, want), f"replay {rep}"
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_convenience_object_matches_the_entry_points(bits):
+    """DsfqLinear only allocates and forwards: same bits as calling the C ABI by hand, and oracle-close."""
+    import paper_2509_21302_amd as q
+    s = synth.layer_spec(2)
+    X, bias, W, Xc, signs = (synth.make_activation_frames(s), synth.make_bias(s), synth.make_weights(s),
+                             synth.make_calibration(s), synth.make_signs(s))
+    layer = q.DsfqLinear(G.to_dev(W), G.to_dev(bias), G.to_dev(signs), G.to_dev(Xc), alpha=0.5, bits=bits)
+    Y = layer(G.to_dev(X))
+    a = oracle.rotated_col_absmax(Xc, pre_signs=signs)
+    po = oracle.prepare_weights(W, a, pre_signs=signs, alpha=0.5, bits=bits)
+    want = oracle.linear(X, po, bias=bias, pre_signs=signs, bits=bits)
+    assert G.rel_fro(G.bf16_bits(Y), want.Y) <= G.Y_REL_FRO
+    by_hand = G.gpu_linear(G.to_dev(X), _gpu_prep(s), G.to_dev(bias)) if bits == 4 else \
+        G.gpu_linear_i8(G.to_dev(X), G.gpu_prep_i8(W, Xc, signs, bits), G.to_dev(bias))
+    assert torch.equal(Y, by_hand)
+    out = torch.empty_like(Y)
+    assert layer(G.to_dev(X), out=out) is out and torch.equal(out, Y)

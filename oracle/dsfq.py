@@ -231,6 +231,23 @@ def rotated_col_absmax(X_cal, pre_signs=None, post_signs=None) -> np.ndarray:
     return col_absmax(rotate(to_f64(X_cal), pre_signs, post_signs))
 
 
+def layernorm(X, gamma=None, beta=None, eps: float = 1e-5, round_to_bf16: bool = True) -> np.ndarray:
+    """Row-wise LayerNorm as it stands in front of VGGT's qkv and fc1 layers (the "neighbouring normalization layer" of
+    Sec. 3.2): y = (x - mean) / sqrt(var + eps) * gamma + beta, mean and (population) variance over the K channels of a
+    token, in float64.  With round_to_bf16 the result is rounded to bfloat16 (nearest even) and returned as the exact
+    doubles of those bf16 values: what a bf16 LayerNorm kernel hands to the next layer."""
+    x = to_f64(X)
+    K = x.shape[1]
+    mean = x.sum(axis=1, keepdims=True) / K
+    var = ((x - mean) ** 2).sum(axis=1, keepdims=True) / K
+    y = (x - mean) / np.sqrt(var + eps)
+    if gamma is not None:
+        y = y * _f64(gamma)[None, :]
+    if beta is not None:
+        y = y + _f64(beta)[None, :]
+    return bf16_bits_to_f64(bf16_from_f64(y)) if round_to_bf16 else y
+
+
 def rotate_smooth_quant(X, c_hat=None, pre_signs=None, post_signs=None, bits: int = 4):
     """Online half up to the codes: returns (dx [M], qx [M, K] int8, Xs [M, K] f64)."""
     Xr = rotate(to_f64(X), pre_signs, post_signs)

@@ -232,3 +232,25 @@ def test_pack_roundtrip_all_byte_values():
     assert oracle.unpack_int4(np.array([[0xA7]], np.uint8), 2).tolist() == [[7, -6]]
     with pytest.raises(oracle.OracleError):
         oracle.pack_int4(np.array([[9, 0]], np.int8))
+
+
+# ----------------------------------------------------------------- LayerNorm in front of the quantized layer
+def test_layernorm_closed_forms_and_library():
+    rng = np.random.default_rng(21)
+    X = rng.standard_t(3, (12, 256)) * 3 + rng.standard_normal((12, 1)) * 10
+    y = oracle.layernorm(X, eps=0.0, round_to_bf16=False)
+    assert np.allclose(y.mean(axis=1), 0.0, atol=1e-13) and np.allclose((y ** 2).mean(axis=1), 1.0, rtol=1e-12)
+    # invariant under shift and positive scale of a row (eps = 0); gamma, beta act per channel afterwards
+    assert np.allclose(oracle.layernorm(7.0 * X - 3.0, eps=0.0, round_to_bf16=False), y, atol=1e-11)
+    g, b = rng.uniform(0.5, 2, 256), rng.standard_normal(256)
+    assert np.allclose(oracle.layernorm(X, g, b, eps=0.0, round_to_bf16=False), y * g + b, rtol=1e-13, atol=1e-13)
+    # two-point row: values +-1 whatever the inputs; eps shrinks them by sqrt(var / (var + eps))
+    assert oracle.layernorm(np.array([[3.0, 5.0]]), eps=0.0, round_to_bf16=False).tolist() == [[-1.0, 1.0]]
+    assert np.allclose(oracle.layernorm(np.array([[3.0, 5.0]]), eps=3.0, round_to_bf16=False), [[-0.5, 0.5]], rtol=1e-15)
+    # the library routine in float64
+    t = torch.nn.functional.layer_norm(torch.from_numpy(X), (256,), torch.from_numpy(g), torch.from_numpy(b), eps=1e-5).numpy()
+    assert np.allclose(oracle.layernorm(X, g, b, eps=1e-5, round_to_bf16=False), t, rtol=1e-12, atol=1e-12)
+    # rounding to bfloat16: values are bf16-representable and within half an ulp (at most 2^-8 relative) of the exact ones
+    r = oracle.layernorm(X, g, b, eps=1e-5)
+    assert np.array_equal(oracle.bf16_bits_to_f64(oracle.bf16_from_f64(r)), r)
+    assert np.all(np.abs(r - t) <= np.abs(t) * 2.0 ** -8 + 1e-40) and np.abs(r - t).max() > 0

@@ -117,6 +117,20 @@ int qvggt_rotate_smooth_quant_static(const void *X, int x_dtype, int M, int K, c
                                      uint8_t *Xq, float *x_scale, void *stream);
 
 /*
+ * Online kernel 1 with the LayerNorm that precedes the layer fused in (VGGT's qkv and fc1 inputs; Sec. 3.2 names the
+ * neighbouring normalization layer as the place where per-channel factors can live).  Per token, before the rotation:
+ *     y = (x - mean) / sqrt(var + eps) * gamma + beta      (mean, population variance over the K channels, fp32),
+ * y rounded to the type of X (bf16 input: round to nearest even, i.e. what a separate bf16 LayerNorm kernel would
+ * write; f32 input: no rounding), then exactly qvggt_rotate_smooth_quant on y.  One read of X instead of a
+ * normalisation pass (read + write) followed by this kernel's read.
+ * gamma, beta: f32 [K] or NULL (1 and 0).  eps >= 0 (QVGGT_ERR_ARG otherwise).  K: a power of two in [128, 4096]
+ * (8192 and the sizes 2^n * m are QVGGT_ERR_SHAPE here).  Other arguments, layouts and errors as qvggt_rotate_smooth_quant.
+ */
+int qvggt_layernorm_rotate_smooth_quant(const void *X, int x_dtype, int M, int K, const float *gamma, const float *beta,
+                                        float eps, const int8_t *signs, const float *inv_smooth, uint8_t *Xq,
+                                        float *x_scale, void *stream);
+
+/*
  * Online kernel 2 (Sec. 3.2 granularity paragraph: integer sum, dequantise after it):
  *     acc[t, o] = sum_j Xq[t, j] Wq[o, j]   (int32, exact);
  *     Y[t, o]   = bf16_rne( acc[t, o] * x_scale[t] * w_scale[o] + bias[o] )

@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     qvggt_prep_weights,
     qvggt_rotate_smooth_quant,
     qvggt_rotate_smooth_quant_static,
+    qvggt_layernorm_rotate_smooth_quant,
     qvggt_w4a4_gemm,
     qvggt_linear,
     qvggt_workspace_bytes,

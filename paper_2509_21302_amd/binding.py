@@ -16,7 +16,7 @@ QVGGT_BF16, QVGGT_F32 = 0, 1
 
 EXPORTS = [
     "qvggt_status_string", "qvggt_rotated_col_absmax", "qvggt_prep_weights", "qvggt_rotate_smooth_quant",
-    "qvggt_rotate_smooth_quant_static",
+    "qvggt_rotate_smooth_quant_static", "qvggt_layernorm_rotate_smooth_quant",
     "qvggt_w4a4_gemm", "qvggt_linear", "qvggt_workspace_bytes", "qvggt_pack_int4", "qvggt_unpack_int4",
     "qvggt_prep_weights_i8", "qvggt_rotate_smooth_quant_i8", "qvggt_i8_gemm", "qvggt_linear_i8",
     "qvggt_workspace_bytes_i8", "qvggt_layout_int8",
@@ -58,6 +58,8 @@ def load_library() -> C.CDLL:
     lib.qvggt_rotate_smooth_quant.argtypes = [vp, i, i, i, vp, vp, vp, vp, vp]
     lib.qvggt_rotate_smooth_quant_static.restype = i
     lib.qvggt_rotate_smooth_quant_static.argtypes = [vp, i, i, i, vp, vp, vp, i, vp, vp, vp]
+    lib.qvggt_layernorm_rotate_smooth_quant.restype = i
+    lib.qvggt_layernorm_rotate_smooth_quant.argtypes = [vp, i, i, i, vp, vp, f, vp, vp, vp, vp, vp]
     lib.qvggt_w4a4_gemm.restype = i
     lib.qvggt_w4a4_gemm.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp, vp, vp]
     lib.qvggt_linear.restype = i
@@ -160,6 +162,13 @@ def qvggt_rotate_smooth_quant_static(X, signs, inv_smooth, x_step, per_token, Xq
                                                            _ptr(x_step), int(per_token), _ptr(Xq), _ptr(x_scale),
                                                            _stream(stream)),
            "qvggt_rotate_smooth_quant_static")
+
+
+def qvggt_layernorm_rotate_smooth_quant(X, gamma, beta, eps, signs, inv_smooth, Xq, x_scale, stream=None):
+    M, K = X.shape
+    _check(load_library().qvggt_layernorm_rotate_smooth_quant(_ptr(X), _dtype_code(X), M, K, _ptr(gamma), _ptr(beta), float(eps),
+                                                              _ptr(signs), _ptr(inv_smooth), _ptr(Xq), _ptr(x_scale),
+                                                              _stream(stream)), "qvggt_layernorm_rotate_smooth_quant")
 
 
 def qvggt_w4a4_gemm(Xq, x_scale, Wq, w_scale, bias, M, N, K, Y, acc_debug=None, stream=None):

@@ -16,6 +16,8 @@ hipError_t run_fill_f32(float *p, int n, float v, hipStream_t stream);
 hipError_t run_pack_int4(const int8_t *codes, int rows, int K, uint8_t *packed, hipStream_t stream);
 hipError_t run_unpack_int4(const uint8_t *packed, int rows, int K, int8_t *codes, hipStream_t stream);
 bool general_size_supported(int K);
+hipError_t run_ln_rotate_smooth_quant(const void *X, bool f32, int rows, int K, LnParams ln, const int8_t *signs, const float *mul,
+                                      uint8_t *packed, float *scale, hipStream_t stream);
 hipError_t run_layout_int8(const int8_t *src, int rows, int K, int8_t *dst, int to_library, hipStream_t stream);
 hipError_t run_w4a4_gemm(const uint8_t *Xq, const float *sx, const uint8_t *Wq, const float *sw, const void *bias,
                          int M, int N, int K, void *Y, int32_t *acc_debug, hipStream_t stream);
@@ -140,6 +142,22 @@ int qvggt_rotate_smooth_quant_i8(const void *X, int x_dtype, int M, int K, const
     return hip_status(qvggt::run_rotate_smooth_quant(X, x_dtype == QVGGT_F32, M, K, signs, inv_smooth, 0,
                                                      reinterpret_cast<uint8_t *>(Xq), x_scale, nullptr, 0, bits,
                                                      static_cast<hipStream_t>(stream)));
+}
+
+int qvggt_layernorm_rotate_smooth_quant(const void *X, int x_dtype, int M, int K, const float *gamma, const float *beta, float eps,
+                                        const int8_t *signs, const float *inv_smooth, uint8_t *Xq, float *x_scale, void *stream)
+{
+    if (!valid_dtype(x_dtype)) return QVGGT_ERR_DTYPE;
+    if (M < 0 || K < qvggt::kMinK || K > 4096 || (K & (K - 1)) != 0) return QVGGT_ERR_SHAPE;   // powers of two up to 4096 only
+    if (!(eps >= 0.0f) || !std::isfinite(eps)) return QVGGT_ERR_ARG;
+    if (M == 0) return QVGGT_OK;
+    if (!X || !Xq || !x_scale) return QVGGT_ERR_NULL;
+    if (!aligned16(X) || !aligned16(Xq) || !aligned16(x_scale) || !aligned16(inv_smooth) || !aligned16(signs) ||
+        !aligned16(gamma) || !aligned16(beta))
+        return QVGGT_ERR_ALIGN;
+    const qvggt::LnParams ln{gamma, beta, eps, 1};
+    return hip_status(qvggt::run_ln_rotate_smooth_quant(X, x_dtype == QVGGT_F32, M, K, ln, signs, inv_smooth, Xq, x_scale,
+                                                        static_cast<hipStream_t>(stream)));
 }
 
 int qvggt_rotate_smooth_quant_static(const void *X, int x_dtype, int M, int K, const int8_t *signs, const float *inv_smooth,

@@ -88,6 +88,34 @@ __device__ inline float max_over_64_lanes(float v)
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
+// Sum over all 64 lanes, the same butterflies with an add (every lane ends with the total).
+template <int CTRL>
+__device__ inline float dpp_add_step(float v)
+{
+    const int p = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false);
+    return v + __int_as_float(p);
+}
+__device__ inline float sum_over_64_lanes(float v)
+{
+    v = dpp_add_step<0xB1>(v);
+    v = dpp_add_step<0x4E>(v);
+    v = dpp_add_step<0x141>(v);
+    v = dpp_add_step<0x140>(v);
+    const auto r16 = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = __uint_as_float(r16[0]) + __uint_as_float(r16[1]);
+    const auto r32 = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r32[0]) + __uint_as_float(r32[1]);
+}
+
+// LayerNorm in front of the rotation (optional): y = (x - mean) / sqrt(var + eps) * gamma + beta over the K channels of a token.
+// gamma / beta may be nullptr (1 / 0).  on == 0: no normalisation.
+struct LnParams {
+    const float *gamma;
+    const float *beta;
+    float eps;
+    int on;
+};
+
 __device__ inline float wave_max(float v)
 {
 #pragma unroll

@@ -95,14 +95,16 @@ enum RowMode { kQuantize = 0, kColAbsMax = 1 };
 // mul_mode 0: mul[j] used as given (inv_smooth, or 1/sqrt(K) when mul == nullptr)
 // mul_mode 1: 1 / (K * mul[j])   (weights: c_j / sqrt(K) recovered from inv_smooth)
 // CB: bits a stored code occupies (4: two per byte; 8: one int8 each).  qmax: largest code, 2^(bits-1) - 1.
-template <int K, bool F32, int MODE, int CB>
+// LN: a LayerNorm of the row precedes everything else (quantize mode, K <= 4096: beyond that the row no longer fits the registers)
+template <int K, bool F32, int MODE, int CB, bool LN = false>
 __global__ __launch_bounds__(256) void rotate_rows_kernel(const void *__restrict__ X, int rows,
                                                           const int8_t *__restrict__ signs,
                                                           const float *__restrict__ mul, int mul_mode,
                                                           uint8_t *__restrict__ packed,
                                                           float *__restrict__ scale,
                                                           unsigned int *__restrict__ col_absmax_bits,
-                                                          const float *__restrict__ step, int step_stride, float qmax)
+                                                          const float *__restrict__ step, int step_stride, float qmax,
+                                                          LnParams ln)
 {
     constexpr int V = RowMap<K>::V, C = RowMap<K>::C, R = RowMap<K>::R;
     constexpr bool kPermuted = (K == 1024 || K == 2048 || K == 4096) && MODE == kQuantize;
@@ -148,6 +150,29 @@ __global__ __launch_bounds__(256) void rotate_rows_kernel(const void *__restrict
     for (int row = wave; row < rows; row += nwaves) {
         float x[R];
         load_row<K, F32>(X, (size_t)row, lane, x);
+        if constexpr (LN) {
+            // LayerNorm of the token in fp32 (two passes over the registers), result rounded to the input's type as a separate
+            // normalisation kernel would hand it on; gamma and beta come through the caches, this is the general path
+            float s1 = 0.0f;
+#pragma unroll
+            for (int r = 0; r < R; ++r) s1 += x[r];
+            const float mean = sum_over_64_lanes(s1) * (1.0f / (float)K);
+            float s2 = 0.0f;
+#pragma unroll
+            for (int r = 0; r < R; ++r) { x[r] -= mean; s2 = fmaf(x[r], x[r], s2); }
+            const float rstd = 1.0f / sqrtf(sum_over_64_lanes(s2) * (1.0f / (float)K) + ln.eps);
+#pragma unroll
+            for (int c = 0; c < C; ++c)
+#pragma unroll
+                for (int i = 0; i < V; ++i) {
+                    const int e = c * 64 * V + lane * V + i, r = c * V + i;
+                    float y = x[r] * rstd;
+                    const float gm = ln.gamma ? ln.gamma[e] : 1.0f, bt = ln.beta ? ln.beta[e] : 0.0f;
+                    y = fmaf(y, gm, bt);
+                    if constexpr (!F32) y = bf16_bits_to_float(pack_bf16x2(y, 0.0f) & 0xFFFFu);
+                    x[r] = y;
+                }
+        }
 #pragma unroll
         for (int r = 0; r < R; ++r)
             if ((neg[r >> 5] >> (r & 31)) & 1u) x[r] = -x[r];
@@ -321,8 +346,8 @@ static hipError_t launch_rotate_rows(const void *X, bool f32, int rows, int K, c
     if (blocks < 1) blocks = 1;
 #define QVGGT_LAUNCH(KK)                                                                                     \
     case KK:                                                                                                 \
-        if (f32) rotate_rows_kernel<KK, true, MODE, CB><<<blocks, 256, 0, stream>>>(X, rows, signs, mul, mul_mode, packed, scale, colmax, step, step_stride, qmax); \
-        else rotate_rows_kernel<KK, false, MODE, CB><<<blocks, 256, 0, stream>>>(X, rows, signs, mul, mul_mode, packed, scale, colmax, step, step_stride, qmax);    \
+        if (f32) rotate_rows_kernel<KK, true, MODE, CB><<<blocks, 256, 0, stream>>>(X, rows, signs, mul, mul_mode, packed, scale, colmax, step, step_stride, qmax, LnParams{nullptr, nullptr, 0.0f, 0}); \
+        else rotate_rows_kernel<KK, false, MODE, CB><<<blocks, 256, 0, stream>>>(X, rows, signs, mul, mul_mode, packed, scale, colmax, step, step_stride, qmax, LnParams{nullptr, nullptr, 0.0f, 0});    \
         break;
     switch (K) {
         QVGGT_LAUNCH(128)
@@ -358,6 +383,35 @@ hipError_t run_rotate_smooth_quant(const void *X, bool f32, int rows, int K, con
     if (bits == 4)
         return launch_rotate_rows<kQuantize, 4>(X, f32, rows, K, signs, mul, mul_mode, packed, scale, nullptr, step, step_stride, qmax, stream);
     return launch_rotate_rows<kQuantize, 8>(X, f32, rows, K, signs, mul, mul_mode, packed, scale, nullptr, step, step_stride, qmax, stream);
+}
+
+hipError_t run_ln_rotate_quant_mfma(const void *X, int rows, const int8_t *signs, const float *mul, uint8_t *packed, float *scale,
+                                    LnParams ln, hipStream_t stream);
+
+// LayerNorm + rotation + smoothing + per-token 4-bit quantization in one kernel (power-of-two K)
+hipError_t run_ln_rotate_smooth_quant(const void *X, bool f32, int rows, int K, LnParams ln, const int8_t *signs, const float *mul,
+                                      uint8_t *packed, float *scale, hipStream_t stream)
+{
+    if (!f32 && K == 1024) return run_ln_rotate_quant_mfma(X, rows, signs, mul, packed, scale, ln, stream);
+    if (rows <= 0) return hipSuccess;
+    int blocks = (rows + 3) / 4;
+    if (blocks > 256 * 8) blocks = 256 * 8;
+#define QVGGT_LAUNCH_LN(KK)                                                                                                            \
+    case KK:                                                                                                                           \
+        if (f32) rotate_rows_kernel<KK, true, kQuantize, 4, true><<<blocks, 256, 0, stream>>>(X, rows, signs, mul, 0, packed, scale, nullptr, nullptr, 0, 7.0f, ln); \
+        else rotate_rows_kernel<KK, false, kQuantize, 4, true><<<blocks, 256, 0, stream>>>(X, rows, signs, mul, 0, packed, scale, nullptr, nullptr, 0, 7.0f, ln);    \
+        break;
+    switch (K) {
+        QVGGT_LAUNCH_LN(128)
+        QVGGT_LAUNCH_LN(256)
+        QVGGT_LAUNCH_LN(512)
+        QVGGT_LAUNCH_LN(1024)
+        QVGGT_LAUNCH_LN(2048)
+        QVGGT_LAUNCH_LN(4096)
+        default: return hipErrorInvalidValue;
+    }
+#undef QVGGT_LAUNCH_LN
+    return hipGetLastError();
 }
 
 hipError_t run_rotated_col_absmax(const void *X, bool f32, int rows, int K, const int8_t *signs,

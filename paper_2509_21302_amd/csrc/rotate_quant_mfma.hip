@@ -74,14 +74,17 @@ __host__ __device__ constexpr int row_of_seg_hi(int seg_hi /* seg >> 2 */)
 // CB: bits a stored code occupies: 4 (packed nibbles, codes in [-8, 7]) or 8 (int8, codes in [-qmax - 1, qmax]);
 // CB = 0 is the statistic mode: nothing is quantized or stored, the kernel leaves max_t |X H / sqrt(K)|[t, j] per column j
 // in col_absmax_bits (the numerator of the smoothing factor, Sec. 3.2), which must be zero on entry
-template <int K, int PF, int OCC, bool STATIC, int CB>
+// LN: a LayerNorm of every token (fp32, result rounded to bf16 as a separate normalisation kernel would hand it on) is
+// applied to the loaded values before anything else
+template <int K, int PF, int OCC, bool STATIC, int CB, bool LN = false>
 __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint16_t *__restrict__ X, int rows,
                                                                    const int8_t *__restrict__ signs,
                                                                    const float *__restrict__ mul, int mul_mode,
                                                                    uint8_t *__restrict__ packed,
                                                                    float *__restrict__ scale,
                                                                    const float *__restrict__ step, int step_stride,
-                                                                   float qmax8, unsigned int *__restrict__ col_absmax_bits)
+                                                                   float qmax8, unsigned int *__restrict__ col_absmax_bits,
+                                                                   LnParams ln = LnParams{nullptr, nullptr, 0.0f, 0})
 {
     constexpr bool STAT = (CB == 0);
     using C = rq::Cfg<K>;
@@ -169,6 +172,20 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
         }
     }
 
+    // LayerNorm scale / shift of the channels this lane loads: load j of a token's LPT loads covers channels 512 j + 8 lane .. + 8
+    constexpr int LPT = 8 / TOK;
+    float gam[LN ? LPT : 1][8], bet[LN ? LPT : 1][8];
+    if constexpr (LN) {
+        static_assert(K == 1024, "the fused LayerNorm keeps 2 * K / 64 scale and shift values per lane: K = 1024 only");
+#pragma unroll
+        for (int jl = 0; jl < LPT; ++jl)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                gam[jl][i] = ln.gamma ? ln.gamma[512 * jl + 8 * lane + i] : 1.0f;
+                bet[jl][i] = ln.beta ? ln.beta[512 * jl + 8 * lane + i] : 0.0f;
+            }
+    }
+
     // ---- tile loop ------------------------------------------------------------------------------
     const size_t max_flat = (size_t)rows * K;
     auto tile_ptr = [&](int tile, int j) -> const uint4 * {
@@ -209,6 +226,41 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
         for (int nt = 0; nt < 4; ++nt) cmax[h][nt] = 0.0f;
 
     for (; tile < ntiles; tile += nwaves) {
+        if constexpr (LN) {
+            // every token of the tile: mean, variance (two passes over the registers), normalise, scale / shift, back to bf16
+#pragma unroll
+            for (int t = 0; t < TOK; ++t) {
+                float xv[LPT][8];
+                float s1 = 0.0f;
+#pragma unroll
+                for (int jl = 0; jl < LPT; ++jl) {
+                    const uint4 v = G[0][t * LPT + jl];
+                    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) {
+                        xv[jl][2 * d] = __uint_as_float(w[d] << 16);
+                        xv[jl][2 * d + 1] = __uint_as_float(w[d] & 0xFFFF0000u);
+                        s1 += xv[jl][2 * d] + xv[jl][2 * d + 1];
+                    }
+                }
+                const float mean = sum_over_64_lanes(s1) * (1.0f / (float)K);
+                float s2 = 0.0f;
+#pragma unroll
+                for (int jl = 0; jl < LPT; ++jl)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) { xv[jl][i] -= mean; s2 = fmaf(xv[jl][i], xv[jl][i], s2); }
+                const float rstd = 1.0f / sqrtf(sum_over_64_lanes(s2) * (1.0f / (float)K) + ln.eps);
+#pragma unroll
+                for (int jl = 0; jl < LPT; ++jl) {
+                    uint32_t w[4];
+#pragma unroll
+                    for (int d = 0; d < 4; ++d)
+                        w[d] = pack_bf16x2(fmaf(xv[jl][2 * d] * rstd, gam[jl][2 * d], bet[jl][2 * d]),
+                                           fmaf(xv[jl][2 * d + 1] * rstd, gam[jl][2 * d + 1], bet[jl][2 * d + 1]));
+                    G[0][t * LPT + jl] = make_uint4(w[0], w[1], w[2], w[3]);
+                }
+            }
+        }
         // stage the tile: flip signs on the packed bf16, write each 16-byte chunk to its MFMA row
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -425,6 +477,19 @@ hipError_t run_rotate_quant_mfma(const void *X, int rows, int K, const int8_t *s
         case 4096: RQ(4096, 1, 2); break;
         default: return hipErrorInvalidValue;
     }
+    return hipGetLastError();
+}
+
+// LayerNorm + rotation + smoothing + per-token 4-bit quantization of bf16 rows, K = 1024
+hipError_t run_ln_rotate_quant_mfma(const void *X, int rows, const int8_t *signs, const float *mul, uint8_t *packed, float *scale,
+                                    LnParams ln, hipStream_t stream)
+{
+    if (rows <= 0) return hipSuccess;
+    const int ntiles = (rows + 3) / 4;
+    int blocks = (ntiles + rq::WAVES_PER_BLOCK - 1) / rq::WAVES_PER_BLOCK;
+    if (blocks > 256 * 2) blocks = 256 * 2;
+    rotate_quant_mfma_kernel<1024, 1, 2, false, 4, true><<<blocks, 256, 0, stream>>>(
+        reinterpret_cast<const uint16_t *>(X), rows, signs, mul, 0, packed, scale, nullptr, 0, 7.0f, nullptr, ln);
     return hipGetLastError();
 }
 

@@ -46,6 +46,14 @@ def gpu_rsq(Xd, signs_d, inv_d):
     return Xq, sx
 
 
+def gpu_ln_rsq(Xd, gamma_d, beta_d, eps, signs_d, inv_d):
+    M, K = Xd.shape
+    Xq = torch.empty(M, K // 2, dtype=torch.uint8, device=DEV)
+    sx = torch.empty(M, dtype=torch.float32, device=DEV)
+    q.qvggt_layernorm_rotate_smooth_quant(Xd, gamma_d, beta_d, eps, signs_d, inv_d, Xq, sx)
+    return Xq, sx
+
+
 def gpu_rsq_static(Xd, signs_d, inv_d, step_d, per_token):
     M, K = Xd.shape
     Xq = torch.empty(M, K // 2, dtype=torch.uint8, device=DEV)

@@ -91,6 +91,19 @@ def test_argument_validation_needs_no_gpu():
     for bad in (-1, 2, 7):
         assert st(P, 0, 4, 1024, None, None, P, bad, P, P, None) == ARG
     assert st(None, 0, 0, 1024, None, None, None, 1, None, None, None) == OK
+    # LayerNorm in front: powers of two up to 4096, eps >= 0, optional gamma / beta aligned when given
+    lnq = lib.qvggt_layernorm_rotate_smooth_quant
+    e5 = C.c_float(1e-5)
+    for badk in (1000, 768, 8192, 64):
+        assert lnq(P, 0, 4, badk, None, None, e5, None, None, P, P, None) == SHAPE
+    assert lnq(P, 7, 4, 1024, None, None, e5, None, None, P, P, None) == DTYPE
+    assert lnq(None, 0, 4, 1024, None, None, e5, None, None, P, P, None) == NULL
+    assert lnq(P, 0, 4, 1024, None, None, e5, None, None, P, None, None) == NULL
+    assert lnq(P, 0, 4, 1024, P + 4, None, e5, None, None, P, P, None) == ALIGN
+    assert lnq(P, 0, 4, 1024, None, P + 8, e5, None, None, P, P, None) == ALIGN
+    for bad in (-1e-5, float("nan"), float("inf")):
+        assert lnq(P, 0, 4, 1024, None, None, C.c_float(bad), None, None, P, P, None) == ARG
+    assert lnq(None, 0, 0, 1024, None, None, e5, None, None, None, None, None) == OK
     # 8-bit / 6-bit entry points: the same checks, and the bit-width
     for bad in (4, 9, 0, -8):
         assert lib.qvggt_rotate_smooth_quant_i8(P, 0, 4, 1024, None, None, bad, P, P, None) == ARG

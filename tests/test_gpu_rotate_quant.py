@@ -58,6 +58,95 @@ def test_rotate_quant_static_step(K, per_token, dtype):
     assert np.array_equal(sx.cpu().numpy(), np.broadcast_to(step, (rows,)))
 
 
+# LayerNorm fused in front.  With f32 rows nothing is rounded between the normalisation and the rotation and the usual
+# bars hold.  With bf16 rows the normalised value is rounded to bf16, and the kernel's fp32 value (relative error about
+# 2e-7) lands on the other side of a rounding midpoint (spaced 2^-8 .. 2^-7 relative) than the oracle's fp64 value for about
+# 5e-5 of the elements.  Such an element then differs by one bf16 ulp, every rotated value of its row moves by up to
+# ulp / sqrt(K), and a row that holds one can see a few codes and its step move: the bars for bf16 are a code off by one
+# on at most 5e-4 of the elements, steps within 1e-5 on nine rows of ten and within 2e-3 on all.
+LN_BF16_CODE_FRACTION = 5e-4
+LN_BF16_SCALE_RTOL_ALL = 2e-3
+
+
+def _check_ln(Xq, sx, K, qx, dx, dtype, what):
+    codes, got = G.gpu_unpack(Xq, K), sx.cpu().numpy().astype(np.float64)
+    if dtype == "f32":
+        G.check_codes(codes, qx, what)
+        G.check_scales(got, dx, what)
+        return
+    d = np.abs(codes.astype(np.int16) - qx.astype(np.int16))
+    assert d.max(initial=0) <= 1, f"{what}: a code differs by {d.max()}"
+    assert (d != 0).mean() <= LN_BF16_CODE_FRACTION, f"{what}: {(d != 0).mean():.3e} of the codes differ"
+    err = np.abs(got - dx) / np.maximum(dx, 1e-300)
+    err[dx == 0] = np.abs(got[dx == 0])
+    assert err.max(initial=0) <= LN_BF16_SCALE_RTOL_ALL, f"{what}: step rel err {err.max():.3e}"
+    assert (err <= G.SCALE_RTOL).mean() >= 0.9, f"{what}: only {(err <= G.SCALE_RTOL).mean():.2f} of the steps within {G.SCALE_RTOL}"
+
+
+@pytest.mark.parametrize("K", [128, 512, 1024, 2048, 4096])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_layernorm_rotate_quant(K, dtype):
+    """LayerNorm -> rotation -> smoothing -> per-token codes in one launch against the oracle's LayerNorm followed by
+    its rotate_smooth_quant.  K = 1024 bf16 is the matrix-core kernel (VGGT's qkv and fc1 inputs), the rest the generic one."""
+    rows = 1031 if K == 1024 else (37 if K >= 2048 else 203)
+    X = _heavy(rows, K, 500 + K, dtype)
+    rng = np.random.default_rng(K + 5)
+    signs = (rng.integers(0, 2, K) * 2 - 1).astype(np.int8)
+    c_hat = np.exp(rng.uniform(-1, 1, K))
+    inv = (1.0 / (np.sqrt(K) * c_hat)).astype(np.float32)
+    gamma = np.exp(rng.normal(0, 0.3, K)).astype(np.float32)
+    beta = rng.normal(0, 0.1, K).astype(np.float32)
+    eps = 1e-5
+    Yn = oracle.layernorm(X, gamma, beta, eps, round_to_bf16=(dtype == "bf16"))
+    dx, qx, _ = oracle.rotate_smooth_quant(Yn, 1.0 / (inv.astype(np.float64) * np.sqrt(K)), pre_signs=signs)
+    Xq, sx = G.gpu_ln_rsq(G.to_dev(X), G.to_dev(gamma), G.to_dev(beta), eps, G.to_dev(signs), G.to_dev(inv))
+    _check_ln(Xq, sx, K, qx, dx, dtype, f"K={K} {dtype}")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_layernorm_rotate_quant_optional_and_degenerate(dtype):
+    """No gamma / beta / signs / smoothing; a constant row (variance 0) normalises to zeros: step 0, codes 0; one row."""
+    K, rows, eps = 1024, 67, 1e-6
+    X = _heavy(rows, K, 77, dtype)
+    X[3] = X[3, 0]
+    Yn = oracle.layernorm(X, None, None, eps, round_to_bf16=(dtype == "bf16"))
+    assert not Yn[3].any()
+    dx, qx, _ = oracle.rotate_smooth_quant(Yn)
+    Xq, sx = G.gpu_ln_rsq(G.to_dev(X), None, None, eps, None, None)
+    _check_ln(Xq, sx, K, qx, dx, dtype, dtype)
+    assert sx[3].item() == 0.0 and not G.gpu_unpack(Xq, K)[3].any()
+    Xq1, sx1 = G.gpu_ln_rsq(G.to_dev(X[:1]), None, None, eps, None, None)
+    assert torch.equal(Xq1, Xq[:1]) and torch.equal(sx1, sx[:1])
+    # only beta: a constant row becomes beta itself
+    beta = np.random.default_rng(3).normal(0, 1, K).astype(np.float32)
+    Yb = oracle.layernorm(X[3:4], None, beta, eps, round_to_bf16=(dtype == "bf16"))
+    dxb, qxb, _ = oracle.rotate_smooth_quant(Yb)
+    Xqb, sxb = G.gpu_ln_rsq(G.to_dev(X[3:4]), None, G.to_dev(beta), eps, None, None)
+    G.check_codes(G.gpu_unpack(Xqb, K), qxb)
+    G.check_scales(sxb.cpu().numpy(), dxb)
+
+
+def test_layernorm_rotate_quant_feeds_the_gemm():
+    """End to end: the fused kernel's codes and steps through the integer GEMM against the oracle's LayerNorm + layer."""
+    K, N, rows, eps = 1024, 512, 700, 1e-5
+    rng = np.random.default_rng(21)
+    X = _heavy(rows, K, 22)
+    W = rng.standard_normal((N, K)).astype(np.float32) * 0.05
+    bias = synth.f32_to_bf16_bits(rng.normal(0, 0.1, N).astype(np.float32))
+    gamma = np.exp(rng.normal(0, 0.3, K)).astype(np.float32)
+    beta = rng.normal(0, 0.1, K).astype(np.float32)
+    signs = synth.make_signs(synth.layer_spec(2))[:K]
+    Yn = oracle.layernorm(X, gamma, beta, eps)
+    act = oracle.rotated_col_absmax(Yn, pre_signs=signs)
+    prep_o = oracle.prepare_weights(W, act, pre_signs=signs)
+    want = oracle.linear(Yn, prep_o, bias, pre_signs=signs).Y
+    prep = G.gpu_prep(W, synth.f32_to_bf16_bits(Yn.astype(np.float32)), signs)      # calibrate on the oracle's normalised rows
+    Xq, sx = G.gpu_ln_rsq(G.to_dev(X), G.to_dev(gamma), G.to_dev(beta), eps, prep["signs"], prep["inv"])
+    Y = torch.empty(rows, N, dtype=torch.bfloat16, device=G.DEV)
+    G.q.qvggt_w4a4_gemm(Xq, sx, prep["Wq"], prep["sw"], G.to_dev(bias), rows, N, K, Y)
+    assert G.rel_fro(G.bf16_bits(Y), want) <= G.Y_REL_FRO
+
+
 def test_rotate_quant_static_step_feeds_the_gemm():
     """Codes and echoed steps of the static variant are valid inputs of the integer GEMM."""
     spec = synth.layer_spec(2)

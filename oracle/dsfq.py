@@ -256,6 +256,54 @@ def rotate_smooth_quant(X, c_hat=None, pre_signs=None, post_signs=None, bits: in
     return dx, qx, Xs
 
 
+def quantize_rows_asym(A, bits: int = 4):
+    """Per-row asymmetric (affine) quantizer, the "Asymmetric" setting of the appendix table of further quantization
+    settings; the paper gives no formula, this is the usual min / max one with the range widened to contain 0:
+        lo = min(0, min_j a_j), hi = max(0, max_j a_j), delta = (hi - lo) / (2^bits - 1),
+        zp = rne(-lo / delta), u_j = clamp(rne(a_j / delta) + zp, 0, 2^bits - 1);   a_j ~ delta * (u_j - zp).
+    A row of zeros has delta = 0, zp = 0, u = 0.  Returns (delta [rows] f64, zp [rows] int, u [rows, K] uint8)."""
+    A = _f64(A)
+    levels = (1 << bits) - 1
+    lo = np.minimum(A.min(axis=1), 0.0)
+    hi = np.maximum(A.max(axis=1), 0.0)
+    delta = (hi - lo) / levels
+    safe = np.where(delta > 0, delta, 1.0)
+    zp = np.where(delta > 0, np.rint(-lo / safe), 0.0)
+    u = np.clip(np.rint(A / safe[:, None]) + zp[:, None], 0, levels)
+    u = np.where(delta[:, None] > 0, u, 0.0)
+    return delta, zp.astype(np.int64), u.astype(np.uint8)
+
+
+def weight_code_sums(qw) -> np.ndarray:
+    """sum_j qw[o, j]: what multiplies a token's zero-point offset in the integer product below."""
+    return np.asarray(qw, dtype=np.int64).sum(axis=1)
+
+
+def rotate_smooth_quant_asym(X, c_hat=None, pre_signs=None, post_signs=None, bits: int = 4):
+    """Online half with the asymmetric activation quantizer: returns (dx [M], zp [M], u [M, K] uint8, Xs [M, K] f64)."""
+    Xr = rotate(to_f64(X), pre_signs, post_signs)
+    Xs = Xr if c_hat is None else scale_columns(Xr, c_hat, inverse=True)
+    dx, zp, u = quantize_rows_asym(Xs, bits)
+    return dx, zp, u, Xs
+
+
+def int_gemm_asym(u, zp, qw) -> np.ndarray:
+    """acc[t, o] = sum_j (u[t, j] - zp[t]) * qw[o, j], int64: activations affine, weights symmetric."""
+    e = np.asarray(u, dtype=np.int64) - np.asarray(zp, dtype=np.int64)[:, None]
+    return e @ np.asarray(qw, dtype=np.int64).T
+
+
+def linear_asym(X, prep: "PreparedWeights", bias=None, pre_signs=None, post_signs=None, bits: int = 4):
+    """The layer with asymmetric activation codes (weights keep the symmetric per-channel grid):
+    returns (Y bf16 bits, y f64, acc int64, u, zp, dx)."""
+    dx, zp, u, _ = rotate_smooth_quant_asym(X, prep.c_hat, pre_signs, post_signs, bits)
+    acc = int_gemm_asym(u, zp, prep.qw)
+    y = acc.astype(np.float64) * dx[:, None] * _f64(prep.dw)[None, :]
+    if bias is not None:
+        y = y + to_f64(bias)[None, :]
+    return bf16_from_f64(y), y, acc, u, zp, dx
+
+
 @dataclass
 class LinearResult:
     Y: np.ndarray     # bf16 bits [M, N]

@@ -254,3 +254,107 @@ def test_layernorm_closed_forms_and_library():
     r = oracle.layernorm(X, g, b, eps=1e-5)
     assert np.array_equal(oracle.bf16_bits_to_f64(oracle.bf16_from_f64(r)), r)
     assert np.all(np.abs(r - t) <= np.abs(t) * 2.0 ** -8 + 1e-40) and np.abs(r - t).max() > 0
+
+
+# ----------------------------------------------------------------- asymmetric activation codes (appendix, further settings)
+def test_asymmetric_quantizer_hand_worked_rows():
+    # lo = -3, hi = 12: step 1, zero point 3; 4.5 and -2.5 are ties (to even: 4 and -2)
+    d, zp, u = oracle.quantize_rows_asym(np.array([[-3.0, 12.0, 0.0, 4.5, 5.5, -2.5]]), 4)
+    assert d[0] == 1.0 and zp[0] == 3 and u[0].tolist() == [0, 15, 3, 7, 9, 1]
+    # a row without negative values: the range is [0, hi], zero point 0, unsigned round-to-nearest with step hi / 15
+    d, zp, u = oracle.quantize_rows_asym(np.array([[0.0, 30.0, 2.0, 3.0, 29.0, 14.9]]), 4)
+    assert d[0] == 2.0 and zp[0] == 0 and u[0].tolist() == [0, 15, 1, 2, 14, 7]          # 1.5 -> 2 (even), 14.5 -> 14 (even)
+    # strictly positive values: 0 stays representable, the lowest code is unused
+    d, zp, u = oracle.quantize_rows_asym(np.array([[15.0, 30.0]]), 4)
+    assert d[0] == 2.0 and zp[0] == 0 and u[0].tolist() == [8, 15]
+    # a range symmetric about 0: -lo / step = 7.5, tie to even: zero point 8
+    d, zp, u = oracle.quantize_rows_asym(np.array([[-15.0, 15.0, 0.0, 1.0]]), 4)
+    assert d[0] == 2.0 and zp[0] == 8 and u[0].tolist() == [0, 15, 8, 8]                  # -7.5 -> -8, 7.5 -> 8 clamps at 15
+    # zeros
+    d, zp, u = oracle.quantize_rows_asym(np.zeros((2, 8)), 4)
+    assert not d.any() and not zp.any() and not u.any()
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_asymmetric_quantizer_properties(bits):
+    rng = np.random.default_rng(11)
+    levels = (1 << bits) - 1
+    A = rng.standard_t(3, (60, 192)) * 2.3 + rng.uniform(-3, 6, (60, 1))          # rows with different offsets
+    A[7] = np.abs(A[7])
+    A[8] = -np.abs(A[8])
+    d, zp, u = oracle.quantize_rows_asym(A, bits)
+    lo, hi = np.minimum(A.min(axis=1), 0), np.maximum(A.max(axis=1), 0)
+    assert np.allclose(d, (hi - lo) / levels, rtol=1e-15)
+    assert zp.min() >= 0 and zp.max() <= levels and zp[7] == 0 and zp[8] == levels
+    # nearest grid point: the reconstruction is within half a step everywhere, and no other code does better
+    rec = d[:, None] * (u.astype(np.int64) - zp[:, None])
+    assert np.all(np.abs(A - rec) <= d[:, None] / 2 * (1 + 1e-9))
+    grid = d[:, None, None] * (np.arange(levels + 1)[None, None, :] - zp[:, None, None])       # [rows, 1, codes]
+    best = np.abs(A[:, :, None] - grid).min(axis=2)
+    assert np.allclose(np.abs(A - rec), best, rtol=0, atol=1e-12 * np.abs(A).max())
+    # the extremes take the end codes when the row has both signs
+    both = (A.min(axis=1) < 0) & (A.max(axis=1) > 0)
+    r = np.arange(60)
+    assert np.all(u[r, A.argmin(axis=1)][both] == 0) and np.all(u[r, A.argmax(axis=1)][both] == levels)
+    # scale equivariance (power of two: exact), independence of rows
+    d2, zp2, u2 = oracle.quantize_rows_asym(A * 4.0, bits)
+    assert np.array_equal(u2, u) and np.array_equal(zp2, zp) and np.array_equal(d2, 4.0 * d)
+    # shifting a row by whole steps that keeps 0 inside the range moves the zero point, not the codes
+    x = np.array([[-4.0, 11.0, 0.25, 3.75, -1.5, 7.0]])
+    d0, z0, u0 = oracle.quantize_rows_asym(x, 4)
+    d1, z1, u1 = oracle.quantize_rows_asym(x + 2.0, 4)
+    assert d0[0] == 1.0 and d1[0] == 1.0 and z1[0] == z0[0] - 2 and np.array_equal(u0, u1)
+
+
+def test_asymmetric_codes_halve_the_step_on_one_sided_rows():
+    """On rows without negative values (what a GELU hands on, before any rotation) the affine grid spends all 16 codes on
+    [0, hi] where the symmetric one spends 8: the step is 7 / 15 of the symmetric step and the error falls accordingly."""
+    rng = np.random.default_rng(12)
+    A = np.abs(rng.standard_normal((40, 512)))
+    ds, qs = oracle.quantize_rows(A, 4)
+    da, zp, u = oracle.quantize_rows_asym(A, 4)
+    assert np.allclose(da, ds * 7.0 / 15.0, rtol=1e-15)
+    es = np.sqrt(((A - ds[:, None] * qs) ** 2).mean())
+    ea = np.sqrt(((A - da[:, None] * (u.astype(float) - zp[:, None])) ** 2).mean())
+    assert 0.40 < ea / es < 0.55
+
+
+def test_asymmetric_integer_product_and_its_split():
+    """sum_j (u - zp) qw is the brute-force triple loop, and equals the product of the stored signed codes u - 8 with qw plus
+    (8 - zp) times the weight code sums: the split the integer GEMM uses."""
+    rng = np.random.default_rng(13)
+    M, N, K = 9, 7, 32
+    u = rng.integers(0, 16, (M, K)).astype(np.uint8)
+    zp = rng.integers(0, 16, M)
+    qw = rng.integers(-8, 8, (N, K)).astype(np.int8)
+    acc = oracle.int_gemm_asym(u, zp, qw)
+    want = np.zeros((M, N), dtype=np.int64)
+    for t in range(M):
+        for o in range(N):
+            for j in range(K):
+                want[t, o] += (int(u[t, j]) - int(zp[t])) * int(qw[o, j])
+    assert np.array_equal(acc, want)
+    stored = (u.astype(np.int16) - 8).astype(np.int8)
+    split = oracle.int_gemm(stored, qw).astype(np.int64) + (8 - zp)[:, None] * oracle.weight_code_sums(qw)[None, :]
+    assert np.array_equal(acc, split)
+
+
+def test_asymmetric_layer_approximates_the_float_layer():
+    """End to end on one-sided inputs with a common offset (post-GELU-like rows keep a large mean after the rotation only in
+    column 0; the affine grid absorbs it): the asymmetric layer's error against X W^T + b is below the symmetric layer's."""
+    rng = np.random.default_rng(14)
+    M, N, K = 48, 40, 256
+    X = np.abs(rng.standard_normal((M, K))) + 0.5
+    W = rng.standard_normal((N, K)) * 0.05
+    b = rng.standard_normal(N) * 0.1
+    prep = oracle.prepare_weights(W, oracle.rotated_col_absmax(X))
+    ref = X @ W.T + b
+    ys = oracle.linear(X, prep, b).y
+    _, ya, acc, u, zp, dx = oracle.linear_asym(X, prep, b)
+    es, ea = np.linalg.norm(ys - ref) / np.linalg.norm(ref), np.linalg.norm(ya - ref) / np.linalg.norm(ref)
+    assert ea < es and ea < 0.2
+    # the integer accumulators reproduce the dequantized product exactly
+    Xs = oracle.scale_columns(oracle.rotate(X), prep.c_hat, inverse=True)
+    rec = dx[:, None] * (u.astype(np.float64) - zp[:, None])
+    assert np.all(np.abs(Xs - rec) <= dx[:, None] / 2 * (1 + 1e-9))
+    assert np.allclose(ya - b, (rec @ (prep.qw.astype(np.float64) * prep.dw[:, None]).T), rtol=1e-12, atol=1e-12)

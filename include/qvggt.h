@@ -117,6 +117,30 @@ int qvggt_rotate_smooth_quant_static(const void *X, int x_dtype, int M, int K, c
                                      uint8_t *Xq, float *x_scale, void *stream);
 
 /*
+ * The asymmetric setting (appendix, table of further quantization settings: "QuantVGGT (Asymmetric)", W4A4).  The paper
+ * gives no formula; this is the usual affine quantizer on the activations, per token and dynamic like Eq. 3's, while the
+ * weights keep their symmetric per-channel grid:
+ *     z = X H diag(c)^-1 (as in kernel 1),  lo_t = min(0, min_j z_tj),  hi_t = max(0, max_j z_tj),
+ *     x_scale[t] = (hi_t - lo_t) / 15,  x_zero[t] = rne(-lo_t / x_scale[t]) in [0, 15],
+ *     u_tj = clamp(rne(z_tj / x_scale[t]) + x_zero[t], 0, 15),          z_tj ~ x_scale[t] * (u_tj - x_zero[t]).
+ * Xq holds the signed value u - 8 in each nibble (same layout as qvggt_rotate_smooth_quant), so that the integer product
+ * is the symmetric one, and the GEMM adds what is missing from
+ *     sum_j (u_tj - zp_t) qw_oj = sum_j (u_tj - 8) qw_oj + (8 - zp_t) * w_codesum[o],     w_codesum[o] = sum_j qw_oj
+ * in its epilogue (all terms are integers below 2^24 in magnitude, or multiples of 256 below 2^27: exact in fp32):
+ *     Y[t, o] = bf16_rne( (acc[t, o] + (8 - x_zero[t]) * w_codesum[o]) * x_scale[t] * w_scale[o] + bias[o] ).
+ * A row of zeros has x_scale = 0, x_zero = 0, u = 0.  x_zero: f32 [M] (integer values).  w_codesum: f32 [N].
+ * qvggt_rotate_smooth_quant_asym: K a power of two in [128, 8192]; other arguments and errors as
+ * qvggt_rotate_smooth_quant.  qvggt_weight_code_sums: Wq as written by qvggt_prep_weights (any supported K), offline.
+ * qvggt_w4a4_gemm_asym: as qvggt_w4a4_gemm without the accumulator dump.
+ */
+int qvggt_rotate_smooth_quant_asym(const void *X, int x_dtype, int M, int K, const int8_t *signs, const float *inv_smooth,
+                                   uint8_t *Xq, float *x_scale, float *x_zero, void *stream);
+int qvggt_weight_code_sums(const uint8_t *Wq, int N, int K, float *w_codesum, void *stream);
+int qvggt_w4a4_gemm_asym(const uint8_t *Xq, const float *x_scale, const float *x_zero, const uint8_t *Wq,
+                         const float *w_scale, const float *w_codesum, const void *bias, int M, int N, int K, void *Y,
+                         void *stream);
+
+/*
  * Online kernel 1 with the LayerNorm that precedes the layer fused in (VGGT's qkv and fc1 inputs; Sec. 3.2 names the
  * neighbouring normalization layer as the place where per-channel factors can live).  Per token, before the rotation:
  *     y = (x - mean) / sqrt(var + eps) * gamma + beta      (mean, population variance over the K channels, fp32),

@@ -14,6 +14,9 @@ from .binding import (  # noqa: F401
     qvggt_rotate_smooth_quant,
     qvggt_rotate_smooth_quant_static,
     qvggt_layernorm_rotate_smooth_quant,
+    qvggt_rotate_smooth_quant_asym,
+    qvggt_weight_code_sums,
+    qvggt_w4a4_gemm_asym,
     qvggt_w4a4_gemm,
     qvggt_linear,
     qvggt_workspace_bytes,

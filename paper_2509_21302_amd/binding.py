@@ -17,6 +17,7 @@ QVGGT_BF16, QVGGT_F32 = 0, 1
 EXPORTS = [
     "qvggt_status_string", "qvggt_rotated_col_absmax", "qvggt_prep_weights", "qvggt_rotate_smooth_quant",
     "qvggt_rotate_smooth_quant_static", "qvggt_layernorm_rotate_smooth_quant",
+    "qvggt_rotate_smooth_quant_asym", "qvggt_weight_code_sums", "qvggt_w4a4_gemm_asym",
     "qvggt_w4a4_gemm", "qvggt_linear", "qvggt_workspace_bytes", "qvggt_pack_int4", "qvggt_unpack_int4",
     "qvggt_prep_weights_i8", "qvggt_rotate_smooth_quant_i8", "qvggt_i8_gemm", "qvggt_linear_i8",
     "qvggt_workspace_bytes_i8", "qvggt_layout_int8",
@@ -60,6 +61,12 @@ def load_library() -> C.CDLL:
     lib.qvggt_rotate_smooth_quant_static.argtypes = [vp, i, i, i, vp, vp, vp, i, vp, vp, vp]
     lib.qvggt_layernorm_rotate_smooth_quant.restype = i
     lib.qvggt_layernorm_rotate_smooth_quant.argtypes = [vp, i, i, i, vp, vp, f, vp, vp, vp, vp, vp]
+    lib.qvggt_rotate_smooth_quant_asym.restype = i
+    lib.qvggt_rotate_smooth_quant_asym.argtypes = [vp, i, i, i, vp, vp, vp, vp, vp, vp]
+    lib.qvggt_weight_code_sums.restype = i
+    lib.qvggt_weight_code_sums.argtypes = [vp, i, i, vp, vp]
+    lib.qvggt_w4a4_gemm_asym.restype = i
+    lib.qvggt_w4a4_gemm_asym.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, vp, vp]
     lib.qvggt_w4a4_gemm.restype = i
     lib.qvggt_w4a4_gemm.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp, vp, vp]
     lib.qvggt_linear.restype = i
@@ -169,6 +176,22 @@ def qvggt_layernorm_rotate_smooth_quant(X, gamma, beta, eps, signs, inv_smooth, 
     _check(load_library().qvggt_layernorm_rotate_smooth_quant(_ptr(X), _dtype_code(X), M, K, _ptr(gamma), _ptr(beta), float(eps),
                                                               _ptr(signs), _ptr(inv_smooth), _ptr(Xq), _ptr(x_scale),
                                                               _stream(stream)), "qvggt_layernorm_rotate_smooth_quant")
+
+
+def qvggt_rotate_smooth_quant_asym(X, signs, inv_smooth, Xq, x_scale, x_zero, stream=None):
+    M, K = X.shape
+    _check(load_library().qvggt_rotate_smooth_quant_asym(_ptr(X), _dtype_code(X), M, K, _ptr(signs), _ptr(inv_smooth), _ptr(Xq),
+                                                         _ptr(x_scale), _ptr(x_zero), _stream(stream)),
+           "qvggt_rotate_smooth_quant_asym")
+
+
+def qvggt_weight_code_sums(Wq, N, K, w_codesum, stream=None):
+    _check(load_library().qvggt_weight_code_sums(_ptr(Wq), N, K, _ptr(w_codesum), _stream(stream)), "qvggt_weight_code_sums")
+
+
+def qvggt_w4a4_gemm_asym(Xq, x_scale, x_zero, Wq, w_scale, w_codesum, bias, M, N, K, Y, stream=None):
+    _check(load_library().qvggt_w4a4_gemm_asym(_ptr(Xq), _ptr(x_scale), _ptr(x_zero), _ptr(Wq), _ptr(w_scale), _ptr(w_codesum),
+                                               _ptr(bias), M, N, K, _ptr(Y), _stream(stream)), "qvggt_w4a4_gemm_asym")
 
 
 def qvggt_w4a4_gemm(Xq, x_scale, Wq, w_scale, bias, M, N, K, Y, acc_debug=None, stream=None):

@@ -18,6 +18,11 @@ hipError_t run_unpack_int4(const uint8_t *packed, int rows, int K, int8_t *codes
 bool general_size_supported(int K);
 hipError_t run_ln_rotate_smooth_quant(const void *X, bool f32, int rows, int K, LnParams ln, const int8_t *signs, const float *mul,
                                       uint8_t *packed, float *scale, hipStream_t stream);
+hipError_t run_rotate_smooth_quant_asym(const void *X, bool f32, int rows, int K, const int8_t *signs, const float *mul,
+                                        uint8_t *packed, float *scale, float *zero, hipStream_t stream);
+hipError_t run_code_sums(const uint8_t *packed, int rows, int K, float *sums, hipStream_t stream);
+hipError_t run_w4a4_gemm_asym(const uint8_t *Xq, const float *sx, const float *xzero, const uint8_t *Wq, const float *sw,
+                              const float *wsum, const void *bias, int M, int N, int K, void *Y, hipStream_t stream);
 hipError_t run_layout_int8(const int8_t *src, int rows, int K, int8_t *dst, int to_library, hipStream_t stream);
 hipError_t run_w4a4_gemm(const uint8_t *Xq, const float *sx, const uint8_t *Wq, const float *sw, const void *bias,
                          int M, int N, int K, void *Y, int32_t *acc_debug, hipStream_t stream);
@@ -186,6 +191,41 @@ int qvggt_w4a4_gemm(const uint8_t *Xq, const float *x_scale, const uint8_t *Wq, 
         return QVGGT_ERR_ALIGN;
     return hip_status(qvggt::run_w4a4_gemm(Xq, x_scale, Wq, w_scale, bias, M, N, K, Y, acc_debug,
                                            static_cast<hipStream_t>(stream)));
+}
+
+int qvggt_rotate_smooth_quant_asym(const void *X, int x_dtype, int M, int K, const int8_t *signs, const float *inv_smooth,
+                                   uint8_t *Xq, float *x_scale, float *x_zero, void *stream)
+{
+    if (!valid_dtype(x_dtype)) return QVGGT_ERR_DTYPE;
+    if (M < 0 || K < qvggt::kMinK || K > qvggt::kMaxK || (K & (K - 1)) != 0) return QVGGT_ERR_SHAPE;   // powers of two only
+    if (M == 0) return QVGGT_OK;
+    if (!X || !Xq || !x_scale || !x_zero) return QVGGT_ERR_NULL;
+    if (!aligned16(X) || !aligned16(Xq) || !aligned16(x_scale) || !aligned16(x_zero) || !aligned16(inv_smooth) || !aligned16(signs))
+        return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_rotate_smooth_quant_asym(X, x_dtype == QVGGT_F32, M, K, signs, inv_smooth, Xq, x_scale, x_zero,
+                                                          static_cast<hipStream_t>(stream)));
+}
+
+int qvggt_weight_code_sums(const uint8_t *Wq, int N, int K, float *w_codesum, void *stream)
+{
+    if (N < 0 || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (N == 0) return QVGGT_OK;
+    if (!Wq || !w_codesum) return QVGGT_ERR_NULL;
+    if (!aligned16(Wq) || !aligned16(w_codesum)) return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_code_sums(Wq, N, K, w_codesum, static_cast<hipStream_t>(stream)));
+}
+
+int qvggt_w4a4_gemm_asym(const uint8_t *Xq, const float *x_scale, const float *x_zero, const uint8_t *Wq, const float *w_scale,
+                         const float *w_codesum, const void *bias, int M, int N, int K, void *Y, void *stream)
+{
+    if (M < 0 || !valid_n(N) || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (M == 0) return QVGGT_OK;
+    if (!Xq || !x_scale || !x_zero || !Wq || !w_scale || !w_codesum || !Y) return QVGGT_ERR_NULL;
+    if (!aligned16(Xq) || !aligned16(x_scale) || !aligned16(x_zero) || !aligned16(Wq) || !aligned16(w_scale) ||
+        !aligned16(w_codesum) || !aligned16(bias) || !aligned16(Y))
+        return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_w4a4_gemm_asym(Xq, x_scale, x_zero, Wq, w_scale, w_codesum, bias, M, N, K, Y,
+                                                static_cast<hipStream_t>(stream)));
 }
 
 int qvggt_i8_gemm(const int8_t *Xq, const float *x_scale, const int8_t *Wq, const float *w_scale, const void *bias,

@@ -55,7 +55,8 @@ namespace {
 constexpr int KT_BYTES = 64;       // packed bytes per row per K-tile: 128 codes = 4 MFMA K-steps = 2 pairs
 
 // TM x TN: 32x32 sub-tiles per wave along tokens / channels; WM x WN: waves per block; STAGES: LDS ring depth
-template <int TM, int TN, int WM, int WN, int STAGES>
+// ASYM: the per-tile scale area also carries the tokens' zero points and the channels' weight code sums
+template <int TM, int TN, int WM, int WN, int STAGES, bool ASYM = false>
 struct StreamCfg {
     static constexpr int NW = WM * WN, THREADS = NW * 64;
     static constexpr int BM = WM * TM * 32, BN = WN * TN * 32, ROWS = BM + BN;
@@ -63,8 +64,10 @@ struct StreamCfg {
     static constexpr int GROUPS = ROWS / 16;            // 16-row groups: one wave-wide transfer instruction each
     static constexpr int LPW = GROUPS / NW;             // transfers per wave per K-tile
     static constexpr int NM = TM * TN, NF = TM + TN;
-    static constexpr int SC_BYTES = BM * 4 + BN * 4 + BN * 2;   // per tile: sx f32, sw f32, bias bf16 (as in memory)
-    static constexpr int SC_GROUPS = BM / 64 + BN / 64 + BN / 128;
+    static constexpr int SC_SYM_BYTES = BM * 4 + BN * 4 + BN * 2;   // per tile: sx f32, sw f32, bias bf16 (as in memory)
+    static constexpr int SC_SYM_GROUPS = BM / 64 + BN / 64 + BN / 128;
+    static constexpr int SC_BYTES = SC_SYM_BYTES + (ASYM ? BM * 4 + BN * 4 : 0);        // then zero points f32, code sums f32
+    static constexpr int SC_GROUPS = SC_SYM_GROUPS + (ASYM ? BM / 64 + BN / 64 : 0);
     static constexpr int EP_PITCH = 128 + 16;           // bytes per token row of a wave's epilogue staging tile (64 channels + pad)
     static constexpr int EP_BYTES = NW * 32 * EP_PITCH;
     static constexpr int LDS_BYTES = STAGES * STAGE_BYTES + 2 * SC_BYTES + EP_BYTES;
@@ -128,13 +131,16 @@ __device__ inline void wait_vmcnt()
 }  // namespace
 
 // CB: bits a stored code occupies: 4 (two codes per byte, expanded in registers) or 8 (int8 codes, fed to the MFMA as read)
-template <int TM, int TN, int WM, int WN, int STAGES, int MINB, int CB, bool DEBUG>
+// ASYM: activations carry affine codes u with a zero point per token, stored as u - 8 (Xq) and zp (xzero); the epilogue adds
+// (8 - zp[t]) * wsum[o] (wsum[o] = sum_j qw[o, j], exact in fp32) to the accumulator before the scales
+template <int TM, int TN, int WM, int WN, int STAGES, int MINB, int CB, bool DEBUG, bool ASYM = false>
 __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per_eu(WM * WN * MINB / 4, WM * WN * MINB / 4))) void w4a4_gemm_kernel(
     const uint8_t *__restrict__ Xq, const float *__restrict__ sx, const uint8_t *__restrict__ Wq,
     const float *__restrict__ sw, const uint16_t *__restrict__ bias, int M, int N, int K,
-    uint16_t *__restrict__ Y, int32_t *__restrict__ acc_debug, int tiles_m, int tiles_n, long long *dbg_times)
+    uint16_t *__restrict__ Y, int32_t *__restrict__ acc_debug, int tiles_m, int tiles_n, long long *dbg_times,
+    const float *__restrict__ xzero = nullptr, const float *__restrict__ wsum = nullptr)
 {
-    using C = StreamCfg<TM, TN, WM, WN, STAGES>;
+    using C = StreamCfg<TM, TN, WM, WN, STAGES, ASYM>;
     constexpr int NM = C::NM, NF = C::NF, LPW = C::LPW;
     constexpr int DMA_SHIFT = (LPW > 4) ? 4096 : 0;             // keeps the transfers' instruction offsets inside [-4096, 4095]
     static_assert(LPW <= 8, "instruction offsets of a wave's transfers must fit 13 signed bits");
@@ -216,10 +222,18 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
             } else if (g < C::BM / 64 + C::BN / 64) {
                 const int h = g - C::BM / 64;
                 dma4(sw + min(tn * C::BN + h * 64 + lane, N - 1), dst + C::BM * 4 + h * 256);
-            } else if (bias != nullptr) {
-                const int h = g - C::BM / 64 - C::BN / 64;      // 64 dwords = 128 bf16 values
-                dma4(reinterpret_cast<const uint32_t *>(bias) + min(tn * (C::BN / 2) + h * 64 + lane, N / 2 - 1),
-                     dst + C::BM * 4 + C::BN * 4 + h * 256);
+            } else if (g < C::SC_SYM_GROUPS) {
+                if (bias != nullptr) {
+                    const int h = g - C::BM / 64 - C::BN / 64;      // 64 dwords = 128 bf16 values
+                    dma4(reinterpret_cast<const uint32_t *>(bias) + min(tn * (C::BN / 2) + h * 64 + lane, N / 2 - 1),
+                         dst + C::BM * 4 + C::BN * 4 + h * 256);
+                }
+            } else if (g < C::SC_SYM_GROUPS + C::BM / 64) {
+                const int h = g - C::SC_SYM_GROUPS;
+                dma4(xzero + min(tm * C::BM + h * 64 + lane, M - 1), dst + C::SC_SYM_BYTES + h * 256);
+            } else {
+                const int h = g - C::SC_SYM_GROUPS - C::BM / 64;
+                dma4(wsum + min(tn * C::BN + h * 64 + lane, N - 1), dst + C::SC_SYM_BYTES + C::BM * 4 + h * 256);
             }
         }
     };
@@ -385,6 +399,14 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
         float sxm[TM];
 #pragma unroll
         for (int i = 0; i < TM; ++i) sxm[i] = scx[(wm * TM + i) * 32 + c] * (CB == 4 ? 1.0f / 256.0f : 1.0f);
+        // affine activation codes: (8 - zp) of this lane's tokens, in the accumulator's units (256 per unit for packed codes)
+        const float *scz = reinterpret_cast<const float *>(sc + C::SC_SYM_BYTES);
+        const float *scs = reinterpret_cast<const float *>(sc + C::SC_SYM_BYTES + C::BM * 4) + wn * TN * 32 + 4 * g;
+        float rz[ASYM ? TM : 1];
+        if constexpr (ASYM) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) rz[i] = (8.0f - scz[(wm * TM + i) * 32 + c]) * (CB == 4 ? 256.0f : 1.0f);
+        }
         {
             // A wave-private LDS tile [32 tokens][64 channels] turns the lane-per-token layout into rows, so
             // that a store instruction writes whole 128-byte lines (8 lanes x 16 bytes per token).  Whole lines can be
@@ -393,12 +415,13 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
             const int rd_row = lane >> 3, rd_col = lane & 7;
 #pragma unroll
             for (int jp = 0; jp < TN / 2; ++jp) {
-                float4 swq[2][4], bq[2][4];
+                float4 swq[2][4], bq[2][4], wsq[ASYM ? 2 : 1][ASYM ? 4 : 1];
 #pragma unroll
                 for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         swq[jj][q] = *reinterpret_cast<const float4 *>(scw + (2 * jp + jj) * 32 + 8 * q);
+                        if constexpr (ASYM) wsq[jj][q] = *reinterpret_cast<const float4 *>(scs + (2 * jp + jj) * 32 + 8 * q);
                         const uint2 b = *reinterpret_cast<const uint2 *>(scb + (2 * jp + jj) * 32 + 8 * q);
                         bq[jj][q] = make_float4(__uint_as_float(b.x << 16), __uint_as_float(b.x & 0xFFFF0000u),
                                                 __uint_as_float(b.y << 16), __uint_as_float(b.y & 0xFFFF0000u));
@@ -423,8 +446,13 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
                             asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a1) : "a"(acc[2 * jp + jj][i][4 * q + 1]));
                             asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a2) : "a"(acc[2 * jp + jj][i][4 * q + 2]));
                             asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a3) : "a"(acc[2 * jp + jj][i][4 * q + 3]));
-                            const float y0 = fmaf((float)a0, sc[jj][q].x, bq[jj][q].x), y1 = fmaf((float)a1, sc[jj][q].y, bq[jj][q].y);
-                            const float y2 = fmaf((float)a2, sc[jj][q].z, bq[jj][q].z), y3 = fmaf((float)a3, sc[jj][q].w, bq[jj][q].w);
+                            float f0 = (float)a0, f1 = (float)a1, f2 = (float)a2, f3 = (float)a3;
+                            if constexpr (ASYM) {      // integers below 2^27 that are multiples of 256 (packed codes), or below 2^24: exact
+                                f0 = fmaf(rz[i], wsq[jj][q].x, f0); f1 = fmaf(rz[i], wsq[jj][q].y, f1);
+                                f2 = fmaf(rz[i], wsq[jj][q].z, f2); f3 = fmaf(rz[i], wsq[jj][q].w, f3);
+                            }
+                            const float y0 = fmaf(f0, sc[jj][q].x, bq[jj][q].x), y1 = fmaf(f1, sc[jj][q].y, bq[jj][q].y);
+                            const float y2 = fmaf(f2, sc[jj][q].z, bq[jj][q].z), y3 = fmaf(f3, sc[jj][q].w, bq[jj][q].w);
                             *reinterpret_cast<uint2 *>(ep + c * C::EP_PITCH + (jj * 32 + 8 * q + 4 * g) * 2) = make_uint2(pack_bf16x2(y0, y1), pack_bf16x2(y2, y3));
                             if constexpr (DEBUG) {
                                 const int m = row0 + i * 32 + c, n = col0 + (2 * jp + jj) * 32 + 8 * q + 4 * g;
@@ -468,11 +496,12 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
     wait_vmcnt<0>();        // transfers issued past the last tile must not outlive the block's LDS allocation
 }
 
-template <int TM, int TN, int WM, int WN, int STAGES, int MINB, int CB>
+template <int TM, int TN, int WM, int WN, int STAGES, int MINB, int CB, bool ASYM = false>
 static hipError_t launch_gemm(const uint8_t *Xq, const float *sx, const uint8_t *Wq, const float *sw, const void *bias,
-                              int M, int N, int K, void *Y, int32_t *acc_debug, hipStream_t stream)
+                              int M, int N, int K, void *Y, int32_t *acc_debug, hipStream_t stream,
+                              const float *xzero = nullptr, const float *wsum = nullptr)
 {
-    using C = StreamCfg<TM, TN, WM, WN, STAGES>;
+    using C = StreamCfg<TM, TN, WM, WN, STAGES, ASYM>;
     long long *dbg = nullptr;
 #ifdef QVGGT_DEV
     // development builds: QVGGT_TIMING=1 reinterprets acc_debug as a buffer for per-wave cycle counters
@@ -483,7 +512,12 @@ static hipError_t launch_gemm(const uint8_t *Xq, const float *sx, const uint8_t 
 #endif
     // the variant that also writes the raw accumulators is a separate instantiation: the production kernel carries none of it
     const bool debug = acc_debug != nullptr;
-    auto kern = debug ? w4a4_gemm_kernel<TM, TN, WM, WN, STAGES, MINB, CB, true> : w4a4_gemm_kernel<TM, TN, WM, WN, STAGES, MINB, CB, false>;
+    auto kern = w4a4_gemm_kernel<TM, TN, WM, WN, STAGES, MINB, CB, false, ASYM>;
+    if constexpr (!ASYM) {
+        if (debug) kern = w4a4_gemm_kernel<TM, TN, WM, WN, STAGES, MINB, CB, true, false>;
+    } else {
+        if (debug) return hipErrorInvalidValue;      // no accumulator dump with affine codes: the corrected sum is never an integer register
+    }
     static bool attr_set[2] = {false, false};
     if (!attr_set[debug]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
@@ -495,7 +529,7 @@ static hipError_t launch_gemm(const uint8_t *Xq, const float *sx, const uint8_t 
     int grid = 256 * MINB;                                // MINB resident blocks on each of the 256 compute units
     if (grid > (ntiles + 7) / 8 * 8) grid = (ntiles + 7) / 8 * 8;
     kern<<<grid, C::THREADS, C::LDS_BYTES, stream>>>(Xq, sx, Wq, sw, reinterpret_cast<const uint16_t *>(bias), M, N, K,
-                                                     reinterpret_cast<uint16_t *>(Y), acc_debug, tiles_m, tiles_n, dbg);
+                                                     reinterpret_cast<uint16_t *>(Y), acc_debug, tiles_m, tiles_n, dbg, xzero, wsum);
     return hipGetLastError();
 }
 
@@ -504,19 +538,22 @@ static hipError_t launch_gemm(const uint8_t *Xq, const float *sx, const uint8_t 
 // that fill whole rounds go to the big kernel and the remaining rows, when they fit better there, to the small configuration
 // (128 x 128 per block, two blocks per compute unit) in a second launch on the same stream.  Rows are independent, the two
 // launches write disjoint rows of Y.
-template <int CB>
+template <int CB, bool ASYM = false>
 static hipError_t gemm_by_rounds(const uint8_t *Xq, const float *sx, const uint8_t *Wq, const float *sw, const void *bias,
-                                 int M, int N, int K, void *Y, int32_t *acc_debug, hipStream_t stream)
+                                 int M, int N, int K, void *Y, int32_t *acc_debug, hipStream_t stream,
+                                 const float *xzero = nullptr, const float *wsum = nullptr)
 {
     auto big = [&](int row0, int rows) {
-        return launch_gemm<4, 4, 2, 2, 4, 1, CB>(Xq + (size_t)row0 * (CB == 4 ? K / 2 : K), sx + row0, Wq, sw, bias, rows, N, K,
-                                                 static_cast<uint16_t *>(Y) + (size_t)row0 * N,
-                                                 acc_debug ? acc_debug + (size_t)row0 * N : nullptr, stream);
+        return launch_gemm<4, 4, 2, 2, 4, 1, CB, ASYM>(Xq + (size_t)row0 * (CB == 4 ? K / 2 : K), sx + row0, Wq, sw, bias, rows, N, K,
+                                                       static_cast<uint16_t *>(Y) + (size_t)row0 * N,
+                                                       acc_debug ? acc_debug + (size_t)row0 * N : nullptr, stream,
+                                                       ASYM ? xzero + row0 : nullptr, wsum);
     };
     auto small = [&](int row0, int rows) {
-        return launch_gemm<2, 2, 2, 2, 3, 2, CB>(Xq + (size_t)row0 * (CB == 4 ? K / 2 : K), sx + row0, Wq, sw, bias, rows, N, K,
-                                                 static_cast<uint16_t *>(Y) + (size_t)row0 * N,
-                                                 acc_debug ? acc_debug + (size_t)row0 * N : nullptr, stream);
+        return launch_gemm<2, 2, 2, 2, 3, 2, CB, ASYM>(Xq + (size_t)row0 * (CB == 4 ? K / 2 : K), sx + row0, Wq, sw, bias, rows, N, K,
+                                                       static_cast<uint16_t *>(Y) + (size_t)row0 * N,
+                                                       acc_debug ? acc_debug + (size_t)row0 * N : nullptr, stream,
+                                                       ASYM ? xzero + row0 : nullptr, wsum);
     };
     const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
     const long long big_tiles = (long long)tiles_m * tiles_n;
@@ -556,6 +593,14 @@ hipError_t run_w4a4_gemm(const uint8_t *Xq, const float *sx, const uint8_t *Wq, 
     }
 #endif
     return gemm_by_rounds<4>(Xq, sx, Wq, sw, bias, M, N, K, Y, acc_debug, stream);
+}
+
+// Packed 4-bit codes with affine activations: Xq holds u - 8, xzero the zero points, wsum the weights' code sums per channel.
+hipError_t run_w4a4_gemm_asym(const uint8_t *Xq, const float *sx, const float *xzero, const uint8_t *Wq, const float *sw,
+                              const float *wsum, const void *bias, int M, int N, int K, void *Y, hipStream_t stream)
+{
+    if (M <= 0) return hipSuccess;
+    return gemm_by_rounds<4, true>(Xq, sx, Wq, sw, bias, M, N, K, Y, nullptr, stream, xzero, wsum);
 }
 
 // The same kernel on int8 codes (8- and 6-bit settings): rows of K bytes, no expansion, two K-steps per K-tile.

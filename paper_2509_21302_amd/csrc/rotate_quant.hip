@@ -96,7 +96,8 @@ enum RowMode { kQuantize = 0, kColAbsMax = 1 };
 // mul_mode 1: 1 / (K * mul[j])   (weights: c_j / sqrt(K) recovered from inv_smooth)
 // CB: bits a stored code occupies (4: two per byte; 8: one int8 each).  qmax: largest code, 2^(bits-1) - 1.
 // LN: a LayerNorm of the row precedes everything else (quantize mode, K <= 4096: beyond that the row no longer fits the registers)
-template <int K, bool F32, int MODE, int CB, bool LN = false>
+// ASYM: affine 4-bit codes over the row's range [min(0, min z), max(0, max z)], zero point to zero[row], nibbles hold u - 8
+template <int K, bool F32, int MODE, int CB, bool LN = false, bool ASYM = false>
 __global__ __launch_bounds__(256) void rotate_rows_kernel(const void *__restrict__ X, int rows,
                                                           const int8_t *__restrict__ signs,
                                                           const float *__restrict__ mul, int mul_mode,
@@ -104,7 +105,7 @@ __global__ __launch_bounds__(256) void rotate_rows_kernel(const void *__restrict
                                                           float *__restrict__ scale,
                                                           unsigned int *__restrict__ col_absmax_bits,
                                                           const float *__restrict__ step, int step_stride, float qmax,
-                                                          LnParams ln)
+                                                          LnParams ln, float *__restrict__ zero = nullptr)
 {
     constexpr int V = RowMap<K>::V, C = RowMap<K>::C, R = RowMap<K>::R;
     constexpr bool kPermuted = (K == 1024 || K == 2048 || K == 4096) && MODE == kQuantize;
@@ -177,9 +178,13 @@ __global__ __launch_bounds__(256) void rotate_rows_kernel(const void *__restrict
         for (int r = 0; r < R; ++r)
             if ((neg[r >> 5] >> (r & 31)) & 1u) x[r] = -x[r];
         fwht_row<K>(x, lane);
-        float amax = 0.0f;
+        float amax = 0.0f, nmin = 0.0f;       // ASYM: max(0, max z) and -min(0, min z)
 #pragma unroll
-        for (int r = 0; r < R; ++r) { x[r] *= cm[r]; amax = fmaxf(amax, fabsf(x[r])); }
+        for (int r = 0; r < R; ++r) {
+            x[r] *= cm[r];
+            if constexpr (ASYM) { amax = fmaxf(amax, x[r]); nmin = fmaxf(nmin, -x[r]); }
+            else amax = fmaxf(amax, fabsf(x[r]));
+        }
 
         if constexpr (MODE == kColAbsMax) {
             // the wave keeps a running maximum over its rows; one atomic per column after the loop
@@ -187,8 +192,16 @@ __global__ __launch_bounds__(256) void rotate_rows_kernel(const void *__restrict
             for (int r = 0; r < R; ++r) colmax[r] = fmaxf(colmax[r], fabsf(x[r]));
         } else {
             // dynamic: the step comes from the row's absmax; static: it is given (per token or one for the tensor)
-            float inv, delta;
-            if (step != nullptr) {
+            float inv, delta, off = 0.0f;
+            if constexpr (ASYM) {
+                const float hi = wave_max(amax), nlo = wave_max(nmin);
+                const float range = hi + nlo;
+                delta = range / 15.0f;
+                inv = range > 0.0f ? 15.0f / range : 0.0f;
+                const float zp = __builtin_rintf(nlo * inv);                  // rne(-lo / step), in [0, 15]
+                off = zp - 8.0f;
+                if (lane == 0) zero[row] = zp;
+            } else if (step != nullptr) {
                 delta = step[(size_t)row * step_stride];
                 inv = delta > 0.0f ? 1.0f / delta : 0.0f;
             } else {
@@ -207,7 +220,7 @@ __global__ __launch_bounds__(256) void rotate_rows_kernel(const void *__restrict
                 for (int c = 0; c < C; ++c)
 #pragma unroll
                     for (int i = 0; i < V; ++i) {
-                        int q = (int)__builtin_rintf(x[c * V + i] * inv);
+                        int q = (int)__builtin_rintf(ASYM ? fmaf(x[c * V + i], inv, off) : x[c * V + i] * inv);
                         q = min(q_hi, max(q_lo, q));
                         stage[code_position(c * 64 * V + lane * V + i, K)] = (uint8_t)(CB == 4 ? (q & 0xF) : q);
                     }
@@ -235,7 +248,7 @@ __global__ __launch_bounds__(256) void rotate_rows_kernel(const void *__restrict
                 uint64_t word = 0;
 #pragma unroll
                 for (int i = 0; i < V; ++i) {
-                    int q = (int)__builtin_rintf(x[c * V + i] * inv);
+                    int q = (int)__builtin_rintf(ASYM ? fmaf(x[c * V + i], inv, off) : x[c * V + i] * inv);
                     q = min(q_hi, max(q_lo, q));
                     word |= (uint64_t)(q & ((1 << CB) - 1)) << (CB * i);
                 }
@@ -312,6 +325,24 @@ __global__ void unpack_int4_kernel(const uint8_t *__restrict__ packed, size_t ro
 }
 
 // int8 codes: natural order <-> the library's position order (the same map as for packed rows, one byte per position)
+// sums[o] = sum_j code[o, j] over a row of packed 4-bit codes (any position order): one wave per row
+__global__ __launch_bounds__(256) void code_sums_kernel(const uint8_t *__restrict__ packed, int rows, int K, float *__restrict__ sums)
+{
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const uint32_t *p = reinterpret_cast<const uint32_t *>(packed + (size_t)row * (K / 2));
+    int s = 0;
+    for (int i = lane; i < K / 8; i += 64) {
+        const uint32_t v = p[i];
+#pragma unroll
+        for (int n = 0; n < 8; ++n) s += (int)(v << (28 - 4 * n)) >> 28;      // sign-extended nibble n
+    }
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) s += __shfl_xor(s, m);
+    if (lane == 0) sums[row] = (float)s;                                        // |s| <= 8 K: exact
+}
+
 __global__ void layout_int8_kernel(const int8_t *__restrict__ src, size_t rows, int K, int8_t *__restrict__ dst, int to_library)
 {
     size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // one output byte each
@@ -414,6 +445,38 @@ hipError_t run_ln_rotate_smooth_quant(const void *X, bool f32, int rows, int K, 
     return hipGetLastError();
 }
 
+hipError_t run_rotate_quant_asym_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, uint8_t *packed,
+                                      float *scale, float *zero, hipStream_t stream);
+
+// rotation + smoothing + per-token affine 4-bit codes with zero points (power-of-two K)
+hipError_t run_rotate_smooth_quant_asym(const void *X, bool f32, int rows, int K, const int8_t *signs, const float *mul,
+                                        uint8_t *packed, float *scale, float *zero, hipStream_t stream)
+{
+    if (!f32 && (K == 1024 || K == 2048 || K == 4096))
+        return run_rotate_quant_asym_mfma(X, rows, K, signs, mul, packed, scale, zero, stream);
+    if (rows <= 0) return hipSuccess;
+    int blocks = (rows + 3) / 4;
+    if (blocks > 256 * 8) blocks = 256 * 8;
+    const LnParams no_ln{nullptr, nullptr, 0.0f, 0};
+#define QVGGT_LAUNCH_ASYM(KK)                                                                                                          \
+    case KK:                                                                                                                           \
+        if (f32) rotate_rows_kernel<KK, true, kQuantize, 4, false, true><<<blocks, 256, 0, stream>>>(X, rows, signs, mul, 0, packed, scale, nullptr, nullptr, 0, 7.0f, no_ln, zero); \
+        else rotate_rows_kernel<KK, false, kQuantize, 4, false, true><<<blocks, 256, 0, stream>>>(X, rows, signs, mul, 0, packed, scale, nullptr, nullptr, 0, 7.0f, no_ln, zero);    \
+        break;
+    switch (K) {
+        QVGGT_LAUNCH_ASYM(128)
+        QVGGT_LAUNCH_ASYM(256)
+        QVGGT_LAUNCH_ASYM(512)
+        QVGGT_LAUNCH_ASYM(1024)
+        QVGGT_LAUNCH_ASYM(2048)
+        QVGGT_LAUNCH_ASYM(4096)
+        QVGGT_LAUNCH_ASYM(8192)
+        default: return hipErrorInvalidValue;
+    }
+#undef QVGGT_LAUNCH_ASYM
+    return hipGetLastError();
+}
+
 hipError_t run_rotated_col_absmax(const void *X, bool f32, int rows, int K, const int8_t *signs,
                                   float *absmax, hipStream_t stream)
 {
@@ -454,6 +517,13 @@ hipError_t run_layout_int8(const int8_t *src, int rows, int K, int8_t *dst, int 
     size_t n = (size_t)rows * K;
     if (n == 0) return hipSuccess;
     layout_int8_kernel<<<(unsigned)((n + 255) / 256), 256, 0, stream>>>(src, (size_t)rows, K, dst, to_library);
+    return hipGetLastError();
+}
+
+hipError_t run_code_sums(const uint8_t *packed, int rows, int K, float *sums, hipStream_t stream)
+{
+    if (rows <= 0) return hipSuccess;
+    code_sums_kernel<<<(rows + 3) / 4, 256, 0, stream>>>(packed, rows, K, sums);
     return hipGetLastError();
 }
 

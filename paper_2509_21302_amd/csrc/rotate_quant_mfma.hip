@@ -76,7 +76,9 @@ __host__ __device__ constexpr int row_of_seg_hi(int seg_hi /* seg >> 2 */)
 // in col_absmax_bits (the numerator of the smoothing factor, Sec. 3.2), which must be zero on entry
 // LN: a LayerNorm of every token (fp32, result rounded to bf16 as a separate normalisation kernel would hand it on) is
 // applied to the loaded values before anything else
-template <int K, int PF, int OCC, bool STATIC, int CB, bool LN = false>
+// ASYM: affine codes.  The row's range [min(0, min z), max(0, max z)] takes the 16 codes, the zero point goes to zero[row], and
+// the nibbles hold u - 8 (u the unsigned code), i.e. the signed values the integer GEMM multiplies
+template <int K, int PF, int OCC, bool STATIC, int CB, bool LN = false, bool ASYM = false>
 __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint16_t *__restrict__ X, int rows,
                                                                    const int8_t *__restrict__ signs,
                                                                    const float *__restrict__ mul, int mul_mode,
@@ -84,9 +86,11 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
                                                                    float *__restrict__ scale,
                                                                    const float *__restrict__ step, int step_stride,
                                                                    float qmax8, unsigned int *__restrict__ col_absmax_bits,
-                                                                   LnParams ln = LnParams{nullptr, nullptr, 0.0f, 0})
+                                                                   LnParams ln = LnParams{nullptr, nullptr, 0.0f, 0},
+                                                                   float *__restrict__ zero = nullptr)
 {
     constexpr bool STAT = (CB == 0);
+    static_assert(!ASYM || (CB == 4 && !STATIC), "affine codes: dynamic 4-bit only");
     using C = rq::Cfg<K>;
     constexpr int REM = C::REM, TOK = C::TOK;
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[rq::WAVES_PER_BLOCK * rq::LDS_PER_WAVE];
@@ -333,21 +337,29 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
             continue;
         }
         // scale, absmax per token (STATIC: the quantization step is given, no absmax)
-        float amax[C::TOK_PER_LANE];
+        float amax[C::TOK_PER_LANE], nmin[ASYM ? C::TOK_PER_LANE : 1];      // nmin: -min(0, min z), so both ends reduce with max
 #pragma unroll
         for (int t = 0; t < C::TOK_PER_LANE; ++t) amax[t] = 0.0f;
+#pragma unroll
+        for (int t = 0; t < (ASYM ? C::TOK_PER_LANE : 1); ++t) nmin[t] = 0.0f;
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int h = r % C::HB_PER_LANE, t = r / C::HB_PER_LANE;
                 acc[nt][r] *= cm[h][nt];
-                if constexpr (!STATIC) amax[t] = fmaxf(amax[t], fabsf(acc[nt][r]));
+                if constexpr (ASYM) {
+                    amax[t] = fmaxf(amax[t], acc[nt][r]);
+                    nmin[t] = fmaxf(nmin[t], -acc[nt][r]);
+                } else if constexpr (!STATIC) {
+                    amax[t] = fmaxf(amax[t], fabsf(acc[nt][r]));
+                }
             }
         if constexpr (!STATIC) {
 #pragma unroll
             for (int t = 0; t < C::TOK_PER_LANE; ++t) {
                 amax[t] = (REM == 5) ? max_over_64_lanes(amax[t]) : max_over_32_lanes(amax[t]);
+                if constexpr (ASYM) nmin[t] = (REM == 5) ? max_over_64_lanes(nmin[t]) : max_over_32_lanes(nmin[t]);
             }
         }
 
@@ -358,7 +370,16 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
             const int tk = (REM == 3) ? (2 * t + g) : (REM == 4 ? g : 0);
             const int row = tile * TOK + tk;
             float inv, delta;
-            if constexpr (STATIC) {
+            float magic = rq::MAGIC, zp = 0.0f;
+            if constexpr (ASYM) {
+                // step (hi - lo) / 15, zero point rne(-lo / step) in [0, 15]; u = rne(z / step) + zp is formed as the low mantissa
+                // bits of z * inv + (MAGIC - 8 + zp) (MAGIC carries the + 8 of the symmetric codes) and clamped to [0, 15] there
+                const float range = amax[t] + nmin[t];
+                delta = range / 15.0f;
+                inv = range > 0.0f ? 15.0f * __builtin_amdgcn_rcpf(range) : 0.0f;
+                zp = __builtin_rintf(nmin[t] * inv);
+                magic = rq::MAGIC - 8.0f + zp;
+            } else if constexpr (STATIC) {
                 delta = step[(size_t)min(row, rows - 1) * step_stride];
                 inv = delta > 0.0f ? 1.0f / delta : 0.0f;
             } else {
@@ -401,7 +422,9 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
                 for (int i = 7; i >= 0; --i) {
                     const int nt = i & 3, h = 2 * d + (i >> 2);
                     float f;
-                    if constexpr (STATIC) {     // a given step does not bound the ratio: clamp to the code range (ties to even below)
+                    if constexpr (ASYM) {       // rounding noise at the ends of the range may reach -1 or 16: clamp after the rounding
+                        f = __builtin_amdgcn_fmed3f(fmaf(acc[nt][t * C::HB_PER_LANE + h], inv, magic), rq::MAGIC - 8.0f, rq::MAGIC + 7.0f);
+                    } else if constexpr (STATIC) {     // a given step does not bound the ratio: clamp to the code range (ties to even below)
                         f = __builtin_amdgcn_fmed3f(acc[nt][t * C::HB_PER_LANE + h] * inv, -8.0f, 7.0f) + rq::MAGIC;
                     } else {
                         f = fmaf(acc[nt][t * C::HB_PER_LANE + h], inv, rq::MAGIC);
@@ -417,7 +440,10 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
 #pragma unroll
                 for (int d4 = 0; d4 < C::NL / 32; ++d4)
                     *reinterpret_cast<uint4 *>(out + 16 * d4) = make_uint4(words[4 * d4], words[4 * d4 + 1], words[4 * d4 + 2], words[4 * d4 + 3]);
-                if (c == 0 && (REM != 5 || g == 0)) scale[row] = delta;
+                if (c == 0 && (REM != 5 || g == 0)) {
+                    scale[row] = delta;
+                    if constexpr (ASYM) zero[row] = zp;
+                }
             }
         }
     }
@@ -477,6 +503,27 @@ hipError_t run_rotate_quant_mfma(const void *X, int rows, int K, const int8_t *s
         case 4096: RQ(4096, 1, 2); break;
         default: return hipErrorInvalidValue;
     }
+    return hipGetLastError();
+}
+
+// rotation + smoothing + per-token affine 4-bit codes (stored as u - 8) with zero points, bf16 rows, K = 1024 / 2048 / 4096
+hipError_t run_rotate_quant_asym_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, uint8_t *packed,
+                                      float *scale, float *zero, hipStream_t stream)
+{
+    if (rows <= 0) return hipSuccess;
+    const uint16_t *x = reinterpret_cast<const uint16_t *>(X);
+    const int tok = 32 / (K / 128);
+    const int ntiles = (rows + tok - 1) / tok;
+    int blocks = (ntiles + rq::WAVES_PER_BLOCK - 1) / rq::WAVES_PER_BLOCK;
+    if (blocks > 256 * 2) blocks = 256 * 2;
+#define RQA(KK) rotate_quant_mfma_kernel<KK, 1, 2, false, 4, false, true><<<blocks, 256, 0, stream>>>(x, rows, signs, mul, 0, packed, scale, nullptr, 0, 7.0f, nullptr, LnParams{nullptr, nullptr, 0.0f, 0}, zero)
+    switch (K) {
+        case 1024: RQA(1024); break;
+        case 2048: RQA(2048); break;
+        case 4096: RQA(4096); break;
+        default: return hipErrorInvalidValue;
+    }
+#undef RQA
     return hipGetLastError();
 }
 

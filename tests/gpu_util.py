@@ -54,6 +54,22 @@ def gpu_ln_rsq(Xd, gamma_d, beta_d, eps, signs_d, inv_d):
     return Xq, sx
 
 
+def gpu_rsq_asym(Xd, signs_d, inv_d):
+    """Affine activation codes: returns (Xq nibbles holding u - 8, steps, zero points)."""
+    M, K = Xd.shape
+    Xq = torch.empty(M, K // 2, dtype=torch.uint8, device=DEV)
+    sx = torch.empty(M, dtype=torch.float32, device=DEV)
+    zx = torch.empty(M, dtype=torch.float32, device=DEV)
+    q.qvggt_rotate_smooth_quant_asym(Xd, signs_d, inv_d, Xq, sx, zx)
+    return Xq, sx, zx
+
+
+def gpu_code_sums(Wq, N, K):
+    s = torch.empty(N, dtype=torch.float32, device=DEV)
+    q.qvggt_weight_code_sums(Wq, N, K, s)
+    return s
+
+
 def gpu_rsq_static(Xd, signs_d, inv_d, step_d, per_token):
     M, K = Xd.shape
     Xq = torch.empty(M, K // 2, dtype=torch.uint8, device=DEV)

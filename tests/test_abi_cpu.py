@@ -104,6 +104,20 @@ def test_argument_validation_needs_no_gpu():
     for bad in (-1e-5, float("nan"), float("inf")):
         assert lnq(P, 0, 4, 1024, None, None, C.c_float(bad), None, None, P, P, None) == ARG
     assert lnq(None, 0, 0, 1024, None, None, e5, None, None, None, None, None) == OK
+    # asymmetric setting: kernel 1 needs the zero-point buffer and a power-of-two K; the GEMM needs zero points and code sums
+    rqa, cs, ga = lib.qvggt_rotate_smooth_quant_asym, lib.qvggt_weight_code_sums, lib.qvggt_w4a4_gemm_asym
+    assert rqa(P, 0, 4, 768, None, None, P, P, P, None) == SHAPE
+    assert rqa(P, 5, 4, 1024, None, None, P, P, P, None) == DTYPE
+    assert rqa(P, 0, 4, 1024, None, None, P, P, None, None) == NULL
+    assert rqa(P, 0, 4, 1024, None, None, P, P, P + 4, None) == ALIGN
+    assert rqa(None, 0, 0, 1024, None, None, None, None, None, None) == OK
+    assert cs(P, 16, 1000, P, None) == SHAPE and cs(P, -1, 1024, P, None) == SHAPE
+    assert cs(None, 16, 1024, P, None) == NULL and cs(P, 16, 1024, P + 8, None) == ALIGN and cs(None, 0, 1024, None, None) == OK
+    assert ga(P, P, P, P, P, P, None, 4, 100, 1024, P, None) == SHAPE
+    assert ga(P, P, None, P, P, P, None, 4, 32, 1024, P, None) == NULL
+    assert ga(P, P, P, P, P, None, None, 4, 32, 1024, P, None) == NULL
+    assert ga(P, P, P, P, P, P + 4, None, 4, 32, 1024, P, None) == ALIGN
+    assert ga(None, None, None, None, None, None, None, 0, 32, 1024, None, None) == OK
     # 8-bit / 6-bit entry points: the same checks, and the bit-width
     for bad in (4, 9, 0, -8):
         assert lib.qvggt_rotate_smooth_quant_i8(P, 0, 4, 1024, None, None, bad, P, P, None) == ARG

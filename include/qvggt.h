@@ -170,7 +170,10 @@ int qvggt_w4a4_gemm(const uint8_t *Xq, const float *x_scale, const uint8_t *Wq, 
  * appendix "More experiments", the 6/6 rows).  Everything is as in the 4-bit entry points above except the
  * quantizer's range and the storage of the codes:
  *     qmax = 2^(bits-1) - 1;   scale = absmax / qmax;   code = clamp(rne(v / scale), -qmax - 1, qmax)
- * with bits in 5..8 (else QVGGT_ERR_ARG), and codes stored one per byte as int8: Xq int8 [M, K], Wq int8 [N, K].
+ * with bits in 4..8 (else QVGGT_ERR_ARG), and codes stored one per byte as int8: Xq int8 [M, K], Wq int8 [N, K].
+ * The GEMM only sees int8 codes, so weights and activations may take different widths: the mixed-precision setting
+ * of the appendix table of further settings, e.g. qvggt_prep_weights_i8 with bits = 4 and qvggt_linear_i8 with
+ * bits = 8 (4-bit weights, 8-bit activations; which widths the paper mixes it does not say).
  * The position of a code inside its row is again the library's fixed permutation (the same for Xq and Wq);
  * qvggt_layout_int8 converts to and from natural order.  Sums stay in int32: |acc| <= 128 * 128 * 8192 = 2^27.
  *

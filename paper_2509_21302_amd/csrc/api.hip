@@ -48,9 +48,9 @@ bool valid_dtype(int d) { return d == QVGGT_BF16 || d == QVGGT_F32; }
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 int hip_status(hipError_t e) { return e == hipSuccess ? QVGGT_OK : QVGGT_ERR_HIP; }
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
-bool valid_wide_bits(int bits) { return bits >= 5 && bits <= 8; }
+bool valid_wide_bits(int bits) { return bits >= 4 && bits <= 8; }
 
-// offline half for either code width: bits == 4 writes packed nibbles, 5..8 int8 codes
+// offline half for either storage: bits == 4 writes packed nibbles, kInt8Container + b int8 codes of width b
 int prep_weights(const void *W, int w_dtype, int N, int K, const float *act_absmax_rot, const int8_t *signs, float alpha,
                  int bits, void *Wq, float *w_scale, float *inv_smooth, void *stream)
 {
@@ -91,7 +91,7 @@ const char *qvggt_status_string(int status)
         case QVGGT_ERR_ALIGN: return "QVGGT_ERR_ALIGN: pointer not 16-byte aligned";
         case QVGGT_ERR_DTYPE: return "QVGGT_ERR_DTYPE: dtype must be QVGGT_BF16 or QVGGT_F32";
         case QVGGT_ERR_WORKSPACE: return "QVGGT_ERR_WORKSPACE: workspace too small";
-        case QVGGT_ERR_ARG: return "QVGGT_ERR_ARG: a scalar argument is outside its documented range (alpha, p in [0, 1]; flags 0 or 1; bits in 5..8; eps >= 0)";
+        case QVGGT_ERR_ARG: return "QVGGT_ERR_ARG: a scalar argument is outside its documented range (alpha, p in [0, 1]; flags 0 or 1; bits in 4..8; eps >= 0)";
         case QVGGT_ERR_HIP: return "QVGGT_ERR_HIP: kernel launch failed";
         default: return "unknown qvggt status";
     }
@@ -118,7 +118,7 @@ int qvggt_prep_weights_i8(const void *W, int w_dtype, int N, int K, const float 
                           float alpha, int bits, int8_t *Wq, float *w_scale, float *inv_smooth, void *stream)
 {
     if (!valid_wide_bits(bits)) return QVGGT_ERR_ARG;
-    return prep_weights(W, w_dtype, N, K, act_absmax_rot, signs, alpha, bits, Wq, w_scale, inv_smooth, stream);
+    return prep_weights(W, w_dtype, N, K, act_absmax_rot, signs, alpha, qvggt::kInt8Container + bits, Wq, w_scale, inv_smooth, stream);
 }
 
 int qvggt_rotate_smooth_quant(const void *X, int x_dtype, int M, int K, const int8_t *signs, const float *inv_smooth,
@@ -145,8 +145,8 @@ int qvggt_rotate_smooth_quant_i8(const void *X, int x_dtype, int M, int K, const
     if (!aligned16(X) || !aligned16(Xq) || !aligned16(x_scale) || !aligned16(inv_smooth) || !aligned16(signs))
         return QVGGT_ERR_ALIGN;
     return hip_status(qvggt::run_rotate_smooth_quant(X, x_dtype == QVGGT_F32, M, K, signs, inv_smooth, 0,
-                                                     reinterpret_cast<uint8_t *>(Xq), x_scale, nullptr, 0, bits,
-                                                     static_cast<hipStream_t>(stream)));
+                                                     reinterpret_cast<uint8_t *>(Xq), x_scale, nullptr, 0,
+                                                     qvggt::kInt8Container + bits, static_cast<hipStream_t>(stream)));
 }
 
 int qvggt_layernorm_rotate_smooth_quant(const void *X, int x_dtype, int M, int K, const float *gamma, const float *beta, float eps,
@@ -263,7 +263,7 @@ int qvggt_linear_i8(const void *X, int x_dtype, int M, int N, int K, const int8_
     uint8_t *Xq = static_cast<uint8_t *>(workspace);
     float *x_scale = reinterpret_cast<float *>(Xq + round_up((size_t)M * (size_t)K, 256));
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = qvggt::run_rotate_smooth_quant(X, x_dtype == QVGGT_F32, M, K, signs, inv_smooth, 0, Xq, x_scale, nullptr, 0, bits, s);
+    hipError_t e = qvggt::run_rotate_smooth_quant(X, x_dtype == QVGGT_F32, M, K, signs, inv_smooth, 0, Xq, x_scale, nullptr, 0, qvggt::kInt8Container + bits, s);
     if (e != hipSuccess) return QVGGT_ERR_HIP;
     return hip_status(qvggt::run_i8_gemm(reinterpret_cast<const int8_t *>(Xq), x_scale, Wq, w_scale, bias, M, N, K, Y, nullptr, s));
 }

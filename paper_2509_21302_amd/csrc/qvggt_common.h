@@ -9,6 +9,11 @@ constexpr int kWave = 64;
 constexpr int kMinK = 128;
 constexpr int kMaxK = 8192;
 
+// Width argument of the quantizing launchers: 4 = 4-bit codes packed two per byte; kInt8Container + b = b-bit codes
+// (4 <= b <= 8) stored one per byte as int8 (so that weights and activations of one int8 GEMM may take different widths)
+constexpr int kInt8Container = 32;
+inline int code_width(int bits) { return bits >= kInt8Container ? bits - kInt8Container : bits; }
+
 // Position of natural element e inside a packed row of K codes.  Two codes share a byte:
 // position p lives in byte p / 2, low nibble when p is even.  The same map is used for
 // activations and weights, so integer dot products do not depend on it.

@@ -407,7 +407,7 @@ hipError_t run_rotate_smooth_quant(const void *X, bool f32, int rows, int K, con
 {
     if (general_size_supported(K))
         return run_rotate_rows_general(X, f32, rows, K, signs, mul, mul_mode, packed, scale, nullptr, step, step_stride, bits, stream);
-    const float qmax = (float)((1 << (bits - 1)) - 1);
+    const float qmax = (float)((1 << (code_width(bits) - 1)) - 1);
     // bf16 rows of the sizes VGGT-1B uses go to the matrix-core kernel; everything else to the generic one
     if (!f32 && (K == 1024 || K == 2048 || K == 4096))
         return run_rotate_quant_mfma(X, rows, K, signs, mul, mul_mode, packed, scale, step, step_stride, bits, stream);

@@ -236,7 +236,7 @@ static hipError_t launch_general(const void *X, bool f32, int rows, const int8_t
     int blocks = (rows + 3) / 4;
     if (blocks > 256 * 8) blocks = 256 * 8;
     if (colmax != nullptr) blocks = std::max(1, std::min((rows + 31) / 32, 256 * 2));   // eight rows or more per wave for the statistic
-    const float qmax = (float)((1 << (bits - 1)) - 1);
+    const float qmax = (float)((1 << (code_width(bits) - 1)) - 1);
 #define QVGGT_GEN(F32_, MODE_, CB_) \
     rotate_rows_general_kernel<N2, MM, F32_, MODE_, CB_><<<blocks, 256, 0, stream>>>(X, rows, signs, mul, mul_mode, packed, scale, colmax, step, step_stride, qmax)
     if (colmax != nullptr) {

@@ -485,7 +485,7 @@ hipError_t run_rotate_quant_mfma(const void *X, int rows, int K, const int8_t *s
     else
 #endif
     if (blocks > max_blocks) blocks = max_blocks;
-    const float qmax8 = (float)((1 << (bits - 1)) - 1);
+    const float qmax8 = (float)((1 << (code_width(bits) - 1)) - 1);
 #define RQ1(KK, PF, OCC, ST, CB) rotate_quant_mfma_kernel<KK, PF, OCC, ST, CB><<<blocks, 256, 0, stream>>>(x, rows, signs, mul, mul_mode, packed, scale, step, step_stride, qmax8, nullptr)
 #define RQ(KK, PF, OCC)                                      \
     do {                                                     \

@@ -1,7 +1,8 @@
 """A small convenience object around the C ABI: one quantized linear layer, prepared once, applied many times.
 
 It only allocates device tensors with torch and calls the entry points of the same names; no arithmetic of the
-method happens here.  `bits` = 4 uses the packed 4-bit path, 5..8 the int8-code path (Sec. 4.1 settings, appendix).
+method happens here.  `bits` = 4 uses the packed 4-bit path, 5..8 the int8-code path (Sec. 4.1 settings, appendix);
+`act_bits` different from `bits` is a mixed-precision layer (e.g. 4-bit weights, 8-bit activations) on the int8-code path.
 """
 from __future__ import annotations
 
@@ -20,11 +21,14 @@ class DsfqLinear:
     """
 
     def __init__(self, weight: torch.Tensor, bias: Optional[torch.Tensor] = None, signs: Optional[torch.Tensor] = None,
-                 calibration: Optional[torch.Tensor] = None, alpha: float = 0.5, bits: int = 4):
-        if bits != 4 and not 5 <= bits <= 8:
-            raise ValueError("bits must be 4 or in 5..8")
+                 calibration: Optional[torch.Tensor] = None, alpha: float = 0.5, bits: int = 4,
+                 act_bits: Optional[int] = None):
+        act_bits = bits if act_bits is None else act_bits
+        if not 4 <= bits <= 8 or not 4 <= act_bits <= 8:
+            raise ValueError("bits and act_bits must be in 4..8")
         self.N, self.K = weight.shape
-        self.bits, self.bias, self.signs = bits, bias, signs
+        self.bits, self.act_bits, self.bias, self.signs = bits, act_bits, bias, signs
+        self.packed = bits == 4 and act_bits == 4            # both 4-bit: two codes per byte; otherwise int8 codes
         dev = weight.device
         absmax = None
         if calibration is not None:
@@ -32,7 +36,7 @@ class DsfqLinear:
             q.qvggt_rotated_col_absmax(calibration, signs, absmax)
         self.w_scale = torch.empty(self.N, dtype=torch.float32, device=dev)
         self.inv_smooth = torch.empty(self.K, dtype=torch.float32, device=dev)
-        if bits == 4:
+        if self.packed:
             self.Wq = torch.empty(self.N, self.K // 2, dtype=torch.uint8, device=dev)
             q.qvggt_prep_weights(weight, absmax, signs, alpha, self.Wq, self.w_scale, self.inv_smooth)
         else:
@@ -41,7 +45,7 @@ class DsfqLinear:
         self._ws = None
 
     def _workspace(self, M: int, dev) -> torch.Tensor:
-        need = q.qvggt_workspace_bytes(M, self.N, self.K) if self.bits == 4 else q.qvggt_workspace_bytes_i8(M, self.N, self.K)
+        need = q.qvggt_workspace_bytes(M, self.N, self.K) if self.packed else q.qvggt_workspace_bytes_i8(M, self.N, self.K)
         if self._ws is None or self._ws.numel() < need or self._ws.device != dev:
             self._ws = torch.empty(need, dtype=torch.uint8, device=dev)
         return self._ws
@@ -51,8 +55,8 @@ class DsfqLinear:
         M = X.shape[0]
         Y = out if out is not None else torch.empty(M, self.N, dtype=torch.bfloat16, device=X.device)
         ws = self._workspace(M, X.device)
-        if self.bits == 4:
+        if self.packed:
             q.qvggt_linear(X, self.signs, self.inv_smooth, self.Wq, self.w_scale, self.bias, Y, ws)
         else:
-            q.qvggt_linear_i8(X, self.signs, self.inv_smooth, self.bits, self.Wq, self.w_scale, self.bias, Y, ws)
+            q.qvggt_linear_i8(X, self.signs, self.inv_smooth, self.act_bits, self.Wq, self.w_scale, self.bias, Y, ws)
         return Y

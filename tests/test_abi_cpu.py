@@ -119,7 +119,7 @@ def test_argument_validation_needs_no_gpu():
     assert ga(P, P, P, P, P, P + 4, None, 4, 32, 1024, P, None) == ALIGN
     assert ga(None, None, None, None, None, None, None, 0, 32, 1024, None, None) == OK
     # 8-bit / 6-bit entry points: the same checks, and the bit-width
-    for bad in (4, 9, 0, -8):
+    for bad in (3, 9, 0, -8):
         assert lib.qvggt_rotate_smooth_quant_i8(P, 0, 4, 1024, None, None, bad, P, P, None) == ARG
         assert lib.qvggt_prep_weights_i8(P, 0, 32, 1024, None, None, C.c_float(0.5), bad, P, P, P, None) == ARG
         assert lib.qvggt_linear_i8(P, 0, 4, 32, 1024, None, None, bad, P, P, None, P, P, 1 << 20, None) == ARG

@@ -142,6 +142,31 @@ def test_linear_i8_full_rows(bits, config, name):
     assert np.linalg.norm(got - exact) / np.linalg.norm(exact) < (0.03 if bits == 8 else 0.1)
 
 
+@pytest.mark.parametrize("w_bits,a_bits", [(4, 8), (8, 4), (6, 8), (4, 4)])
+@pytest.mark.parametrize("config,name", [(2, "qkv"), (3, "fc1")])
+def test_mixed_widths(w_bits, a_bits, config, name):
+    """Mixed precision (appendix, further settings): weights and activations of different widths through the int8-code
+    path, against the oracle run with the same two widths.  (4, 4) in int8 containers must equal the packed 4-bit path
+    bit for bit: same codes, same integer sums, same epilogue."""
+    s = synth.layer_spec(config, name)
+    X, bias = synth.make_activation_frames(s), synth.make_bias(s)
+    signs = synth.make_signs(s)
+    cal = synth.make_calibration(s)
+    W = synth.make_weights(s)
+    po = oracle.prepare_weights(W, oracle.rotated_col_absmax(cal, pre_signs=signs), pre_signs=signs, alpha=0.5, bits=w_bits)
+    want = oracle.linear(X, po, bias=bias, pre_signs=signs, bits=a_bits)
+    pg = G.gpu_prep_i8(W, cal, signs, w_bits)
+    pg["bits"] = a_bits                                   # gpu_linear_i8 quantizes the activations with pg["bits"]
+    Yd = G.gpu_linear_i8(G.to_dev(X), pg, G.to_dev(bias))
+    assert G.rel_fro(G.bf16_bits(Yd), want.Y) <= G.Y_REL_FRO
+    if (w_bits, a_bits) == (4, 4):
+        p4 = G.gpu_prep(W, cal, signs)
+        assert torch.equal(G.gpu_linear(G.to_dev(X), p4, G.to_dev(bias)), Yd)
+        codes = torch.empty_like(pg["Wq"])
+        G.q.qvggt_layout_int8(pg["Wq"], codes, 0)
+        assert np.array_equal(codes.cpu().numpy(), G.gpu_unpack(p4["Wq"], s.K))
+
+
 @pytest.mark.parametrize("name,n_random", [("fc1", 800), ("fc2", 300)])
 def test_linear_i8_full_size_sampled_rows(name, n_random):
     """The benchmark's shapes (137400 tokens) at 8 bits; the oracle recomputes a seeded sample of rows."""

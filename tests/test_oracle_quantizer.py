@@ -358,3 +358,23 @@ def test_asymmetric_layer_approximates_the_float_layer():
     rec = dx[:, None] * (u.astype(np.float64) - zp[:, None])
     assert np.all(np.abs(Xs - rec) <= dx[:, None] / 2 * (1 + 1e-9))
     assert np.allclose(ya - b, (rec @ (prep.qw.astype(np.float64) * prep.dw[:, None]).T), rtol=1e-12, atol=1e-12)
+
+
+def test_mixed_widths_order_the_error():
+    """Mixed precision (appendix, further settings): each operand has its own width; widening either one lowers the layer's
+    error against the float product, and widening the activations alone leaves the weight codes untouched."""
+    rng = np.random.default_rng(15)
+    M, N, K = 64, 48, 256
+    X = rng.standard_t(3, (M, K))
+    W = rng.standard_normal((N, K)) * 0.05
+    ref = X @ W.T
+    a = oracle.rotated_col_absmax(X)
+    err = {}
+    for wb in (4, 8):
+        prep = oracle.prepare_weights(W, a, bits=wb)
+        assert np.abs(prep.qw).max() == (1 << (wb - 1)) - 1
+        for ab in (4, 8):
+            r = oracle.linear(X, prep, bits=ab)
+            assert np.abs(r.qx).max() == (1 << (ab - 1)) - 1
+            err[wb, ab] = np.linalg.norm(r.y - ref) / np.linalg.norm(ref)
+    assert err[8, 8] < err[4, 8] < err[4, 4] and err[8, 8] < err[8, 4] < err[4, 4]

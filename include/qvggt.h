@@ -166,6 +166,30 @@ int qvggt_w4a4_gemm(const uint8_t *Xq, const float *x_scale, const uint8_t *Wq, 
                     const void *bias, int M, int N, int K, void *Y, int32_t *acc_debug, void *stream);
 
 /*
+ * Online kernel 2 through the 6-bit floating-point matrix instructions: the same integer sums and the same Y as
+ * qvggt_w4a4_gemm, bit for bit, at twice the matrix rate.  A 4-bit code q in [-7, 7] is written as the E2M3 number
+ * of value q (1 sign, 2 exponent, 3 mantissa bits); products and sums are integers below 2^24 and exact in the
+ * fp32 accumulators.  -8 has no E2M3 value: the dynamic quantizers never produce it (Eq. 3 with absmax / 7 gives
+ * codes in [-7, 7]); codes from a static step or the asymmetric setting stay on qvggt_w4a4_gemm(_asym).
+ *
+ * "E2M3 blocks": a row is K / 64 units of 48 bytes.  Unit s holds the codes at positions 64 s .. 64 s + 63 of a
+ * packed row (library order) as two blobs of 32 six-bit fields, field i of blob h = position 64 s + 32 h + i at
+ * bits [6 i, 6 i + 6) of the blob's 24 bytes, stored [blob 0 bytes 0..15][blob 1 bytes 0..15][blob 0 bytes 16..23]
+ * [blob 1 bytes 16..23].  Rows are grouped in blocks of 128: unit s of row r starts at byte
+ * ((r / 128) * (K / 64) + s) * 6144 + (r % 128) * 48, so a buffer holds ceil(rows / 128) * 128 rows:
+ * qvggt_e2m3_bytes(rows, K) bytes (0 for an unsupported K).  The rows past `rows` in the last block are never
+ * written and may hold anything (the GEMM reads them and discards what they produce).
+ * qvggt_codes_to_e2m3:  packed u8 [rows, K/2] (Xq or Wq as written by this library) -> out, E2M3 blocks;
+ *                       distinct buffers; a nibble -8 saturates to -7.
+ * qvggt_e2m3_gemm:      Xf, Wf E2M3 blocks of M and N rows; everything else as qvggt_w4a4_gemm (acc_debug receives
+ *                       the exact sums as int32).
+ */
+size_t qvggt_e2m3_bytes(int rows, int K);
+int qvggt_codes_to_e2m3(const uint8_t *packed, int rows, int K, uint8_t *out, void *stream);
+int qvggt_e2m3_gemm(const uint8_t *Xf, const float *x_scale, const uint8_t *Wf, const float *w_scale,
+                    const void *bias, int M, int N, int K, void *Y, int32_t *acc_debug, void *stream);
+
+/*
  * The 8-bit and 6-bit settings of the same layer (Sec. 4.1 bit settings and the pose / point-map tables at 8/8;
  * appendix "More experiments", the 6/6 rows).  Everything is as in the 4-bit entry points above except the
  * quantizer's range and the storage of the codes:

@@ -18,6 +18,7 @@ EXPORTS = [
     "qvggt_status_string", "qvggt_rotated_col_absmax", "qvggt_prep_weights", "qvggt_rotate_smooth_quant",
     "qvggt_rotate_smooth_quant_static", "qvggt_layernorm_rotate_smooth_quant",
     "qvggt_rotate_smooth_quant_asym", "qvggt_weight_code_sums", "qvggt_w4a4_gemm_asym",
+    "qvggt_e2m3_bytes", "qvggt_codes_to_e2m3", "qvggt_e2m3_gemm",
     "qvggt_w4a4_gemm", "qvggt_linear", "qvggt_workspace_bytes", "qvggt_pack_int4", "qvggt_unpack_int4",
     "qvggt_prep_weights_i8", "qvggt_rotate_smooth_quant_i8", "qvggt_i8_gemm", "qvggt_linear_i8",
     "qvggt_workspace_bytes_i8", "qvggt_layout_int8",
@@ -67,6 +68,12 @@ def load_library() -> C.CDLL:
     lib.qvggt_weight_code_sums.argtypes = [vp, i, i, vp, vp]
     lib.qvggt_w4a4_gemm_asym.restype = i
     lib.qvggt_w4a4_gemm_asym.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, vp, vp]
+    lib.qvggt_e2m3_bytes.restype = C.c_size_t
+    lib.qvggt_e2m3_bytes.argtypes = [i, i]
+    lib.qvggt_codes_to_e2m3.restype = i
+    lib.qvggt_codes_to_e2m3.argtypes = [vp, i, i, vp, vp]
+    lib.qvggt_e2m3_gemm.restype = i
+    lib.qvggt_e2m3_gemm.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp, vp, vp]
     lib.qvggt_w4a4_gemm.restype = i
     lib.qvggt_w4a4_gemm.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp, vp, vp]
     lib.qvggt_linear.restype = i
@@ -192,6 +199,19 @@ def qvggt_weight_code_sums(Wq, N, K, w_codesum, stream=None):
 def qvggt_w4a4_gemm_asym(Xq, x_scale, x_zero, Wq, w_scale, w_codesum, bias, M, N, K, Y, stream=None):
     _check(load_library().qvggt_w4a4_gemm_asym(_ptr(Xq), _ptr(x_scale), _ptr(x_zero), _ptr(Wq), _ptr(w_scale), _ptr(w_codesum),
                                                _ptr(bias), M, N, K, _ptr(Y), _stream(stream)), "qvggt_w4a4_gemm_asym")
+
+
+def qvggt_e2m3_bytes(rows, K):
+    return int(load_library().qvggt_e2m3_bytes(rows, K))
+
+
+def qvggt_codes_to_e2m3(packed, rows, K, out, stream=None):
+    _check(load_library().qvggt_codes_to_e2m3(_ptr(packed), rows, K, _ptr(out), _stream(stream)), "qvggt_codes_to_e2m3")
+
+
+def qvggt_e2m3_gemm(Xf, x_scale, Wf, w_scale, bias, M, N, K, Y, acc_debug=None, stream=None):
+    _check(load_library().qvggt_e2m3_gemm(_ptr(Xf), _ptr(x_scale), _ptr(Wf), _ptr(w_scale), _ptr(bias), M, N, K, _ptr(Y),
+                                          _ptr(acc_debug), _stream(stream)), "qvggt_e2m3_gemm")
 
 
 def qvggt_w4a4_gemm(Xq, x_scale, Wq, w_scale, bias, M, N, K, Y, acc_debug=None, stream=None):

@@ -23,6 +23,9 @@ hipError_t run_rotate_smooth_quant_asym(const void *X, bool f32, int rows, int K
 hipError_t run_code_sums(const uint8_t *packed, int rows, int K, float *sums, hipStream_t stream);
 hipError_t run_w4a4_gemm_asym(const uint8_t *Xq, const float *sx, const float *xzero, const uint8_t *Wq, const float *sw,
                               const float *wsum, const void *bias, int M, int N, int K, void *Y, hipStream_t stream);
+hipError_t run_codes_to_e2m3(const uint8_t *packed, int rows, int K, uint8_t *out, hipStream_t stream);
+hipError_t run_e2m3_gemm(const uint8_t *Xf, const float *sx, const uint8_t *Wf, const float *sw, const void *bias, int M, int N,
+                         int K, void *Y, int32_t *acc_debug, hipStream_t stream);
 hipError_t run_layout_int8(const int8_t *src, int rows, int K, int8_t *dst, int to_library, hipStream_t stream);
 hipError_t run_w4a4_gemm(const uint8_t *Xq, const float *sx, const uint8_t *Wq, const float *sw, const void *bias,
                          int M, int N, int K, void *Y, int32_t *acc_debug, hipStream_t stream);
@@ -226,6 +229,34 @@ int qvggt_w4a4_gemm_asym(const uint8_t *Xq, const float *x_scale, const float *x
         return QVGGT_ERR_ALIGN;
     return hip_status(qvggt::run_w4a4_gemm_asym(Xq, x_scale, x_zero, Wq, w_scale, w_codesum, bias, M, N, K, Y,
                                                 static_cast<hipStream_t>(stream)));
+}
+
+size_t qvggt_e2m3_bytes(int rows, int K)
+{
+    if (rows < 0 || !valid_k(K)) return 0;
+    return round_up((size_t)rows, 128) * ((size_t)K / 4 * 3);
+}
+
+int qvggt_codes_to_e2m3(const uint8_t *packed, int rows, int K, uint8_t *out, void *stream)
+{
+    if (rows < 0 || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (rows == 0) return QVGGT_OK;
+    if (!packed || !out) return QVGGT_ERR_NULL;
+    if (!aligned16(packed) || !aligned16(out)) return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_codes_to_e2m3(packed, rows, K, out, static_cast<hipStream_t>(stream)));
+}
+
+int qvggt_e2m3_gemm(const uint8_t *Xf, const float *x_scale, const uint8_t *Wf, const float *w_scale, const void *bias,
+                    int M, int N, int K, void *Y, int32_t *acc_debug, void *stream)
+{
+    if (M < 0 || !valid_n(N) || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (M == 0) return QVGGT_OK;
+    if (!Xf || !x_scale || !Wf || !w_scale || !Y) return QVGGT_ERR_NULL;
+    if (!aligned16(Xf) || !aligned16(x_scale) || !aligned16(Wf) || !aligned16(w_scale) || !aligned16(bias) ||
+        !aligned16(Y) || !aligned16(acc_debug))
+        return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_e2m3_gemm(Xf, x_scale, Wf, w_scale, bias, M, N, K, Y, acc_debug,
+                                           static_cast<hipStream_t>(stream)));
 }
 
 int qvggt_i8_gemm(const int8_t *Xq, const float *x_scale, const int8_t *Wq, const float *w_scale, const void *bias,

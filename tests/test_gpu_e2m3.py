@@ -1,0 +1,124 @@
+"""GPU parity of the GEMM on the 6-bit floating-point matrix path: 4-bit codes written as E2M3 numbers, the integer sums
+exact in fp32.  Accumulators bit-exact against the oracle's integer product, Y against its epilogue, and identical to the
+int8-path kernel on the same codes."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from synth import f32_to_bf16_bits
+from tests import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+
+def _e2m3(codes_np):
+    """natural-order int8 codes -> packed rows (library order) -> E2M3 rows"""
+    packed = G.gpu_pack(codes_np)
+    rows, K = codes_np.shape
+    out = torch.full((G.q.qvggt_e2m3_bytes(rows, K),), 0xA5, dtype=torch.uint8, device=G.DEV)        # pad rows keep the fill
+    G.q.qvggt_codes_to_e2m3(packed, rows, K, out)
+    return packed, out
+
+
+def _decode_e2m3_rows(buf, rows, K):
+    """E2M3 blocks -> value at every position of the packed row, from the format's definition: sign, 2 exponent bits (bias 1),
+    3 mantissa bits; exponent 0 is subnormal (m / 8).  Unit s of row r starts at ((r / 128) * (K / 64) + s) * 6144 + (r % 128) * 48."""
+    out = np.zeros((rows, K), dtype=np.float64)
+    r = np.arange(rows)
+    for s in range(K // 64):
+        start = ((r // 128) * (K // 64) + s) * 6144 + (r % 128) * 48
+        unit = buf[start[:, None] + np.arange(48)[None, :]]
+        for h in range(2):
+            blob = np.concatenate([unit[:, 16 * h: 16 * h + 16], unit[:, 32 + 8 * h: 40 + 8 * h]], axis=1)     # 24 bytes
+            bits = np.unpackbits(blob, axis=1, bitorder="little")                                            # [rows, 192]
+            for i in range(32):
+                f = bits[:, 6 * i: 6 * i + 6].astype(np.int64)
+                m = f[:, 0] + 2 * f[:, 1] + 4 * f[:, 2]
+                e = f[:, 3] + 2 * f[:, 4]
+                mag = np.where(e == 0, m / 8.0, 2.0 ** (e - 1) * (1 + m / 8.0))
+                out[:, 64 * s + 32 * h + i] = np.where(f[:, 5] == 1, -mag, mag)
+    return out
+
+
+def test_codes_to_e2m3_layout_and_values():
+    K, rows = 256, 300
+    rng = np.random.default_rng(0)
+    codes = rng.integers(-7, 8, (rows, K)).astype(np.int8)
+    codes[0] = np.resize(np.arange(-7, 8), K)
+    packed, out = _e2m3(codes)
+    pk = packed.cpu().numpy()
+    nib = np.stack([pk & 15, pk >> 4], axis=2).reshape(rows, K).astype(np.int16)          # position p = byte p / 2, nibble p % 2
+    at_position = np.where(nib >= 8, nib - 16, nib)
+    assert np.array_equal(_decode_e2m3_rows(out.cpu().numpy(), rows, K), at_position.astype(np.float64))
+    assert np.array_equal(np.sort(at_position, axis=1), np.sort(codes, axis=1))            # the library order is a permutation of a row
+
+
+def _run(qx, qw, dx, dw, bias_bits, debug=True):
+    M, K = qx.shape
+    N = qw.shape[0]
+    (Xq, Xf), (Wq, Wf) = _e2m3(qx), _e2m3(qw)
+    Y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=G.DEV)
+    acc = torch.full((M, N), 12345, dtype=torch.int32, device=G.DEV) if debug else None
+    G.q.qvggt_e2m3_gemm(Xf, G.to_dev(dx), Wf, G.to_dev(dw), G.to_dev(bias_bits), M, N, K, Y, acc)
+    Y8 = torch.empty_like(Y)
+    G.q.qvggt_w4a4_gemm(Xq, G.to_dev(dx), Wq, G.to_dev(dw), G.to_dev(bias_bits), M, N, K, Y8)
+    return acc, Y, Y8
+
+
+@pytest.mark.parametrize("M,N,K", [(64, 128, 128), (1, 16, 128), (300, 384, 256), (129, 144, 1024), (1374, 3072, 1024),
+                                   (257, 1024, 4096), (33, 48, 8192), (500, 1040, 768)])
+@pytest.mark.parametrize("with_bias", [True, False])
+def test_e2m3_gemm_bit_exact(M, N, K, with_bias):
+    rng = np.random.default_rng(M * 7 + N + K)
+    qx = rng.integers(-7, 8, (M, K)).astype(np.int8)
+    qw = rng.integers(-7, 8, (N, K)).astype(np.int8)
+    dx = np.exp(rng.uniform(-3, 1, M)).astype(np.float32)
+    dw = np.exp(rng.uniform(-5, -2, N)).astype(np.float32)
+    bias_bits = f32_to_bf16_bits((rng.standard_normal(N) * 0.02).astype(np.float32)) if with_bias else None
+    acc, Y, Y8 = _run(qx, qw, dx, dw, bias_bits)
+    want = oracle.int_gemm(qx, qw)
+    assert np.array_equal(acc.cpu().numpy(), want)
+    Yo = oracle.dequant_bias(want, dx, dw, None if bias_bits is None else oracle.to_f64(bias_bits))
+    ulp_off = np.abs(G.bf16_bits(Y).astype(np.int32) - Yo.astype(np.int32))
+    assert ulp_off.max() <= 1 and (ulp_off != 0).mean() < 5e-3
+    assert torch.equal(Y, Y8)                                    # the int8-path kernel gives the same bits
+
+
+def test_e2m3_gemm_extreme_sums():
+    """Every product +49 or -49 over the longest row: |acc| = 49 * 8192 needs 19 bits, exact in fp32 whatever the order."""
+    M, N, K = 40, 32, 8192
+    qx = np.full((M, K), 7, dtype=np.int8)
+    qx[1::2] = -7
+    qw = np.full((N, K), 7, dtype=np.int8)
+    qw[::3] = -7
+    qw[5, ::2] = 0
+    acc, Y, Y8 = _run(qx, qw, np.ones(M, np.float32), np.ones(N, np.float32), None)
+    assert np.array_equal(acc.cpu().numpy(), oracle.int_gemm(qx, qw))
+    assert torch.equal(Y, Y8)
+
+
+@pytest.mark.parametrize("M,N,K", [(66000, 512, 256), (65700, 768, 128), (16500, 4096, 1024)])
+def test_e2m3_gemm_both_tile_shapes(M, N, K):
+    """Whole rounds of 256 x 256 tiles plus a remainder that goes to the 128 x 128 configuration: sampled rows (both sides of the
+    seam, the last rows) bit-exact; every row written."""
+    tiles_n = (N + 255) // 256
+    seam = ((M + 255) // 256 * tiles_n // 256 * 256 // tiles_n) * 256
+    assert 0 < seam < M
+    gen = torch.Generator(device="cpu").manual_seed(M)
+    qx = torch.randint(-7, 8, (M, K), generator=gen, dtype=torch.int8).numpy()
+    qw = torch.randint(-7, 8, (N, K), generator=gen, dtype=torch.int8).numpy()
+    rng = np.random.default_rng(M)
+    dx = np.exp(rng.uniform(-3, 1, M)).astype(np.float32)
+    dw = np.exp(rng.uniform(-8, -4, N)).astype(np.float32)
+    acc, Y, Y8 = _run(qx, qw, dx, dw, None)
+    rows = np.unique(np.concatenate([np.arange(0, 8), np.arange(seam - 300, min(seam + 300, M)), np.arange(M - 200, M),
+                                     rng.choice(M, 200, replace=False)]))
+    idx = torch.from_numpy(rows).to(G.DEV)
+    want = oracle.int_gemm(qx[rows], qw)
+    assert np.array_equal(acc[idx].cpu().numpy(), want)
+    Yo = oracle.dequant_bias(want, dx[rows], dw, None)
+    ulp_off = np.abs(G.bf16_bits(Y[idx]).astype(np.int32) - Yo.astype(np.int32))
+    assert ulp_off.max() <= 1 and (ulp_off != 0).mean() < 5e-3
+    assert not torch.isnan(Y.float()).any().item()
+    assert torch.equal(Y, Y8)

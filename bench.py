@@ -1,10 +1,13 @@
 """Benchmark of the W4A4 DSFQ linear path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 5] [--bits 4] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 5] [--bits 4] [--matrix-path e2m3] [--no-cpu-baseline]
 
-A step is one pass of the whole online path (rotate + smooth + per-token quantize, int4 GEMM,
-dequant + bias epilogue: qvggt_linear) over every layer of the chosen synthetic config, inputs
-resident in HBM.  Prints one JSON line.  The default workload is the benchmark's configs[4]
+A step is one pass of the whole online path (rotate + smooth + per-token quantize, int4 x int4 GEMM,
+dequant + bias epilogue) over every layer of the chosen synthetic config, inputs resident in HBM.
+At 4 bits the default matrix path writes the codes as E2M3 numbers and multiplies them on the 6-bit
+floating-point matrix instructions (qvggt_linear_e2m3: the same integer sums and outputs, bit for bit,
+as the int8-instruction path qvggt_linear, which --matrix-path int8 times as the headline and the default
+run reports beside it as "w4a4_int8_path").  Prints one JSON line.  The default workload is the benchmark's configs[4]
 (fc1 and fc2 of the VGGT-1B MLP at 100 frames), the largest single-GPU configuration and the
 one the throughput targets are stated on.  --bits 8 / 6 time the same layers in the 8-bit / 6-bit setting (int8
 codes); the default 4-bit run also reports the 8-bit setting as a side measurement ("w8a8").
@@ -21,6 +24,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 INT8_PEAK_TOPS = 5000.0      # MI355X dense int8 MFMA, published (5.0 POP/s)
+FP6_PEAK_TOPS = 10100.0      # MI355X dense fp6 MFMA, published (10.1 PFLOP/s)
 METRIC = "W4A4 GEMM TOPS (% int8 MFMA peak) + rotate-quant GB/s at VGGT-1B shapes"
 
 
@@ -31,6 +35,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=5, choices=[2, 3, 4, 5])
     ap.add_argument("--bits", type=int, default=4, choices=[4, 6, 8], help="quantization setting timed as the headline")
+    ap.add_argument("--matrix-path", default="e2m3", choices=["e2m3", "int8"],
+                    help="4-bit setting: codes as E2M3 numbers on the 6-bit floating-point matrix instructions, or on the int8 ones")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--headline-only", action="store_true",
                     help="skip the side measurements (8-bit setting, calibration reductions): what the profiles under profiles/ are taken with")
@@ -79,6 +85,8 @@ def main():
                  sx=torch.empty(s.M, dtype=torch.float32, device=dev), prep={})
         L["Xq4"] = L["Xq"].view(-1)[: s.M * s.K // 2].view(s.M, s.K // 2)
         L["Xq8"] = L["Xq"].view(torch.int8)
+        L["Xf"] = L["Xq"].view(-1)[: q.qvggt_e2m3_bytes(s.M, s.K)]          # E2M3 blocks: 3/4 byte per code, rows padded to 128
+        assert L["Xf"].numel() == q.qvggt_e2m3_bytes(s.M, s.K) and L["ws"].numel() >= q.qvggt_workspace_bytes_e2m3(s.M, s.N, s.K)
         for bits in sorted({args.bits} if args.headline_only else {args.bits, 4, 8}):
             sw = torch.empty(s.N, dtype=torch.float32, device=dev)
             inv = torch.empty(s.K, dtype=torch.float32, device=dev)
@@ -89,31 +97,43 @@ def main():
                 Wq = torch.empty(s.N, s.K, dtype=torch.int8, device=dev)
                 q.qvggt_prep_weights_i8(Wd, a, signs, 0.5, bits, Wq, sw, inv)
             L["prep"][bits] = dict(Wq=Wq, sw=sw, inv=inv)
+            if bits == 4:
+                Wf = torch.empty(q.qvggt_e2m3_bytes(s.N, s.K), dtype=torch.uint8, device=dev)
+                q.qvggt_codes_to_e2m3(Wq, s.N, s.K, Wf)
+                L["prep"]["e2m3"] = dict(Wq=Wf, sw=sw, inv=inv)
         layers.append(L)
     torch.cuda.synchronize()
 
     def linear(L, bits):
         P = L["prep"][bits]
-        if bits == 4:
+        if bits == "e2m3":
+            q.qvggt_linear_e2m3(L["X"], L["signs"], P["inv"], P["Wq"], P["sw"], L["bias"], L["Y"], L["ws"])
+        elif bits == 4:
             q.qvggt_linear(L["X"], L["signs"], P["inv"], P["Wq"], P["sw"], L["bias"], L["Y"], L["ws"])
         else:
             q.qvggt_linear_i8(L["X"], L["signs"], P["inv"], bits, P["Wq"], P["sw"], L["bias"], L["Y"], L["ws"])
 
     def rotate_quant(L, bits):
         P, s = L["prep"][bits], L["spec"]
-        if bits == 4:
+        if bits == "e2m3":
+            q.qvggt_rotate_smooth_quant_e2m3(L["X"], L["signs"], P["inv"], L["Xf"], L["sx"])
+        elif bits == 4:
             q.qvggt_rotate_smooth_quant(L["X"], L["signs"], P["inv"], L["Xq4"], L["sx"])
         else:
             q.qvggt_rotate_smooth_quant_i8(L["X"], L["signs"], P["inv"], bits, L["Xq8"], L["sx"])
 
     def gemm(L, bits):
         P, s = L["prep"][bits], L["spec"]
-        if bits == 4:
+        if bits == "e2m3":
+            q.qvggt_e2m3_gemm(L["Xf"], L["sx"], P["Wq"], P["sw"], L["bias"], s.M, s.N, s.K, L["Y"], None)
+        elif bits == 4:
             q.qvggt_w4a4_gemm(L["Xq4"], L["sx"], P["Wq"], P["sw"], L["bias"], s.M, s.N, s.K, L["Y"], None)
         else:
             q.qvggt_i8_gemm(L["Xq8"], L["sx"], P["Wq"], P["sw"], L["bias"], s.M, s.N, s.K, L["Y"], None)
 
-    def step(bits=args.bits):
+    headline = "e2m3" if (args.bits == 4 and args.matrix_path == "e2m3") else args.bits
+
+    def step(bits=headline):
         for L in layers:
             linear(L, bits)
 
@@ -150,46 +170,57 @@ def main():
             rq = float(np.mean([ev[k][i][0].elapsed_time(ev[k][i][1]) for k in range(steps)]))
             gm = float(np.mean([ev[k][i][1].elapsed_time(ev[k][i][2]) for k in range(steps)]))
             x_bytes = 2 if s.x_dtype == "bf16" else 4
-            rq_bytes = s.M * (x_bytes * s.K + s.K * (0.5 if bits == 4 else 1.0) + 4)          # X in, codes out, scale out
+            code_bytes = {"e2m3": 0.75, 4: 0.5}.get(bits, 1.0)
+            rq_bytes = s.M * (x_bytes * s.K + s.K * code_bytes + 4)                           # X in, codes out, scale out
             gemm_ops = 2.0 * s.M * s.N * s.K
             per_layer[s.name] = dict(M=s.M, K=s.K, N=s.N, rotate_quant_ms=rq, rotate_quant_GBps=rq_bytes / rq / 1e6,
                                      gemm_ms=gm, gemm_TOPS=gemm_ops / gm / 1e9)
             rq_ms_all += rq; gemm_ms_all += gm; rq_bytes_all += rq_bytes; gemm_ops_all += gemm_ops
         return per_layer, rq_ms_all, gemm_ms_all, rq_bytes_all, gemm_ops_all
 
-    per_layer, rq_ms_all, gemm_ms_all, rq_bytes_all, gemm_ops_all = per_kernel(args.bits, args.steps)
+    per_layer, rq_ms_all, gemm_ms_all, rq_bytes_all, gemm_ops_all = per_kernel(headline, args.steps)
     n_layers = len(layers)
     gemm_tops = gemm_ops_all / gemm_ms_all / 1e9
     rq_gbps = rq_bytes_all / rq_ms_all / 1e6
 
     # side measurement: the 8-bit setting on the same layers (whole path, then per kernel), outside the headline's timed region
-    side = None
-    if args.bits == 4 and not args.headline_only:
+    def side_run(key):
         n = max(3, args.steps // 4)
         for _ in range(2):
-            step(8)
+            step(key)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(n):
-            step(8)
+            step(key)
         torch.cuda.synchronize()
         ms8 = (time.perf_counter() - t0) * 1e3 / n
-        pl8, rq8, gm8, rqb8, ops8 = per_kernel(8, n)
-        side = dict(steps=n, ms_per_step=ms8, value_TOPS=ops_per_step / (ms8 * 1e-3) / 1e12, gemm_TOPS=ops8 / gm8 / 1e9,
+        pl8, rq8, gm8, rqb8, ops8 = per_kernel(key, n)
+        return dict(steps=n, ms_per_step=ms8, value_TOPS=ops_per_step / (ms8 * 1e-3) / 1e12, gemm_TOPS=ops8 / gm8 / 1e9,
                     gemm_frac_int8_peak=ops8 / gm8 / 1e9 / INT8_PEAK_TOPS, rotate_quant_GBps=rqb8 / rq8 / 1e6,
                     rotate_quant_frac_hbm_peak=rqb8 / rq8 / 1e6 / HBM_PEAK_GBS, per_layer=pl8)
+
+    side, side_int8_path = None, None
+    if args.bits == 4 and not args.headline_only:
+        side = side_run(8)
+        if headline == "e2m3":
+            side_int8_path = side_run(4)
     # HBM bytes per launch measured with rocprofv3 counters (see profiles/); None if that file is absent
     traffic, traffic_rq = None, None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         try:
             t = json.load(open(tpath)).get(f"config{args.config}", {})
-            if args.bits == 4:
+            if headline == "e2m3":
+                traffic, traffic_rq = t.get("e2m3_gemm_bytes_per_launch"), t.get("rotate_quant_e2m3_bytes_per_launch")
+            elif args.bits == 4:
                 traffic, traffic_rq = t.get("w4a4_gemm_bytes_per_launch"), t.get("rotate_quant_bytes_per_launch")
         except Exception:
             traffic, traffic_rq = None, None
-    roofline = dict(kernel="w4a4_gemm_kernel", bound="mfma", achieved=gemm_tops, peak=INT8_PEAK_TOPS, unit="TOP/s",
-                    frac=gemm_tops / INT8_PEAK_TOPS, traffic=traffic,
+    # the contraction is priced against the peak of the matrix instructions it runs on
+    mfma_peak = FP6_PEAK_TOPS if headline == "e2m3" else INT8_PEAK_TOPS
+    roofline = dict(kernel="e2m3_gemm_kernel" if headline == "e2m3" else "w4a4_gemm_kernel", bound="mfma", achieved=gemm_tops,
+                    peak=mfma_peak, unit="TFLOP/s" if headline == "e2m3" else "TOP/s",
+                    frac=gemm_tops / mfma_peak, traffic=traffic,
                     ops_per_launch=gemm_ops_all / n_layers, avg_launch_ms=gemm_ms_all / n_layers)
     roofline_rq = dict(kernel="rotate_quant_mfma_kernel", bound="hbm", achieved=rq_gbps, peak=HBM_PEAK_GBS, unit="GB/s",
                        frac=rq_gbps / HBM_PEAK_GBS, traffic=traffic_rq,
@@ -274,7 +305,8 @@ def main():
     out = {
         "metric": METRIC if args.bits == 4 else METRIC.replace("W4A4", f"W{args.bits}A{args.bits}"), "value": value, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": ("int4" if args.bits == 4 else f"int{args.bits} in int8") + " (int8 MFMA, int32 accumulate)", "data": "synthetic",
+        "dtype": ("int4 codes as fp6 E2M3 (fp6 MFMA, fp32 accumulate: exact integer sums)" if headline == "e2m3" else
+                  ("int4" if args.bits == 4 else f"int{args.bits} in int8") + " (int8 MFMA, int32 accumulate)"), "data": "synthetic",
         "config": {"workload": f"BASELINE configs[{args.config - 1}]: " + ", ".join(
             f"{L['spec'].name} {L['spec'].M}x{L['spec'].K}->{L['spec'].N}" for L in layers),
             "tokens": s0.M, "frames": s0.frames, "layers": [L["spec"].name for L in layers], "parallelism": "1 GPU"},
@@ -284,6 +316,8 @@ def main():
     }
     if side is not None:
         out["w8a8"] = side
+    if side_int8_path is not None:
+        out["w4a4_int8_path"] = side_int8_path
     if nfds is not None:
         out["calibration_reductions"] = nfds
     print(json.dumps(out))

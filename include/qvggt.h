@@ -183,8 +183,20 @@ int qvggt_w4a4_gemm(const uint8_t *Xq, const float *x_scale, const uint8_t *Wq, 
  *                       distinct buffers; a nibble -8 saturates to -7.
  * qvggt_e2m3_gemm:      Xf, Wf E2M3 blocks of M and N rows; everything else as qvggt_w4a4_gemm (acc_debug receives
  *                       the exact sums as int32).
+ * qvggt_rotate_smooth_quant_e2m3:  online kernel 1 writing E2M3 blocks directly (the same codes and steps as
+ *                       qvggt_rotate_smooth_quant; a code 0 may carry a sign bit).  bf16 X with K = 1024, 2048 or 4096 only:
+ *                       other K are QVGGT_ERR_SHAPE, f32 X is QVGGT_ERR_DTYPE (use qvggt_rotate_smooth_quant and
+ *                       qvggt_codes_to_e2m3 there).
+ * qvggt_linear_e2m3:    both kernels on one stream, as qvggt_linear; Wf = qvggt_codes_to_e2m3 of qvggt_prep_weights'
+ *                       Wq; workspace of qvggt_workspace_bytes_e2m3(M, N, K) bytes; same restriction on X and K.
  */
 size_t qvggt_e2m3_bytes(int rows, int K);
+int qvggt_rotate_smooth_quant_e2m3(const void *X, int x_dtype, int M, int K, const int8_t *signs,
+                                   const float *inv_smooth, uint8_t *Xf, float *x_scale, void *stream);
+size_t qvggt_workspace_bytes_e2m3(int M, int N, int K);
+int qvggt_linear_e2m3(const void *X, int x_dtype, int M, int N, int K, const int8_t *signs, const float *inv_smooth,
+                      const uint8_t *Wf, const float *w_scale, const void *bias, void *Y, void *workspace,
+                      size_t workspace_bytes, void *stream);
 int qvggt_codes_to_e2m3(const uint8_t *packed, int rows, int K, uint8_t *out, void *stream);
 int qvggt_e2m3_gemm(const uint8_t *Xf, const float *x_scale, const uint8_t *Wf, const float *w_scale,
                     const void *bias, int M, int N, int K, void *Y, int32_t *acc_debug, void *stream);

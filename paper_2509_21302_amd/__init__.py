@@ -18,6 +18,9 @@ from .binding import (  # noqa: F401
     qvggt_weight_code_sums,
     qvggt_w4a4_gemm_asym,
     qvggt_e2m3_bytes,
+    qvggt_rotate_smooth_quant_e2m3,
+    qvggt_workspace_bytes_e2m3,
+    qvggt_linear_e2m3,
     qvggt_codes_to_e2m3,
     qvggt_e2m3_gemm,
     qvggt_w4a4_gemm,

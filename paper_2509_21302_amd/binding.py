@@ -19,6 +19,7 @@ EXPORTS = [
     "qvggt_rotate_smooth_quant_static", "qvggt_layernorm_rotate_smooth_quant",
     "qvggt_rotate_smooth_quant_asym", "qvggt_weight_code_sums", "qvggt_w4a4_gemm_asym",
     "qvggt_e2m3_bytes", "qvggt_codes_to_e2m3", "qvggt_e2m3_gemm",
+    "qvggt_rotate_smooth_quant_e2m3", "qvggt_workspace_bytes_e2m3", "qvggt_linear_e2m3",
     "qvggt_w4a4_gemm", "qvggt_linear", "qvggt_workspace_bytes", "qvggt_pack_int4", "qvggt_unpack_int4",
     "qvggt_prep_weights_i8", "qvggt_rotate_smooth_quant_i8", "qvggt_i8_gemm", "qvggt_linear_i8",
     "qvggt_workspace_bytes_i8", "qvggt_layout_int8",
@@ -68,6 +69,12 @@ def load_library() -> C.CDLL:
     lib.qvggt_weight_code_sums.argtypes = [vp, i, i, vp, vp]
     lib.qvggt_w4a4_gemm_asym.restype = i
     lib.qvggt_w4a4_gemm_asym.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, vp, vp]
+    lib.qvggt_rotate_smooth_quant_e2m3.restype = i
+    lib.qvggt_rotate_smooth_quant_e2m3.argtypes = [vp, i, i, i, vp, vp, vp, vp, vp]
+    lib.qvggt_workspace_bytes_e2m3.restype = C.c_size_t
+    lib.qvggt_workspace_bytes_e2m3.argtypes = [i, i, i]
+    lib.qvggt_linear_e2m3.restype = i
+    lib.qvggt_linear_e2m3.argtypes = [vp, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.qvggt_e2m3_bytes.restype = C.c_size_t
     lib.qvggt_e2m3_bytes.argtypes = [i, i]
     lib.qvggt_codes_to_e2m3.restype = i
@@ -199,6 +206,24 @@ def qvggt_weight_code_sums(Wq, N, K, w_codesum, stream=None):
 def qvggt_w4a4_gemm_asym(Xq, x_scale, x_zero, Wq, w_scale, w_codesum, bias, M, N, K, Y, stream=None):
     _check(load_library().qvggt_w4a4_gemm_asym(_ptr(Xq), _ptr(x_scale), _ptr(x_zero), _ptr(Wq), _ptr(w_scale), _ptr(w_codesum),
                                                _ptr(bias), M, N, K, _ptr(Y), _stream(stream)), "qvggt_w4a4_gemm_asym")
+
+
+def qvggt_rotate_smooth_quant_e2m3(X, signs, inv_smooth, Xf, x_scale, stream=None):
+    M, K = X.shape
+    _check(load_library().qvggt_rotate_smooth_quant_e2m3(_ptr(X), _dtype_code(X), M, K, _ptr(signs), _ptr(inv_smooth), _ptr(Xf),
+                                                         _ptr(x_scale), _stream(stream)), "qvggt_rotate_smooth_quant_e2m3")
+
+
+def qvggt_workspace_bytes_e2m3(M, N, K):
+    return int(load_library().qvggt_workspace_bytes_e2m3(M, N, K))
+
+
+def qvggt_linear_e2m3(X, signs, inv_smooth, Wf, w_scale, bias, Y, workspace, stream=None):
+    M, K = X.shape
+    N = Y.shape[1]
+    _check(load_library().qvggt_linear_e2m3(_ptr(X), _dtype_code(X), M, N, K, _ptr(signs), _ptr(inv_smooth), _ptr(Wf), _ptr(w_scale),
+                                            _ptr(bias), _ptr(Y), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                            _stream(stream)), "qvggt_linear_e2m3")
 
 
 def qvggt_e2m3_bytes(rows, K):

@@ -23,6 +23,8 @@ hipError_t run_rotate_smooth_quant_asym(const void *X, bool f32, int rows, int K
 hipError_t run_code_sums(const uint8_t *packed, int rows, int K, float *sums, hipStream_t stream);
 hipError_t run_w4a4_gemm_asym(const uint8_t *Xq, const float *sx, const float *xzero, const uint8_t *Wq, const float *sw,
                               const float *wsum, const void *bias, int M, int N, int K, void *Y, hipStream_t stream);
+hipError_t run_rotate_quant_e2m3_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, uint8_t *out,
+                                      float *scale, hipStream_t stream);
 hipError_t run_codes_to_e2m3(const uint8_t *packed, int rows, int K, uint8_t *out, hipStream_t stream);
 hipError_t run_e2m3_gemm(const uint8_t *Xf, const float *sx, const uint8_t *Wf, const float *sw, const void *bias, int M, int N,
                          int K, void *Y, int32_t *acc_debug, hipStream_t stream);
@@ -244,6 +246,48 @@ int qvggt_codes_to_e2m3(const uint8_t *packed, int rows, int K, uint8_t *out, vo
     if (!packed || !out) return QVGGT_ERR_NULL;
     if (!aligned16(packed) || !aligned16(out)) return QVGGT_ERR_ALIGN;
     return hip_status(qvggt::run_codes_to_e2m3(packed, rows, K, out, static_cast<hipStream_t>(stream)));
+}
+
+static bool e2m3_direct(int x_dtype, int K) { return x_dtype == QVGGT_BF16 && (K == 1024 || K == 2048 || K == 4096); }
+
+int qvggt_rotate_smooth_quant_e2m3(const void *X, int x_dtype, int M, int K, const int8_t *signs, const float *inv_smooth,
+                                   uint8_t *Xf, float *x_scale, void *stream)
+{
+    if (!valid_dtype(x_dtype)) return QVGGT_ERR_DTYPE;
+    if (M < 0 || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (!e2m3_direct(x_dtype, K)) return x_dtype == QVGGT_BF16 ? QVGGT_ERR_SHAPE : QVGGT_ERR_DTYPE;
+    if (M == 0) return QVGGT_OK;
+    if (!X || !Xf || !x_scale) return QVGGT_ERR_NULL;
+    if (!aligned16(X) || !aligned16(Xf) || !aligned16(x_scale) || !aligned16(inv_smooth) || !aligned16(signs))
+        return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_rotate_quant_e2m3_mfma(X, M, K, signs, inv_smooth, Xf, x_scale, static_cast<hipStream_t>(stream)));
+}
+
+size_t qvggt_workspace_bytes_e2m3(int M, int N, int K)
+{
+    if (M < 0 || !valid_n(N) || !valid_k(K)) return 0;
+    return round_up(qvggt_e2m3_bytes(M, K), 256) + round_up((size_t)M * sizeof(float), 256);
+}
+
+int qvggt_linear_e2m3(const void *X, int x_dtype, int M, int N, int K, const int8_t *signs, const float *inv_smooth,
+                      const uint8_t *Wf, const float *w_scale, const void *bias, void *Y, void *workspace,
+                      size_t workspace_bytes, void *stream)
+{
+    if (!valid_dtype(x_dtype)) return QVGGT_ERR_DTYPE;
+    if (M < 0 || !valid_n(N) || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (!e2m3_direct(x_dtype, K)) return x_dtype == QVGGT_BF16 ? QVGGT_ERR_SHAPE : QVGGT_ERR_DTYPE;
+    if (M == 0) return QVGGT_OK;
+    if (!X || !Wf || !w_scale || !Y || !workspace) return QVGGT_ERR_NULL;
+    if (!aligned16(X) || !aligned16(Wf) || !aligned16(w_scale) || !aligned16(bias) || !aligned16(Y) ||
+        !aligned16(workspace) || !aligned16(inv_smooth) || !aligned16(signs))
+        return QVGGT_ERR_ALIGN;
+    if (workspace_bytes < qvggt_workspace_bytes_e2m3(M, N, K)) return QVGGT_ERR_WORKSPACE;
+    uint8_t *Xf = static_cast<uint8_t *>(workspace);
+    float *x_scale = reinterpret_cast<float *>(Xf + round_up(qvggt_e2m3_bytes(M, K), 256));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = qvggt::run_rotate_quant_e2m3_mfma(X, M, K, signs, inv_smooth, Xf, x_scale, s);
+    if (e != hipSuccess) return QVGGT_ERR_HIP;
+    return hip_status(qvggt::run_e2m3_gemm(Xf, x_scale, Wf, w_scale, bias, M, N, K, Y, nullptr, s));
 }
 
 int qvggt_e2m3_gemm(const uint8_t *Xf, const float *x_scale, const uint8_t *Wf, const float *w_scale, const void *bias,

@@ -72,6 +72,7 @@ __host__ __device__ constexpr int row_of_seg_hi(int seg_hi /* seg >> 2 */)
 }  // namespace rq
 
 // CB: bits a stored code occupies: 4 (packed nibbles, codes in [-8, 7]) or 8 (int8, codes in [-qmax - 1, qmax]);
+// CB = 6: 4-bit codes written as E2M3 numbers in the 128-row blocks the 6-bit matrix path reads (dynamic steps only: codes in [-7, 7]);
 // CB = 0 is the statistic mode: nothing is quantized or stored, the kernel leaves max_t |X H / sqrt(K)|[t, j] per column j
 // in col_absmax_bits (the numerator of the smoothing factor, Sec. 3.2), which must be zero on entry
 // LN: a LayerNorm of every token (fp32, result rounded to bf16 as a separate normalisation kernel would hand it on) is
@@ -91,6 +92,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
 {
     constexpr bool STAT = (CB == 0);
     static_assert(!ASYM || (CB == 4 && !STATIC), "affine codes: dynamic 4-bit only");
+    static_assert(CB != 6 || !STATIC, "E2M3 has no -8: dynamic steps only");
     using C = rq::Cfg<K>;
     constexpr int REM = C::REM, TOK = C::TOK;
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[rq::WAVES_PER_BLOCK * rq::LDS_PER_WAVE];
@@ -215,11 +217,21 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
             for (int j = 0; j < 8; ++j) dst[j] = load16(tile_ptr(t, j));
         }
     };
+    // E2M3 output at K = 4096: a token's 64 units lie 6 KiB apart in the output, 48 bytes each; the four waves of a block take
+    // four consecutive tokens and flush them together through LDS, so that memory sees runs of 192 bytes per unit (48-byte
+    // pieces cost 190 us more at 137400 tokens).  The block then iterates as one: same trip count, barriers inside the loop.
+    constexpr bool BLOCK_FLUSH = (CB == 6 && REM == 5);
+    __shared__ __attribute__((aligned(16))) uint8_t flush_all[BLOCK_FLUSH ? 4 * 64 * 48 : 16];
     uint4 G[PF][8];
     int tile = wave;
 #pragma unroll
-    for (int p = 0; p < PF; ++p)
+    for (int p = 0; p < PF; ++p) {
         if (tile + p * nwaves < ntiles) load_tile(tile + p * nwaves, G[p]);
+        else if constexpr (BLOCK_FLUSH) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) G[p][j] = make_uint4(0u, 0u, 0u, 0u);
+        }
+    }
     const int wr_base = ((lane >> 4) * rq::LDS_PITCH) + (lane & 15) * 16;
     const int rd_base = c * rq::LDS_PITCH + g * 16;
 
@@ -229,7 +241,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) cmax[h][nt] = 0.0f;
 
-    for (; tile < ntiles; tile += nwaves) {
+    for (; (BLOCK_FLUSH ? tile - wave_in_block : tile) < ntiles; tile += nwaves) {
         if constexpr (LN) {
             // every token of the tile: mean, variance (two passes over the registers), normalise, scale / shift, back to bf16
 #pragma unroll
@@ -384,9 +396,63 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
                 inv = delta > 0.0f ? 1.0f / delta : 0.0f;
             } else {
                 // hardware reciprocal (1 ulp) instead of two IEEE divisions: |z| * inv <= qmax (1 + 2^-22) still rounds to qmax
-                const float qmax = (CB == 4) ? 7.0f : qmax8;
+                const float qmax = (CB == 4 || CB == 6) ? 7.0f : qmax8;
                 delta = amax[t] / qmax;
                 inv = amax[t] > 0.0f ? qmax * __builtin_amdgcn_rcpf(amax[t]) : 0.0f;
+            }
+            if constexpr (CB == 6) {
+                // The lane's NL codes are positions P0 .. P0 + NL - 1 of the row, i.e. NL / 32 whole blobs; field f of a blob is local
+                // index 32 bb + f = nt + 4 h.  The conversion instruction takes the even fields from its first operand and the odd
+                // ones from its second; integers up to 7 are E2M3 numbers, so it is exact.
+                typedef float v16f __attribute__((ext_vector_type(16)));
+                typedef unsigned int v6u __attribute__((ext_vector_type(6)));
+                const int P0 = c * (K / 32) + (REM == 5 ? g * 64 : 0);
+#pragma unroll
+                for (int bb = 0; bb < C::NL / 32; ++bb) {
+                    v16f ev, od;
+#pragma unroll
+                    for (int k = 0; k < 16; ++k) {
+                        const int h = 8 * bb + k / 2;
+                        // rounded exactly as the packed codes are: one fused rounding onto the integer grid of the magic constant
+                        ev[k] = fmaf(acc[(2 * k) & 3][t * C::HB_PER_LANE + h], inv, rq::MAGIC) - rq::MAGIC;
+                        od[k] = fmaf(acc[(2 * k + 1) & 3][t * C::HB_PER_LANE + h], inv, rq::MAGIC) - rq::MAGIC;
+                    }
+                    const v6u blob = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(ev, od, 1.0f);
+                    if constexpr (REM == 5) {
+                        // K = 4096: the lane holds both blobs of unit 2 c + g, i.e. that unit's 48 bytes of this wave's token; they go
+                        // to the block's flush area [unit][wave][48 bytes]
+                        uint8_t *slot = flush_all + (2 * c + g) * 192 + wave_in_block * 48;
+                        if (bb == 0) {
+                            *reinterpret_cast<uint4 *>(slot) = make_uint4(blob[0], blob[1], blob[2], blob[3]);
+                            *reinterpret_cast<uint2 *>(slot + 32) = make_uint2(blob[4], blob[5]);
+                        } else {
+                            *reinterpret_cast<uint4 *>(slot + 16) = make_uint4(blob[0], blob[1], blob[2], blob[3]);
+                            *reinterpret_cast<uint2 *>(slot + 40) = make_uint2(blob[4], blob[5]);
+                        }
+                        continue;
+                    }
+                    if (row < rows) {
+                        const int pb = P0 / 32 + bb;            // blob of the row: unit pb / 2, half pb % 2
+                        uint8_t *u = packed + ((size_t)(row / 128) * (K / 64) + (pb >> 1)) * 6144 + (size_t)(row % 128) * 48;
+                        *reinterpret_cast<uint4 *>(u + (pb & 1) * 16) = make_uint4(blob[0], blob[1], blob[2], blob[3]);
+                        *reinterpret_cast<uint2 *>(u + 32 + (pb & 1) * 8) = make_uint2(blob[4], blob[5]);
+                    }
+                }
+                if constexpr (REM == 5) {
+                    __syncthreads();
+                    // the block's four tokens are rows row4 .. row4 + 3 of one 128-row block: 192 contiguous bytes per unit
+                    const int row4 = tile - wave_in_block;
+                    uint8_t *rb = packed + (size_t)(row4 / 128) * (K / 64) * 6144 + (size_t)(row4 % 128) * 48;
+#pragma unroll
+                    for (int i = 0; i < 3; ++i) {
+                        const int j = i * 256 + (int)threadIdx.x, unit = j / 12, within = j - 12 * unit;     // 16-byte chunk j of 768
+                        if (row4 + within / 3 < rows)
+                            *reinterpret_cast<uint4 *>(rb + (size_t)unit * 6144 + within * 16) = *reinterpret_cast<const uint4 *>(flush_all + j * 16);
+                    }
+                    __syncthreads();
+                }
+                if (row < rows && c == 0 && (REM != 5 || g == 0)) scale[row] = delta;
+                continue;
             }
             if constexpr (CB == 8) {
                 // four codes per word: byte i of word d is local index 4*d + i = nt + 4*h  ->  nt = i, h = d
@@ -524,6 +590,27 @@ hipError_t run_rotate_quant_asym_mfma(const void *X, int rows, int K, const int8
         default: return hipErrorInvalidValue;
     }
 #undef RQA
+    return hipGetLastError();
+}
+
+// rotation + smoothing + per-token 4-bit codes as E2M3 blocks (what the 6-bit matrix GEMM reads), bf16 rows, K = 1024 / 2048 / 4096
+hipError_t run_rotate_quant_e2m3_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, uint8_t *out,
+                                      float *scale, hipStream_t stream)
+{
+    if (rows <= 0) return hipSuccess;
+    const uint16_t *x = reinterpret_cast<const uint16_t *>(X);
+    const int tok = 32 / (K / 128);
+    const int ntiles = (rows + tok - 1) / tok;
+    int blocks = (ntiles + rq::WAVES_PER_BLOCK - 1) / rq::WAVES_PER_BLOCK;
+    if (blocks > 256 * 2) blocks = 256 * 2;
+#define RQE(KK) rotate_quant_mfma_kernel<KK, 1, 2, false, 6><<<blocks, 256, 0, stream>>>(x, rows, signs, mul, 0, out, scale, nullptr, 0, 7.0f, nullptr)
+    switch (K) {
+        case 1024: RQE(1024); break;
+        case 2048: RQE(2048); break;
+        case 4096: RQE(4096); break;
+        default: return hipErrorInvalidValue;
+    }
+#undef RQE
     return hipGetLastError();
 }
 

@@ -118,6 +118,22 @@ def test_argument_validation_needs_no_gpu():
     assert ga(P, P, P, P, P, None, None, 4, 32, 1024, P, None) == NULL
     assert ga(P, P, P, P, P, P + 4, None, 4, 32, 1024, P, None) == ALIGN
     assert ga(None, None, None, None, None, None, None, 0, 32, 1024, None, None) == OK
+    # 6-bit floating-point matrix path: format size, converter, GEMM, direct kernel 1 (bf16, K = 1024 / 2048 / 4096 only)
+    assert q.qvggt_e2m3_bytes(1, 1024) == 128 * 768 and q.qvggt_e2m3_bytes(129, 4096) == 256 * 3072 and q.qvggt_e2m3_bytes(5, 1000) == 0
+    cv, eg, re, le = lib.qvggt_codes_to_e2m3, lib.qvggt_e2m3_gemm, lib.qvggt_rotate_smooth_quant_e2m3, lib.qvggt_linear_e2m3
+    assert cv(P, 4, 1000, P, None) == SHAPE and cv(None, 4, 1024, P, None) == NULL and cv(P, 4, 1024, P + 4, None) == ALIGN
+    assert cv(None, 0, 1024, None, None) == OK
+    assert eg(P, P, P, P, None, 4, 100, 1024, P, None, None) == SHAPE
+    assert eg(P, P, None, P, None, 4, 32, 1024, P, None, None) == NULL
+    assert eg(P, P, P, P, P + 4, 4, 32, 1024, P, None, None) == ALIGN
+    assert eg(None, None, None, None, None, 0, 32, 1024, None, None, None) == OK
+    assert re(P, 0, 4, 512, None, None, P, P, None) == SHAPE and re(P, 1, 4, 1024, None, None, P, P, None) == DTYPE
+    assert re(P, 0, 4, 1024, None, None, None, P, None) == NULL and re(None, 0, 0, 1024, None, None, None, None, None) == OK
+    need6 = q.qvggt_workspace_bytes_e2m3(100, 32, 1024)
+    assert need6 >= 128 * 768 + 400
+    assert le(P, 0, 100, 32, 1024, None, None, P, P, None, P, P, need6 - 1, None) == WORKSPACE
+    assert le(P, 0, 100, 32, 768, None, None, P, P, None, P, P, need6, None) == SHAPE
+    assert le(P, 1, 100, 32, 1024, None, None, P, P, None, P, P, need6, None) == DTYPE
     # 8-bit / 6-bit entry points: the same checks, and the bit-width
     for bad in (3, 9, 0, -8):
         assert lib.qvggt_rotate_smooth_quant_i8(P, 0, 4, 1024, None, None, bad, P, P, None) == ARG

@@ -122,3 +122,65 @@ def test_e2m3_gemm_both_tile_shapes(M, N, K):
     assert ulp_off.max() <= 1 and (ulp_off != 0).mean() < 5e-3
     assert not torch.isnan(Y.float()).any().item()
     assert torch.equal(Y, Y8)
+
+
+def _heavy_bf16(rows, K, seed):
+    import synth
+    rng = np.random.default_rng(seed)
+    x = rng.standard_t(3, (rows, K)).astype(np.float32)
+    x[:, rng.choice(K, max(1, K // 100), replace=False)] *= 50
+    x[: min(5, rows)] *= 20
+    return synth.f32_to_bf16_bits(x)
+
+
+@pytest.mark.parametrize("K,rows", [(1024, 1031), (2048, 300), (4096, 203)])
+def test_rotate_quant_e2m3_is_kernel_1_in_another_format(K, rows):
+    """Kernel 1 writing E2M3 blocks directly: decoded values equal the oracle's codes at the library's positions to the usual
+    bar, equal the converted output of the packed-code kernel exactly, and the steps are the same floats."""
+    X = _heavy_bf16(rows, K, 900 + K)
+    X[7] = 0
+    rng = np.random.default_rng(K + 1)
+    signs = (rng.integers(0, 2, K) * 2 - 1).astype(np.int8)
+    c_hat = np.exp(rng.uniform(-1, 1, K))
+    inv = (1.0 / (np.sqrt(K) * c_hat)).astype(np.float32)
+    Xd, sd, invd = G.to_dev(X), G.to_dev(signs), G.to_dev(inv)
+    Xq, sx = G.gpu_rsq(Xd, sd, invd)
+    Xf = torch.full((G.q.qvggt_e2m3_bytes(rows, K),), 0xA5, dtype=torch.uint8, device=G.DEV)
+    sxf = torch.empty(rows, dtype=torch.float32, device=G.DEV)
+    G.q.qvggt_rotate_smooth_quant_e2m3(Xd, sd, invd, Xf, sxf)
+    assert torch.equal(sx, sxf)
+    got = _decode_e2m3_rows(Xf.cpu().numpy(), rows, K)
+    conv = torch.full_like(Xf, 0xA5)
+    G.q.qvggt_codes_to_e2m3(Xq, rows, K, conv)
+    assert np.array_equal(got, _decode_e2m3_rows(conv.cpu().numpy(), rows, K))           # -0 and 0 compare equal
+    assert not got[7].any()
+    # against the oracle: positions -> natural order through the library's own unpack of the packed rows is not used here;
+    # a row's codes are compared as multisets per unit-independent statistic, and element-wise via the packed kernel's parity
+    dx, qx, _ = oracle.rotate_smooth_quant(X, 1.0 / (inv.astype(np.float64) * np.sqrt(K)), pre_signs=signs)
+    G.check_scales(sxf.cpu().numpy(), dx)
+    G.check_codes(G.gpu_unpack(Xq, K), qx)                       # the packed kernel is at parity, and the E2M3 output equals it
+    assert np.abs(got).max() <= 7
+
+
+@pytest.mark.parametrize("name,M", [("fc1", 3000), ("fc2", 700)])
+def test_linear_e2m3_matches_the_oracle_and_the_int8_path(name, M):
+    """Whole online path through the 6-bit matrix instructions against the oracle's layer; bit-identical to qvggt_linear."""
+    import synth
+    s = synth.layer_spec(5, name)
+    K, N = s.K, s.N
+    rng = np.random.default_rng(M)
+    X = _heavy_bf16(M, K, 40 + M)
+    W = synth.make_weights(s)
+    bias = synth.make_bias(s)
+    signs = synth.make_signs(s)
+    cal = X[:512]
+    po = oracle.prepare_weights(W, oracle.rotated_col_absmax(cal, pre_signs=signs), pre_signs=signs)
+    want = oracle.linear(X, po, bias=bias, pre_signs=signs)
+    pg = G.gpu_prep(W, cal, signs)
+    Wf = torch.empty(G.q.qvggt_e2m3_bytes(N, K), dtype=torch.uint8, device=G.DEV)
+    G.q.qvggt_codes_to_e2m3(pg["Wq"], N, K, Wf)
+    Y = torch.empty(M, N, dtype=torch.bfloat16, device=G.DEV)
+    ws = torch.empty(G.q.qvggt_workspace_bytes_e2m3(M, N, K), dtype=torch.uint8, device=G.DEV)
+    G.q.qvggt_linear_e2m3(G.to_dev(X), pg["signs"], pg["inv"], Wf, pg["sw"], G.to_dev(bias), Y, ws)
+    assert G.rel_fro(G.bf16_bits(Y), want.Y) <= G.Y_REL_FRO
+    assert torch.equal(Y, G.gpu_linear(G.to_dev(X), pg, G.to_dev(bias)))

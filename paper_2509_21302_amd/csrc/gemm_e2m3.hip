@@ -4,7 +4,7 @@
 //   Y[t, o]   = bf16( acc[t, o] * sx[t] * sw[o] + bias[o] )
 //
 // with every 4-bit code q in [-7, 7] written as the E2M3 number of the same value (1 sign, 2 exponent, 3 mantissa bits:
-// 0, 1, 2, ..., 7 are all representable) and multiplied by v_mfma_scale_f32_32x32x64_f8f6f4 with unit scales.  Products are
+// 0, 1, 2, ..., 7 are all representable) and multiplied by v_mfma_f32_32x32x64_f8f6f4 (no block scales).  Products are
 // integers of magnitude <= 49 and sums of magnitude <= 49 * 8192 < 2^24, so the fp32 accumulators hold the integer sum
 // exactly, in any order of addition: the result is the int32 accumulator of the int8 path, bit for bit.  On gfx950 this
 // MFMA retires 64 codes per row in the time the int8 one retires 32, and a lane's operand comes from LDS as it is (no
@@ -44,7 +44,10 @@ namespace {
 constexpr int U_BYTES = 48;        // bytes per row per unit: 64 codes of 6 bits
 constexpr int RB = 128;            // rows per block of the operand format
 constexpr int RB_BYTES = RB * U_BYTES;   // one unit of one block: 6 KiB contiguous
-constexpr int UNIT_SCALE_ONE = 0x7F7F7F7F;   // E8M0 exponent 127 = 2^0 in every byte: unit block scales
+// Scale operands of the matrix builtin.  Constant zeros make the compiler emit the instruction form without block scales
+// (v_mfma_f32_32x32x64_f8f6f4: products as they are), one instruction per MFMA instead of two; 0x7F7F7F7F (E8M0 exponent 127 = 2^0
+// in every byte) is the explicit unit scale and gives the same sums.
+constexpr int UNIT_SCALE_ONE = 0;
 
 template <int TM, int TN, int WM, int WN, int STAGES>
 struct E2m3Cfg {
@@ -264,7 +267,9 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
         // the barrier it has landed for every wave, and every wave is done reading unit q - 1, whose stage is refilled now
         auto unit = [&](auto buf_c, auto fresh_c) {
             constexpr bool FRESH = decltype(fresh_c)::value;
+#ifndef QVGGT_E2M3_NO_WAIT
             e_wait_vmcnt<(STAGES - 3) * LPW>();
+#endif
             __syncthreads();
             if (FRESH && tile + slots < tile_end) {
                 int tnext = tile + slots;

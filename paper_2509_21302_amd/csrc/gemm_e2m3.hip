@@ -109,7 +109,7 @@ template <int TM, int TN, int WM, int WN, int STAGES, int MINB, bool DEBUG>
 __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per_eu(WM * WN * MINB / 4, WM * WN * MINB / 4))) void e2m3_gemm_kernel(
     const uint8_t *__restrict__ Xf, const float *__restrict__ sx, const uint8_t *__restrict__ Wf,
     const float *__restrict__ sw, const uint16_t *__restrict__ bias, int M, int N, int K,
-    uint16_t *__restrict__ Y, int32_t *__restrict__ acc_debug, int tiles_m, int tiles_n)
+    uint16_t *__restrict__ Y, int32_t *__restrict__ acc_debug, int tiles_m, int tiles_n, long long *dbg_times)
 {
     using C = E2m3Cfg<TM, TN, WM, WN, STAGES>;
     constexpr int NM = C::NM, NF = C::NF, LPW = C::LPW;
@@ -262,15 +262,25 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
 
     const int c = lane & 31, g = lane >> 5;
     int cs = 0, sb = 0;                                   // ring stage being computed on, scale buffer of the current tile
+#ifdef QVGGT_DEV
+    long long t_main = 0, t_epi = 0, t_bar = 0, t_start = clock64(), w_start = wall_clock64(); int n_tiles = 0;
+#endif
     for (int tile = first_tile; tile < tile_end; tile += slots) {
+#ifdef QVGGT_DEV
+        const long long t0 = clock64();
+#endif
         // unit q of the stream: unit q + 1 has landed for this wave once at most STAGES - 3 later units are outstanding; after
         // the barrier it has landed for every wave, and every wave is done reading unit q - 1, whose stage is refilled now
         auto unit = [&](auto buf_c, auto fresh_c) {
             constexpr bool FRESH = decltype(fresh_c)::value;
-#ifndef QVGGT_E2M3_NO_WAIT
-            e_wait_vmcnt<(STAGES - 3) * LPW>();
+#ifdef QVGGT_DEV
+            const long long tb0 = clock64();
 #endif
+            e_wait_vmcnt<(STAGES - 3) * LPW>();
             __syncthreads();
+#ifdef QVGGT_DEV
+            t_bar += clock64() - tb0;
+#endif
             if (FRESH && tile + slots < tile_end) {
                 int tnext = tile + slots;
                 asm volatile("" : "+s"(tnext));
@@ -288,6 +298,9 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
             unit(I1{}, BF{});
         }
 
+#ifdef QVGGT_DEV
+        const long long t1 = clock64(); t_main += t1 - t0;
+#endif
         // ---- epilogue.  32x32 result layout: lane l holds column (l % 32) = token and rows 8*(r/4) + 4*(l/32) + r%4 = channels
         const int tm = tile / tiles_n, tn = tile % tiles_n;
         const int row0 = tm * C::BM + wm * TM * 32, col0 = tn * C::BN + wn * TN * 32;
@@ -361,7 +374,16 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
             }
         }
         sb ^= 1;
+#ifdef QVGGT_DEV
+        t_epi += clock64() - t1; ++n_tiles;
+#endif
     }
+#ifdef QVGGT_DEV
+    if (dbg_times != nullptr && lane == 0) {
+        long long *o = dbg_times + ((size_t)blockIdx.x * C::NW + wave) * 8;
+        o[0] = t_main; o[1] = t_epi; o[2] = t_bar; o[3] = clock64() - t_start; o[4] = n_tiles; o[5] = wall_clock64() - w_start;
+    }
+#endif
     e_wait_vmcnt<0>();      // transfers issued past the last tile must not outlive the block's LDS allocation
 }
 
@@ -408,6 +430,14 @@ static hipError_t launch_e2m3(const uint8_t *Xf, const float *sx, const uint8_t 
                               int M, int N, int K, void *Y, int32_t *acc_debug, hipStream_t stream)
 {
     using C = E2m3Cfg<TM, TN, WM, WN, STAGES>;
+    long long *dbg = nullptr;
+#ifdef QVGGT_DEV
+    // development builds: QVGGT_TIMING=1 reinterprets acc_debug as a buffer for per-wave cycle counters
+    if (getenv("QVGGT_TIMING") && acc_debug != nullptr) {
+        dbg = reinterpret_cast<long long *>(acc_debug);
+        acc_debug = nullptr;
+    }
+#endif
     const bool debug = acc_debug != nullptr;
     auto kern = debug ? e2m3_gemm_kernel<TM, TN, WM, WN, STAGES, MINB, true> : e2m3_gemm_kernel<TM, TN, WM, WN, STAGES, MINB, false>;
     static bool attr_set[2] = {false, false};
@@ -421,12 +451,11 @@ static hipError_t launch_e2m3(const uint8_t *Xf, const float *sx, const uint8_t 
     int grid = 256 * MINB;
     if (grid > (ntiles + 7) / 8 * 8) grid = (ntiles + 7) / 8 * 8;
     kern<<<grid, C::THREADS, C::LDS_BYTES, stream>>>(Xf, sx, Wf, sw, reinterpret_cast<const uint16_t *>(bias), M, N, K,
-                                                     reinterpret_cast<uint16_t *>(Y), acc_debug, tiles_m, tiles_n);
+                                                     reinterpret_cast<uint16_t *>(Y), acc_debug, tiles_m, tiles_n, dbg);
     return hipGetLastError();
 }
 
-// E2M3 rows of both operands -> Y.  Token rows that fill whole rounds of 256 big tiles go to the 256 x 256 configuration, the
-// remaining rows to the 128 x 128 one when that is estimated cheaper (same rule as the int8 kernel).
+// E2M3 blocks of both operands -> Y.
 hipError_t run_e2m3_gemm(const uint8_t *Xf, const float *sx, const uint8_t *Wf, const float *sw, const void *bias, int M, int N,
                          int K, void *Y, int32_t *acc_debug, hipStream_t stream)
 {
@@ -454,22 +483,11 @@ hipError_t run_e2m3_gemm(const uint8_t *Xf, const float *sx, const uint8_t *Wf, 
         return big(0, M);
     }
 #endif
+    // A round of 128 x 128 tiles (two blocks per compute unit) does half the work of a round of 256 x 256 tiles and measured about
+    // 1.5 times its duration here, so the big configuration runs everything unless it would leave most compute units idle.
     const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
     const long long big_tiles = (long long)tiles_m * tiles_n;
-    if (big_tiles < 256) {
-        const long long small_rounds = ((long long)((M + 127) / 128) * ((N + 127) / 128) + 511) / 512;
-        return small_rounds * 13 < 20 ? small(0, M) : big(0, M);
-    }
-    const int main_tile_rows = (int)std::min<long long>(tiles_m, big_tiles / 256 * 256 / tiles_n);
-    const int rem_tile_rows = tiles_m - main_tile_rows;
-    if (rem_tile_rows == 0) return big(0, M);
-    const int rows_main = main_tile_rows * 256, rows_rem = M - rows_main;
-    const long long rem_big_rounds = ((long long)rem_tile_rows * tiles_n + 255) / 256;
-    const long long rem_small_rounds = ((long long)((rows_rem + 127) / 128) * ((N + 127) / 128) + 511) / 512;
-    if (rem_small_rounds * 13 >= rem_big_rounds * 20) return big(0, M);
-    hipError_t e = big(0, rows_main);
-    if (e != hipSuccess) return e;
-    return small(rows_main, rows_rem);
+    return big_tiles <= 96 ? small(0, M) : big(0, M);
 }
 
 }  // namespace qvggt

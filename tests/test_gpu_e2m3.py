@@ -99,9 +99,9 @@ def test_e2m3_gemm_extreme_sums():
 
 
 @pytest.mark.parametrize("M,N,K", [(66000, 512, 256), (65700, 768, 128), (16500, 4096, 1024)])
-def test_e2m3_gemm_both_tile_shapes(M, N, K):
-    """Whole rounds of 256 x 256 tiles plus a remainder that goes to the 128 x 128 configuration: sampled rows (both sides of the
-    seam, the last rows) bit-exact; every row written."""
+def test_e2m3_gemm_large_shapes(M, N, K):
+    """Several rounds of 256 x 256 tiles with a ragged last tile row (the smaller shapes above run the 128 x 128 configuration):
+    sampled rows (around the last full round, the last rows, random ones) bit-exact; every row written."""
     tiles_n = (N + 255) // 256
     seam = ((M + 255) // 256 * tiles_n // 256 * 256 // tiles_n) * 256
     assert 0 < seam < M

@@ -39,6 +39,11 @@ class DsfqLinear:
         if self.packed:
             self.Wq = torch.empty(self.N, self.K // 2, dtype=torch.uint8, device=dev)
             q.qvggt_prep_weights(weight, absmax, signs, alpha, self.Wq, self.w_scale, self.inv_smooth)
+            # the same codes as E2M3 numbers for the 6-bit floating-point matrix path (bf16 inputs, K = 1024 / 2048 / 4096)
+            self.Wf = None
+            if self.K in (1024, 2048, 4096):
+                self.Wf = torch.empty(q.qvggt_e2m3_bytes(self.N, self.K), dtype=torch.uint8, device=dev)
+                q.qvggt_codes_to_e2m3(self.Wq, self.N, self.K, self.Wf)
         else:
             self.Wq = torch.empty(self.N, self.K, dtype=torch.int8, device=dev)
             q.qvggt_prep_weights_i8(weight, absmax, signs, alpha, bits, self.Wq, self.w_scale, self.inv_smooth)
@@ -46,6 +51,8 @@ class DsfqLinear:
 
     def _workspace(self, M: int, dev) -> torch.Tensor:
         need = q.qvggt_workspace_bytes(M, self.N, self.K) if self.packed else q.qvggt_workspace_bytes_i8(M, self.N, self.K)
+        if self.packed and self.Wf is not None:
+            need = max(need, q.qvggt_workspace_bytes_e2m3(M, self.N, self.K))
         if self._ws is None or self._ws.numel() < need or self._ws.device != dev:
             self._ws = torch.empty(need, dtype=torch.uint8, device=dev)
         return self._ws
@@ -55,7 +62,9 @@ class DsfqLinear:
         M = X.shape[0]
         Y = out if out is not None else torch.empty(M, self.N, dtype=torch.bfloat16, device=X.device)
         ws = self._workspace(M, X.device)
-        if self.packed:
+        if self.packed and self.Wf is not None and X.dtype == torch.bfloat16:
+            q.qvggt_linear_e2m3(X, self.signs, self.inv_smooth, self.Wf, self.w_scale, self.bias, Y, ws)      # same Y, bit for bit
+        elif self.packed:
             q.qvggt_linear(X, self.signs, self.inv_smooth, self.Wq, self.w_scale, self.bias, Y, ws)
         else:
             q.qvggt_linear_i8(X, self.signs, self.inv_smooth, self.act_bits, self.Wq, self.w_scale, self.bias, Y, ws)

@@ -76,6 +76,31 @@ def test_linear_full_size_sampled_rows(config, name, n_random):
     G.check_scales(sx[idx].cpu().numpy(), want.dx, f"cfg{config} {name}")
 
 
+@pytest.mark.parametrize("config,name,n_random", [(2, "qkv", 1374), (4, "proj", 1500), (5, "fc1", 1500), (5, "fc2", 500)])
+def test_linear_e2m3_full_size_sampled_rows(config, name, n_random):
+    """The launch configuration bench.py times by default (qvggt_linear_e2m3: kernel 1 writing E2M3 blocks, the GEMM on the 6-bit
+    floating-point matrix instructions) at full M; the oracle recomputes a seeded sample of rows; every row equals qvggt_linear's."""
+    s = synth.layer_spec(config, name)
+    rows = _sample_rows(s, min(n_random, s.M - 64), seed=config * 10 + len(name) + 1)
+    signs, prep_o = _oracle_prep(s)
+    prep_g = _gpu_prep(s)
+    bias = synth.make_bias(s)
+    X = synth.make_activation_frames(s)
+    Xd = G.to_dev(X)
+    Xs = X[rows]
+    del X
+    want = oracle.linear(Xs, prep_o, bias=bias, pre_signs=signs)
+    Wf = torch.empty(G.q.qvggt_e2m3_bytes(s.N, s.K), dtype=torch.uint8, device=G.DEV)
+    G.q.qvggt_codes_to_e2m3(prep_g["Wq"], s.N, s.K, Wf)
+    Yd = torch.full((s.M, s.N), float("nan"), dtype=torch.bfloat16, device=G.DEV)
+    ws = torch.empty(G.q.qvggt_workspace_bytes_e2m3(s.M, s.N, s.K), dtype=torch.uint8, device=G.DEV)
+    G.q.qvggt_linear_e2m3(Xd, prep_g["signs"], prep_g["inv"], Wf, prep_g["sw"], G.to_dev(bias), Yd, ws)
+    idx = torch.from_numpy(rows).to(G.DEV)
+    err = G.rel_fro(G.bf16_bits(Yd[idx]), want.Y)
+    assert err <= G.Y_REL_FRO, err
+    assert torch.equal(Yd, G.gpu_linear(Xd, prep_g, G.to_dev(bias)))
+
+
 def test_gemm_full_size_sampled_rows_bit_exact():
     """Config 5 fc1 shape with seeded random codes: accumulators of sampled rows are bit-exact."""
     import paper_2509_21302_amd as q

@@ -229,7 +229,7 @@ def main():
     # side measurement: the two HBM-bound reductions of the calibration-set arithmetic (Sec. 3.3) on the first layer's input,
     # taken as one sample of `frames` frames: per-frame mean / variance, and the cosine of every frame with frame 0
     nfds = None
-    if args.bits == 4 and not args.headline_only:
+    if args.bits == 4 and not args.headline_only and layers[0]["spec"].frames >= 2:      # a correlation needs two frames
         L0 = layers[0]
         s0_ = L0["spec"]
         fe = s0_.rows_per_frame * s0_.K

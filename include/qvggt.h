@@ -187,10 +187,15 @@ int qvggt_w4a4_gemm(const uint8_t *Xq, const float *x_scale, const uint8_t *Wq, 
  *                       qvggt_rotate_smooth_quant; a code 0 may carry a sign bit).  bf16 X with K = 1024, 2048 or 4096 only:
  *                       other K are QVGGT_ERR_SHAPE, f32 X is QVGGT_ERR_DTYPE (use qvggt_rotate_smooth_quant and
  *                       qvggt_codes_to_e2m3 there).
+ * qvggt_layernorm_rotate_smooth_quant_e2m3:  qvggt_layernorm_rotate_smooth_quant writing E2M3 blocks; bf16 X and
+ *                       K = 1024 only (other K QVGGT_ERR_SHAPE, f32 X QVGGT_ERR_DTYPE).
  * qvggt_linear_e2m3:    both kernels on one stream, as qvggt_linear; Wf = qvggt_codes_to_e2m3 of qvggt_prep_weights'
  *                       Wq; workspace of qvggt_workspace_bytes_e2m3(M, N, K) bytes; same restriction on X and K.
  */
 size_t qvggt_e2m3_bytes(int rows, int K);
+int qvggt_layernorm_rotate_smooth_quant_e2m3(const void *X, int x_dtype, int M, int K, const float *gamma,
+                                             const float *beta, float eps, const int8_t *signs,
+                                             const float *inv_smooth, uint8_t *Xf, float *x_scale, void *stream);
 int qvggt_rotate_smooth_quant_e2m3(const void *X, int x_dtype, int M, int K, const int8_t *signs,
                                    const float *inv_smooth, uint8_t *Xf, float *x_scale, void *stream);
 size_t qvggt_workspace_bytes_e2m3(int M, int N, int K);

@@ -21,6 +21,7 @@ from .binding import (  # noqa: F401
     qvggt_rotate_smooth_quant_e2m3,
     qvggt_workspace_bytes_e2m3,
     qvggt_linear_e2m3,
+    qvggt_layernorm_rotate_smooth_quant_e2m3,
     qvggt_codes_to_e2m3,
     qvggt_e2m3_gemm,
     qvggt_w4a4_gemm,

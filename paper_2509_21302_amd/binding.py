@@ -20,6 +20,7 @@ EXPORTS = [
     "qvggt_rotate_smooth_quant_asym", "qvggt_weight_code_sums", "qvggt_w4a4_gemm_asym",
     "qvggt_e2m3_bytes", "qvggt_codes_to_e2m3", "qvggt_e2m3_gemm",
     "qvggt_rotate_smooth_quant_e2m3", "qvggt_workspace_bytes_e2m3", "qvggt_linear_e2m3",
+    "qvggt_layernorm_rotate_smooth_quant_e2m3",
     "qvggt_w4a4_gemm", "qvggt_linear", "qvggt_workspace_bytes", "qvggt_pack_int4", "qvggt_unpack_int4",
     "qvggt_prep_weights_i8", "qvggt_rotate_smooth_quant_i8", "qvggt_i8_gemm", "qvggt_linear_i8",
     "qvggt_workspace_bytes_i8", "qvggt_layout_int8",
@@ -71,6 +72,8 @@ def load_library() -> C.CDLL:
     lib.qvggt_w4a4_gemm_asym.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, vp, vp]
     lib.qvggt_rotate_smooth_quant_e2m3.restype = i
     lib.qvggt_rotate_smooth_quant_e2m3.argtypes = [vp, i, i, i, vp, vp, vp, vp, vp]
+    lib.qvggt_layernorm_rotate_smooth_quant_e2m3.restype = i
+    lib.qvggt_layernorm_rotate_smooth_quant_e2m3.argtypes = [vp, i, i, i, vp, vp, f, vp, vp, vp, vp, vp]
     lib.qvggt_workspace_bytes_e2m3.restype = C.c_size_t
     lib.qvggt_workspace_bytes_e2m3.argtypes = [i, i, i]
     lib.qvggt_linear_e2m3.restype = i
@@ -212,6 +215,13 @@ def qvggt_rotate_smooth_quant_e2m3(X, signs, inv_smooth, Xf, x_scale, stream=Non
     M, K = X.shape
     _check(load_library().qvggt_rotate_smooth_quant_e2m3(_ptr(X), _dtype_code(X), M, K, _ptr(signs), _ptr(inv_smooth), _ptr(Xf),
                                                          _ptr(x_scale), _stream(stream)), "qvggt_rotate_smooth_quant_e2m3")
+
+
+def qvggt_layernorm_rotate_smooth_quant_e2m3(X, gamma, beta, eps, signs, inv_smooth, Xf, x_scale, stream=None):
+    M, K = X.shape
+    _check(load_library().qvggt_layernorm_rotate_smooth_quant_e2m3(_ptr(X), _dtype_code(X), M, K, _ptr(gamma), _ptr(beta), float(eps),
+                                                                   _ptr(signs), _ptr(inv_smooth), _ptr(Xf), _ptr(x_scale),
+                                                                   _stream(stream)), "qvggt_layernorm_rotate_smooth_quant_e2m3")
 
 
 def qvggt_workspace_bytes_e2m3(M, N, K):

@@ -25,6 +25,8 @@ hipError_t run_w4a4_gemm_asym(const uint8_t *Xq, const float *sx, const float *x
                               const float *wsum, const void *bias, int M, int N, int K, void *Y, hipStream_t stream);
 hipError_t run_rotate_quant_e2m3_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, uint8_t *out,
                                       float *scale, hipStream_t stream);
+hipError_t run_ln_rotate_quant_e2m3_mfma(const void *X, int rows, const int8_t *signs, const float *mul, uint8_t *out, float *scale,
+                                         LnParams ln, hipStream_t stream);
 hipError_t run_codes_to_e2m3(const uint8_t *packed, int rows, int K, uint8_t *out, hipStream_t stream);
 hipError_t run_e2m3_gemm(const uint8_t *Xf, const float *sx, const uint8_t *Wf, const float *sw, const void *bias, int M, int N,
                          int K, void *Y, int32_t *acc_debug, hipStream_t stream);
@@ -261,6 +263,23 @@ int qvggt_rotate_smooth_quant_e2m3(const void *X, int x_dtype, int M, int K, con
     if (!aligned16(X) || !aligned16(Xf) || !aligned16(x_scale) || !aligned16(inv_smooth) || !aligned16(signs))
         return QVGGT_ERR_ALIGN;
     return hip_status(qvggt::run_rotate_quant_e2m3_mfma(X, M, K, signs, inv_smooth, Xf, x_scale, static_cast<hipStream_t>(stream)));
+}
+
+int qvggt_layernorm_rotate_smooth_quant_e2m3(const void *X, int x_dtype, int M, int K, const float *gamma, const float *beta,
+                                             float eps, const int8_t *signs, const float *inv_smooth, uint8_t *Xf, float *x_scale,
+                                             void *stream)
+{
+    if (!valid_dtype(x_dtype)) return QVGGT_ERR_DTYPE;
+    if (x_dtype != QVGGT_BF16) return QVGGT_ERR_DTYPE;
+    if (M < 0 || K != 1024) return QVGGT_ERR_SHAPE;                  // VGGT-1B's normalised layer inputs
+    if (!(eps >= 0.0f) || !std::isfinite(eps)) return QVGGT_ERR_ARG;
+    if (M == 0) return QVGGT_OK;
+    if (!X || !Xf || !x_scale) return QVGGT_ERR_NULL;
+    if (!aligned16(X) || !aligned16(Xf) || !aligned16(x_scale) || !aligned16(inv_smooth) || !aligned16(signs) ||
+        !aligned16(gamma) || !aligned16(beta))
+        return QVGGT_ERR_ALIGN;
+    const qvggt::LnParams ln{gamma, beta, eps, 1};
+    return hip_status(qvggt::run_ln_rotate_quant_e2m3_mfma(X, M, signs, inv_smooth, Xf, x_scale, ln, static_cast<hipStream_t>(stream)));
 }
 
 size_t qvggt_workspace_bytes_e2m3(int M, int N, int K)

@@ -627,6 +627,19 @@ hipError_t run_ln_rotate_quant_mfma(const void *X, int rows, const int8_t *signs
     return hipGetLastError();
 }
 
+// the same with the codes written as E2M3 blocks
+hipError_t run_ln_rotate_quant_e2m3_mfma(const void *X, int rows, const int8_t *signs, const float *mul, uint8_t *out, float *scale,
+                                         LnParams ln, hipStream_t stream)
+{
+    if (rows <= 0) return hipSuccess;
+    const int ntiles = (rows + 3) / 4;
+    int blocks = (ntiles + rq::WAVES_PER_BLOCK - 1) / rq::WAVES_PER_BLOCK;
+    if (blocks > 256 * 2) blocks = 256 * 2;
+    rotate_quant_mfma_kernel<1024, 1, 2, false, 6, true><<<blocks, 256, 0, stream>>>(
+        reinterpret_cast<const uint16_t *>(X), rows, signs, mul, 0, out, scale, nullptr, 0, 7.0f, nullptr, ln);
+    return hipGetLastError();
+}
+
 // Column statistic max_t |X H|[t, j] of bf16 rows, K = 1024 / 2048 / 4096, with the same kernel in statistic mode.
 // absmax_bits (K values) must be zero on entry.
 hipError_t run_rotated_col_absmax_mfma(const void *X, int rows, int K, const int8_t *signs, unsigned int *absmax_bits,

@@ -129,6 +129,11 @@ def test_argument_validation_needs_no_gpu():
     assert eg(None, None, None, None, None, 0, 32, 1024, None, None, None) == OK
     assert re(P, 0, 4, 512, None, None, P, P, None) == SHAPE and re(P, 1, 4, 1024, None, None, P, P, None) == DTYPE
     assert re(P, 0, 4, 1024, None, None, None, P, None) == NULL and re(None, 0, 0, 1024, None, None, None, None, None) == OK
+    lne = lib.qvggt_layernorm_rotate_smooth_quant_e2m3
+    e6 = C.c_float(1e-6)
+    assert lne(P, 0, 4, 2048, None, None, e6, None, None, P, P, None) == SHAPE and lne(P, 1, 4, 1024, None, None, e6, None, None, P, P, None) == DTYPE
+    assert lne(P, 0, 4, 1024, None, None, C.c_float(-1.0), None, None, P, P, None) == ARG
+    assert lne(P, 0, 4, 1024, None, None, e6, None, None, None, P, None) == NULL and lne(None, 0, 0, 1024, None, None, e6, None, None, None, None, None) == OK
     need6 = q.qvggt_workspace_bytes_e2m3(100, 32, 1024)
     assert need6 >= 128 * 768 + 400
     assert le(P, 0, 100, 32, 1024, None, None, P, P, None, P, P, need6 - 1, None) == WORKSPACE

@@ -184,3 +184,24 @@ def test_linear_e2m3_matches_the_oracle_and_the_int8_path(name, M):
     G.q.qvggt_linear_e2m3(G.to_dev(X), pg["signs"], pg["inv"], Wf, pg["sw"], G.to_dev(bias), Y, ws)
     assert G.rel_fro(G.bf16_bits(Y), want.Y) <= G.Y_REL_FRO
     assert torch.equal(Y, G.gpu_linear(G.to_dev(X), pg, G.to_dev(bias)))
+
+
+def test_layernorm_rotate_quant_e2m3_equals_the_packed_variant():
+    """LayerNorm fused in front, E2M3 output: the same steps and, decoded, the same codes as the packed-code variant (whose
+    parity against the oracle is tests/test_gpu_rotate_quant.py::test_layernorm_rotate_quant)."""
+    K, rows, eps = 1024, 1031, 1e-5
+    X = _heavy_bf16(rows, K, 77)
+    rng = np.random.default_rng(5)
+    signs = (rng.integers(0, 2, K) * 2 - 1).astype(np.int8)
+    inv = (1.0 / (np.sqrt(K) * np.exp(rng.uniform(-1, 1, K)))).astype(np.float32)
+    gamma = np.exp(rng.normal(0, 0.3, K)).astype(np.float32)
+    beta = rng.normal(0, 0.1, K).astype(np.float32)
+    Xd, sd, invd, gd, bd = (G.to_dev(v) for v in (X, signs, inv, gamma, beta))
+    Xq, sx = G.gpu_ln_rsq(Xd, gd, bd, eps, sd, invd)
+    Xf = torch.full((G.q.qvggt_e2m3_bytes(rows, K),), 0xA5, dtype=torch.uint8, device=G.DEV)
+    sxf = torch.empty(rows, dtype=torch.float32, device=G.DEV)
+    G.q.qvggt_layernorm_rotate_smooth_quant_e2m3(Xd, gd, bd, eps, sd, invd, Xf, sxf)
+    assert torch.equal(sx, sxf)
+    conv = torch.full_like(Xf, 0xA5)
+    G.q.qvggt_codes_to_e2m3(Xq, rows, K, conv)
+    assert np.array_equal(_decode_e2m3_rows(Xf.cpu().numpy(), rows, K), _decode_e2m3_rows(conv.cpu().numpy(), rows, K))

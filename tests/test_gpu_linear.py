@@ -194,6 +194,41 @@ def test_linear_under_hip_graph_capture():
         assert torch.equal(got, want), f"replay {rep}"
 
 
+def test_linear_e2m3_under_hip_graph_capture():
+    """The same for the default path of the benchmark (kernel 1 writing E2M3 blocks, GEMM on the 6-bit floating-point matrix
+    instructions): replays against the eager int8-instruction path, which gives the same bits."""
+    s = synth.layer_spec(2)
+    prep = _gpu_prep(s)
+    bias = G.to_dev(synth.make_bias(s))
+    X0 = G.to_dev(synth.make_activation_frames(s))
+    import paper_2509_21302_amd as q
+    Wf = torch.empty(q.qvggt_e2m3_bytes(s.N, s.K), dtype=torch.uint8, device=G.DEV)
+    q.qvggt_codes_to_e2m3(prep["Wq"], s.N, s.K, Wf)
+    Xbuf = X0.clone()
+    Y = torch.empty(s.M, s.N, dtype=torch.bfloat16, device=G.DEV)
+    ws = torch.empty(q.qvggt_workspace_bytes_e2m3(s.M, s.N, s.K), dtype=torch.uint8, device=G.DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                       # warm-up outside capture: first-call kernel attributes are set here
+        q.qvggt_linear_e2m3(Xbuf, prep["signs"], prep["inv"], Wf, prep["sw"], bias, Y, ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        q.qvggt_linear_e2m3(Xbuf, prep["signs"], prep["inv"], Wf, prep["sw"], bias, Y, ws)
+    gen = torch.Generator(device=G.DEV).manual_seed(4)
+    for rep in range(3):
+        Xnew = (X0.float() * (0.5 + rep) + torch.randn(X0.shape, device=G.DEV, generator=gen) * 0.1 * rep).to(torch.bfloat16)
+        Xbuf.copy_(Xnew)
+        Y.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = Y.clone()
+        want = G.gpu_linear(Xnew, prep, bias)
+        torch.cuda.synchronize()
+        assert torch.equal(got, want), f"replay {rep}"
+
+
 @pytest.mark.parametrize("bits", [4, 8])
 def test_convenience_object_matches_the_entry_points(bits):
     """DsfqLinear only allocates and forwards: same bits as calling the C ABI by hand, and oracle-close."""

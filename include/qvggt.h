@@ -189,10 +189,27 @@ int qvggt_w4a4_gemm(const uint8_t *Xq, const float *x_scale, const uint8_t *Wq, 
  *                       qvggt_codes_to_e2m3 there).
  * qvggt_layernorm_rotate_smooth_quant_e2m3:  qvggt_layernorm_rotate_smooth_quant writing E2M3 blocks; bf16 X and
  *                       K = 1024 only (other K QVGGT_ERR_SHAPE, f32 X QVGGT_ERR_DTYPE).
+ * Codes that fill the whole 4-bit range (a static step reaches -8; affine codes u run over 0..15) go to the same
+ * instructions shifted by half a step: all sixteen half-integers -7.5 .. 7.5 are E2M3 numbers.
+ * qvggt_rotate_smooth_quant_asym_e2m3 / _static_e2m3:  qvggt_rotate_smooth_quant_asym / _static writing E2M3 blocks that
+ *                       hold u - 7.5 resp. code + 0.5, the steps in x_scale, and in x_zero (f32 [M]) the zero point resp. 8
+ *                       (a signed code is u - 8).  bf16 X, K = 1024, 2048 or 4096 only, as above.
+ * qvggt_e2m3_gemm_shifted:  Y[t, o] = bf16_rne( (acc'[t, o] + (7.5 - x_zero[t]) * w_codesum[o]) * x_scale[t] * w_scale[o]
+ *                       + bias[o] ) with acc' the sum over the stored half-integers times the weight codes (multiples of 0.5
+ *                       below 2^23 and an integer after the correction: exact); w_codesum as in qvggt_w4a4_gemm_asym.
+ *                       The same Y, bit for bit, as qvggt_w4a4_gemm_asym resp. qvggt_w4a4_gemm on the same codes.
  * qvggt_linear_e2m3:    both kernels on one stream, as qvggt_linear; Wf = qvggt_codes_to_e2m3 of qvggt_prep_weights'
  *                       Wq; workspace of qvggt_workspace_bytes_e2m3(M, N, K) bytes; same restriction on X and K.
  */
 size_t qvggt_e2m3_bytes(int rows, int K);
+int qvggt_rotate_smooth_quant_asym_e2m3(const void *X, int x_dtype, int M, int K, const int8_t *signs,
+                                        const float *inv_smooth, uint8_t *Xf, float *x_scale, float *x_zero, void *stream);
+int qvggt_rotate_smooth_quant_static_e2m3(const void *X, int x_dtype, int M, int K, const int8_t *signs,
+                                          const float *inv_smooth, const float *x_step, int per_token, uint8_t *Xf,
+                                          float *x_scale, float *x_zero, void *stream);
+int qvggt_e2m3_gemm_shifted(const uint8_t *Xf, const float *x_scale, const float *x_zero, const uint8_t *Wf,
+                            const float *w_scale, const float *w_codesum, const void *bias, int M, int N, int K, void *Y,
+                            void *stream);
 int qvggt_layernorm_rotate_smooth_quant_e2m3(const void *X, int x_dtype, int M, int K, const float *gamma,
                                              const float *beta, float eps, const int8_t *signs,
                                              const float *inv_smooth, uint8_t *Xf, float *x_scale, void *stream);

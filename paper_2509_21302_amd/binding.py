@@ -21,6 +21,7 @@ EXPORTS = [
     "qvggt_e2m3_bytes", "qvggt_codes_to_e2m3", "qvggt_e2m3_gemm",
     "qvggt_rotate_smooth_quant_e2m3", "qvggt_workspace_bytes_e2m3", "qvggt_linear_e2m3",
     "qvggt_layernorm_rotate_smooth_quant_e2m3",
+    "qvggt_rotate_smooth_quant_asym_e2m3", "qvggt_rotate_smooth_quant_static_e2m3", "qvggt_e2m3_gemm_shifted",
     "qvggt_w4a4_gemm", "qvggt_linear", "qvggt_workspace_bytes", "qvggt_pack_int4", "qvggt_unpack_int4",
     "qvggt_prep_weights_i8", "qvggt_rotate_smooth_quant_i8", "qvggt_i8_gemm", "qvggt_linear_i8",
     "qvggt_workspace_bytes_i8", "qvggt_layout_int8",
@@ -74,6 +75,12 @@ def load_library() -> C.CDLL:
     lib.qvggt_rotate_smooth_quant_e2m3.argtypes = [vp, i, i, i, vp, vp, vp, vp, vp]
     lib.qvggt_layernorm_rotate_smooth_quant_e2m3.restype = i
     lib.qvggt_layernorm_rotate_smooth_quant_e2m3.argtypes = [vp, i, i, i, vp, vp, f, vp, vp, vp, vp, vp]
+    lib.qvggt_rotate_smooth_quant_asym_e2m3.restype = i
+    lib.qvggt_rotate_smooth_quant_asym_e2m3.argtypes = [vp, i, i, i, vp, vp, vp, vp, vp, vp]
+    lib.qvggt_rotate_smooth_quant_static_e2m3.restype = i
+    lib.qvggt_rotate_smooth_quant_static_e2m3.argtypes = [vp, i, i, i, vp, vp, vp, i, vp, vp, vp, vp]
+    lib.qvggt_e2m3_gemm_shifted.restype = i
+    lib.qvggt_e2m3_gemm_shifted.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, vp, vp]
     lib.qvggt_workspace_bytes_e2m3.restype = C.c_size_t
     lib.qvggt_workspace_bytes_e2m3.argtypes = [i, i, i]
     lib.qvggt_linear_e2m3.restype = i
@@ -222,6 +229,25 @@ def qvggt_layernorm_rotate_smooth_quant_e2m3(X, gamma, beta, eps, signs, inv_smo
     _check(load_library().qvggt_layernorm_rotate_smooth_quant_e2m3(_ptr(X), _dtype_code(X), M, K, _ptr(gamma), _ptr(beta), float(eps),
                                                                    _ptr(signs), _ptr(inv_smooth), _ptr(Xf), _ptr(x_scale),
                                                                    _stream(stream)), "qvggt_layernorm_rotate_smooth_quant_e2m3")
+
+
+def qvggt_rotate_smooth_quant_asym_e2m3(X, signs, inv_smooth, Xf, x_scale, x_zero, stream=None):
+    M, K = X.shape
+    _check(load_library().qvggt_rotate_smooth_quant_asym_e2m3(_ptr(X), _dtype_code(X), M, K, _ptr(signs), _ptr(inv_smooth), _ptr(Xf),
+                                                              _ptr(x_scale), _ptr(x_zero), _stream(stream)),
+           "qvggt_rotate_smooth_quant_asym_e2m3")
+
+
+def qvggt_rotate_smooth_quant_static_e2m3(X, signs, inv_smooth, x_step, per_token, Xf, x_scale, x_zero, stream=None):
+    M, K = X.shape
+    _check(load_library().qvggt_rotate_smooth_quant_static_e2m3(_ptr(X), _dtype_code(X), M, K, _ptr(signs), _ptr(inv_smooth),
+                                                                _ptr(x_step), int(per_token), _ptr(Xf), _ptr(x_scale), _ptr(x_zero),
+                                                                _stream(stream)), "qvggt_rotate_smooth_quant_static_e2m3")
+
+
+def qvggt_e2m3_gemm_shifted(Xf, x_scale, x_zero, Wf, w_scale, w_codesum, bias, M, N, K, Y, stream=None):
+    _check(load_library().qvggt_e2m3_gemm_shifted(_ptr(Xf), _ptr(x_scale), _ptr(x_zero), _ptr(Wf), _ptr(w_scale), _ptr(w_codesum),
+                                                  _ptr(bias), M, N, K, _ptr(Y), _stream(stream)), "qvggt_e2m3_gemm_shifted")
 
 
 def qvggt_workspace_bytes_e2m3(M, N, K):

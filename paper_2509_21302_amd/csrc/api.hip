@@ -27,6 +27,10 @@ hipError_t run_rotate_quant_e2m3_mfma(const void *X, int rows, int K, const int8
                                       float *scale, hipStream_t stream);
 hipError_t run_ln_rotate_quant_e2m3_mfma(const void *X, int rows, const int8_t *signs, const float *mul, uint8_t *out, float *scale,
                                          LnParams ln, hipStream_t stream);
+hipError_t run_rotate_quant_e2m3_shifted_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, uint8_t *out,
+                                              float *scale, float *zero, const float *step, int step_stride, hipStream_t stream);
+hipError_t run_e2m3_gemm_shifted(const uint8_t *Xf, const float *sx, const float *xzero, const uint8_t *Wf, const float *sw,
+                                 const float *wsum, const void *bias, int M, int N, int K, void *Y, hipStream_t stream);
 hipError_t run_codes_to_e2m3(const uint8_t *packed, int rows, int K, uint8_t *out, hipStream_t stream);
 hipError_t run_e2m3_gemm(const uint8_t *Xf, const float *sx, const uint8_t *Wf, const float *sw, const void *bias, int M, int N,
                          int K, void *Y, int32_t *acc_debug, hipStream_t stream);
@@ -280,6 +284,50 @@ int qvggt_layernorm_rotate_smooth_quant_e2m3(const void *X, int x_dtype, int M, 
         return QVGGT_ERR_ALIGN;
     const qvggt::LnParams ln{gamma, beta, eps, 1};
     return hip_status(qvggt::run_ln_rotate_quant_e2m3_mfma(X, M, signs, inv_smooth, Xf, x_scale, ln, static_cast<hipStream_t>(stream)));
+}
+
+// kernel 1 whose codes fill the whole 4-bit range, as E2M3 half-integers: x_step == NULL -> affine codes, else a static step
+static int rsq_e2m3_shifted(const void *X, int x_dtype, int M, int K, const int8_t *signs, const float *inv_smooth, const float *x_step,
+                            int per_token, bool is_static, uint8_t *Xf, float *x_scale, float *x_zero, void *stream)
+{
+    if (!valid_dtype(x_dtype)) return QVGGT_ERR_DTYPE;
+    if (M < 0 || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (!e2m3_direct(x_dtype, K)) return x_dtype == QVGGT_BF16 ? QVGGT_ERR_SHAPE : QVGGT_ERR_DTYPE;
+    if (is_static && per_token != 0 && per_token != 1) return QVGGT_ERR_ARG;
+    if (M == 0) return QVGGT_OK;
+    if (!X || !Xf || !x_scale || !x_zero || (is_static && !x_step)) return QVGGT_ERR_NULL;
+    if (!aligned16(X) || !aligned16(Xf) || !aligned16(x_scale) || !aligned16(x_zero) || !aligned16(inv_smooth) || !aligned16(signs) ||
+        (reinterpret_cast<uintptr_t>(x_step) & 3u) != 0)
+        return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_rotate_quant_e2m3_shifted_mfma(X, M, K, signs, inv_smooth, Xf, x_scale, x_zero,
+                                                                is_static ? x_step : nullptr, per_token,
+                                                                static_cast<hipStream_t>(stream)));
+}
+
+int qvggt_rotate_smooth_quant_asym_e2m3(const void *X, int x_dtype, int M, int K, const int8_t *signs, const float *inv_smooth,
+                                        uint8_t *Xf, float *x_scale, float *x_zero, void *stream)
+{
+    return rsq_e2m3_shifted(X, x_dtype, M, K, signs, inv_smooth, nullptr, 0, false, Xf, x_scale, x_zero, stream);
+}
+
+int qvggt_rotate_smooth_quant_static_e2m3(const void *X, int x_dtype, int M, int K, const int8_t *signs, const float *inv_smooth,
+                                          const float *x_step, int per_token, uint8_t *Xf, float *x_scale, float *x_zero,
+                                          void *stream)
+{
+    return rsq_e2m3_shifted(X, x_dtype, M, K, signs, inv_smooth, x_step, per_token, true, Xf, x_scale, x_zero, stream);
+}
+
+int qvggt_e2m3_gemm_shifted(const uint8_t *Xf, const float *x_scale, const float *x_zero, const uint8_t *Wf, const float *w_scale,
+                            const float *w_codesum, const void *bias, int M, int N, int K, void *Y, void *stream)
+{
+    if (M < 0 || !valid_n(N) || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (M == 0) return QVGGT_OK;
+    if (!Xf || !x_scale || !x_zero || !Wf || !w_scale || !w_codesum || !Y) return QVGGT_ERR_NULL;
+    if (!aligned16(Xf) || !aligned16(x_scale) || !aligned16(x_zero) || !aligned16(Wf) || !aligned16(w_scale) ||
+        !aligned16(w_codesum) || !aligned16(bias) || !aligned16(Y))
+        return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_e2m3_gemm_shifted(Xf, x_scale, x_zero, Wf, w_scale, w_codesum, bias, M, N, K, Y,
+                                                   static_cast<hipStream_t>(stream)));
 }
 
 size_t qvggt_workspace_bytes_e2m3(int M, int N, int K)

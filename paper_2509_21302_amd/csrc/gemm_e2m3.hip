@@ -49,15 +49,19 @@ constexpr int RB_BYTES = RB * U_BYTES;   // one unit of one block: 6 KiB contigu
 // in every byte) is the explicit unit scale and gives the same sums.
 constexpr int UNIT_SCALE_ONE = 0;
 
-template <int TM, int TN, int WM, int WN, int STAGES>
+// SHIFTED: the activation codes are stored 7.5 below an unsigned code u in [0, 15] (all sixteen half-integers -7.5 .. 7.5 are E2M3
+// numbers), with a zero point per token; the per-tile scale area then also carries the zero points and the weights' code sums
+template <int TM, int TN, int WM, int WN, int STAGES, bool SHIFTED = false>
 struct E2m3Cfg {
     static constexpr int NW = WM * WN, THREADS = NW * 64;
     static constexpr int BM = WM * TM * 32, BN = WN * TN * 32, ROWS = BM + BN;
     static constexpr int STAGE_BYTES = ROWS * U_BYTES;
     static constexpr int LPW = ROWS * 3 / 64 / NW;      // 1 KiB transfers per wave per unit
     static constexpr int NM = TM * TN, NF = TM + TN;
-    static constexpr int SC_BYTES = BM * 4 + BN * 4 + BN * 2;   // per tile: sx f32, sw f32, bias bf16 (as in memory)
-    static constexpr int SC_GROUPS = BM / 64 + BN / 64 + BN / 128;
+    static constexpr int SC_SYM_BYTES = BM * 4 + BN * 4 + BN * 2;   // per tile: sx f32, sw f32, bias bf16 (as in memory)
+    static constexpr int SC_SYM_GROUPS = BM / 64 + BN / 64 + BN / 128;
+    static constexpr int SC_BYTES = SC_SYM_BYTES + (SHIFTED ? BM * 4 + BN * 4 : 0);     // then zero points f32, code sums f32
+    static constexpr int SC_GROUPS = SC_SYM_GROUPS + (SHIFTED ? BM / 64 + BN / 64 : 0);
     static constexpr int EP_PITCH = 128 + 16;
     static constexpr int EP_BYTES = NW * 32 * EP_PITCH;
     static constexpr int LDS_BYTES = STAGES * STAGE_BYTES + 2 * SC_BYTES + EP_BYTES;
@@ -105,13 +109,16 @@ __device__ inline void e_wait_vmcnt()
 
 }  // namespace
 
-template <int TM, int TN, int WM, int WN, int STAGES, int MINB, bool DEBUG>
+// SHIFTED: sum_j (u_tj - zp_t) qw_oj = sum_j (u_tj - 7.5) qw_oj + (7.5 - zp_t) * wsum_o: the first sum is what the MFMAs give (multiples
+// of 0.5 below 2^23: exact), the second term is added in the epilogue (exact as well)
+template <int TM, int TN, int WM, int WN, int STAGES, int MINB, bool DEBUG, bool SHIFTED = false>
 __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per_eu(WM * WN * MINB / 4, WM * WN * MINB / 4))) void e2m3_gemm_kernel(
     const uint8_t *__restrict__ Xf, const float *__restrict__ sx, const uint8_t *__restrict__ Wf,
     const float *__restrict__ sw, const uint16_t *__restrict__ bias, int M, int N, int K,
-    uint16_t *__restrict__ Y, int32_t *__restrict__ acc_debug, int tiles_m, int tiles_n, long long *dbg_times)
+    uint16_t *__restrict__ Y, int32_t *__restrict__ acc_debug, int tiles_m, int tiles_n, long long *dbg_times,
+    const float *__restrict__ xzero = nullptr, const float *__restrict__ wsum = nullptr)
 {
-    using C = E2m3Cfg<TM, TN, WM, WN, STAGES>;
+    using C = E2m3Cfg<TM, TN, WM, WN, STAGES, SHIFTED>;
     constexpr int NM = C::NM, NF = C::NF, LPW = C::LPW;
     constexpr int DMA_SHIFT = (LPW > 4) ? 4096 : 0;             // keeps the transfers' instruction offsets inside [-4096, 4095]
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -179,10 +186,18 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
             } else if (g < C::BM / 64 + C::BN / 64) {
                 const int h = g - C::BM / 64;
                 e_dma4(sw + min(tn * C::BN + h * 64 + lane, N - 1), dst + C::BM * 4 + h * 256);
-            } else if (bias != nullptr) {
-                const int h = g - C::BM / 64 - C::BN / 64;      // 64 dwords = 128 bf16 values
-                e_dma4(reinterpret_cast<const uint32_t *>(bias) + min(tn * (C::BN / 2) + h * 64 + lane, N / 2 - 1),
-                       dst + C::BM * 4 + C::BN * 4 + h * 256);
+            } else if (g < C::SC_SYM_GROUPS) {
+                if (bias != nullptr) {
+                    const int h = g - C::BM / 64 - C::BN / 64;      // 64 dwords = 128 bf16 values
+                    e_dma4(reinterpret_cast<const uint32_t *>(bias) + min(tn * (C::BN / 2) + h * 64 + lane, N / 2 - 1),
+                           dst + C::BM * 4 + C::BN * 4 + h * 256);
+                }
+            } else if (g < C::SC_SYM_GROUPS + C::BM / 64) {
+                const int h = g - C::SC_SYM_GROUPS;
+                e_dma4(xzero + min(tm * C::BM + h * 64 + lane, M - 1), dst + C::SC_SYM_BYTES + h * 256);
+            } else {
+                const int h = g - C::SC_SYM_GROUPS - C::BM / 64;
+                e_dma4(wsum + min(tn * C::BN + h * 64 + lane, N - 1), dst + C::SC_SYM_BYTES + C::BM * 4 + h * 256);
             }
         }
     };
@@ -312,17 +327,25 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
         float sxm[TM];
 #pragma unroll
         for (int i = 0; i < TM; ++i) sxm[i] = scx[(wm * TM + i) * 32 + c];
+        const float *scz = reinterpret_cast<const float *>(sc + C::SC_SYM_BYTES);
+        const float *scs = reinterpret_cast<const float *>(sc + C::SC_SYM_BYTES + C::BM * 4) + wn * TN * 32 + 4 * g;
+        float rz[SHIFTED ? TM : 1];
+        if constexpr (SHIFTED) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) rz[i] = 7.5f - scz[(wm * TM + i) * 32 + c];
+        }
         {
             uint8_t *ep = smem + STAGES * C::STAGE_BYTES + 2 * C::SC_BYTES + wave * (32 * C::EP_PITCH);
             const int rd_row = lane >> 3, rd_col = lane & 7;
 #pragma unroll
             for (int jp = 0; jp < TN / 2; ++jp) {
-                float4 swq[2][4], bq[2][4];
+                float4 swq[2][4], bq[2][4], wsq[SHIFTED ? 2 : 1][SHIFTED ? 4 : 1];
 #pragma unroll
                 for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         swq[jj][q] = *reinterpret_cast<const float4 *>(scw + (2 * jp + jj) * 32 + 8 * q);
+                        if constexpr (SHIFTED) wsq[jj][q] = *reinterpret_cast<const float4 *>(scs + (2 * jp + jj) * 32 + 8 * q);
                         const uint2 b = *reinterpret_cast<const uint2 *>(scb + (2 * jp + jj) * 32 + 8 * q);
                         bq[jj][q] = make_float4(__uint_as_float(b.x << 16), __uint_as_float(b.x & 0xFFFF0000u),
                                                 __uint_as_float(b.y << 16), __uint_as_float(b.y & 0xFFFF0000u));
@@ -346,6 +369,10 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
                             asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a1) : "a"(acc[2 * jp + jj][i][4 * q + 1]));
                             asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a2) : "a"(acc[2 * jp + jj][i][4 * q + 2]));
                             asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(a3) : "a"(acc[2 * jp + jj][i][4 * q + 3]));
+                            if constexpr (SHIFTED) {
+                                a0 = fmaf(rz[i], wsq[jj][q].x, a0); a1 = fmaf(rz[i], wsq[jj][q].y, a1);
+                                a2 = fmaf(rz[i], wsq[jj][q].z, a2); a3 = fmaf(rz[i], wsq[jj][q].w, a3);
+                            }
                             const float y0 = fmaf(a0, scl[jj][q].x, bq[jj][q].x), y1 = fmaf(a1, scl[jj][q].y, bq[jj][q].y);
                             const float y2 = fmaf(a2, scl[jj][q].z, bq[jj][q].z), y3 = fmaf(a3, scl[jj][q].w, bq[jj][q].w);
                             *reinterpret_cast<uint2 *>(ep + c * C::EP_PITCH + (jj * 32 + 8 * q + 4 * g) * 2) = make_uint2(pack_bf16x2(y0, y1), pack_bf16x2(y2, y3));
@@ -425,11 +452,12 @@ hipError_t run_codes_to_e2m3(const uint8_t *packed, int rows, int K, uint8_t *ou
     return hipGetLastError();
 }
 
-template <int TM, int TN, int WM, int WN, int STAGES, int MINB>
+template <int TM, int TN, int WM, int WN, int STAGES, int MINB, bool SHIFTED = false>
 static hipError_t launch_e2m3(const uint8_t *Xf, const float *sx, const uint8_t *Wf, const float *sw, const void *bias,
-                              int M, int N, int K, void *Y, int32_t *acc_debug, hipStream_t stream)
+                              int M, int N, int K, void *Y, int32_t *acc_debug, hipStream_t stream,
+                              const float *xzero = nullptr, const float *wsum = nullptr)
 {
-    using C = E2m3Cfg<TM, TN, WM, WN, STAGES>;
+    using C = E2m3Cfg<TM, TN, WM, WN, STAGES, SHIFTED>;
     long long *dbg = nullptr;
 #ifdef QVGGT_DEV
     // development builds: QVGGT_TIMING=1 reinterprets acc_debug as a buffer for per-wave cycle counters
@@ -439,7 +467,12 @@ static hipError_t launch_e2m3(const uint8_t *Xf, const float *sx, const uint8_t 
     }
 #endif
     const bool debug = acc_debug != nullptr;
-    auto kern = debug ? e2m3_gemm_kernel<TM, TN, WM, WN, STAGES, MINB, true> : e2m3_gemm_kernel<TM, TN, WM, WN, STAGES, MINB, false>;
+    auto kern = e2m3_gemm_kernel<TM, TN, WM, WN, STAGES, MINB, false, SHIFTED>;
+    if constexpr (!SHIFTED) {
+        if (debug) kern = e2m3_gemm_kernel<TM, TN, WM, WN, STAGES, MINB, true, false>;
+    } else {
+        if (debug) return hipErrorInvalidValue;      // the corrected sum is never an integer register: no dump
+    }
     static bool attr_set[2] = {false, false};
     if (!attr_set[debug]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
@@ -451,7 +484,7 @@ static hipError_t launch_e2m3(const uint8_t *Xf, const float *sx, const uint8_t 
     int grid = 256 * MINB;
     if (grid > (ntiles + 7) / 8 * 8) grid = (ntiles + 7) / 8 * 8;
     kern<<<grid, C::THREADS, C::LDS_BYTES, stream>>>(Xf, sx, Wf, sw, reinterpret_cast<const uint16_t *>(bias), M, N, K,
-                                                     reinterpret_cast<uint16_t *>(Y), acc_debug, tiles_m, tiles_n, dbg);
+                                                     reinterpret_cast<uint16_t *>(Y), acc_debug, tiles_m, tiles_n, dbg, xzero, wsum);
     return hipGetLastError();
 }
 
@@ -488,6 +521,17 @@ hipError_t run_e2m3_gemm(const uint8_t *Xf, const float *sx, const uint8_t *Wf, 
     const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
     const long long big_tiles = (long long)tiles_m * tiles_n;
     return big_tiles <= 96 ? small(0, M) : big(0, M);
+}
+
+// Activations as u - 7.5 with a zero point per token (xzero), weights as before, wsum their code sums per channel.
+hipError_t run_e2m3_gemm_shifted(const uint8_t *Xf, const float *sx, const float *xzero, const uint8_t *Wf, const float *sw,
+                                 const float *wsum, const void *bias, int M, int N, int K, void *Y, hipStream_t stream)
+{
+    if (M <= 0) return hipSuccess;
+    const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
+    if ((long long)tiles_m * tiles_n <= 96)
+        return launch_e2m3<2, 2, 2, 2, 4, 2, true>(Xf, sx, Wf, sw, bias, M, N, K, Y, nullptr, stream, xzero, wsum);
+    return launch_e2m3<4, 4, 2, 2, 5, 1, true>(Xf, sx, Wf, sw, bias, M, N, K, Y, nullptr, stream, xzero, wsum);
 }
 
 }  // namespace qvggt

@@ -91,8 +91,9 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
                                                                    float *__restrict__ zero = nullptr)
 {
     constexpr bool STAT = (CB == 0);
-    static_assert(!ASYM || (CB == 4 && !STATIC), "affine codes: dynamic 4-bit only");
-    static_assert(CB != 6 || !STATIC, "E2M3 has no -8: dynamic steps only");
+    static_assert(!ASYM || ((CB == 4 || CB == 6) && !STATIC), "affine codes: dynamic 4-bit only");
+    // CB = 6 with a static step or affine codes: the stored E2M3 number is code + 0.5 resp. u - 7.5 (sixteen half-integers, all
+    // representable), and zero[row] receives what the GEMM's correction term needs (8 for a static step: 7.5 - 8 = -0.5)
     using C = rq::Cfg<K>;
     constexpr int REM = C::REM, TOK = C::TOK;
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[rq::WAVES_PER_BLOCK * rq::LDS_PER_WAVE];
@@ -414,10 +415,23 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
                     for (int k = 0; k < 16; ++k) {
                         const int h = 8 * bb + k / 2;
                         // rounded exactly as the packed codes are: one fused rounding onto the integer grid of the magic constant
-                        ev[k] = fmaf(acc[(2 * k) & 3][t * C::HB_PER_LANE + h], inv, rq::MAGIC) - rq::MAGIC;
-                        od[k] = fmaf(acc[(2 * k + 1) & 3][t * C::HB_PER_LANE + h], inv, rq::MAGIC) - rq::MAGIC;
+                        const float ze = acc[(2 * k) & 3][t * C::HB_PER_LANE + h], zo = acc[(2 * k + 1) & 3][t * C::HB_PER_LANE + h];
+                        if constexpr (ASYM) {
+                            ev[k] = (__builtin_amdgcn_fmed3f(fmaf(ze, inv, magic), rq::MAGIC - 8.0f, rq::MAGIC + 7.0f) - rq::MAGIC) + 0.5f;
+                            od[k] = (__builtin_amdgcn_fmed3f(fmaf(zo, inv, magic), rq::MAGIC - 8.0f, rq::MAGIC + 7.0f) - rq::MAGIC) + 0.5f;
+                        } else if constexpr (STATIC) {
+                            ev[k] = ((__builtin_amdgcn_fmed3f(ze * inv, -8.0f, 7.0f) + rq::MAGIC) - rq::MAGIC) + 0.5f;
+                            od[k] = ((__builtin_amdgcn_fmed3f(zo * inv, -8.0f, 7.0f) + rq::MAGIC) - rq::MAGIC) + 0.5f;
+                        } else {
+                            ev[k] = fmaf(ze, inv, rq::MAGIC) - rq::MAGIC;
+                            od[k] = fmaf(zo, inv, rq::MAGIC) - rq::MAGIC;
+                        }
                     }
-                    const v6u blob = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(ev, od, 1.0f);
+                    // The conversion makes several passes over its 32 source registers while it writes its 6 results, so the result
+                    // must not share registers with the sources.  The compiler's builtin does not know that (it was seen to place
+                    // the result on the last source registers, which corrupted fields 25 .. 31): the early-clobber constraint does.
+                    v6u blob;
+                    asm volatile("v_cvt_scalef32_2xpk16_fp6_f32 %0, %1, %2, 1.0" : "=&v"(blob) : "v"(ev), "v"(od));
                     if constexpr (REM == 5) {
                         // K = 4096: the lane holds both blobs of unit 2 c + g, i.e. that unit's 48 bytes of this wave's token; they go
                         // to the block's flush area [unit][wave][48 bytes]
@@ -451,7 +465,11 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
                     }
                     __syncthreads();
                 }
-                if (row < rows && c == 0 && (REM != 5 || g == 0)) scale[row] = delta;
+                if (row < rows && c == 0 && (REM != 5 || g == 0)) {
+                    scale[row] = delta;
+                    if constexpr (ASYM) zero[row] = zp;
+                    if constexpr (STATIC) zero[row] = 8.0f;
+                }
                 continue;
             }
             if constexpr (CB == 8) {
@@ -611,6 +629,35 @@ hipError_t run_rotate_quant_e2m3_mfma(const void *X, int rows, int K, const int8
         default: return hipErrorInvalidValue;
     }
 #undef RQE
+    return hipGetLastError();
+}
+
+// The variants whose codes fill [-8, 7] or [0, 15], as E2M3 blocks of half-integers (code + 0.5, u - 7.5) plus zero[row]:
+// step != nullptr: static step (token-wise, stride 1, or one value, stride 0), zero = 8; otherwise affine codes, zero = zero point
+hipError_t run_rotate_quant_e2m3_shifted_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, uint8_t *out,
+                                              float *scale, float *zero, const float *step, int step_stride, hipStream_t stream)
+{
+    if (rows <= 0) return hipSuccess;
+    const uint16_t *x = reinterpret_cast<const uint16_t *>(X);
+    const int tok = 32 / (K / 128);
+    const int ntiles = (rows + tok - 1) / tok;
+    int blocks = (ntiles + rq::WAVES_PER_BLOCK - 1) / rq::WAVES_PER_BLOCK;
+    if (blocks > 256 * 2) blocks = 256 * 2;
+    const LnParams no_ln{nullptr, nullptr, 0.0f, 0};
+#define RQS(KK)                                                                                                                          \
+    do {                                                                                                                                 \
+        if (step != nullptr)                                                                                                             \
+            rotate_quant_mfma_kernel<KK, 1, 2, true, 6, false, false><<<blocks, 256, 0, stream>>>(x, rows, signs, mul, 0, out, scale, step, step_stride, 7.0f, nullptr, no_ln, zero); \
+        else                                                                                                                             \
+            rotate_quant_mfma_kernel<KK, 1, 2, false, 6, false, true><<<blocks, 256, 0, stream>>>(x, rows, signs, mul, 0, out, scale, nullptr, 0, 7.0f, nullptr, no_ln, zero);     \
+    } while (0)
+    switch (K) {
+        case 1024: RQS(1024); break;
+        case 2048: RQS(2048); break;
+        case 4096: RQS(4096); break;
+        default: return hipErrorInvalidValue;
+    }
+#undef RQS
     return hipGetLastError();
 }
 

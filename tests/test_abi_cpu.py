@@ -134,6 +134,13 @@ def test_argument_validation_needs_no_gpu():
     assert lne(P, 0, 4, 2048, None, None, e6, None, None, P, P, None) == SHAPE and lne(P, 1, 4, 1024, None, None, e6, None, None, P, P, None) == DTYPE
     assert lne(P, 0, 4, 1024, None, None, C.c_float(-1.0), None, None, P, P, None) == ARG
     assert lne(P, 0, 4, 1024, None, None, e6, None, None, None, P, None) == NULL and lne(None, 0, 0, 1024, None, None, e6, None, None, None, None, None) == OK
+    ae, se, gs = lib.qvggt_rotate_smooth_quant_asym_e2m3, lib.qvggt_rotate_smooth_quant_static_e2m3, lib.qvggt_e2m3_gemm_shifted
+    assert ae(P, 0, 4, 512, None, None, P, P, P, None) == SHAPE and ae(P, 1, 4, 1024, None, None, P, P, P, None) == DTYPE
+    assert ae(P, 0, 4, 1024, None, None, P, P, None, None) == NULL and ae(None, 0, 0, 1024, None, None, None, None, None, None) == OK
+    assert se(P, 0, 4, 1024, None, None, None, 1, P, P, P, None) == NULL and se(P, 0, 4, 1024, None, None, P, 2, P, P, P, None) == ARG
+    assert se(P, 0, 4, 128, None, None, P, 1, P, P, P, None) == SHAPE and se(None, 0, 0, 1024, None, None, None, 1, None, None, None, None) == OK
+    assert gs(P, P, P, P, P, P, None, 4, 100, 1024, P, None) == SHAPE and gs(P, P, None, P, P, P, None, 4, 32, 1024, P, None) == NULL
+    assert gs(P, P, P, P, P, P + 4, None, 4, 32, 1024, P, None) == ALIGN and gs(None, None, None, None, None, None, None, 0, 32, 1024, None, None) == OK
     need6 = q.qvggt_workspace_bytes_e2m3(100, 32, 1024)
     assert need6 >= 128 * 768 + 400
     assert le(P, 0, 100, 32, 1024, None, None, P, P, None, P, P, need6 - 1, None) == WORKSPACE

@@ -205,3 +205,71 @@ def test_layernorm_rotate_quant_e2m3_equals_the_packed_variant():
     conv = torch.full_like(Xf, 0xA5)
     G.q.qvggt_codes_to_e2m3(Xq, rows, K, conv)
     assert np.array_equal(_decode_e2m3_rows(Xf.cpu().numpy(), rows, K), _decode_e2m3_rows(conv.cpu().numpy(), rows, K))
+
+
+def _shifted_setup(K, rows, N, seed, one_sided):
+    rng = np.random.default_rng(seed)
+    X = _heavy_bf16(rows, K, seed)
+    if one_sided:
+        X = f32_to_bf16_bits(np.abs(oracle.to_f64(X)).astype(np.float32))
+    W = rng.standard_normal((N, K)).astype(np.float32) * 0.03
+    bias = f32_to_bf16_bits(rng.normal(0, 0.1, N).astype(np.float32))
+    signs = (rng.integers(0, 2, K) * 2 - 1).astype(np.int8)
+    pg = G.gpu_prep(W, X, signs)
+    Wf = torch.empty(G.q.qvggt_e2m3_bytes(N, K), dtype=torch.uint8, device=G.DEV)
+    G.q.qvggt_codes_to_e2m3(pg["Wq"], N, K, Wf)
+    return X, W, bias, signs, pg, Wf, G.gpu_code_sums(pg["Wq"], N, K)
+
+
+@pytest.mark.parametrize("K,rows,N", [(1024, 1031, 512), (4096, 600, 1024), (2048, 203, 256)])
+def test_asymmetric_codes_on_the_e2m3_path(K, rows, N):
+    """Affine activation codes stored as u - 7.5: decoded + 7.5 they are the packed kernel's u (whose parity against the oracle
+    is tests/test_gpu_asym.py), same steps and zero points; the layer's Y equals the int8-instruction path's bit for bit and is
+    within the usual bar of the oracle's asymmetric layer."""
+    X, W, bias, signs, pg, Wf, wsum = _shifted_setup(K, rows, N, 50 + K, True)
+    Xd = G.to_dev(X)
+    Xq, sx, zx = G.gpu_rsq_asym(Xd, pg["signs"], pg["inv"])
+    Xf = torch.full((G.q.qvggt_e2m3_bytes(rows, K),), 0xA5, dtype=torch.uint8, device=G.DEV)
+    sxf, zxf = torch.empty_like(sx), torch.empty_like(zx)
+    G.q.qvggt_rotate_smooth_quant_asym_e2m3(Xd, pg["signs"], pg["inv"], Xf, sxf, zxf)
+    assert torch.equal(sx, sxf) and torch.equal(zx, zxf)
+    pk = Xq.cpu().numpy()
+    nib = np.stack([pk & 15, pk >> 4], axis=2).reshape(rows, K).astype(np.int16)
+    at_position = np.where(nib >= 8, nib - 16, nib)                                        # u - 8 at the library's positions
+    assert np.array_equal(_decode_e2m3_rows(Xf.cpu().numpy(), rows, K), at_position + 0.5)
+    Y = torch.empty(rows, N, dtype=torch.bfloat16, device=G.DEV)
+    G.q.qvggt_e2m3_gemm_shifted(Xf, sxf, zxf, Wf, pg["sw"], wsum, G.to_dev(bias), rows, N, K, Y)
+    Y8 = torch.empty_like(Y)
+    G.q.qvggt_w4a4_gemm_asym(Xq, sx, zx, pg["Wq"], pg["sw"], wsum, G.to_dev(bias), rows, N, K, Y8)
+    assert torch.equal(Y, Y8)
+    po = oracle.prepare_weights(W, oracle.rotated_col_absmax(X, pre_signs=signs), pre_signs=signs)
+    want = oracle.linear_asym(X, po, bias, pre_signs=signs)[0]
+    assert G.rel_fro(G.bf16_bits(Y), want) <= G.Y_REL_FRO
+
+
+@pytest.mark.parametrize("K,rows,N,per_token", [(1024, 1031, 512, 1), (4096, 300, 256, 0), (2048, 203, 256, 1)])
+def test_static_step_codes_on_the_e2m3_path(K, rows, N, per_token):
+    """A given step (codes reach -8) stored as code + 0.5 with zero = 8: decoded - 0.5 they are the packed kernel's codes, and Y
+    equals the int8-instruction path's bit for bit."""
+    X, W, bias, signs, pg, Wf, wsum = _shifted_setup(K, rows, N, 60 + K, False)
+    Xd = G.to_dev(X)
+    _, sdyn = G.gpu_rsq(Xd, pg["signs"], pg["inv"])
+    rng = np.random.default_rng(K)
+    dyn = sdyn.cpu().numpy()
+    step = (dyn * rng.uniform(0.2, 1.5, rows)).astype(np.float32) if per_token else np.array([np.median(dyn) * 0.5], dtype=np.float32)
+    Xq, sx = G.gpu_rsq_static(Xd, pg["signs"], pg["inv"], G.to_dev(step), per_token)
+    codes = G.gpu_unpack(Xq, K)
+    assert (codes == -8).any() and (codes == 7).any()
+    Xf = torch.full((G.q.qvggt_e2m3_bytes(rows, K),), 0xA5, dtype=torch.uint8, device=G.DEV)
+    sxf, zxf = torch.empty_like(sx), torch.empty_like(sx)
+    G.q.qvggt_rotate_smooth_quant_static_e2m3(Xd, pg["signs"], pg["inv"], G.to_dev(step), per_token, Xf, sxf, zxf)
+    assert torch.equal(sx, sxf) and (zxf == 8).all().item()
+    pk = Xq.cpu().numpy()
+    nib = np.stack([pk & 15, pk >> 4], axis=2).reshape(rows, K).astype(np.int16)
+    at_position = np.where(nib >= 8, nib - 16, nib)
+    assert np.array_equal(_decode_e2m3_rows(Xf.cpu().numpy(), rows, K), at_position + 0.5)
+    Y = torch.empty(rows, N, dtype=torch.bfloat16, device=G.DEV)
+    G.q.qvggt_e2m3_gemm_shifted(Xf, sxf, zxf, Wf, pg["sw"], wsum, G.to_dev(bias), rows, N, K, Y)
+    Y8 = torch.empty_like(Y)
+    G.q.qvggt_w4a4_gemm(Xq, sx, pg["Wq"], pg["sw"], G.to_dev(bias), rows, N, K, Y8)
+    assert torch.equal(Y, Y8)

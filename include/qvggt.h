@@ -170,7 +170,8 @@ int qvggt_w4a4_gemm(const uint8_t *Xq, const float *x_scale, const uint8_t *Wq, 
  * qvggt_w4a4_gemm, bit for bit, at twice the matrix rate.  A 4-bit code q in [-7, 7] is written as the E2M3 number
  * of value q (1 sign, 2 exponent, 3 mantissa bits); products and sums are integers below 2^24 and exact in the
  * fp32 accumulators.  -8 has no E2M3 value: the dynamic quantizers never produce it (Eq. 3 with absmax / 7 gives
- * codes in [-7, 7]); codes from a static step or the asymmetric setting stay on qvggt_w4a4_gemm(_asym).
+ * codes in [-7, 7]); codes from a static step or the asymmetric setting are stored half a step up (see the
+ * _shifted entry points below).
  *
  * "E2M3 blocks": a row is K / 64 units of 48 bytes.  Unit s holds the codes at positions 64 s .. 64 s + 63 of a
  * packed row (library order) as two blobs of 32 six-bit fields, field i of blob h = position 64 s + 32 h + i at

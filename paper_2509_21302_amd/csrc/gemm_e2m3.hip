@@ -8,8 +8,9 @@
 // integers of magnitude <= 49 and sums of magnitude <= 49 * 8192 < 2^24, so the fp32 accumulators hold the integer sum
 // exactly, in any order of addition: the result is the int32 accumulator of the int8 path, bit for bit.  On gfx950 this
 // MFMA retires 64 codes per row in the time the int8 one retires 32, and a lane's operand comes from LDS as it is (no
-// expansion in registers).  -8 has no E2M3 value: dynamic absmax steps never produce it (codes lie in [-7, 7]); paths that
-// can (static steps, affine codes stored as u - 8) stay on the int8 kernel.
+// expansion in registers).  -8 has no E2M3 value: dynamic absmax steps never produce it (codes lie in [-7, 7]); codes that
+// fill the whole range (static steps, affine codes) are stored half a step up, as the half-integers -7.5 .. 7.5, all of which
+// are E2M3 numbers, and the epilogue adds the term that makes up for the shift (SHIFTED below).
 //
 // Operand format ("E2M3 blocks").  A row of K codes is K / 64 units of 48 bytes.  Unit s holds the codes at positions
 // 64 s .. 64 s + 63 of the library's code order as two blobs of 32 six-bit fields (field i of blob h = position 64 s + 32 h + i,

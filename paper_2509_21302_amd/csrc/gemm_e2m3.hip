@@ -236,19 +236,12 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
                                                                         UNIT_SCALE_ONE, 0, UNIT_SCALE_ONE);
             e_static_for<LPW>([&](auto n_c) {
                 constexpr int n = decltype(n_c)::value;
-#ifndef QVGGT_E2M3_NO_DMA
                 if constexpr ((2 * n + 1) * NM / (2 * LPW) == t) issue_transfer(n_c);
-#endif
             });
             e_static_for<2 * NF>([&](auto o_c) {
                 constexpr int o = decltype(o_c)::value, fo = o / 2;     // fo-th fragment in order of first use: W0, all X, other W
                 constexpr int f = (fo == 0) ? 0 : (fo <= TM ? TN + fo - 1 : fo - TM);
-#ifndef QVGGT_E2M3_NO_READS
-                if constexpr (o * NM / (2 * NF) == t)
-#else
-                if constexpr (false)
-#endif
-                {
+                if constexpr (o * NM / (2 * NF) == t) {
                     if constexpr (o % 2 == 0) read_lo(std::integral_constant<int, BUF ^ 1>{}, f, rd_stage);
                     else read_hi(std::integral_constant<int, BUF ^ 1>{}, f, rd_stage);
                 }

@@ -146,7 +146,7 @@ def test_chained_mlp_fc1_gelu_fc2():
     Yd = G.gpu_linear(actd, g2, G.to_dev(b2))
     assert G.rel_fro(G.bf16_bits(actd), act) <= G.Y_REL_FRO
     err = G.rel_fro(G.bf16_bits(Yd), want.Y)
-    assert err <= 3 * G.Y_REL_FRO, err   # two quantized layers in sequence: see the design doc on the chained tolerance
+    assert err <= 3 * G.Y_REL_FRO, err   # two quantized layers in sequence: rows whose fc1 codes flipped differ by a few percent after the second quantizer
 
 
 def test_linear_matches_its_two_kernels():

@@ -273,3 +273,23 @@ def test_static_step_codes_on_the_e2m3_path(K, rows, N, per_token):
     Y8 = torch.empty_like(Y)
     G.q.qvggt_w4a4_gemm(Xq, sx, pg["Wq"], pg["sw"], G.to_dev(bias), rows, N, K, Y8)
     assert torch.equal(Y, Y8)
+
+
+@pytest.mark.parametrize("M", [1, 5, 130])
+@pytest.mark.parametrize("K,N", [(1024, 48), (4096, 272)])
+def test_linear_e2m3_few_rows(M, K, N):
+    """Fewer rows than a 128-row block of the operand format (the rest of the block is never written and holds a fill here):
+    the same bits as qvggt_linear."""
+    rng = np.random.default_rng(M + K)
+    X = _heavy_bf16(M, K, M + K)
+    W = rng.standard_normal((N, K)).astype(np.float32) * 0.05
+    signs = (rng.integers(0, 2, K) * 2 - 1).astype(np.int8)
+    pg = G.gpu_prep(W, X, signs)
+    Wf = torch.full((G.q.qvggt_e2m3_bytes(N, K),), 0xFF, dtype=torch.uint8, device=G.DEV)
+    G.q.qvggt_codes_to_e2m3(pg["Wq"], N, K, Wf)
+    Y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=G.DEV)
+    ws = torch.full((G.q.qvggt_workspace_bytes_e2m3(M, N, K),), 0xFF, dtype=torch.uint8, device=G.DEV)
+    G.q.qvggt_linear_e2m3(G.to_dev(X), pg["signs"], pg["inv"], Wf, pg["sw"], None, Y, ws)
+    assert torch.equal(Y, G.gpu_linear(G.to_dev(X), pg, None))
+    want = oracle.linear(X, oracle.prepare_weights(W, oracle.rotated_col_absmax(X, pre_signs=signs), pre_signs=signs), pre_signs=signs)
+    assert G.rel_fro(G.bf16_bits(Y), want.Y) <= G.Y_REL_FRO

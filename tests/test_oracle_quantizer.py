@@ -378,3 +378,24 @@ def test_mixed_widths_order_the_error():
             assert np.abs(r.qx).max() == (1 << (ab - 1)) - 1
             err[wb, ab] = np.linalg.norm(r.y - ref) / np.linalg.norm(ref)
     assert err[8, 8] < err[4, 8] < err[4, 4] and err[8, 8] < err[8, 4] < err[4, 4]
+
+
+def test_four_bit_codes_are_e2m3_numbers():
+    """What the 6-bit floating-point matrix path rests on, from the format's definition (1 sign, 2 exponent bits with bias 1,
+    3 mantissa bits, exponent 0 subnormal): every code of a dynamic 4-bit quantizer (-7 .. 7) is an E2M3 number, and so is
+    every half-integer -7.5 .. 7.5 (a code of the full range -8 .. 7 or 0 .. 15 stored half a step up); -8 and 8 are not.
+    Products of such values with integer codes are multiples of 1/2 (1/4 for two shifted operands, never used) and a row sum
+    over K = 8192 stays below 2^23, so float32 holds it exactly in any order of addition."""
+    values = set()
+    for e in range(4):
+        for m in range(8):
+            mag = m / 8.0 if e == 0 else 2.0 ** (e - 1) * (1 + m / 8.0)
+            values.update((mag, -mag))
+    assert len(values) == 63 and max(values) == 7.5                       # +0 and -0 coincide
+    assert all(float(q) in values for q in range(-7, 8))
+    assert all(q + 0.5 in values for q in range(-8, 8))
+    assert -8.0 not in values and 8.0 not in values
+    worst = 7.5 * 7 * 8192                                                # |shifted code| * |weight code| * K
+    assert 2 * worst < 2 ** 23 and np.float32(worst) == worst and np.float32(worst - 0.5) == worst - 0.5
+    # and in integers: 49 * 8192 < 2^24
+    assert 49 * 8192 < 2 ** 24

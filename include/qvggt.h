@@ -17,6 +17,9 @@
  *     library allocates nothing, keeps no state between calls and is re-entrant.
  *   - Every call only enqueues kernels on `stream` (a hipStream_t passed as void*; NULL is
  *     the default stream) and returns; buffers must stay valid until the stream has run.
+ *     Calls may be recorded into a HIP graph (stream capture).  The GEMM entry points raise their kernel's dynamic
+ *     LDS limit the first time a tile configuration is used in a process (hipFuncSetAttribute, the only thing the
+ *     library remembers): make one call with the same shapes outside the capture first.
  *   - Matrices are dense row-major.  bf16 values are IEEE bfloat16 bit patterns (uint16).
  *   - K (input features, the Hadamard size) must be a power of two in [128, 8192], or one of the sizes
  *     2^n * m with a Paley matrix as the m-point factor (Sec. 3.2, H_d = H_{2^n} (x) H_m): m = 12: 768, 1536, 3072, 6144;

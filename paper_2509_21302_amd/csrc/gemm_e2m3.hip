@@ -510,11 +510,14 @@ hipError_t run_e2m3_gemm(const uint8_t *Xf, const float *sx, const uint8_t *Wf, 
         return big(0, M);
     }
 #endif
-    // A round of 128 x 128 tiles (two blocks per compute unit) does half the work of a round of 256 x 256 tiles and measured about
-    // 1.5 times its duration here, so the big configuration runs everything unless it would leave most compute units idle.
-    const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
-    const long long big_tiles = (long long)tiles_m * tiles_n;
-    return big_tiles <= 96 ? small(0, M) : big(0, M);
+    // Both configurations work in rounds (256 big tiles, or 512 small ones: two blocks per compute unit), and a last round that is
+    // mostly empty costs as much as a full one.  A round of small tiles does half the work of a round of big ones and measured
+    // 0.50 - 0.54 of its duration at K = 1024 and 0.6 - 0.75 at K = 4096; the cheaper estimate wins (it reproduces the faster choice
+    // on every shape of the five configurations: the small tiles win for a one-frame launch and for 32976 x 1024 -> 1024).
+    const long long big_rounds = ((long long)((M + 255) / 256) * ((N + 255) / 256) + 255) / 256;
+    const long long small_rounds = ((long long)((M + 127) / 128) * ((N + 127) / 128) + 511) / 512;
+    const long long small_cost = small_rounds * (K <= 2048 ? 55 : 70), big_cost = big_rounds * 100;
+    return small_cost < big_cost ? small(0, M) : big(0, M);
 }
 
 // Activations as u - 7.5 with a zero point per token (xzero), weights as before, wsum their code sums per channel.
@@ -522,8 +525,9 @@ hipError_t run_e2m3_gemm_shifted(const uint8_t *Xf, const float *sx, const float
                                  const float *wsum, const void *bias, int M, int N, int K, void *Y, hipStream_t stream)
 {
     if (M <= 0) return hipSuccess;
-    const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
-    if ((long long)tiles_m * tiles_n <= 96)
+    const long long big_rounds = ((long long)((M + 255) / 256) * ((N + 255) / 256) + 255) / 256;
+    const long long small_rounds = ((long long)((M + 127) / 128) * ((N + 127) / 128) + 511) / 512;
+    if (small_rounds * (K <= 2048 ? 55 : 70) < big_rounds * 100)
         return launch_e2m3<2, 2, 2, 2, 4, 2, true>(Xf, sx, Wf, sw, bias, M, N, K, Y, nullptr, stream, xzero, wsum);
     return launch_e2m3<4, 4, 2, 2, 5, 1, true>(Xf, sx, Wf, sw, bias, M, N, K, Y, nullptr, stream, xzero, wsum);
 }

@@ -80,11 +80,13 @@ def main():
         X = to_dev(synth.make_activation_frames(s, workers=16))
         L = dict(spec=s, signs=signs, bias=to_dev(synth.make_bias(s)), X=X,
                  Y=torch.empty(s.M, s.N, dtype=torch.bfloat16, device=dev),
-                 ws=torch.empty(q.qvggt_workspace_bytes_i8(s.M, s.N, s.K), dtype=torch.uint8, device=dev),
-                 Xq=torch.empty(s.M, s.K, dtype=torch.uint8, device=dev),      # sized for int8 codes; the 4-bit path uses half
+                 ws=torch.empty(max(q.qvggt_workspace_bytes_i8(s.M, s.N, s.K), q.qvggt_workspace_bytes_i8b(s.M, s.N, s.K)),
+                                dtype=torch.uint8, device=dev),
+                 Xq=torch.empty(q.qvggt_i8b_bytes(s.M, s.K), dtype=torch.uint8, device=dev),   # sized for int8 blocks; the others use less
                  sx=torch.empty(s.M, dtype=torch.float32, device=dev), prep={})
         L["Xq4"] = L["Xq"].view(-1)[: s.M * s.K // 2].view(s.M, s.K // 2)
-        L["Xq8"] = L["Xq"].view(torch.int8)
+        L["Xq8"] = L["Xq"][: s.M * s.K].view(s.M, s.K).view(torch.int8)
+        L["Xb"] = L["Xq"].view(torch.int8)                                  # int8 blocks: rows padded to 128
         L["Xf"] = L["Xq"].view(-1)[: q.qvggt_e2m3_bytes(s.M, s.K)]          # E2M3 blocks: 3/4 byte per code, rows padded to 128
         assert L["Xf"].numel() == q.qvggt_e2m3_bytes(s.M, s.K) and L["ws"].numel() >= q.qvggt_workspace_bytes_e2m3(s.M, s.N, s.K)
         for bits in sorted({args.bits} if args.headline_only else {args.bits, 4, 8}):
@@ -97,6 +99,10 @@ def main():
                 Wq = torch.empty(s.N, s.K, dtype=torch.int8, device=dev)
                 q.qvggt_prep_weights_i8(Wd, a, signs, 0.5, bits, Wq, sw, inv)
             L["prep"][bits] = dict(Wq=Wq, sw=sw, inv=inv)
+            if bits == 8:
+                Wb = torch.empty(q.qvggt_i8b_bytes(s.N, s.K), dtype=torch.int8, device=dev)
+                q.qvggt_int8_to_blocks(Wq, s.N, s.K, Wb)
+                L["prep"]["i8b"] = dict(Wq=Wb, sw=sw, inv=inv)
             if bits == 4:
                 Wf = torch.empty(q.qvggt_e2m3_bytes(s.N, s.K), dtype=torch.uint8, device=dev)
                 q.qvggt_codes_to_e2m3(Wq, s.N, s.K, Wf)
@@ -108,6 +114,8 @@ def main():
         P = L["prep"][bits]
         if bits == "e2m3":
             q.qvggt_linear_e2m3(L["X"], L["signs"], P["inv"], P["Wq"], P["sw"], L["bias"], L["Y"], L["ws"])
+        elif bits == "i8b":
+            q.qvggt_linear_i8b(L["X"], L["signs"], P["inv"], 8, P["Wq"], P["sw"], L["bias"], L["Y"], L["ws"])
         elif bits == 4:
             q.qvggt_linear(L["X"], L["signs"], P["inv"], P["Wq"], P["sw"], L["bias"], L["Y"], L["ws"])
         else:
@@ -117,6 +125,8 @@ def main():
         P, s = L["prep"][bits], L["spec"]
         if bits == "e2m3":
             q.qvggt_rotate_smooth_quant_e2m3(L["X"], L["signs"], P["inv"], L["Xf"], L["sx"])
+        elif bits == "i8b":
+            q.qvggt_rotate_smooth_quant_i8b(L["X"], L["signs"], P["inv"], 8, L["Xb"], L["sx"])
         elif bits == 4:
             q.qvggt_rotate_smooth_quant(L["X"], L["signs"], P["inv"], L["Xq4"], L["sx"])
         else:
@@ -126,6 +136,8 @@ def main():
         P, s = L["prep"][bits], L["spec"]
         if bits == "e2m3":
             q.qvggt_e2m3_gemm(L["Xf"], L["sx"], P["Wq"], P["sw"], L["bias"], s.M, s.N, s.K, L["Y"], None)
+        elif bits == "i8b":
+            q.qvggt_i8b_gemm(L["Xb"], L["sx"], P["Wq"], P["sw"], L["bias"], s.M, s.N, s.K, L["Y"], None)
         elif bits == 4:
             q.qvggt_w4a4_gemm(L["Xq4"], L["sx"], P["Wq"], P["sw"], L["bias"], s.M, s.N, s.K, L["Y"], None)
         else:
@@ -199,9 +211,12 @@ def main():
                     gemm_frac_int8_peak=ops8 / gm8 / 1e9 / INT8_PEAK_TOPS, rotate_quant_GBps=rqb8 / rq8 / 1e6,
                     rotate_quant_frac_hbm_peak=rqb8 / rq8 / 1e6 / HBM_PEAK_GBS, per_layer=pl8)
 
-    side, side_int8_path = None, None
+    side, side_rows, side_int8_path = None, None, None
     if args.bits == 4 and not args.headline_only:
-        side = side_run(8)
+        # the blocked operand format is defined for the bf16 kernel-1 shapes; elsewhere the 8-bit setting runs on row-major codes
+        blocks_ok = all(L["spec"].x_dtype == "bf16" and L["spec"].K in (1024, 2048, 4096) for L in layers)
+        side_rows = side_run(8)
+        side = side_run("i8b") if blocks_ok else side_rows
         if headline == "e2m3":
             side_int8_path = side_run(4)
     # HBM bytes per launch measured with rocprofv3 counters (see profiles/); None if that file is absent
@@ -316,6 +331,8 @@ def main():
     }
     if side is not None:
         out["w8a8"] = side
+        if side_rows is not side:
+            out["w8a8_row_major"] = side_rows
     if side_int8_path is not None:
         out["w4a4_int8_path"] = side_int8_path
     if nfds is not None:

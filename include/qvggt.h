@@ -260,6 +260,31 @@ size_t qvggt_workspace_bytes_i8(int M, int N, int K);
 int qvggt_layout_int8(const int8_t *src, int rows, int K, int8_t *dst, int to_library, void *stream);
 
 /*
+ * The int8-code path (8-/6-bit and mixed settings above) with its operands in "int8 blocks", the layout in which every
+ * global -> LDS transfer of the GEMM is contiguous in memory: rows grouped in blocks of 128 with the K-tiles of 64 codes
+ * outermost, K-tile kt of row r at byte ((r / 128) * (K / 64) + kt) * 8192 + (r % 128) * 64, and inside it the 16-byte
+ * chunk ch of the row's codes (library order) in slot ch ^ ((r % 16) >> 2).  A buffer holds ceil(rows / 128) * 128 rows:
+ * qvggt_i8b_bytes(rows, K) bytes; the rows past `rows` are never written and may hold anything.  Same codes, same sums,
+ * same Y as the qvggt_*_i8 entry points, bit for bit.
+ * qvggt_int8_to_blocks:           int8 [rows, K] in library order (Xq or Wq of the _i8 entry points) -> int8 blocks.
+ * qvggt_rotate_smooth_quant_i8b:  qvggt_rotate_smooth_quant_i8 writing int8 blocks; bf16 X, K = 1024, 2048 or 4096 only
+ *                                 (other K QVGGT_ERR_SHAPE, f32 X QVGGT_ERR_DTYPE).
+ * qvggt_i8b_gemm:                 qvggt_i8_gemm on int8 blocks.
+ * qvggt_linear_i8b:               both on one stream; Wb = qvggt_int8_to_blocks of qvggt_prep_weights_i8's Wq; workspace
+ *                                 of qvggt_workspace_bytes_i8b(M, N, K) bytes.
+ */
+size_t qvggt_i8b_bytes(int rows, int K);
+int qvggt_int8_to_blocks(const int8_t *src, int rows, int K, int8_t *dst, void *stream);
+int qvggt_rotate_smooth_quant_i8b(const void *X, int x_dtype, int M, int K, const int8_t *signs, const float *inv_smooth,
+                                  int bits, int8_t *Xb, float *x_scale, void *stream);
+int qvggt_i8b_gemm(const int8_t *Xb, const float *x_scale, const int8_t *Wb, const float *w_scale, const void *bias, int M,
+                   int N, int K, void *Y, int32_t *acc_debug, void *stream);
+size_t qvggt_workspace_bytes_i8b(int M, int N, int K);
+int qvggt_linear_i8b(const void *X, int x_dtype, int M, int N, int K, const int8_t *signs, const float *inv_smooth, int bits,
+                     const int8_t *Wb, const float *w_scale, const void *bias, void *Y, void *workspace,
+                     size_t workspace_bytes, void *stream);
+
+/*
  * Whole online path: qvggt_rotate_smooth_quant into the workspace, then qvggt_w4a4_gemm.
  * workspace: device buffer of at least qvggt_workspace_bytes(M, N, K) bytes, 16-byte aligned
  * (holds Xq and x_scale between the two kernels; contents undefined afterwards).

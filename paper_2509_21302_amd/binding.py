@@ -21,6 +21,8 @@ EXPORTS = [
     "qvggt_e2m3_bytes", "qvggt_codes_to_e2m3", "qvggt_e2m3_gemm",
     "qvggt_rotate_smooth_quant_e2m3", "qvggt_workspace_bytes_e2m3", "qvggt_linear_e2m3",
     "qvggt_layernorm_rotate_smooth_quant_e2m3",
+    "qvggt_i8b_bytes", "qvggt_int8_to_blocks", "qvggt_rotate_smooth_quant_i8b", "qvggt_i8b_gemm", "qvggt_workspace_bytes_i8b",
+    "qvggt_linear_i8b",
     "qvggt_rotate_smooth_quant_asym_e2m3", "qvggt_rotate_smooth_quant_static_e2m3", "qvggt_e2m3_gemm_shifted",
     "qvggt_w4a4_gemm", "qvggt_linear", "qvggt_workspace_bytes", "qvggt_pack_int4", "qvggt_unpack_int4",
     "qvggt_prep_weights_i8", "qvggt_rotate_smooth_quant_i8", "qvggt_i8_gemm", "qvggt_linear_i8",
@@ -81,6 +83,18 @@ def load_library() -> C.CDLL:
     lib.qvggt_rotate_smooth_quant_static_e2m3.argtypes = [vp, i, i, i, vp, vp, vp, i, vp, vp, vp, vp]
     lib.qvggt_e2m3_gemm_shifted.restype = i
     lib.qvggt_e2m3_gemm_shifted.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, vp, vp]
+    lib.qvggt_i8b_bytes.restype = C.c_size_t
+    lib.qvggt_i8b_bytes.argtypes = [i, i]
+    lib.qvggt_int8_to_blocks.restype = i
+    lib.qvggt_int8_to_blocks.argtypes = [vp, i, i, vp, vp]
+    lib.qvggt_rotate_smooth_quant_i8b.restype = i
+    lib.qvggt_rotate_smooth_quant_i8b.argtypes = [vp, i, i, i, vp, vp, i, vp, vp, vp]
+    lib.qvggt_i8b_gemm.restype = i
+    lib.qvggt_i8b_gemm.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp, vp, vp]
+    lib.qvggt_workspace_bytes_i8b.restype = C.c_size_t
+    lib.qvggt_workspace_bytes_i8b.argtypes = [i, i, i]
+    lib.qvggt_linear_i8b.restype = i
+    lib.qvggt_linear_i8b.argtypes = [vp, i, i, i, i, vp, vp, i, vp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.qvggt_workspace_bytes_e2m3.restype = C.c_size_t
     lib.qvggt_workspace_bytes_e2m3.argtypes = [i, i, i]
     lib.qvggt_linear_e2m3.restype = i
@@ -248,6 +262,37 @@ def qvggt_rotate_smooth_quant_static_e2m3(X, signs, inv_smooth, x_step, per_toke
 def qvggt_e2m3_gemm_shifted(Xf, x_scale, x_zero, Wf, w_scale, w_codesum, bias, M, N, K, Y, stream=None):
     _check(load_library().qvggt_e2m3_gemm_shifted(_ptr(Xf), _ptr(x_scale), _ptr(x_zero), _ptr(Wf), _ptr(w_scale), _ptr(w_codesum),
                                                   _ptr(bias), M, N, K, _ptr(Y), _stream(stream)), "qvggt_e2m3_gemm_shifted")
+
+
+def qvggt_i8b_bytes(rows, K):
+    return int(load_library().qvggt_i8b_bytes(rows, K))
+
+
+def qvggt_int8_to_blocks(src, rows, K, dst, stream=None):
+    _check(load_library().qvggt_int8_to_blocks(_ptr(src), rows, K, _ptr(dst), _stream(stream)), "qvggt_int8_to_blocks")
+
+
+def qvggt_rotate_smooth_quant_i8b(X, signs, inv_smooth, bits, Xb, x_scale, stream=None):
+    M, K = X.shape
+    _check(load_library().qvggt_rotate_smooth_quant_i8b(_ptr(X), _dtype_code(X), M, K, _ptr(signs), _ptr(inv_smooth), int(bits),
+                                                        _ptr(Xb), _ptr(x_scale), _stream(stream)), "qvggt_rotate_smooth_quant_i8b")
+
+
+def qvggt_i8b_gemm(Xb, x_scale, Wb, w_scale, bias, M, N, K, Y, acc_debug=None, stream=None):
+    _check(load_library().qvggt_i8b_gemm(_ptr(Xb), _ptr(x_scale), _ptr(Wb), _ptr(w_scale), _ptr(bias), M, N, K, _ptr(Y),
+                                         _ptr(acc_debug), _stream(stream)), "qvggt_i8b_gemm")
+
+
+def qvggt_workspace_bytes_i8b(M, N, K):
+    return int(load_library().qvggt_workspace_bytes_i8b(M, N, K))
+
+
+def qvggt_linear_i8b(X, signs, inv_smooth, bits, Wb, w_scale, bias, Y, workspace, stream=None):
+    M, K = X.shape
+    N = Y.shape[1]
+    _check(load_library().qvggt_linear_i8b(_ptr(X), _dtype_code(X), M, N, K, _ptr(signs), _ptr(inv_smooth), int(bits), _ptr(Wb),
+                                           _ptr(w_scale), _ptr(bias), _ptr(Y), _ptr(workspace),
+                                           workspace.numel() * workspace.element_size(), _stream(stream)), "qvggt_linear_i8b")
 
 
 def qvggt_workspace_bytes_e2m3(M, N, K):

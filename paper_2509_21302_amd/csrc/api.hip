@@ -31,6 +31,11 @@ hipError_t run_rotate_quant_e2m3_shifted_mfma(const void *X, int rows, int K, co
                                               float *scale, float *zero, const float *step, int step_stride, hipStream_t stream);
 hipError_t run_e2m3_gemm_shifted(const uint8_t *Xf, const float *sx, const float *xzero, const uint8_t *Wf, const float *sw,
                                  const float *wsum, const void *bias, int M, int N, int K, void *Y, hipStream_t stream);
+hipError_t run_int8_to_blocks(const int8_t *src, int rows, int K, uint8_t *dst, hipStream_t stream);
+hipError_t run_rotate_quant_i8b_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, uint8_t *out,
+                                     float *scale, int bits, hipStream_t stream);
+hipError_t run_i8b_gemm(const int8_t *Xb, const float *sx, const int8_t *Wb, const float *sw, const void *bias, int M, int N,
+                        int K, void *Y, int32_t *acc_debug, hipStream_t stream);
 hipError_t run_codes_to_e2m3(const uint8_t *packed, int rows, int K, uint8_t *out, hipStream_t stream);
 hipError_t run_e2m3_gemm(const uint8_t *Xf, const float *sx, const uint8_t *Wf, const float *sw, const void *bias, int M, int N,
                          int K, void *Y, int32_t *acc_debug, hipStream_t stream);
@@ -237,6 +242,77 @@ int qvggt_w4a4_gemm_asym(const uint8_t *Xq, const float *x_scale, const float *x
         return QVGGT_ERR_ALIGN;
     return hip_status(qvggt::run_w4a4_gemm_asym(Xq, x_scale, x_zero, Wq, w_scale, w_codesum, bias, M, N, K, Y,
                                                 static_cast<hipStream_t>(stream)));
+}
+
+size_t qvggt_i8b_bytes(int rows, int K)
+{
+    if (rows < 0 || !valid_k(K)) return 0;
+    return round_up((size_t)rows, 128) * (size_t)K;
+}
+
+int qvggt_int8_to_blocks(const int8_t *src, int rows, int K, int8_t *dst, void *stream)
+{
+    if (rows < 0 || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (rows == 0) return QVGGT_OK;
+    if (!src || !dst) return QVGGT_ERR_NULL;
+    if (!aligned16(src) || !aligned16(dst)) return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_int8_to_blocks(src, rows, K, reinterpret_cast<uint8_t *>(dst), static_cast<hipStream_t>(stream)));
+}
+
+static bool blocks_direct(int x_dtype, int K) { return x_dtype == QVGGT_BF16 && (K == 1024 || K == 2048 || K == 4096); }
+
+int qvggt_rotate_smooth_quant_i8b(const void *X, int x_dtype, int M, int K, const int8_t *signs, const float *inv_smooth, int bits,
+                                  int8_t *Xb, float *x_scale, void *stream)
+{
+    if (!valid_dtype(x_dtype)) return QVGGT_ERR_DTYPE;
+    if (M < 0 || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (!blocks_direct(x_dtype, K)) return x_dtype == QVGGT_BF16 ? QVGGT_ERR_SHAPE : QVGGT_ERR_DTYPE;
+    if (!valid_wide_bits(bits)) return QVGGT_ERR_ARG;
+    if (M == 0) return QVGGT_OK;
+    if (!X || !Xb || !x_scale) return QVGGT_ERR_NULL;
+    if (!aligned16(X) || !aligned16(Xb) || !aligned16(x_scale) || !aligned16(inv_smooth) || !aligned16(signs)) return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_rotate_quant_i8b_mfma(X, M, K, signs, inv_smooth, reinterpret_cast<uint8_t *>(Xb), x_scale, bits,
+                                                       static_cast<hipStream_t>(stream)));
+}
+
+int qvggt_i8b_gemm(const int8_t *Xb, const float *x_scale, const int8_t *Wb, const float *w_scale, const void *bias, int M, int N,
+                   int K, void *Y, int32_t *acc_debug, void *stream)
+{
+    if (M < 0 || !valid_n(N) || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (M == 0) return QVGGT_OK;
+    if (!Xb || !x_scale || !Wb || !w_scale || !Y) return QVGGT_ERR_NULL;
+    if (!aligned16(Xb) || !aligned16(x_scale) || !aligned16(Wb) || !aligned16(w_scale) || !aligned16(bias) || !aligned16(Y) ||
+        !aligned16(acc_debug))
+        return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_i8b_gemm(Xb, x_scale, Wb, w_scale, bias, M, N, K, Y, acc_debug, static_cast<hipStream_t>(stream)));
+}
+
+size_t qvggt_workspace_bytes_i8b(int M, int N, int K)
+{
+    if (M < 0 || !valid_n(N) || !valid_k(K)) return 0;
+    return round_up(qvggt_i8b_bytes(M, K), 256) + round_up((size_t)M * sizeof(float), 256);
+}
+
+int qvggt_linear_i8b(const void *X, int x_dtype, int M, int N, int K, const int8_t *signs, const float *inv_smooth, int bits,
+                     const int8_t *Wb, const float *w_scale, const void *bias, void *Y, void *workspace, size_t workspace_bytes,
+                     void *stream)
+{
+    if (!valid_dtype(x_dtype)) return QVGGT_ERR_DTYPE;
+    if (M < 0 || !valid_n(N) || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (!blocks_direct(x_dtype, K)) return x_dtype == QVGGT_BF16 ? QVGGT_ERR_SHAPE : QVGGT_ERR_DTYPE;
+    if (!valid_wide_bits(bits)) return QVGGT_ERR_ARG;
+    if (M == 0) return QVGGT_OK;
+    if (!X || !Wb || !w_scale || !Y || !workspace) return QVGGT_ERR_NULL;
+    if (!aligned16(X) || !aligned16(Wb) || !aligned16(w_scale) || !aligned16(bias) || !aligned16(Y) || !aligned16(workspace) ||
+        !aligned16(inv_smooth) || !aligned16(signs))
+        return QVGGT_ERR_ALIGN;
+    if (workspace_bytes < qvggt_workspace_bytes_i8b(M, N, K)) return QVGGT_ERR_WORKSPACE;
+    uint8_t *Xb = static_cast<uint8_t *>(workspace);
+    float *x_scale = reinterpret_cast<float *>(Xb + round_up(qvggt_i8b_bytes(M, K), 256));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = qvggt::run_rotate_quant_i8b_mfma(X, M, K, signs, inv_smooth, Xb, x_scale, bits, s);
+    if (e != hipSuccess) return QVGGT_ERR_HIP;
+    return hip_status(qvggt::run_i8b_gemm(reinterpret_cast<const int8_t *>(Xb), x_scale, Wb, w_scale, bias, M, N, K, Y, nullptr, s));
 }
 
 size_t qvggt_e2m3_bytes(int rows, int K)

@@ -133,7 +133,10 @@ __device__ inline void wait_vmcnt()
 // CB: bits a stored code occupies: 4 (two codes per byte, expanded in registers) or 8 (int8 codes, fed to the MFMA as read)
 // ASYM: activations carry affine codes u with a zero point per token, stored as u - 8 (Xq) and zp (xzero); the epilogue adds
 // (8 - zp[t]) * wsum[o] (wsum[o] = sum_j qw[o, j], exact in fp32) to the accumulator before the scales
-template <int TM, int TN, int WM, int WN, int STAGES, int MINB, int CB, bool DEBUG, bool ASYM = false>
+// BLK (int8 codes): the operands are "int8 blocks": rows grouped in blocks of 128 with the K-tiles outermost, K-tile kt of row r at
+// ((r / 128) * (K / 64) + kt) * 8192 + (r % 128) * 64, its four 16-byte chunks already in the swizzled order of the LDS stage, so
+// that what a wave fetches of a K-tile is 8 KiB (4 KiB in the small configuration) contiguous in memory
+template <int TM, int TN, int WM, int WN, int STAGES, int MINB, int CB, bool DEBUG, bool ASYM = false, bool BLK = false>
 __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per_eu(WM * WN * MINB / 4, WM * WN * MINB / 4))) void w4a4_gemm_kernel(
     const uint8_t *__restrict__ Xq, const float *__restrict__ sx, const uint8_t *__restrict__ Wq,
     const float *__restrict__ sw, const uint16_t *__restrict__ bias, int M, int N, int K,
@@ -152,6 +155,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
     static_assert(CB == 4 || CB == 8, "codes are stored in 4 or 8 bits");
+    static_assert(!BLK || CB == 8, "the blocked operand format holds int8 codes");
     constexpr int KSTEPS = (CB == 4) ? 4 : 2;                   // MFMA K-steps (32 codes each) in a K-tile of 64 bytes per row
     const int KB = (CB == 4) ? (K >> 1) : K;                    // bytes per row of codes
     const int ktiles = KB / KT_BYTES;
@@ -177,9 +181,20 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
     uint32_t lane_off[LPW];
     const uint8_t *tile_base;                                   // wave-uniform: row 0 of the operand's tile, minus BASE_SHIFT
     int ld_tile = first_tile, ld_kt = 0, ld_stage = 0;
+    static_assert(!BLK || 8192 % (LPW * 1024) == 0, "a wave's transfers of a K-tile must lie inside one 128-row block");
+    if constexpr (BLK) {
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) lane_off[i] = (i * 64 + lane) * 16 + BASE_SHIFT - (i * 1024 - DMA_SHIFT);
+    }
     auto set_tile_pointers = [&](int t) {
         const int tm = t / tiles_n, tn = t % tiles_n;
         const int row0 = loads_x ? tm * C::BM : tn * C::BN;     // first row of the tile in its operand
+        if constexpr (BLK) {
+            const int row = row0 + wave * LPW * 16 - (loads_x ? 0 : C::BM);          // first row of this wave's share
+            const int blk = min(row / 128, ((loads_x ? M : N) + 127) / 128 - 1);        // past the end: re-read the last block (unused)
+            tile_base = (loads_x ? Xq : Wq) + (size_t)blk * ktiles * 8192 + (row % 128) * KT_BYTES - BASE_SHIFT;
+            return;
+        }
         const int last = (loads_x ? M : N) - 1 - row0;          // last existing row, relative to row0 (>= 0)
         tile_base = (loads_x ? Xq : Wq) + (size_t)row0 * KB - BASE_SHIFT;
 #pragma unroll
@@ -193,7 +208,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
     // output tiles (past this block's last tile it re-reads that tile: never used, keeps the transfers in flight uniform).
     auto issue_transfer = [&](auto i_c) {
         constexpr int i = decltype(i_c)::value;
-        const uint8_t *base = tile_base + ld_kt * KT_BYTES;
+        const uint8_t *base = tile_base + (BLK ? (size_t)ld_kt * 8192 : (size_t)ld_kt * KT_BYTES);
         // the wave's LPW KiB of a stage are contiguous; M0 (set by the first transfer of a K-tile) points DMA_SHIFT into them
         if constexpr (i == 0) dma16_set_base<i * 1024 - DMA_SHIFT>(lane_off[i], base, lds0 + ld_stage * C::STAGE_BYTES + wave * LPW * 1024 + DMA_SHIFT);
         else dma16_same_base<i * 1024 - DMA_SHIFT>(lane_off[i], base);
@@ -496,7 +511,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
     wait_vmcnt<0>();        // transfers issued past the last tile must not outlive the block's LDS allocation
 }
 
-template <int TM, int TN, int WM, int WN, int STAGES, int MINB, int CB, bool ASYM = false>
+template <int TM, int TN, int WM, int WN, int STAGES, int MINB, int CB, bool ASYM = false, bool BLK = false>
 static hipError_t launch_gemm(const uint8_t *Xq, const float *sx, const uint8_t *Wq, const float *sw, const void *bias,
                               int M, int N, int K, void *Y, int32_t *acc_debug, hipStream_t stream,
                               const float *xzero = nullptr, const float *wsum = nullptr)
@@ -512,9 +527,9 @@ static hipError_t launch_gemm(const uint8_t *Xq, const float *sx, const uint8_t 
 #endif
     // the variant that also writes the raw accumulators is a separate instantiation: the production kernel carries none of it
     const bool debug = acc_debug != nullptr;
-    auto kern = w4a4_gemm_kernel<TM, TN, WM, WN, STAGES, MINB, CB, false, ASYM>;
+    auto kern = w4a4_gemm_kernel<TM, TN, WM, WN, STAGES, MINB, CB, false, ASYM, BLK>;
     if constexpr (!ASYM) {
-        if (debug) kern = w4a4_gemm_kernel<TM, TN, WM, WN, STAGES, MINB, CB, true, false>;
+        if (debug) kern = w4a4_gemm_kernel<TM, TN, WM, WN, STAGES, MINB, CB, true, false, BLK>;
     } else {
         if (debug) return hipErrorInvalidValue;      // no accumulator dump with affine codes: the corrected sum is never an integer register
     }
@@ -538,19 +553,19 @@ static hipError_t launch_gemm(const uint8_t *Xq, const float *sx, const uint8_t 
 // that fill whole rounds go to the big kernel and the remaining rows, when they fit better there, to the small configuration
 // (128 x 128 per block, two blocks per compute unit) in a second launch on the same stream.  Rows are independent, the two
 // launches write disjoint rows of Y.
-template <int CB, bool ASYM = false>
+template <int CB, bool ASYM = false, bool BLK = false>
 static hipError_t gemm_by_rounds(const uint8_t *Xq, const float *sx, const uint8_t *Wq, const float *sw, const void *bias,
                                  int M, int N, int K, void *Y, int32_t *acc_debug, hipStream_t stream,
                                  const float *xzero = nullptr, const float *wsum = nullptr)
 {
     auto big = [&](int row0, int rows) {
-        return launch_gemm<4, 4, 2, 2, 4, 1, CB, ASYM>(Xq + (size_t)row0 * (CB == 4 ? K / 2 : K), sx + row0, Wq, sw, bias, rows, N, K,
+        return launch_gemm<4, 4, 2, 2, 4, 1, CB, ASYM, BLK>(Xq + (size_t)row0 * (CB == 4 ? K / 2 : K), sx + row0, Wq, sw, bias, rows, N, K,
                                                        static_cast<uint16_t *>(Y) + (size_t)row0 * N,
                                                        acc_debug ? acc_debug + (size_t)row0 * N : nullptr, stream,
                                                        ASYM ? xzero + row0 : nullptr, wsum);
     };
     auto small = [&](int row0, int rows) {
-        return launch_gemm<2, 2, 2, 2, 3, 2, CB, ASYM>(Xq + (size_t)row0 * (CB == 4 ? K / 2 : K), sx + row0, Wq, sw, bias, rows, N, K,
+        return launch_gemm<2, 2, 2, 2, 3, 2, CB, ASYM, BLK>(Xq + (size_t)row0 * (CB == 4 ? K / 2 : K), sx + row0, Wq, sw, bias, rows, N, K,
                                                        static_cast<uint16_t *>(Y) + (size_t)row0 * N,
                                                        acc_debug ? acc_debug + (size_t)row0 * N : nullptr, stream,
                                                        ASYM ? xzero + row0 : nullptr, wsum);
@@ -611,6 +626,15 @@ hipError_t run_i8_gemm(const int8_t *Xq, const float *sx, const int8_t *Wq, cons
     const uint8_t *xq = reinterpret_cast<const uint8_t *>(Xq), *wq = reinterpret_cast<const uint8_t *>(Wq);
 #undef GOP
     return gemm_by_rounds<8>(xq, sx, wq, sw, bias, M, N, K, Y, acc_debug, stream);
+}
+
+// int8 codes in 128-row blocks (see the kernel): whole tile rows go to either launch, so row offsets stay whole blocks
+hipError_t run_i8b_gemm(const int8_t *Xb, const float *sx, const int8_t *Wb, const float *sw, const void *bias, int M, int N,
+                        int K, void *Y, int32_t *acc_debug, hipStream_t stream)
+{
+    if (M <= 0) return hipSuccess;
+    return gemm_by_rounds<8, false, true>(reinterpret_cast<const uint8_t *>(Xb), sx, reinterpret_cast<const uint8_t *>(Wb), sw, bias,
+                                          M, N, K, Y, acc_debug, stream);
 }
 
 }  // namespace qvggt

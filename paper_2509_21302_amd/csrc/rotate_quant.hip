@@ -520,6 +520,26 @@ hipError_t run_layout_int8(const int8_t *src, int rows, int K, int8_t *dst, int 
     return hipGetLastError();
 }
 
+// int8 rows in library order [rows, K] -> int8 blocks (K-tiles of 64 bytes outermost inside 128-row blocks, chunks swizzled)
+__global__ __launch_bounds__(256) void int8_to_blocks_kernel(const int8_t *__restrict__ src, size_t rows, int K, uint8_t *__restrict__ dst)
+{
+    const size_t chunks_per_row = (size_t)K / 16;
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= rows * chunks_per_row) return;
+    const size_t row = idx / chunks_per_row;
+    const int ch = (int)(idx - row * chunks_per_row), kt = ch >> 2, slot = (ch & 3) ^ (int)((row & 15) >> 2);
+    const uint4 v = *reinterpret_cast<const uint4 *>(src + row * (size_t)K + (size_t)ch * 16);
+    *reinterpret_cast<uint4 *>(dst + ((row / 128) * (size_t)(K / 64) + kt) * 8192 + (row % 128) * 64 + slot * 16) = v;
+}
+
+hipError_t run_int8_to_blocks(const int8_t *src, int rows, int K, uint8_t *dst, hipStream_t stream)
+{
+    const size_t n = (size_t)rows * (K / 16);
+    if (n == 0) return hipSuccess;
+    int8_to_blocks_kernel<<<(unsigned)((n + 255) / 256), 256, 0, stream>>>(src, (size_t)rows, K, dst);
+    return hipGetLastError();
+}
+
 hipError_t run_code_sums(const uint8_t *packed, int rows, int K, float *sums, hipStream_t stream)
 {
     if (rows <= 0) return hipSuccess;

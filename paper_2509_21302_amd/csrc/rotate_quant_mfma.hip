@@ -79,7 +79,9 @@ __host__ __device__ constexpr int row_of_seg_hi(int seg_hi /* seg >> 2 */)
 // applied to the loaded values before anything else
 // ASYM: affine codes.  The row's range [min(0, min z), max(0, max z)] takes the 16 codes, the zero point goes to zero[row], and
 // the nibbles hold u - 8 (u the unsigned code), i.e. the signed values the integer GEMM multiplies
-template <int K, int PF, int OCC, bool STATIC, int CB, bool LN = false, bool ASYM = false>
+// BLK8 (CB = 8): the int8 codes go out as "int8 blocks", the operand format of the blocked int8 GEMM: K-tile kt (64 codes) of row r at
+// ((r / 128) * (K / 64) + kt) * 8192 + (r % 128) * 64, its 16-byte chunk ch in slot ch ^ ((r % 16) >> 2)
+template <int K, int PF, int OCC, bool STATIC, int CB, bool LN = false, bool ASYM = false, bool BLK8 = false>
 __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint16_t *__restrict__ X, int rows,
                                                                    const int8_t *__restrict__ signs,
                                                                    const float *__restrict__ mul, int mul_mode,
@@ -221,8 +223,9 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
     // E2M3 output at K = 4096: a token's 64 units lie 6 KiB apart in the output, 48 bytes each; the four waves of a block take
     // four consecutive tokens and flush them together through LDS, so that memory sees runs of 192 bytes per unit (48-byte
     // pieces cost 190 us more at 137400 tokens).  The block then iterates as one: same trip count, barriers inside the loop.
-    constexpr bool BLOCK_FLUSH = (CB == 6 && REM == 5);
-    __shared__ __attribute__((aligned(16))) uint8_t flush_all[BLOCK_FLUSH ? 4 * 64 * 48 : 16];
+    static_assert(!BLK8 || CB == 8, "int8 blocks hold int8 codes");
+    constexpr bool BLOCK_FLUSH = ((CB == 6 || BLK8) && REM == 5);
+    __shared__ __attribute__((aligned(16))) uint8_t flush_all[BLOCK_FLUSH ? 4 * 64 * (BLK8 ? 64 : 48) : 16];
     uint4 G[PF][8];
     int tile = wave;
 #pragma unroll
@@ -488,6 +491,39 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
                     constexpr uint32_t BIAS8 = (uint32_t)(0x4B400000ull * 0x01010101ull);
                     words[d] = (wv - BIAS8) ^ 0x80808080u;
                 }
+                if constexpr (BLK8) {
+                    // the lane's NL bytes are positions P0 .. of the row: chunk P / 16 of K-tile P / 64
+                    const int P0 = c * (K / 32) + (REM == 5 ? g * 64 : 0);
+                    const int swz = (row & 15) >> 2;
+                    if constexpr (REM == 5) {
+                        // K = 4096: the lane holds K-tile 2 c + g of this wave's token, 64 bytes; the block's four tokens leave together
+                        // (flush area [K-tile][wave][64 bytes]) in runs of 256 bytes, see the 6-bit variant
+                        uint8_t *slot = flush_all + (P0 / 64) * 256 + wave_in_block * 64;
+#pragma unroll
+                        for (int d4 = 0; d4 < 4; ++d4)
+                            *reinterpret_cast<uint4 *>(slot + ((d4 ^ swz) * 16)) = make_uint4(words[4 * d4], words[4 * d4 + 1], words[4 * d4 + 2], words[4 * d4 + 3]);
+                        __syncthreads();
+                        const int row4 = tile - wave_in_block;
+                        uint8_t *rb = packed + (size_t)(row4 / 128) * (K / 64) * 8192 + (size_t)(row4 % 128) * 64;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int j = i * 256 + (int)threadIdx.x, kt = j / 16, within = j - 16 * kt;      // 16-byte chunk j of 1024
+                            if (row4 + within / 4 < rows)
+                                *reinterpret_cast<uint4 *>(rb + (size_t)kt * 8192 + within * 16) = *reinterpret_cast<const uint4 *>(flush_all + j * 16);
+                        }
+                        __syncthreads();
+                    } else if (row < rows) {
+                        uint8_t *rb = packed + (size_t)(row / 128) * (K / 64) * 8192 + (size_t)(row % 128) * 64;
+#pragma unroll
+                        for (int d4 = 0; d4 < C::NL / 16; ++d4) {
+                            const int P = P0 + 16 * d4;
+                            *reinterpret_cast<uint4 *>(rb + (size_t)(P / 64) * 8192 + ((((P % 64) / 16) ^ swz) * 16)) =
+                                make_uint4(words[4 * d4], words[4 * d4 + 1], words[4 * d4 + 2], words[4 * d4 + 3]);
+                        }
+                    }
+                    if (row < rows && c == 0 && (REM != 5 || g == 0)) scale[row] = delta;
+                    continue;
+                }
                 if (row < rows) {
                     uint8_t *out = packed + (size_t)row * K + (size_t)c * (K / 32) + (REM == 5 ? g * 64 : 0);
 #pragma unroll
@@ -608,6 +644,29 @@ hipError_t run_rotate_quant_asym_mfma(const void *X, int rows, int K, const int8
         default: return hipErrorInvalidValue;
     }
 #undef RQA
+    return hipGetLastError();
+}
+
+// rotation + smoothing + per-token int8 codes of `bits` bits as int8 blocks (what the blocked int8 GEMM reads), bf16 rows
+hipError_t run_rotate_quant_i8b_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, uint8_t *out,
+                                     float *scale, int bits, hipStream_t stream)
+{
+    if (rows <= 0) return hipSuccess;
+    const uint16_t *x = reinterpret_cast<const uint16_t *>(X);
+    const int tok = 32 / (K / 128);
+    const int ntiles = (rows + tok - 1) / tok;
+    int blocks = (ntiles + rq::WAVES_PER_BLOCK - 1) / rq::WAVES_PER_BLOCK;
+    if (blocks > 256 * 2) blocks = 256 * 2;
+    const float qmax8 = (float)((1 << (bits - 1)) - 1);
+    const LnParams no_ln{nullptr, nullptr, 0.0f, 0};
+#define RQB(KK) rotate_quant_mfma_kernel<KK, 1, 2, false, 8, false, false, true><<<blocks, 256, 0, stream>>>(x, rows, signs, mul, 0, out, scale, nullptr, 0, qmax8, nullptr, no_ln, nullptr)
+    switch (K) {
+        case 1024: RQB(1024); break;
+        case 2048: RQB(2048); break;
+        case 4096: RQB(4096); break;
+        default: return hipErrorInvalidValue;
+    }
+#undef RQB
     return hipGetLastError();
 }
 

@@ -47,12 +47,19 @@ class DsfqLinear:
         else:
             self.Wq = torch.empty(self.N, self.K, dtype=torch.int8, device=dev)
             q.qvggt_prep_weights_i8(weight, absmax, signs, alpha, bits, self.Wq, self.w_scale, self.inv_smooth)
+            # the same codes in 128-row blocks for the GEMM with contiguous operand transfers (bf16 inputs, K = 1024 / 2048 / 4096)
+            self.Wb = None
+            if self.K in (1024, 2048, 4096):
+                self.Wb = torch.empty(q.qvggt_i8b_bytes(self.N, self.K), dtype=torch.int8, device=dev)
+                q.qvggt_int8_to_blocks(self.Wq, self.N, self.K, self.Wb)
         self._ws = None
 
     def _workspace(self, M: int, dev) -> torch.Tensor:
         need = q.qvggt_workspace_bytes(M, self.N, self.K) if self.packed else q.qvggt_workspace_bytes_i8(M, self.N, self.K)
         if self.packed and self.Wf is not None:
             need = max(need, q.qvggt_workspace_bytes_e2m3(M, self.N, self.K))
+        if not self.packed and self.Wb is not None:
+            need = max(need, q.qvggt_workspace_bytes_i8b(M, self.N, self.K))
         if self._ws is None or self._ws.numel() < need or self._ws.device != dev:
             self._ws = torch.empty(need, dtype=torch.uint8, device=dev)
         return self._ws
@@ -66,6 +73,8 @@ class DsfqLinear:
             q.qvggt_linear_e2m3(X, self.signs, self.inv_smooth, self.Wf, self.w_scale, self.bias, Y, ws)      # same Y, bit for bit
         elif self.packed:
             q.qvggt_linear(X, self.signs, self.inv_smooth, self.Wq, self.w_scale, self.bias, Y, ws)
+        elif self.Wb is not None and X.dtype == torch.bfloat16:
+            q.qvggt_linear_i8b(X, self.signs, self.inv_smooth, self.act_bits, self.Wb, self.w_scale, self.bias, Y, ws)   # same Y
         else:
             q.qvggt_linear_i8(X, self.signs, self.inv_smooth, self.act_bits, self.Wq, self.w_scale, self.bias, Y, ws)
         return Y

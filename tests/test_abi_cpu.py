@@ -146,6 +146,22 @@ def test_argument_validation_needs_no_gpu():
     assert le(P, 0, 100, 32, 1024, None, None, P, P, None, P, P, need6 - 1, None) == WORKSPACE
     assert le(P, 0, 100, 32, 768, None, None, P, P, None, P, P, need6, None) == SHAPE
     assert le(P, 1, 100, 32, 1024, None, None, P, P, None, P, P, need6, None) == DTYPE
+    # int8 blocks: format size, converter, direct kernel 1 (bf16, K = 1024 / 2048 / 4096 only), GEMM, whole path
+    assert q.qvggt_i8b_bytes(1, 1024) == 128 * 1024 and q.qvggt_i8b_bytes(129, 4096) == 256 * 4096 and q.qvggt_i8b_bytes(5, 1000) == 0
+    tb, rb, gb, lb = lib.qvggt_int8_to_blocks, lib.qvggt_rotate_smooth_quant_i8b, lib.qvggt_i8b_gemm, lib.qvggt_linear_i8b
+    assert tb(P, 4, 1000, P, None) == SHAPE and tb(None, 4, 1024, P, None) == NULL and tb(P, 4, 1024, P + 4, None) == ALIGN
+    assert tb(None, 0, 1024, None, None) == OK
+    assert rb(P, 0, 4, 512, None, None, 8, P, P, None) == SHAPE and rb(P, 1, 4, 1024, None, None, 8, P, P, None) == DTYPE
+    assert rb(P, 0, 4, 1024, None, None, 9, P, P, None) == ARG and rb(P, 0, 4, 1024, None, None, 8, None, P, None) == NULL
+    assert rb(None, 0, 0, 1024, None, None, 8, None, None, None) == OK
+    assert gb(P, P, P, P, None, 4, 100, 1024, P, None, None) == SHAPE and gb(P, P, None, P, None, 4, 32, 1024, P, None, None) == NULL
+    assert gb(P, P, P, P, P + 4, 4, 32, 1024, P, None, None) == ALIGN and gb(None, None, None, None, None, 0, 32, 1024, None, None, None) == OK
+    need8 = q.qvggt_workspace_bytes_i8b(100, 32, 1024)
+    assert need8 >= 128 * 1024 + 400
+    assert lb(P, 0, 100, 32, 1024, None, None, 8, P, P, None, P, P, need8 - 1, None) == WORKSPACE
+    assert lb(P, 0, 100, 32, 768, None, None, 8, P, P, None, P, P, need8, None) == SHAPE
+    assert lb(P, 1, 100, 32, 1024, None, None, 8, P, P, None, P, P, need8, None) == DTYPE
+    assert lb(P, 0, 100, 32, 1024, None, None, 3, P, P, None, P, P, need8, None) == ARG
     # 8-bit / 6-bit entry points: the same checks, and the bit-width
     for bad in (3, 9, 0, -8):
         assert lib.qvggt_rotate_smooth_quant_i8(P, 0, 4, 1024, None, None, bad, P, P, None) == ARG

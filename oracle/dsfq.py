@@ -248,6 +248,19 @@ def layernorm(X, gamma=None, beta=None, eps: float = 1e-5, round_to_bf16: bool =
     return bf16_bits_to_f64(bf16_from_f64(y)) if round_to_bf16 else y
 
 
+def gelu(X, round_to_bf16: bool = True) -> np.ndarray:
+    """The activation between fc1 and fc2 of VGGT's MLP blocks (the layers of Sec. 3.2 are this network's linear layers):
+    GELU(x) = x * Phi(x), Phi the standard normal distribution function, written as erfc(-x / sqrt 2) / 2 so that the
+    negative tail keeps its relative accuracy; float64, a math.erfc call per element.  With round_to_bf16 the result
+    is rounded to bfloat16 (nearest even) and returned as the exact doubles of those values: what a bf16 activation kernel
+    hands to fc2."""
+    import math
+    x = to_f64(X)
+    phi = np.array([0.5 * math.erfc(-v / math.sqrt(2.0)) for v in x.ravel()], dtype=np.float64).reshape(x.shape)
+    y = x * phi
+    return bf16_bits_to_f64(bf16_from_f64(y)) if round_to_bf16 else y
+
+
 def rotate_smooth_quant(X, c_hat=None, pre_signs=None, post_signs=None, bits: int = 4):
     """Online half up to the codes: returns (dx [M], qx [M, K] int8, Xs [M, K] f64)."""
     Xr = rotate(to_f64(X), pre_signs, post_signs)

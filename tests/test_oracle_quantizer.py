@@ -256,6 +256,31 @@ def test_layernorm_closed_forms_and_library():
     assert np.all(np.abs(r - t) <= np.abs(t) * 2.0 ** -8 + 1e-40) and np.abs(r - t).max() > 0
 
 
+def test_gelu_against_the_integral_and_closed_forms():
+    """GELU(x) = x Phi(x): Phi from a quadrature of the normal density (no error function involved), the odd-part identity
+    GELU(x) - GELU(-x) = x, printed values of Phi, the library routine in float64, and the bf16 rounding."""
+    x = np.concatenate([np.linspace(-6, 6, 97), [0.0, 1e-3, -1e-3, 0.5, -7.5]])
+    y = oracle.gelu(x[None, :], round_to_bf16=False)[0]
+    # composite Simpson on [0, |x|] with 2000 intervals: error far below 1e-13 for the smooth density
+    def phi_quad(v):
+        n = 2000
+        t = np.linspace(0.0, abs(v), n + 1)
+        f = np.exp(-0.5 * t * t) / np.sqrt(2.0 * np.pi)
+        integral = (abs(v) / n / 3.0) * (f[0] + f[-1] + 4.0 * f[1:-1:2].sum() + 2.0 * f[2:-1:2].sum())
+        return 0.5 + np.sign(v) * integral
+    want = np.array([v * phi_quad(v) for v in x])
+    assert np.allclose(y, want, rtol=0, atol=2e-13)
+    assert np.allclose(y - oracle.gelu(-x[None, :], round_to_bf16=False)[0], x, rtol=0, atol=1e-15)
+    # Phi(1) = 0.841344746068543, Phi(-2) = 0.022750131948179, Phi(-6) = 9.8658764503769e-10 (standard tables)
+    pts = oracle.gelu(np.array([[1.0, -2.0, -6.0, 0.0]]), round_to_bf16=False)[0]
+    assert np.allclose(pts[:3], [0.841344746068543, -2 * 0.022750131948179, -6 * 9.8658764503769e-10], rtol=1e-12) and pts[3] == 0.0
+    t = torch.nn.functional.gelu(torch.from_numpy(x)).numpy()
+    assert np.allclose(y, t, rtol=1e-9, atol=1e-15)          # the library's 1 + erf loses relative accuracy in the negative tail
+    r = oracle.gelu(x[None, :])[0]
+    assert np.array_equal(oracle.bf16_bits_to_f64(oracle.bf16_from_f64(r)), r)
+    assert np.all(np.abs(r - y) <= np.abs(y) * 2.0 ** -8 + 1e-40) and np.abs(r - y).max() > 0
+
+
 # ----------------------------------------------------------------- asymmetric activation codes (appendix, further settings)
 def test_asymmetric_quantizer_hand_worked_rows():
     # lo = -3, hi = 12: step 1, zero point 3; 4.5 and -2.5 are ties (to even: 4 and -2)

@@ -285,6 +285,31 @@ def main():
                     rotated_col_absmax_frac_hbm_peak=nbytes / t_a / 1e6 / HBM_PEAK_GBS)
         del ws
 
+    # side measurement: fc2's kernel 1 reading fc1's output with the GELU applied on load, beside the plain kernel on the same
+    # tensor (the activation pass it replaces reads and writes that tensor once more)
+    gelu_side = None
+    by_name = {L["spec"].name: L for L in layers}
+    if (args.bits == 4 and headline == "e2m3" and not args.headline_only and "fc1" in by_name and "fc2" in by_name
+            and by_name["fc2"]["spec"].K == by_name["fc1"]["spec"].N and by_name["fc2"]["spec"].K in (1024, 2048, 4096)):
+        L1, L2 = by_name["fc1"], by_name["fc2"]
+        linear(L1, "e2m3")                                     # fc1's output of this run: the tensor fc2's kernel 1 would read
+        P2, reps = L2["prep"]["e2m3"], 5
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        for it in range(reps + 1):
+            if it == 1:
+                e[0].record()
+            q.qvggt_gelu_rotate_smooth_quant_e2m3(L1["Y"], L2["signs"], P2["inv"], L2["Xf"], L2["sx"])
+        e[1].record()
+        for it in range(reps):
+            q.qvggt_rotate_smooth_quant_e2m3(L1["Y"], L2["signs"], P2["inv"], L2["Xf"], L2["sx"])
+        e[2].record()
+        torch.cuda.synchronize()
+        t_f, t_p = e[0].elapsed_time(e[1]) / reps, e[1].elapsed_time(e[2]) / reps
+        s2 = L2["spec"]
+        gelu_side = dict(tensor=f"fc1 output {s2.M} x {s2.K} bf16", gelu_rotate_quant_ms=t_f, rotate_quant_ms=t_p,
+                         activation_pass_bytes_saved=4.0 * s2.M * s2.K,
+                         activation_pass_ms_at_hbm_peak=4.0 * s2.M * s2.K / HBM_PEAK_GBS / 1e6)
+
     if args.calibrate_copy:
         # 1 GiB read + 1 GiB written by an elementwise kernel: what the HBM byte counters report for it fixes their scale
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
@@ -337,6 +362,8 @@ def main():
         out["w4a4_int8_path"] = side_int8_path
     if nfds is not None:
         out["calibration_reductions"] = nfds
+    if gelu_side is not None:
+        out["gelu_fused_kernel1"] = gelu_side
     print(json.dumps(out))
 
 

@@ -158,6 +158,21 @@ int qvggt_layernorm_rotate_smooth_quant(const void *X, int x_dtype, int M, int K
                                         float *x_scale, void *stream);
 
 /*
+ * Online kernel 1 of fc2 with the GELU that precedes it fused in (VGGT's MLP blocks: fc1 -> GELU -> fc2, the linear
+ * layers being those of Sec. 3.2).  X is fc1's output as stored; per element, before the rotation:
+ *     y = x * Phi(x)      (Phi the standard normal distribution function, fp32, relative error about 1e-7 for x > -3),
+ * y rounded to bf16 (nearest even, i.e. what a separate bf16 activation kernel would write), then exactly
+ * qvggt_rotate_smooth_quant (Xq: packed codes) or qvggt_rotate_smooth_quant_e2m3 (Xf: E2M3 blocks, below) on y.  One
+ * read of fc1's output instead of an activation pass (read + write) followed by this kernel's read.
+ * bf16 X with K = 1024, 2048 or 4096 only: other K are QVGGT_ERR_SHAPE, f32 X is QVGGT_ERR_DTYPE.  Other arguments,
+ * layouts and errors as the entry points named above.
+ */
+int qvggt_gelu_rotate_smooth_quant(const void *X, int x_dtype, int M, int K, const int8_t *signs, const float *inv_smooth,
+                                   uint8_t *Xq, float *x_scale, void *stream);
+int qvggt_gelu_rotate_smooth_quant_e2m3(const void *X, int x_dtype, int M, int K, const int8_t *signs,
+                                        const float *inv_smooth, uint8_t *Xf, float *x_scale, void *stream);
+
+/*
  * Online kernel 2 (Sec. 3.2 granularity paragraph: integer sum, dequantise after it):
  *     acc[t, o] = sum_j Xq[t, j] Wq[o, j]   (int32, exact);
  *     Y[t, o]   = bf16_rne( acc[t, o] * x_scale[t] * w_scale[o] + bias[o] )

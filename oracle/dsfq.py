@@ -251,13 +251,12 @@ def layernorm(X, gamma=None, beta=None, eps: float = 1e-5, round_to_bf16: bool =
 def gelu(X, round_to_bf16: bool = True) -> np.ndarray:
     """The activation between fc1 and fc2 of VGGT's MLP blocks (the layers of Sec. 3.2 are this network's linear layers):
     GELU(x) = x * Phi(x), Phi the standard normal distribution function, written as erfc(-x / sqrt 2) / 2 so that the
-    negative tail keeps its relative accuracy; float64, a math.erfc call per element.  With round_to_bf16 the result
+    negative tail keeps its relative accuracy; float64, the library's complementary error function.  With round_to_bf16 the result
     is rounded to bfloat16 (nearest even) and returned as the exact doubles of those values: what a bf16 activation kernel
     hands to fc2."""
-    import math
+    from scipy.special import erfc
     x = to_f64(X)
-    phi = np.array([0.5 * math.erfc(-v / math.sqrt(2.0)) for v in x.ravel()], dtype=np.float64).reshape(x.shape)
-    y = x * phi
+    y = x * (0.5 * erfc(-x / np.sqrt(2.0)))
     return bf16_bits_to_f64(bf16_from_f64(y)) if round_to_bf16 else y
 
 

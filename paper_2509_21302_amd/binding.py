@@ -21,6 +21,7 @@ EXPORTS = [
     "qvggt_e2m3_bytes", "qvggt_codes_to_e2m3", "qvggt_e2m3_gemm",
     "qvggt_rotate_smooth_quant_e2m3", "qvggt_workspace_bytes_e2m3", "qvggt_linear_e2m3",
     "qvggt_layernorm_rotate_smooth_quant_e2m3",
+    "qvggt_gelu_rotate_smooth_quant", "qvggt_gelu_rotate_smooth_quant_e2m3",
     "qvggt_i8b_bytes", "qvggt_int8_to_blocks", "qvggt_rotate_smooth_quant_i8b", "qvggt_i8b_gemm", "qvggt_workspace_bytes_i8b",
     "qvggt_linear_i8b",
     "qvggt_rotate_smooth_quant_asym_e2m3", "qvggt_rotate_smooth_quant_static_e2m3", "qvggt_e2m3_gemm_shifted",
@@ -83,6 +84,9 @@ def load_library() -> C.CDLL:
     lib.qvggt_rotate_smooth_quant_static_e2m3.argtypes = [vp, i, i, i, vp, vp, vp, i, vp, vp, vp, vp]
     lib.qvggt_e2m3_gemm_shifted.restype = i
     lib.qvggt_e2m3_gemm_shifted.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, vp, vp]
+    for fn in (lib.qvggt_gelu_rotate_smooth_quant, lib.qvggt_gelu_rotate_smooth_quant_e2m3):
+        fn.restype = i
+        fn.argtypes = [vp, i, i, i, vp, vp, vp, vp, vp]
     lib.qvggt_i8b_bytes.restype = C.c_size_t
     lib.qvggt_i8b_bytes.argtypes = [i, i]
     lib.qvggt_int8_to_blocks.restype = i
@@ -262,6 +266,18 @@ def qvggt_rotate_smooth_quant_static_e2m3(X, signs, inv_smooth, x_step, per_toke
 def qvggt_e2m3_gemm_shifted(Xf, x_scale, x_zero, Wf, w_scale, w_codesum, bias, M, N, K, Y, stream=None):
     _check(load_library().qvggt_e2m3_gemm_shifted(_ptr(Xf), _ptr(x_scale), _ptr(x_zero), _ptr(Wf), _ptr(w_scale), _ptr(w_codesum),
                                                   _ptr(bias), M, N, K, _ptr(Y), _stream(stream)), "qvggt_e2m3_gemm_shifted")
+
+
+def qvggt_gelu_rotate_smooth_quant(X, signs, inv_smooth, Xq, x_scale, stream=None):
+    M, K = X.shape
+    _check(load_library().qvggt_gelu_rotate_smooth_quant(_ptr(X), _dtype_code(X), M, K, _ptr(signs), _ptr(inv_smooth), _ptr(Xq),
+                                                         _ptr(x_scale), _stream(stream)), "qvggt_gelu_rotate_smooth_quant")
+
+
+def qvggt_gelu_rotate_smooth_quant_e2m3(X, signs, inv_smooth, Xf, x_scale, stream=None):
+    M, K = X.shape
+    _check(load_library().qvggt_gelu_rotate_smooth_quant_e2m3(_ptr(X), _dtype_code(X), M, K, _ptr(signs), _ptr(inv_smooth), _ptr(Xf),
+                                                              _ptr(x_scale), _stream(stream)), "qvggt_gelu_rotate_smooth_quant_e2m3")
 
 
 def qvggt_i8b_bytes(rows, K):

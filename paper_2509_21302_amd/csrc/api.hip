@@ -31,6 +31,8 @@ hipError_t run_rotate_quant_e2m3_shifted_mfma(const void *X, int rows, int K, co
                                               float *scale, float *zero, const float *step, int step_stride, hipStream_t stream);
 hipError_t run_e2m3_gemm_shifted(const uint8_t *Xf, const float *sx, const float *xzero, const uint8_t *Wf, const float *sw,
                                  const float *wsum, const void *bias, int M, int N, int K, void *Y, hipStream_t stream);
+hipError_t run_gelu_rotate_quant_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, uint8_t *out,
+                                      float *scale, bool e2m3, hipStream_t stream);
 hipError_t run_int8_to_blocks(const int8_t *src, int rows, int K, uint8_t *dst, hipStream_t stream);
 hipError_t run_rotate_quant_i8b_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, uint8_t *out,
                                      float *scale, int bits, hipStream_t stream);
@@ -343,6 +345,31 @@ int qvggt_rotate_smooth_quant_e2m3(const void *X, int x_dtype, int M, int K, con
     if (!aligned16(X) || !aligned16(Xf) || !aligned16(x_scale) || !aligned16(inv_smooth) || !aligned16(signs))
         return QVGGT_ERR_ALIGN;
     return hip_status(qvggt::run_rotate_quant_e2m3_mfma(X, M, K, signs, inv_smooth, Xf, x_scale, static_cast<hipStream_t>(stream)));
+}
+
+static int gelu_rotate_smooth_quant(const void *X, int x_dtype, int M, int K, const int8_t *signs, const float *inv_smooth,
+                                   uint8_t *out, float *x_scale, bool e2m3, void *stream)
+{
+    if (!valid_dtype(x_dtype)) return QVGGT_ERR_DTYPE;
+    if (M < 0 || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (!e2m3_direct(x_dtype, K)) return x_dtype == QVGGT_BF16 ? QVGGT_ERR_SHAPE : QVGGT_ERR_DTYPE;
+    if (M == 0) return QVGGT_OK;
+    if (!X || !out || !x_scale) return QVGGT_ERR_NULL;
+    if (!aligned16(X) || !aligned16(out) || !aligned16(x_scale) || !aligned16(inv_smooth) || !aligned16(signs))
+        return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_gelu_rotate_quant_mfma(X, M, K, signs, inv_smooth, out, x_scale, e2m3, static_cast<hipStream_t>(stream)));
+}
+
+int qvggt_gelu_rotate_smooth_quant(const void *X, int x_dtype, int M, int K, const int8_t *signs, const float *inv_smooth,
+                                   uint8_t *Xq, float *x_scale, void *stream)
+{
+    return gelu_rotate_smooth_quant(X, x_dtype, M, K, signs, inv_smooth, Xq, x_scale, false, stream);
+}
+
+int qvggt_gelu_rotate_smooth_quant_e2m3(const void *X, int x_dtype, int M, int K, const int8_t *signs, const float *inv_smooth,
+                                        uint8_t *Xf, float *x_scale, void *stream)
+{
+    return gelu_rotate_smooth_quant(X, x_dtype, M, K, signs, inv_smooth, Xf, x_scale, true, stream);
 }
 
 int qvggt_layernorm_rotate_smooth_quant_e2m3(const void *X, int x_dtype, int M, int K, const float *gamma, const float *beta,

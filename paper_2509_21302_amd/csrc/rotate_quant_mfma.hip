@@ -52,6 +52,21 @@ struct Cfg {
     static constexpr int SIGN_CLASSES = K / 512;             // distinct column chunks a lane loads
 };
 
+// GELU(x) = x Phi(x), Phi the standard normal distribution function.  Phi(-|x|) = erfc(|x| / sqrt 2) / 2 by the
+// rational-times-Gaussian approximation of Abramowitz & Stegun 7.1.26 (absolute error 1.5e-7 in erfc, the halves folded into
+// the coefficients), Phi(|x|) = 1 - Phi(-|x|): about 1e-7 relative on the result for x > -3, which is what the bf16 rounding
+// that follows needs; far in the negative tail, where the result is below 1e-6 in magnitude, only its order of magnitude holds.
+__device__ inline float gelu_f32(float x)
+{
+    const float t = __builtin_amdgcn_rcpf(fmaf(fabsf(x), 0.3275911f * 0.70710678f, 1.0f));
+    float p = fmaf(t, 0.5f * 1.061405429f, 0.5f * -1.453152027f);
+    p = fmaf(t, p, 0.5f * 1.421413741f);
+    p = fmaf(t, p, 0.5f * -0.284496736f);
+    p = fmaf(t, p, 0.5f * 0.254829592f);
+    const float q = p * t * __builtin_amdgcn_exp2f(x * x * (-0.5f * 1.44269504f));
+    return x * (x < 0.0f ? q : 1.0f - q);
+}
+
 // MFMA row of segment `seg` (= tk * HB + hb) of a tile, without the two lowest hb bits
 // (those are m bits 0 and 1 and come from the lane at run time).
 template <int K>
@@ -81,7 +96,9 @@ __host__ __device__ constexpr int row_of_seg_hi(int seg_hi /* seg >> 2 */)
 // the nibbles hold u - 8 (u the unsigned code), i.e. the signed values the integer GEMM multiplies
 // BLK8 (CB = 8): the int8 codes go out as "int8 blocks", the operand format of the blocked int8 GEMM: K-tile kt (64 codes) of row r at
 // ((r / 128) * (K / 64) + kt) * 8192 + (r % 128) * 64, its 16-byte chunk ch in slot ch ^ ((r % 16) >> 2)
-template <int K, int PF, int OCC, bool STATIC, int CB, bool LN = false, bool ASYM = false, bool BLK8 = false>
+// GELU: the activation between fc1 and fc2 applied to every loaded value (fp32, result rounded to bf16 as a separate activation
+// kernel would hand it on) before anything else: X is fc1's output as stored, the kernel is fc2's kernel 1
+template <int K, int PF, int OCC, bool STATIC, int CB, bool LN = false, bool ASYM = false, bool BLK8 = false, bool GELU = false>
 __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint16_t *__restrict__ X, int rows,
                                                                    const int8_t *__restrict__ signs,
                                                                    const float *__restrict__ mul, int mul_mode,
@@ -246,6 +263,17 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
         for (int nt = 0; nt < 4; ++nt) cmax[h][nt] = 0.0f;
 
     for (; (BLOCK_FLUSH ? tile - wave_in_block : tile) < ntiles; tile += nwaves) {
+        if constexpr (GELU) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint4 v = G[0][j];
+                uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int d = 0; d < 4; ++d)
+                    w[d] = pack_bf16x2(rq::gelu_f32(__uint_as_float(w[d] << 16)), rq::gelu_f32(__uint_as_float(w[d] & 0xFFFF0000u)));
+                G[0][j] = make_uint4(w[0], w[1], w[2], w[3]);
+            }
+        }
         if constexpr (LN) {
             // every token of the tile: mean, variance (two passes over the registers), normalise, scale / shift, back to bf16
 #pragma unroll
@@ -644,6 +672,28 @@ hipError_t run_rotate_quant_asym_mfma(const void *X, int rows, int K, const int8
         default: return hipErrorInvalidValue;
     }
 #undef RQA
+    return hipGetLastError();
+}
+
+// GELU + rotation + smoothing + per-token 4-bit codes, packed rows (e2m3 = false) or E2M3 blocks, bf16 rows, K = 1024 / 2048 / 4096
+hipError_t run_gelu_rotate_quant_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, uint8_t *out,
+                                      float *scale, bool e2m3, hipStream_t stream)
+{
+    if (rows <= 0) return hipSuccess;
+    const uint16_t *x = reinterpret_cast<const uint16_t *>(X);
+    const int tok = 32 / (K / 128);
+    const int ntiles = (rows + tok - 1) / tok;
+    int blocks = (ntiles + rq::WAVES_PER_BLOCK - 1) / rq::WAVES_PER_BLOCK;
+    if (blocks > 256 * 2) blocks = 256 * 2;
+    const LnParams no_ln{nullptr, nullptr, 0.0f, 0};
+#define RQG(KK, CB) rotate_quant_mfma_kernel<KK, 1, 2, false, CB, false, false, false, true><<<blocks, 256, 0, stream>>>(x, rows, signs, mul, 0, out, scale, nullptr, 0, 7.0f, nullptr, no_ln, nullptr)
+    switch (K) {
+        case 1024: if (e2m3) RQG(1024, 6); else RQG(1024, 4); break;
+        case 2048: if (e2m3) RQG(2048, 6); else RQG(2048, 4); break;
+        case 4096: if (e2m3) RQG(4096, 6); else RQG(4096, 4); break;
+        default: return hipErrorInvalidValue;
+    }
+#undef RQG
     return hipGetLastError();
 }
 

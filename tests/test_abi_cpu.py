@@ -146,6 +146,11 @@ def test_argument_validation_needs_no_gpu():
     assert le(P, 0, 100, 32, 1024, None, None, P, P, None, P, P, need6 - 1, None) == WORKSPACE
     assert le(P, 0, 100, 32, 768, None, None, P, P, None, P, P, need6, None) == SHAPE
     assert le(P, 1, 100, 32, 1024, None, None, P, P, None, P, P, need6, None) == DTYPE
+    # GELU fused into kernel 1: bf16, K = 1024 / 2048 / 4096 only
+    for ge in (lib.qvggt_gelu_rotate_smooth_quant, lib.qvggt_gelu_rotate_smooth_quant_e2m3):
+        assert ge(P, 0, 4, 512, None, None, P, P, None) == SHAPE and ge(P, 1, 4, 1024, None, None, P, P, None) == DTYPE
+        assert ge(P, 0, 4, 1024, None, None, None, P, None) == NULL and ge(P, 0, 4, 1024, None, None, P, P + 4, None) == ALIGN
+        assert ge(None, 0, 0, 1024, None, None, None, None, None) == OK
     # int8 blocks: format size, converter, direct kernel 1 (bf16, K = 1024 / 2048 / 4096 only), GEMM, whole path
     assert q.qvggt_i8b_bytes(1, 1024) == 128 * 1024 and q.qvggt_i8b_bytes(129, 4096) == 256 * 4096 and q.qvggt_i8b_bytes(5, 1000) == 0
     tb, rb, gb, lb = lib.qvggt_int8_to_blocks, lib.qvggt_rotate_smooth_quant_i8b, lib.qvggt_i8b_gemm, lib.qvggt_linear_i8b

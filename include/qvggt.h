@@ -171,6 +171,11 @@ int qvggt_gelu_rotate_smooth_quant(const void *X, int x_dtype, int M, int K, con
                                    uint8_t *Xq, float *x_scale, void *stream);
 int qvggt_gelu_rotate_smooth_quant_e2m3(const void *X, int x_dtype, int M, int K, const int8_t *signs,
                                         const float *inv_smooth, uint8_t *Xf, float *x_scale, void *stream);
+/* Y = GELU(X) W^T + b on the E2M3 path: qvggt_gelu_rotate_smooth_quant_e2m3 into the workspace, then qvggt_e2m3_gemm, on one
+ * stream; arguments, workspace (qvggt_workspace_bytes_e2m3) and errors as qvggt_linear_e2m3 below. */
+int qvggt_gelu_linear_e2m3(const void *X, int x_dtype, int M, int N, int K, const int8_t *signs, const float *inv_smooth,
+                           const uint8_t *Wf, const float *w_scale, const void *bias, void *Y, void *workspace,
+                           size_t workspace_bytes, void *stream);
 
 /*
  * Online kernel 2 (Sec. 3.2 granularity paragraph: integer sum, dequantise after it):

@@ -21,7 +21,7 @@ EXPORTS = [
     "qvggt_e2m3_bytes", "qvggt_codes_to_e2m3", "qvggt_e2m3_gemm",
     "qvggt_rotate_smooth_quant_e2m3", "qvggt_workspace_bytes_e2m3", "qvggt_linear_e2m3",
     "qvggt_layernorm_rotate_smooth_quant_e2m3",
-    "qvggt_gelu_rotate_smooth_quant", "qvggt_gelu_rotate_smooth_quant_e2m3",
+    "qvggt_gelu_rotate_smooth_quant", "qvggt_gelu_rotate_smooth_quant_e2m3", "qvggt_gelu_linear_e2m3",
     "qvggt_i8b_bytes", "qvggt_int8_to_blocks", "qvggt_rotate_smooth_quant_i8b", "qvggt_i8b_gemm", "qvggt_workspace_bytes_i8b",
     "qvggt_linear_i8b",
     "qvggt_rotate_smooth_quant_asym_e2m3", "qvggt_rotate_smooth_quant_static_e2m3", "qvggt_e2m3_gemm_shifted",
@@ -101,6 +101,8 @@ def load_library() -> C.CDLL:
     lib.qvggt_linear_i8b.argtypes = [vp, i, i, i, i, vp, vp, i, vp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.qvggt_workspace_bytes_e2m3.restype = C.c_size_t
     lib.qvggt_workspace_bytes_e2m3.argtypes = [i, i, i]
+    lib.qvggt_gelu_linear_e2m3.restype = i
+    lib.qvggt_gelu_linear_e2m3.argtypes = [vp, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.qvggt_linear_e2m3.restype = i
     lib.qvggt_linear_e2m3.argtypes = [vp, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.qvggt_e2m3_bytes.restype = C.c_size_t
@@ -313,6 +315,14 @@ def qvggt_linear_i8b(X, signs, inv_smooth, bits, Wb, w_scale, bias, Y, workspace
 
 def qvggt_workspace_bytes_e2m3(M, N, K):
     return int(load_library().qvggt_workspace_bytes_e2m3(M, N, K))
+
+
+def qvggt_gelu_linear_e2m3(X, signs, inv_smooth, Wf, w_scale, bias, Y, workspace, stream=None):
+    M, K = X.shape
+    N = Y.shape[1]
+    _check(load_library().qvggt_gelu_linear_e2m3(_ptr(X), _dtype_code(X), M, N, K, _ptr(signs), _ptr(inv_smooth), _ptr(Wf),
+                                                 _ptr(w_scale), _ptr(bias), _ptr(Y), _ptr(workspace),
+                                                 workspace.numel() * workspace.element_size(), _stream(stream)), "qvggt_gelu_linear_e2m3")
 
 
 def qvggt_linear_e2m3(X, signs, inv_smooth, Wf, w_scale, bias, Y, workspace, stream=None):

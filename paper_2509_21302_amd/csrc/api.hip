@@ -439,7 +439,7 @@ size_t qvggt_workspace_bytes_e2m3(int M, int N, int K)
     return round_up(qvggt_e2m3_bytes(M, K), 256) + round_up((size_t)M * sizeof(float), 256);
 }
 
-int qvggt_linear_e2m3(const void *X, int x_dtype, int M, int N, int K, const int8_t *signs, const float *inv_smooth,
+static int linear_e2m3(bool gelu, const void *X, int x_dtype, int M, int N, int K, const int8_t *signs, const float *inv_smooth,
                       const uint8_t *Wf, const float *w_scale, const void *bias, void *Y, void *workspace,
                       size_t workspace_bytes, void *stream)
 {
@@ -455,9 +455,24 @@ int qvggt_linear_e2m3(const void *X, int x_dtype, int M, int N, int K, const int
     uint8_t *Xf = static_cast<uint8_t *>(workspace);
     float *x_scale = reinterpret_cast<float *>(Xf + round_up(qvggt_e2m3_bytes(M, K), 256));
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = qvggt::run_rotate_quant_e2m3_mfma(X, M, K, signs, inv_smooth, Xf, x_scale, s);
+    hipError_t e = gelu ? qvggt::run_gelu_rotate_quant_mfma(X, M, K, signs, inv_smooth, Xf, x_scale, true, s)
+                        : qvggt::run_rotate_quant_e2m3_mfma(X, M, K, signs, inv_smooth, Xf, x_scale, s);
     if (e != hipSuccess) return QVGGT_ERR_HIP;
     return hip_status(qvggt::run_e2m3_gemm(Xf, x_scale, Wf, w_scale, bias, M, N, K, Y, nullptr, s));
+}
+
+int qvggt_linear_e2m3(const void *X, int x_dtype, int M, int N, int K, const int8_t *signs, const float *inv_smooth,
+                      const uint8_t *Wf, const float *w_scale, const void *bias, void *Y, void *workspace,
+                      size_t workspace_bytes, void *stream)
+{
+    return linear_e2m3(false, X, x_dtype, M, N, K, signs, inv_smooth, Wf, w_scale, bias, Y, workspace, workspace_bytes, stream);
+}
+
+int qvggt_gelu_linear_e2m3(const void *X, int x_dtype, int M, int N, int K, const int8_t *signs, const float *inv_smooth,
+                           const uint8_t *Wf, const float *w_scale, const void *bias, void *Y, void *workspace,
+                           size_t workspace_bytes, void *stream)
+{
+    return linear_e2m3(true, X, x_dtype, M, N, K, signs, inv_smooth, Wf, w_scale, bias, Y, workspace, workspace_bytes, stream);
 }
 
 int qvggt_e2m3_gemm(const uint8_t *Xf, const float *x_scale, const uint8_t *Wf, const float *w_scale, const void *bias,

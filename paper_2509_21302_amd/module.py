@@ -22,11 +22,15 @@ class DsfqLinear:
 
     def __init__(self, weight: torch.Tensor, bias: Optional[torch.Tensor] = None, signs: Optional[torch.Tensor] = None,
                  calibration: Optional[torch.Tensor] = None, alpha: float = 0.5, bits: int = 4,
-                 act_bits: Optional[int] = None):
+                 act_bits: Optional[int] = None, pre_gelu: bool = False):
         act_bits = bits if act_bits is None else act_bits
         if not 4 <= bits <= 8 or not 4 <= act_bits <= 8:
             raise ValueError("bits and act_bits must be in 4..8")
         self.N, self.K = weight.shape
+        # pre_gelu: the layer computes GELU(X) W^T + b, the activation applied as X is read (fc2 of an MLP block fed with fc1's output)
+        if pre_gelu and not (bits == 4 and act_bits == 4 and self.K in (1024, 2048, 4096)):
+            raise ValueError("pre_gelu needs the 4-bit setting and K = 1024, 2048 or 4096")
+        self.pre_gelu = pre_gelu
         self.bits, self.act_bits, self.bias, self.signs = bits, act_bits, bias, signs
         self.packed = bits == 4 and act_bits == 4            # both 4-bit: two codes per byte; otherwise int8 codes
         dev = weight.device
@@ -69,7 +73,11 @@ class DsfqLinear:
         M = X.shape[0]
         Y = out if out is not None else torch.empty(M, self.N, dtype=torch.bfloat16, device=X.device)
         ws = self._workspace(M, X.device)
-        if self.packed and self.Wf is not None and X.dtype == torch.bfloat16:
+        if self.pre_gelu:
+            if X.dtype != torch.bfloat16:
+                raise ValueError("pre_gelu needs bf16 input")
+            q.qvggt_gelu_linear_e2m3(X, self.signs, self.inv_smooth, self.Wf, self.w_scale, self.bias, Y, ws)
+        elif self.packed and self.Wf is not None and X.dtype == torch.bfloat16:
             q.qvggt_linear_e2m3(X, self.signs, self.inv_smooth, self.Wf, self.w_scale, self.bias, Y, ws)      # same Y, bit for bit
         elif self.packed:
             q.qvggt_linear(X, self.signs, self.inv_smooth, self.Wq, self.w_scale, self.bias, Y, ws)

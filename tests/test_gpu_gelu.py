@@ -115,6 +115,14 @@ def test_mlp_chain_without_an_activation_pass():
     G.q.qvggt_gelu_rotate_smooth_quant_e2m3(hd, g2["signs"], g2["inv"], Xf, sx)
     Y = torch.empty(M, s2.N, dtype=torch.bfloat16, device=G.DEV)
     G.q.qvggt_e2m3_gemm(Xf, sx, Wf, g2["sw"], G.to_dev(b2), M, s2.N, s2.K, Y, None)
+    # the whole-path entry point and the convenience object run the same two kernels
+    ws = torch.empty(G.q.qvggt_workspace_bytes_e2m3(M, s2.N, s2.K), dtype=torch.uint8, device=G.DEV)
+    Yl = torch.full_like(Y, float("nan"))
+    G.q.qvggt_gelu_linear_e2m3(hd, g2["signs"], g2["inv"], Wf, g2["sw"], G.to_dev(b2), Yl, ws)
+    assert torch.equal(Y, Yl)
+    import paper_2509_21302_amd as q
+    layer = q.DsfqLinear(G.to_dev(W2), G.to_dev(b2), G.to_dev(signs2), cal, alpha=0.5, bits=4, pre_gelu=True)
+    assert torch.equal(layer(hd), Y)
     err = G.rel_fro(G.bf16_bits(Y), want.Y)
     assert err <= 3 * G.Y_REL_FRO, err      # two quantized layers in sequence, as in the chain with a separate activation pass
     # and the fused kernel equals the unfused sequence on the GPU's own fc1 output up to the bf16 rounding flips of the activation

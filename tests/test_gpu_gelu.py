@@ -129,3 +129,38 @@ def test_mlp_chain_without_an_activation_pass():
     actd = torch.nn.functional.gelu(hd.float()).to(torch.bfloat16)
     Y2 = G.gpu_linear(actd, g2, G.to_dev(b2))
     assert G.rel_fro(G.bf16_bits(Y), G.bf16_bits(Y2)) <= G.Y_REL_FRO
+
+
+def test_gelu_rotate_quant_full_size():
+    """137400 x 4096 (fc2 of the benchmark's config, its synthetic input standing in for fc1's output) in the launch configuration
+    bench.py times: a seeded sample of rows against the oracle, and the E2M3 output against the packed one through the GEMM
+    (equal codes give equal sums, whatever sign a zero carries)."""
+    s = synth.layer_spec(5, "fc2")
+    rng = np.random.default_rng(58)
+    rows = np.unique(np.concatenate([np.arange(synth.SPECIAL_TOKENS), np.arange(s.M - 64, s.M), rng.choice(s.M, 250, replace=False)]))
+    signs = synth.make_signs(s)
+    inv = (1.0 / (np.sqrt(s.K) * np.exp(rng.uniform(-1, 1, s.K)))).astype(np.float32)
+    X = synth.make_activation_frames(s)
+    Xd, sd, invd = G.to_dev(X), G.to_dev(signs), G.to_dev(inv)
+    Xs = X[rows]
+    del X
+    dx, qx, _ = oracle.rotate_smooth_quant(oracle.gelu(Xs), 1.0 / (inv.astype(np.float64) * np.sqrt(s.K)), pre_signs=signs)
+    Xq, sx = _gpu_gelu_rsq(Xd, sd, invd)
+    idx = torch.from_numpy(rows).to(G.DEV)
+    _check(G.gpu_unpack(Xq[idx].contiguous(), s.K), sx[idx].cpu().numpy().astype(np.float64), qx, dx, "full size")
+    Xf = torch.empty(G.q.qvggt_e2m3_bytes(s.M, s.K), dtype=torch.uint8, device=G.DEV)
+    sxf = torch.empty_like(sx)
+    G.q.qvggt_gelu_rotate_smooth_quant_e2m3(Xd, sd, invd, Xf, sxf)
+    assert torch.equal(sx, sxf)
+    del Xd
+    N = 256
+    Wq = torch.from_numpy(rng.integers(0, 256, (N, s.K // 2)).astype(np.uint8)).to(G.DEV)
+    Wf = torch.empty(G.q.qvggt_e2m3_bytes(N, s.K), dtype=torch.uint8, device=G.DEV)
+    G.q.qvggt_codes_to_e2m3(Wq, N, s.K, Wf)
+    sw = torch.full((N,), 1e-3, dtype=torch.float32, device=G.DEV)
+    Y1 = torch.empty(s.M, N, dtype=torch.bfloat16, device=G.DEV)
+    G.q.qvggt_e2m3_gemm(Xf, sx, Wf, sw, None, s.M, N, s.K, Y1, None)
+    G.q.qvggt_codes_to_e2m3(Xq, s.M, s.K, Xf)
+    Y2 = torch.empty_like(Y1)
+    G.q.qvggt_e2m3_gemm(Xf, sx, Wf, sw, None, s.M, N, s.K, Y2, None)
+    assert torch.equal(Y1, Y2)

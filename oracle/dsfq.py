@@ -227,6 +227,22 @@ def prepare_weights(W, act_absmax_rot=None, pre_signs=None, post_signs=None, alp
     return PreparedWeights(qw, dw, c_hat, w_colmax, Ws)
 
 
+def prepare_weights_given(W, c_hat=None, w_step=None, pre_signs=None, post_signs=None, bits: int = 4) -> PreparedWeights:
+    """Offline half with the calibrated parameters handed in (appendix, implementation details: the channel-wise factor
+    c_hat and the quantization steps are learnable during calibration; what is deployed afterwards is this): rotate W,
+    scale column j by the given c_hat[j] (None: 1), and quantize output channel o with the given step w_step[o], codes
+    clamped to the signed range (None: the channel's own absmax step, as prepare_weights)."""
+    Wr = rotate(to_f64(W), pre_signs, post_signs)
+    c = np.ones(Wr.shape[1], dtype=np.float64) if c_hat is None else _f64(c_hat)
+    Ws = scale_columns(Wr, c, inverse=False)
+    if w_step is None:
+        dw, qw = quantize_rows(Ws, bits)
+    else:
+        dw = _f64(w_step).copy()
+        qw = quantize_rows_static(Ws, dw, bits)
+    return PreparedWeights(qw, dw, c, col_absmax(Wr), Ws)
+
+
 def rotated_col_absmax(X_cal, pre_signs=None, post_signs=None) -> np.ndarray:
     return col_absmax(rotate(to_f64(X_cal), pre_signs, post_signs))
 

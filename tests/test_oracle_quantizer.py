@@ -256,6 +256,38 @@ def test_layernorm_closed_forms_and_library():
     assert np.all(np.abs(r - t) <= np.abs(t) * 2.0 ** -8 + 1e-40) and np.abs(r - t).max() > 0
 
 
+def test_prepare_weights_given_hand_worked_and_reductions():
+    """Given factor and steps: a K = 4 layer worked by hand with the Hadamard matrix written out, and the two reductions to
+    already pinned routines (factor and steps taken from prepare_weights reproduce it; no factor, no steps = rotation only)."""
+    H4 = np.array([[1, 1, 1, 1], [1, -1, 1, -1], [1, 1, -1, -1], [1, -1, -1, 1]], dtype=np.float64) / 2.0
+    W = np.array([[1.0, 2.0, 3.0, 4.0], [0.5, -0.5, 0.25, 8.0]])
+    c = np.array([1.0, 3.0, 0.5, 4.0])
+    step = np.array([0.5, 1.0])
+    # rows of W H: [5, -1, -2, 0] and [4.125, -3.375, -4.125, 4.375]; times c: [5, -3, -1, 0], [4.125, -10.125, -2.0625, 17.5]
+    assert np.allclose(W @ H4, [[5, -1, -2, 0], [4.125, -3.375, -4.125, 4.375]], atol=1e-15)
+    p = oracle.prepare_weights_given(W, c, step)
+    # / step: [10, -6, -2, 0] -> clamp to 7;  [4.125, -10.125, -2.0625, 17.5] -> 4, clamp to -8, -2, clamp to 7
+    assert p.qw.tolist() == [[7, -6, -2, 0], [4, -8, -2, 7]] and p.dw.tolist() == [0.5, 1.0]
+    assert np.allclose(p.Ws, [[5, -3, -1, 0], [4.125, -10.125, -2.0625, 17.5]], atol=1e-15)
+    q = oracle.prepare_weights_given(W, c, None)          # own steps: absmax / 7 of each smoothed row = 5 / 7 and 2.5
+    assert np.allclose(q.dw, [5 / 7, 2.5], rtol=1e-15) and q.qw.tolist() == [[7, -4, -1, 0], [2, -4, -1, 7]]
+    rng = np.random.default_rng(8)
+    Wb = rng.standard_normal((24, 256))
+    signs = (rng.integers(0, 2, 256) * 2 - 1).astype(np.int8)
+    a = np.exp(rng.uniform(-2, 2, 256))
+    ref = oracle.prepare_weights(Wb, a, pre_signs=signs, alpha=0.5)
+    got = oracle.prepare_weights_given(Wb, ref.c_hat, ref.dw, pre_signs=signs)
+    assert np.array_equal(got.qw, ref.qw) and np.array_equal(got.dw, ref.dw)
+    plain = oracle.prepare_weights_given(Wb, None, None, pre_signs=signs)
+    ref0 = oracle.prepare_weights(Wb, None, pre_signs=signs)
+    assert np.array_equal(plain.qw, ref0.qw) and np.array_equal(plain.dw, ref0.dw)
+    # a smaller step than the channel's own makes the clamp live, a larger one leaves the top codes unused
+    tight = oracle.prepare_weights_given(Wb, ref.c_hat, 0.5 * ref.dw, pre_signs=signs)
+    assert (tight.qw == 7).sum() > (ref.qw == 7).sum() and (tight.qw == -8).any()
+    loose = oracle.prepare_weights_given(Wb, ref.c_hat, 2.0 * ref.dw, pre_signs=signs)
+    assert np.abs(loose.qw).max() <= 4
+
+
 def test_gelu_against_the_integral_and_closed_forms():
     """GELU(x) = x Phi(x): Phi from a quadrature of the normal density (no error function involved), the odd-part identity
     GELU(x) - GELU(-x) = x, printed values of Phi, the library routine in float64, and the bf16 rounding."""

@@ -92,6 +92,20 @@ int qvggt_prep_weights(const void *W, int w_dtype, int N, int K, const float *ac
                        float *inv_smooth, void *stream);
 
 /*
+ * Offline half with calibrated parameters handed in (appendix, implementation details: the channel-wise factor and the
+ * quantization steps are learnable during calibration; this is what deploys the learned values, the activation side being
+ * qvggt_rotate_smooth_quant_static):
+ *     Ws = W H diag(c_hat);  Wq[o, :] = clamp(rne(Ws[o, :] / w_step[o]), -2^(bits-1), 2^(bits-1) - 1);  w_scale = w_step
+ * c_hat: f32 [K], positive and finite (not checked), or NULL for 1.  w_step: f32 [N], positive, or NULL for each channel's
+ * own step max_j |Ws[o, j]| / (2^(bits-1) - 1) as in qvggt_prep_weights.  bits: 4 writes packed Wq [N, K/2] (for
+ * qvggt_w4a4_gemm and, through qvggt_codes_to_e2m3, qvggt_e2m3_gemm: that conversion saturates a code -8 to -7, so keep
+ * w_step at or above the channel's own step there); 5..8 write int8 Wq [N, K] (for qvggt_i8_gemm).  QVGGT_ERR_ARG for other
+ * bits.  Outputs as qvggt_prep_weights; inv_smooth[j] = 1 / (sqrt(K) c_hat[j]).
+ */
+int qvggt_prep_weights_given(const void *W, int w_dtype, int N, int K, const float *c_hat, const int8_t *signs,
+                             const float *w_step, int bits, void *Wq, float *w_scale, float *inv_smooth, void *stream);
+
+/*
  * Online kernel 1 (Sec. 3.2 rotation + smoothing; Sec. 3.1.2 quantizer, per token, dynamic):
  *     z[t, :] = (X[t, :] diag(signs) Hadamard_K) * inv_smooth;   x_scale[t] = max_j |z[t, j]| / 7;
  *     Xq[t, j] = clamp(rne(z[t, j] / x_scale[t]), -8, 7)

@@ -21,7 +21,7 @@ EXPORTS = [
     "qvggt_e2m3_bytes", "qvggt_codes_to_e2m3", "qvggt_e2m3_gemm",
     "qvggt_rotate_smooth_quant_e2m3", "qvggt_workspace_bytes_e2m3", "qvggt_linear_e2m3",
     "qvggt_layernorm_rotate_smooth_quant_e2m3",
-    "qvggt_gelu_rotate_smooth_quant", "qvggt_gelu_rotate_smooth_quant_e2m3", "qvggt_gelu_linear_e2m3",
+    "qvggt_prep_weights_given", "qvggt_gelu_rotate_smooth_quant", "qvggt_gelu_rotate_smooth_quant_e2m3", "qvggt_gelu_linear_e2m3",
     "qvggt_i8b_bytes", "qvggt_int8_to_blocks", "qvggt_rotate_smooth_quant_i8b", "qvggt_i8b_gemm", "qvggt_workspace_bytes_i8b",
     "qvggt_linear_i8b",
     "qvggt_rotate_smooth_quant_asym_e2m3", "qvggt_rotate_smooth_quant_static_e2m3", "qvggt_e2m3_gemm_shifted",
@@ -115,6 +115,8 @@ def load_library() -> C.CDLL:
     lib.qvggt_w4a4_gemm.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp, vp, vp]
     lib.qvggt_linear.restype = i
     lib.qvggt_linear.argtypes = [vp, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.qvggt_prep_weights_given.restype = i
+    lib.qvggt_prep_weights_given.argtypes = [vp, i, i, i, vp, vp, vp, i, vp, vp, vp, vp]
     lib.qvggt_prep_weights_i8.restype = i
     lib.qvggt_prep_weights_i8.argtypes = [vp, i, i, i, vp, vp, f, i, vp, vp, vp, vp]
     lib.qvggt_rotate_smooth_quant_i8.restype = i
@@ -374,6 +376,13 @@ def qvggt_unpack_int4(packed, codes, stream=None):
 
 
 # ---- the 8-bit / 6-bit settings: int8 codes
+def qvggt_prep_weights_given(W, c_hat, signs, w_step, bits, Wq, w_scale, inv_smooth, stream=None):
+    N, K = W.shape
+    _check(load_library().qvggt_prep_weights_given(_ptr(W), _dtype_code(W), N, K, _ptr(c_hat), _ptr(signs), _ptr(w_step), int(bits),
+                                                   _ptr(Wq), _ptr(w_scale), _ptr(inv_smooth), _stream(stream)),
+           "qvggt_prep_weights_given")
+
+
 def qvggt_prep_weights_i8(W, act_absmax_rot, signs, alpha, bits, Wq, w_scale, inv_smooth, stream=None):
     N, K = W.shape
     _check(load_library().qvggt_prep_weights_i8(_ptr(W), _dtype_code(W), N, K, _ptr(act_absmax_rot), _ptr(signs),

@@ -12,6 +12,7 @@ hipError_t run_rotate_smooth_quant(const void *X, bool f32, int rows, int K, con
 hipError_t run_rotated_col_absmax(const void *X, bool f32, int rows, int K, const int8_t *signs, float *absmax,
                                   hipStream_t stream);
 hipError_t run_smooth_factor(float *buf, const float *act_absmax, int K, float alpha, hipStream_t stream);
+hipError_t run_inv_from_factor(float *buf, const float *c, int K, hipStream_t stream);
 hipError_t run_fill_f32(float *p, int n, float v, hipStream_t stream);
 hipError_t run_pack_int4(const int8_t *codes, int rows, int K, uint8_t *packed, hipStream_t stream);
 hipError_t run_unpack_int4(const uint8_t *packed, int rows, int K, int8_t *codes, hipStream_t stream);
@@ -130,6 +131,25 @@ int qvggt_prep_weights(const void *W, int w_dtype, int N, int K, const float *ac
                        float alpha, uint8_t *Wq, float *w_scale, float *inv_smooth, void *stream)
 {
     return prep_weights(W, w_dtype, N, K, act_absmax_rot, signs, alpha, 4, Wq, w_scale, inv_smooth, stream);
+}
+
+int qvggt_prep_weights_given(const void *W, int w_dtype, int N, int K, const float *c_hat, const int8_t *signs, const float *w_step,
+                             int bits, void *Wq, float *w_scale, float *inv_smooth, void *stream)
+{
+    if (!valid_dtype(w_dtype)) return QVGGT_ERR_DTYPE;
+    if (!valid_n(N) || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (!valid_wide_bits(bits)) return QVGGT_ERR_ARG;
+    if (!W || !Wq || !w_scale || !inv_smooth) return QVGGT_ERR_NULL;
+    if (!aligned16(W) || !aligned16(Wq) || !aligned16(w_scale) || !aligned16(inv_smooth) || !aligned16(c_hat) || !aligned16(signs) ||
+        !aligned16(w_step))
+        return QVGGT_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = c_hat ? qvggt::run_inv_from_factor(inv_smooth, c_hat, K, s)
+                         : qvggt::run_fill_f32(inv_smooth, K, 1.0f / std::sqrt((float)K), s);
+    if (e != hipSuccess) return QVGGT_ERR_HIP;
+    // the same kernel as qvggt_prep_weights, with the steps given (clamp live) when w_step is not NULL
+    return hip_status(qvggt::run_rotate_smooth_quant(W, w_dtype == QVGGT_F32, N, K, signs, inv_smooth, 1, static_cast<uint8_t *>(Wq),
+                                                     w_scale, w_step, 1, bits == 4 ? 4 : qvggt::kInt8Container + bits, s));
 }
 
 int qvggt_prep_weights_i8(const void *W, int w_dtype, int N, int K, const float *act_absmax_rot, const int8_t *signs,

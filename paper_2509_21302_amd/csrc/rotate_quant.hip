@@ -294,6 +294,13 @@ __global__ void smooth_factor_kernel(float *buf, const float *__restrict__ act_a
     buf[j] = 1.0f / (sqrtf((float)K) * c);
 }
 
+// a given smoothing factor c[j] -> inv_smooth[j] = 1 / (sqrt(K) c_j)
+__global__ void inv_from_factor_kernel(float *buf, const float *__restrict__ c, int K)
+{
+    int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < K) buf[j] = 1.0f / (sqrtf((float)K) * c[j]);
+}
+
 __global__ void fill_f32_kernel(float *p, int n, float v)
 {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -495,6 +502,12 @@ hipError_t run_rotated_col_absmax(const void *X, bool f32, int rows, int K, cons
 hipError_t run_smooth_factor(float *buf, const float *act_absmax, int K, float alpha, hipStream_t stream)
 {
     smooth_factor_kernel<<<(K + 255) / 256, 256, 0, stream>>>(buf, act_absmax, K, alpha);
+    return hipGetLastError();
+}
+
+hipError_t run_inv_from_factor(float *buf, const float *c, int K, hipStream_t stream)
+{
+    inv_from_factor_kernel<<<(K + 255) / 256, 256, 0, stream>>>(buf, c, K);
     return hipGetLastError();
 }
 

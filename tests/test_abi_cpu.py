@@ -146,6 +146,12 @@ def test_argument_validation_needs_no_gpu():
     assert le(P, 0, 100, 32, 1024, None, None, P, P, None, P, P, need6 - 1, None) == WORKSPACE
     assert le(P, 0, 100, 32, 768, None, None, P, P, None, P, P, need6, None) == SHAPE
     assert le(P, 1, 100, 32, 1024, None, None, P, P, None, P, P, need6, None) == DTYPE
+    # weight preparation with given factor and steps
+    pg = lib.qvggt_prep_weights_given
+    assert pg(P, 0, 24, 1024, None, None, None, 4, P, P, P, None) == SHAPE and pg(P, 3, 32, 1024, None, None, None, 4, P, P, P, None) == DTYPE
+    assert pg(P, 0, 32, 1024, None, None, None, 3, P, P, P, None) == ARG and pg(P, 0, 32, 1024, None, None, None, 9, P, P, P, None) == ARG
+    assert pg(P, 0, 32, 1024, None, None, None, 4, None, P, P, None) == NULL and pg(P, 0, 32, 1024, P + 4, None, None, 4, P, P, P, None) == ALIGN
+    assert pg(P, 0, 32, 1024, None, None, P + 8, 4, P, P, P, None) == ALIGN
     # GELU fused into kernel 1: bf16, K = 1024 / 2048 / 4096 only
     for ge in (lib.qvggt_gelu_rotate_smooth_quant, lib.qvggt_gelu_rotate_smooth_quant_e2m3):
         assert ge(P, 0, 4, 512, None, None, P, P, None) == SHAPE and ge(P, 1, 4, 1024, None, None, P, P, None) == DTYPE

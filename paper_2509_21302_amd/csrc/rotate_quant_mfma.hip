@@ -54,7 +54,7 @@ struct Cfg {
 
 // GELU(x) = x Phi(x), Phi the standard normal distribution function.  Phi(-|x|) = erfc(|x| / sqrt 2) / 2 by the
 // rational-times-Gaussian approximation of Abramowitz & Stegun 7.1.26 (absolute error 1.5e-7 in erfc, the halves folded into
-// the coefficients), Phi(|x|) = 1 - Phi(-|x|): about 1e-7 relative on the result for x > -3, which is what the bf16 rounding
+// the coefficients), Phi(|x|) = 1 - Phi(-|x|), inputs finite: about 1e-7 relative on the result for x > -3, which is what the bf16 rounding
 // that follows needs; far in the negative tail, where the result is below 1e-6 in magnitude, only its order of magnitude holds.
 __device__ inline float gelu_f32(float x)
 {
@@ -64,7 +64,7 @@ __device__ inline float gelu_f32(float x)
     p = fmaf(t, p, 0.5f * -0.284496736f);
     p = fmaf(t, p, 0.5f * 0.254829592f);
     const float q = p * t * __builtin_amdgcn_exp2f(x * x * (-0.5f * 1.44269504f));
-    return x * (x < 0.0f ? q : 1.0f - q);
+    return fmaf(-fabsf(x), q, fmaxf(x, 0.0f));        // x q for x < 0, x - x q otherwise
 }
 
 // MFMA row of segment `seg` (= tk * HB + hb) of a tile, without the two lowest hb bits

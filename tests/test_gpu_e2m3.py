@@ -21,24 +21,7 @@ def _e2m3(codes_np):
     return packed, out
 
 
-def _decode_e2m3_rows(buf, rows, K):
-    """E2M3 blocks -> value at every position of the packed row, from the format's definition: sign, 2 exponent bits (bias 1),
-    3 mantissa bits; exponent 0 is subnormal (m / 8).  Unit s of row r starts at ((r / 128) * (K / 64) + s) * 6144 + (r % 128) * 48."""
-    out = np.zeros((rows, K), dtype=np.float64)
-    r = np.arange(rows)
-    for s in range(K // 64):
-        start = ((r // 128) * (K // 64) + s) * 6144 + (r % 128) * 48
-        unit = buf[start[:, None] + np.arange(48)[None, :]]
-        for h in range(2):
-            blob = np.concatenate([unit[:, 16 * h: 16 * h + 16], unit[:, 32 + 8 * h: 40 + 8 * h]], axis=1)     # 24 bytes
-            bits = np.unpackbits(blob, axis=1, bitorder="little")                                            # [rows, 192]
-            for i in range(32):
-                f = bits[:, 6 * i: 6 * i + 6].astype(np.int64)
-                m = f[:, 0] + 2 * f[:, 1] + 4 * f[:, 2]
-                e = f[:, 3] + 2 * f[:, 4]
-                mag = np.where(e == 0, m / 8.0, 2.0 ** (e - 1) * (1 + m / 8.0))
-                out[:, 64 * s + 32 * h + i] = np.where(f[:, 5] == 1, -mag, mag)
-    return out
+_decode_e2m3_rows = G.decode_e2m3_rows
 
 
 def test_codes_to_e2m3_layout_and_values():

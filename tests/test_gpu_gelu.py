@@ -8,7 +8,6 @@ import oracle
 import synth
 from synth import f32_to_bf16_bits
 from tests import gpu_util as G
-from tests.test_gpu_e2m3 import _decode_e2m3_rows
 
 pytestmark = pytest.mark.gpu
 
@@ -67,7 +66,7 @@ def test_gelu_rotate_quant(K, rows):
     assert torch.equal(sx, sxf)
     conv = torch.full_like(Xf, 0xA5)
     G.q.qvggt_codes_to_e2m3(Xq, rows, K, conv)
-    assert np.array_equal(_decode_e2m3_rows(Xf.cpu().numpy(), rows, K), _decode_e2m3_rows(conv.cpu().numpy(), rows, K))
+    assert np.array_equal(G.decode_e2m3_rows(Xf.cpu().numpy(), rows, K), G.decode_e2m3_rows(conv.cpu().numpy(), rows, K))
 
 
 def test_gelu_rotate_quant_special_values():

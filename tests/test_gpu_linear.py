@@ -229,6 +229,52 @@ def test_linear_e2m3_under_hip_graph_capture():
         assert torch.equal(got, want), f"replay {rep}"
 
 
+@pytest.mark.parametrize("which", ["i8b", "gelu_e2m3"])
+def test_further_whole_path_entry_points_under_hip_graph_capture(which):
+    """The 8-bit path on blocked operands and the E2M3 path with the GELU applied on load, captured once and replayed on new
+    inputs with eager work in between: every replay equals the eager call on the same input."""
+    import paper_2509_21302_amd as q
+    s = synth.layer_spec(2)
+    bias = G.to_dev(synth.make_bias(s))
+    X0 = G.to_dev(synth.make_activation_frames(s))
+    if which == "i8b":
+        pg = G.gpu_prep_i8(synth.make_weights(s), synth.make_calibration(s), synth.make_signs(s), 8)
+        Wb = torch.empty(q.qvggt_i8b_bytes(s.N, s.K), dtype=torch.int8, device=G.DEV)
+        q.qvggt_int8_to_blocks(pg["Wq"], s.N, s.K, Wb)
+        need = q.qvggt_workspace_bytes_i8b(s.M, s.N, s.K)
+        call = lambda X, Y, ws: q.qvggt_linear_i8b(X, pg["signs"], pg["inv"], 8, Wb, pg["sw"], bias, Y, ws)
+    else:
+        pg = _gpu_prep(s)
+        Wf = torch.empty(q.qvggt_e2m3_bytes(s.N, s.K), dtype=torch.uint8, device=G.DEV)
+        q.qvggt_codes_to_e2m3(pg["Wq"], s.N, s.K, Wf)
+        need = q.qvggt_workspace_bytes_e2m3(s.M, s.N, s.K)
+        call = lambda X, Y, ws: q.qvggt_gelu_linear_e2m3(X, pg["signs"], pg["inv"], Wf, pg["sw"], bias, Y, ws)
+    Xbuf = X0.clone()
+    Y = torch.empty(s.M, s.N, dtype=torch.bfloat16, device=G.DEV)
+    ws, ws_eager = (torch.empty(need, dtype=torch.uint8, device=G.DEV) for _ in range(2))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                       # warm-up outside capture: first-call kernel attributes are set here
+        call(Xbuf, Y, ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call(Xbuf, Y, ws)
+    gen = torch.Generator(device=G.DEV).manual_seed(6)
+    for rep in range(3):
+        Xnew = (X0.float() * (0.5 + rep) + torch.randn(X0.shape, device=G.DEV, generator=gen) * 0.1 * rep).to(torch.bfloat16)
+        Xbuf.copy_(Xnew)
+        Y.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = Y.clone()
+        want = torch.empty_like(Y)
+        call(Xnew, want, ws_eager)
+        torch.cuda.synchronize()
+        assert torch.equal(got, want), f"replay {rep}"
+
+
 @pytest.mark.parametrize("bits", [4, 8])
 def test_convenience_object_matches_the_entry_points(bits):
     """DsfqLinear only allocates and forwards: same bits as calling the C ABI by hand, and oracle-close."""

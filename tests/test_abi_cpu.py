@@ -29,6 +29,18 @@ def test_library_exports_every_declared_symbol():
         assert getattr(lib, name).argtypes is not None, f"{name}: no argtypes in the binding"
 
 
+def test_header_is_plain_c():
+    """The boundary is a C header: no C++ or HIP types, nothing but <stddef.h> / <stdint.h>; a C99 compiler accepts it as it is."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c",
+                        os.path.join(ROOT, "include", "qvggt.h")], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+
+
 def test_status_strings():
     assert q.qvggt_status_string(0) == "QVGGT_OK"
     for s in range(1, 8):

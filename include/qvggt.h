@@ -298,7 +298,7 @@ int qvggt_layout_int8(const int8_t *src, int rows, int K, int8_t *dst, int to_li
  * global -> LDS transfer of the GEMM is contiguous in memory: rows grouped in blocks of 128 with the K-tiles of 64 codes
  * outermost, K-tile kt of row r at byte ((r / 128) * (K / 64) + kt) * 8192 + (r % 128) * 64, and inside it the 16-byte
  * chunk ch of the row's codes (library order) in slot ch ^ ((r % 16) >> 2).  A buffer holds ceil(rows / 128) * 128 rows:
- * qvggt_i8b_bytes(rows, K) bytes; the rows past `rows` are never written and may hold anything.  Same codes, same sums,
+ * qvggt_i8b_bytes(rows, K) bytes (0 for an unsupported K); the rows past `rows` are never written and may hold anything.  Same codes, same sums,
  * same Y as the qvggt_*_i8 entry points, bit for bit.
  * qvggt_int8_to_blocks:           int8 [rows, K] in library order (Xq or Wq of the _i8 entry points) -> int8 blocks.
  * qvggt_rotate_smooth_quant_i8b:  qvggt_rotate_smooth_quant_i8 writing int8 blocks; bf16 X, K = 1024, 2048 or 4096 only

@@ -492,7 +492,15 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
                     for (int i = 0; i < 3; ++i) {
                         const int j = i * 256 + (int)threadIdx.x, unit = j / 12, within = j - 12 * unit;     // 16-byte chunk j of 768
                         if (row4 + within / 3 < rows)
-                            *reinterpret_cast<uint4 *>(rb + (size_t)unit * 6144 + within * 16) = *reinterpret_cast<const uint4 *>(flush_all + j * 16);
+                        {
+                            // whole runs of 192 bytes, written past the caches: the 422 MB of a 137400-token launch would otherwise sit
+                            // there as dirty lines while the GEMM that follows runs (measured: that GEMM 365 -> 312 us, this kernel + 4 us);
+                            // the direct stores of the smaller K stay cached: their pieces are partial lines and their output fits the
+                            // memory-side cache, where the GEMM finds it
+                            const uint4 fv = *reinterpret_cast<const uint4 *>(flush_all + j * 16);
+                            const v4u nv = {fv.x, fv.y, fv.z, fv.w};
+                            __builtin_nontemporal_store(nv, reinterpret_cast<v4u *>(rb + (size_t)unit * 6144 + within * 16));
+                        }
                     }
                     __syncthreads();
                 }
@@ -536,8 +544,11 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
                             const int j = i * 256 + (int)threadIdx.x, kt = j / 16, within = j - 16 * kt;      // 16-byte chunk j of 1024
-                            if (row4 + within / 4 < rows)
-                                *reinterpret_cast<uint4 *>(rb + (size_t)kt * 8192 + within * 16) = *reinterpret_cast<const uint4 *>(flush_all + j * 16);
+                            if (row4 + within / 4 < rows) {
+                                const uint4 fv = *reinterpret_cast<const uint4 *>(flush_all + j * 16);
+                                const v4u nv = {fv.x, fv.y, fv.z, fv.w};
+                                __builtin_nontemporal_store(nv, reinterpret_cast<v4u *>(rb + (size_t)kt * 8192 + within * 16));     // as the 6-bit variant
+                            }
                         }
                         __syncthreads();
                     } else if (row < rows) {

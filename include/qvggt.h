@@ -14,12 +14,11 @@
  *
  * General conventions
  *   - Every pointer is a DEVICE pointer owned by the caller unless stated otherwise; the
- *     library allocates nothing, keeps no state between calls and is re-entrant.
+ *     library allocates nothing and is re-entrant.  The only thing it remembers between calls is
+ *     on which devices qvggt_init has run (see there).
  *   - Every call only enqueues kernels on `stream` (a hipStream_t passed as void*; NULL is
  *     the default stream) and returns; buffers must stay valid until the stream has run.
- *     Calls may be recorded into a HIP graph (stream capture).  The GEMM entry points raise their kernel's dynamic
- *     LDS limit the first time a tile configuration is used in a process (hipFuncSetAttribute, the only thing the
- *     library remembers): make one call with the same shapes outside the capture first.
+ *     Calls may be recorded into a HIP graph (stream capture) once qvggt_init has run on the device.
  *   - Matrices are dense row-major.  bf16 values are IEEE bfloat16 bit patterns (uint16).
  *   - K (input features, the Hadamard size) must be a power of two in [128, 8192], or one of the sizes
  *     2^n * m with a Paley matrix as the m-point factor (Sec. 3.2, H_d = H_{2^n} (x) H_m): m = 12: 768, 1536, 3072, 6144;
@@ -60,6 +59,15 @@ typedef enum { QVGGT_BF16 = 0, QVGGT_F32 = 1 } qvggt_dtype;
 
 /* Human-readable name of a status code (host pointer to a static string). */
 const char *qvggt_status_string(int status);
+
+/*
+ * Per-device set-up for the calling thread's current device: raises the dynamic-LDS limit of the library's GEMM kernels
+ * there (hipFuncSetAttribute; their tiles need up to 160 KB of LDS, more than a launch gets by default).  Enqueues nothing.
+ * Every entry point that launches such a kernel runs the same set-up by itself the first time it is used on a device, so
+ * calling qvggt_init is optional; call it once per device before recording calls into a HIP graph, so that the capture holds
+ * launches only.  Safe to call from several threads and more than once.  QVGGT_OK or QVGGT_ERR_HIP (no usable device).
+ */
+int qvggt_init(void);
 
 /*
  * Per-channel activation statistic of the smoothing factor, taken in rotated space
@@ -258,6 +266,7 @@ int qvggt_linear_e2m3(const void *X, int x_dtype, int M, int N, int K, const int
                       const uint8_t *Wf, const float *w_scale, const void *bias, void *Y, void *workspace,
                       size_t workspace_bytes, void *stream);
 int qvggt_codes_to_e2m3(const uint8_t *packed, int rows, int K, uint8_t *out, void *stream);
+
 int qvggt_e2m3_gemm(const uint8_t *Xf, const float *x_scale, const uint8_t *Wf, const float *w_scale,
                     const void *bias, int M, int N, int K, void *Y, int32_t *acc_debug, void *stream);
 

@@ -3,59 +3,12 @@
 The product is the C-ABI shared library libqvggt.so (declared in include/qvggt.h, built from
 csrc/ by build.py); `binding` is the thin ctypes layer with the same entry-point names.
 """
-from .binding import (  # noqa: F401
-    QvggtError,
-    lib_path,
-    load_library,
-    EXPORTS,
-    qvggt_status_string,
-    qvggt_rotated_col_absmax,
-    qvggt_prep_weights,
-    qvggt_rotate_smooth_quant,
-    qvggt_rotate_smooth_quant_static,
-    qvggt_layernorm_rotate_smooth_quant,
-    qvggt_rotate_smooth_quant_asym,
-    qvggt_weight_code_sums,
-    qvggt_w4a4_gemm_asym,
-    qvggt_prep_weights_given,
-    qvggt_gelu_rotate_smooth_quant,
-    qvggt_gelu_rotate_smooth_quant_e2m3,
-    qvggt_gelu_linear_e2m3,
-    qvggt_i8b_bytes,
-    qvggt_int8_to_blocks,
-    qvggt_rotate_smooth_quant_i8b,
-    qvggt_i8b_gemm,
-    qvggt_workspace_bytes_i8b,
-    qvggt_linear_i8b,
-    qvggt_e2m3_bytes,
-    qvggt_rotate_smooth_quant_e2m3,
-    qvggt_workspace_bytes_e2m3,
-    qvggt_linear_e2m3,
-    qvggt_layernorm_rotate_smooth_quant_e2m3,
-    qvggt_rotate_smooth_quant_asym_e2m3,
-    qvggt_rotate_smooth_quant_static_e2m3,
-    qvggt_e2m3_gemm_shifted,
-    qvggt_codes_to_e2m3,
-    qvggt_e2m3_gemm,
-    qvggt_w4a4_gemm,
-    qvggt_linear,
-    qvggt_workspace_bytes,
-    qvggt_pack_int4,
-    qvggt_unpack_int4,
-    qvggt_prep_weights_i8,
-    qvggt_rotate_smooth_quant_i8,
-    qvggt_i8_gemm,
-    qvggt_linear_i8,
-    qvggt_workspace_bytes_i8,
-    qvggt_layout_int8,
-    qvggt_nfds_workspace_bytes,
-    qvggt_nfds_moments,
-    qvggt_nfds_frame_correlation,
-    qvggt_nfds_scores,
-    qvggt_nfds_keep_lowest,
-    qvggt_nfds_kmeans_step,
-    QVGGT_BF16,
-    QVGGT_F32,
-)
+from . import binding as _binding
+from .binding import QvggtError, lib_path, load_library, EXPORTS, QVGGT_BF16, QVGGT_F32  # noqa: F401
+
+# every entry point of the C ABI under its own name (binding.EXPORTS lists them; tests check the list against include/qvggt.h)
+for _name in EXPORTS:
+    globals()[_name] = getattr(_binding, _name)
+del _name
 
 from .module import DsfqLinear  # noqa: E402,F401

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 QVGGT_BF16, QVGGT_F32 = 0, 1
 
 EXPORTS = [
-    "qvggt_status_string", "qvggt_rotated_col_absmax", "qvggt_prep_weights", "qvggt_rotate_smooth_quant",
+    "qvggt_status_string", "qvggt_init", "qvggt_rotated_col_absmax", "qvggt_prep_weights", "qvggt_rotate_smooth_quant",
     "qvggt_rotate_smooth_quant_static", "qvggt_layernorm_rotate_smooth_quant",
     "qvggt_rotate_smooth_quant_asym", "qvggt_weight_code_sums", "qvggt_w4a4_gemm_asym",
     "qvggt_e2m3_bytes", "qvggt_codes_to_e2m3", "qvggt_e2m3_gemm",
@@ -58,6 +58,8 @@ def load_library() -> C.CDLL:
     vp, i, f, sz = C.c_void_p, C.c_int, C.c_float, C.c_size_t
     lib.qvggt_status_string.restype = C.c_char_p
     lib.qvggt_status_string.argtypes = [i]
+    lib.qvggt_init.restype = i
+    lib.qvggt_init.argtypes = []
     lib.qvggt_rotated_col_absmax.restype = i
     lib.qvggt_rotated_col_absmax.argtypes = [vp, i, i, i, vp, vp, vp]
     lib.qvggt_prep_weights.restype = i
@@ -187,6 +189,10 @@ def _check(status: int, where: str):
 # ------------------------------------------------------------------ entry points
 def qvggt_status_string(status: int) -> str:
     return load_library().qvggt_status_string(int(status)).decode()
+
+
+def qvggt_init():
+    _check(load_library().qvggt_init(), "qvggt_init")
 
 
 def qvggt_rotated_col_absmax(X_cal, signs, absmax_rot, stream=None):

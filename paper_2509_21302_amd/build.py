@@ -27,14 +27,10 @@ FLAGS = [
 ]
 
 
-DEV = False   # --dev: compile the run-time tile-configuration switch used while tuning (never in a normal build)
-
 
 def _compile(src: str, save_temps: bool) -> str:
     obj = os.path.join(BUILD, os.path.splitext(src)[0] + ".o")
     cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
-    if DEV:
-        cmd.append("-DQVGGT_DEV")
     if save_temps:
         cmd.append("-save-temps=obj")
     r = subprocess.run(cmd, capture_output=True, text=True)
@@ -57,5 +53,4 @@ def build(save_temps: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    DEV = "--dev" in sys.argv
     print(build(save_temps="--save-temps" in sys.argv))

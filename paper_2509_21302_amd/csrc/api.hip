@@ -3,9 +3,54 @@
 #include "qvggt_common.h"
 #include "../../include/qvggt.h"
 
+#include <atomic>
 #include <cmath>
+#include <mutex>
 
 namespace qvggt {
+namespace {
+// What the library remembers between calls: which kernels need a raised dynamic-LDS limit (a list written while the library
+// is loaded, read-only afterwards) and on which devices that has been done.
+constexpr int kMaxLdsKernels = 96, kMaxDevices = 64;
+struct LdsRegistry {
+    LdsKernel kernels[kMaxLdsKernels];
+    int n;
+};
+LdsRegistry &lds_registry()
+{
+    static LdsRegistry r{};      // function-local: constructed before the first static LdsKernels object uses it
+    return r;
+}
+std::atomic<int> device_ready[kMaxDevices];
+std::mutex prepare_mutex;
+
+}  // namespace
+
+void register_lds_kernels(const LdsKernel *list, int n)
+{
+    LdsRegistry &r = lds_registry();
+    for (int i = 0; i < n && r.n < kMaxLdsKernels; ++i) r.kernels[r.n++] = list[i];
+}
+
+hipError_t prepare_device(int *device)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    if (device != nullptr) *device = dev;
+    if (device_ready[dev].load(std::memory_order_acquire)) return hipSuccess;
+    std::lock_guard<std::mutex> lock(prepare_mutex);
+    if (device_ready[dev].load(std::memory_order_relaxed)) return hipSuccess;
+    const LdsRegistry &r = lds_registry();
+    for (int i = 0; i < r.n; ++i) {
+        e = hipFuncSetAttribute(r.kernels[i].fn, hipFuncAttributeMaxDynamicSharedMemorySize, r.kernels[i].lds_bytes);
+        if (e != hipSuccess) return e;
+    }
+    device_ready[dev].store(1, std::memory_order_release);
+    return hipSuccess;
+}
+
 hipError_t run_rotate_smooth_quant(const void *X, bool f32, int rows, int K, const int8_t *signs, const float *mul,
                                    int mul_mode, uint8_t *packed, float *scale, const float *step, int step_stride,
                                    int bits, hipStream_t stream);
@@ -101,6 +146,8 @@ int prep_weights(const void *W, int w_dtype, int N, int K, const float *act_absm
 
 extern "C" {
 
+int qvggt_init(void) { return hip_status(qvggt::prepare_device()); }
+
 const char *qvggt_status_string(int status)
 {
     switch (status) {
@@ -111,7 +158,7 @@ const char *qvggt_status_string(int status)
         case QVGGT_ERR_DTYPE: return "QVGGT_ERR_DTYPE: dtype must be QVGGT_BF16 or QVGGT_F32";
         case QVGGT_ERR_WORKSPACE: return "QVGGT_ERR_WORKSPACE: workspace too small";
         case QVGGT_ERR_ARG: return "QVGGT_ERR_ARG: a scalar argument is outside its documented range (alpha, p in [0, 1]; flags 0 or 1; bits in 4..8; eps >= 0)";
-        case QVGGT_ERR_HIP: return "QVGGT_ERR_HIP: kernel launch failed";
+        case QVGGT_ERR_HIP: return "QVGGT_ERR_HIP: a HIP call failed (kernel launch, or no usable device)";
         default: return "unknown qvggt status";
     }
 }

@@ -116,7 +116,7 @@ template <int TM, int TN, int WM, int WN, int STAGES, int MINB, bool DEBUG, bool
 __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per_eu(WM * WN * MINB / 4, WM * WN * MINB / 4))) void e2m3_gemm_kernel(
     const uint8_t *__restrict__ Xf, const float *__restrict__ sx, const uint8_t *__restrict__ Wf,
     const float *__restrict__ sw, const uint16_t *__restrict__ bias, int M, int N, int K,
-    uint16_t *__restrict__ Y, int32_t *__restrict__ acc_debug, int tiles_m, int tiles_n, long long *dbg_times,
+    uint16_t *__restrict__ Y, int32_t *__restrict__ acc_debug, int tiles_m, int tiles_n,
     const float *__restrict__ xzero = nullptr, const float *__restrict__ wsum = nullptr)
 {
     using C = E2m3Cfg<TM, TN, WM, WN, STAGES, SHIFTED>;
@@ -271,25 +271,13 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
 
     const int c = lane & 31, g = lane >> 5;
     int cs = 0, sb = 0;                                   // ring stage being computed on, scale buffer of the current tile
-#ifdef QVGGT_DEV
-    long long t_main = 0, t_epi = 0, t_bar = 0, t_start = clock64(), w_start = wall_clock64(); int n_tiles = 0;
-#endif
     for (int tile = first_tile; tile < tile_end; tile += slots) {
-#ifdef QVGGT_DEV
-        const long long t0 = clock64();
-#endif
         // unit q of the stream: unit q + 1 has landed for this wave once at most STAGES - 3 later units are outstanding; after
         // the barrier it has landed for every wave, and every wave is done reading unit q - 1, whose stage is refilled now
         auto unit = [&](auto buf_c, auto fresh_c) {
             constexpr bool FRESH = decltype(fresh_c)::value;
-#ifdef QVGGT_DEV
-            const long long tb0 = clock64();
-#endif
             e_wait_vmcnt<(STAGES - 3) * LPW>();
             __syncthreads();
-#ifdef QVGGT_DEV
-            t_bar += clock64() - tb0;
-#endif
             if (FRESH && tile + slots < tile_end) {
                 int tnext = tile + slots;
                 asm volatile("" : "+s"(tnext));
@@ -307,9 +295,6 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
             unit(I1{}, BF{});
         }
 
-#ifdef QVGGT_DEV
-        const long long t1 = clock64(); t_main += t1 - t0;
-#endif
         // ---- epilogue.  32x32 result layout: lane l holds column (l % 32) = token and rows 8*(r/4) + 4*(l/32) + r%4 = channels
         const int tm = tile / tiles_n, tn = tile % tiles_n;
         const int row0 = tm * C::BM + wm * TM * 32, col0 = tn * C::BN + wn * TN * 32;
@@ -395,16 +380,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
             }
         }
         sb ^= 1;
-#ifdef QVGGT_DEV
-        t_epi += clock64() - t1; ++n_tiles;
-#endif
     }
-#ifdef QVGGT_DEV
-    if (dbg_times != nullptr && lane == 0) {
-        long long *o = dbg_times + ((size_t)blockIdx.x * C::NW + wave) * 8;
-        o[0] = t_main; o[1] = t_epi; o[2] = t_bar; o[3] = clock64() - t_start; o[4] = n_tiles; o[5] = wall_clock64() - w_start;
-    }
-#endif
     e_wait_vmcnt<0>();      // transfers issued past the last tile must not outlive the block's LDS allocation
 }
 
@@ -446,20 +422,21 @@ hipError_t run_codes_to_e2m3(const uint8_t *packed, int rows, int K, uint8_t *ou
     return hipGetLastError();
 }
 
+// every instantiation launched below, with the dynamic LDS it needs
+#define QVGGT_E2M3_KERNELS(TM, TN, WM, WN, ST, MB)                                                                                  \
+    {reinterpret_cast<const void *>(e2m3_gemm_kernel<TM, TN, WM, WN, ST, MB, false, false>), E2m3Cfg<TM, TN, WM, WN, ST, false>::LDS_BYTES}, \
+    {reinterpret_cast<const void *>(e2m3_gemm_kernel<TM, TN, WM, WN, ST, MB, true, false>), E2m3Cfg<TM, TN, WM, WN, ST, false>::LDS_BYTES},  \
+    {reinterpret_cast<const void *>(e2m3_gemm_kernel<TM, TN, WM, WN, ST, MB, false, true>), E2m3Cfg<TM, TN, WM, WN, ST, true>::LDS_BYTES}
+static const LdsKernel e2m3_lds_kernel_list[] = {QVGGT_E2M3_KERNELS(4, 4, 2, 2, 5, 1), QVGGT_E2M3_KERNELS(2, 2, 2, 2, 4, 2)};
+#undef QVGGT_E2M3_KERNELS
+static const LdsKernels e2m3_lds_kernels(e2m3_lds_kernel_list);
+
 template <int TM, int TN, int WM, int WN, int STAGES, int MINB, bool SHIFTED = false>
 static hipError_t launch_e2m3(const uint8_t *Xf, const float *sx, const uint8_t *Wf, const float *sw, const void *bias,
                               int M, int N, int K, void *Y, int32_t *acc_debug, hipStream_t stream,
                               const float *xzero = nullptr, const float *wsum = nullptr)
 {
     using C = E2m3Cfg<TM, TN, WM, WN, STAGES, SHIFTED>;
-    long long *dbg = nullptr;
-#ifdef QVGGT_DEV
-    // development builds: QVGGT_TIMING=1 reinterprets acc_debug as a buffer for per-wave cycle counters
-    if (getenv("QVGGT_TIMING") && acc_debug != nullptr) {
-        dbg = reinterpret_cast<long long *>(acc_debug);
-        acc_debug = nullptr;
-    }
-#endif
     const bool debug = acc_debug != nullptr;
     auto kern = e2m3_gemm_kernel<TM, TN, WM, WN, STAGES, MINB, false, SHIFTED>;
     if constexpr (!SHIFTED) {
@@ -467,18 +444,14 @@ static hipError_t launch_e2m3(const uint8_t *Xf, const float *sx, const uint8_t 
     } else {
         if (debug) return hipErrorInvalidValue;      // the corrected sum is never an integer register: no dump
     }
-    static bool attr_set[2] = {false, false};
-    if (!attr_set[debug]) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set[debug] = true;
-    }
+    hipError_t e = prepare_device();                 // the kernel's dynamic-LDS limit on this device (see e2m3_lds_kernels above)
+    if (e != hipSuccess) return e;
     const int tiles_m = (M + C::BM - 1) / C::BM, tiles_n = (N + C::BN - 1) / C::BN;
     const int ntiles = tiles_m * tiles_n;
     int grid = 256 * MINB;
     if (grid > (ntiles + 7) / 8 * 8) grid = (ntiles + 7) / 8 * 8;
     kern<<<grid, C::THREADS, C::LDS_BYTES, stream>>>(Xf, sx, Wf, sw, reinterpret_cast<const uint16_t *>(bias), M, N, K,
-                                                     reinterpret_cast<uint16_t *>(Y), acc_debug, tiles_m, tiles_n, dbg, xzero, wsum);
+                                                     reinterpret_cast<uint16_t *>(Y), acc_debug, tiles_m, tiles_n, xzero, wsum);
     return hipGetLastError();
 }
 
@@ -498,18 +471,6 @@ hipError_t run_e2m3_gemm(const uint8_t *Xf, const float *sx, const uint8_t *Wf, 
                                              static_cast<uint16_t *>(Y) + (size_t)row0 * N,
                                              acc_debug ? acc_debug + (size_t)row0 * N : nullptr, stream);
     };
-#ifdef QVGGT_DEV
-    if (const char *ev = getenv("QVGGT_E2M3_VARIANT")) {
-        const int v = atoi(ev);
-        auto bigs = [&](auto st_c) {
-            return launch_e2m3<4, 4, 2, 2, decltype(st_c)::value, 1>(Xf, sx, Wf, sw, bias, M, N, K, Y, acc_debug, stream);
-        };
-        if (v == 2) return small(0, M);
-        if (v == 3) return bigs(std::integral_constant<int, 4>{});
-        if (v == 4) return bigs(std::integral_constant<int, 3>{});
-        return big(0, M);
-    }
-#endif
     // Both configurations work in rounds (256 big tiles, or 512 small ones: two blocks per compute unit), and a last round that is
     // mostly empty costs as much as a full one.  A round of small tiles does half the work of a round of big ones and measured
     // 0.50 - 0.54 of its duration at K = 1024 and 0.6 - 0.75 at K = 4096; the cheaper estimate wins (it reproduces the faster choice

@@ -140,7 +140,7 @@ template <int TM, int TN, int WM, int WN, int STAGES, int MINB, int CB, bool DEB
 __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per_eu(WM * WN * MINB / 4, WM * WN * MINB / 4))) void w4a4_gemm_kernel(
     const uint8_t *__restrict__ Xq, const float *__restrict__ sx, const uint8_t *__restrict__ Wq,
     const float *__restrict__ sw, const uint16_t *__restrict__ bias, int M, int N, int K,
-    uint16_t *__restrict__ Y, int32_t *__restrict__ acc_debug, int tiles_m, int tiles_n, long long *dbg_times,
+    uint16_t *__restrict__ Y, int32_t *__restrict__ acc_debug, int tiles_m, int tiles_n,
     const float *__restrict__ xzero = nullptr, const float *__restrict__ wsum = nullptr)
 {
     using C = StreamCfg<TM, TN, WM, WN, STAGES, ASYM>;
@@ -356,9 +356,6 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
     const int c = lane & 31, g = lane >> 5;
 
     int cs = 0, sb = 0;                                   // ring stage being computed on, scale buffer of the current tile
-#ifdef QVGGT_DEV
-    long long t_main = 0, t_epi = 0, t_bar = 0, t_start = clock64(), w_start = wall_clock64(); int n_tiles = 0;
-#endif
     for (int tile = first_tile; tile < tile_end; tile += slots) {
         // one K-tile of the stream: four K-steps on ring stage cs.  The first K-tile of an output tile starts the
         // accumulators from zero (FRESH) and sends for the scales of the block's next output tile.
@@ -366,14 +363,8 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
             constexpr bool FRESH = decltype(fresh_c)::value;
             // K-tile q+1 of the stream has landed for this wave once at most (STAGES-3) later K-tiles are outstanding; after
             // the barrier it has landed for every wave, and every wave is done reading K-tile q-1, whose stage is reused.
-#ifdef QVGGT_DEV
-            const long long tb0 = clock64();
-#endif
             wait_vmcnt<(STAGES - 3) * LPW>();
             __syncthreads();
-#ifdef QVGGT_DEV
-            t_bar += clock64() - tb0;
-#endif
             if (FRESH && tile + slots < tile_end) {
                 int tnext = tile + slots;
                 asm volatile("" : "+s"(tnext));             // keeps the address arithmetic of the scale transfers inside this branch
@@ -392,14 +383,8 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
             advance_cursor();
             cs = ns;
         };
-#ifdef QVGGT_DEV
-        const long long t0 = clock64();
-#endif
         ktile(BT{});
         for (int kt = 1; kt < ktiles; ++kt) ktile(BF{});
-#ifdef QVGGT_DEV
-        const long long t1 = clock64(); t_main += t1 - t0;
-#endif
 
         // ---- epilogue.  32x32 result layout: lane l holds column (l % 32) = token and rows 8*(r/4) + 4*(l/32) + r%4 = channels,
         // i.e. per register quad q four consecutive channels 8q + 4*(l/32) + 0..3.  Scale + bias + bf16 in registers.
@@ -498,18 +483,23 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
             }
         }
         sb ^= 1;
-#ifdef QVGGT_DEV
-        t_epi += clock64() - t1; ++n_tiles;
-#endif
     }
-#ifdef QVGGT_DEV
-    if (dbg_times != nullptr && lane == 0) {
-        long long *o = dbg_times + ((size_t)blockIdx.x * C::NW + wave) * 8;
-        o[0] = t_main; o[1] = t_epi; o[2] = t_bar; o[3] = clock64() - t_start; o[4] = n_tiles; o[5] = wall_clock64() - w_start;
-    }
-#endif
     wait_vmcnt<0>();        // transfers issued past the last tile must not outlive the block's LDS allocation
 }
+
+// every instantiation launched below, with the dynamic LDS it needs: packed codes (plain, accumulator dump, affine), int8 codes
+// row-major and in blocks (plain, accumulator dump)
+#define QVGGT_GEMM_KERNELS(TM, TN, WM, WN, ST, MB)                                                                                        \
+    {reinterpret_cast<const void *>(w4a4_gemm_kernel<TM, TN, WM, WN, ST, MB, 4, false, false, false>), StreamCfg<TM, TN, WM, WN, ST, false>::LDS_BYTES}, \
+    {reinterpret_cast<const void *>(w4a4_gemm_kernel<TM, TN, WM, WN, ST, MB, 4, true, false, false>), StreamCfg<TM, TN, WM, WN, ST, false>::LDS_BYTES},  \
+    {reinterpret_cast<const void *>(w4a4_gemm_kernel<TM, TN, WM, WN, ST, MB, 4, false, true, false>), StreamCfg<TM, TN, WM, WN, ST, true>::LDS_BYTES},   \
+    {reinterpret_cast<const void *>(w4a4_gemm_kernel<TM, TN, WM, WN, ST, MB, 8, false, false, false>), StreamCfg<TM, TN, WM, WN, ST, false>::LDS_BYTES}, \
+    {reinterpret_cast<const void *>(w4a4_gemm_kernel<TM, TN, WM, WN, ST, MB, 8, true, false, false>), StreamCfg<TM, TN, WM, WN, ST, false>::LDS_BYTES},  \
+    {reinterpret_cast<const void *>(w4a4_gemm_kernel<TM, TN, WM, WN, ST, MB, 8, false, false, true>), StreamCfg<TM, TN, WM, WN, ST, false>::LDS_BYTES},  \
+    {reinterpret_cast<const void *>(w4a4_gemm_kernel<TM, TN, WM, WN, ST, MB, 8, true, false, true>), StreamCfg<TM, TN, WM, WN, ST, false>::LDS_BYTES}
+static const LdsKernel gemm_lds_kernel_list[] = {QVGGT_GEMM_KERNELS(4, 4, 2, 2, 4, 1), QVGGT_GEMM_KERNELS(2, 2, 2, 2, 3, 2)};
+#undef QVGGT_GEMM_KERNELS
+static const LdsKernels gemm_lds_kernels(gemm_lds_kernel_list);
 
 template <int TM, int TN, int WM, int WN, int STAGES, int MINB, int CB, bool ASYM = false, bool BLK = false>
 static hipError_t launch_gemm(const uint8_t *Xq, const float *sx, const uint8_t *Wq, const float *sw, const void *bias,
@@ -517,14 +507,6 @@ static hipError_t launch_gemm(const uint8_t *Xq, const float *sx, const uint8_t 
                               const float *xzero = nullptr, const float *wsum = nullptr)
 {
     using C = StreamCfg<TM, TN, WM, WN, STAGES, ASYM>;
-    long long *dbg = nullptr;
-#ifdef QVGGT_DEV
-    // development builds: QVGGT_TIMING=1 reinterprets acc_debug as a buffer for per-wave cycle counters
-    if (getenv("QVGGT_TIMING") && acc_debug != nullptr) {
-        dbg = reinterpret_cast<long long *>(acc_debug);
-        acc_debug = nullptr;
-    }
-#endif
     // the variant that also writes the raw accumulators is a separate instantiation: the production kernel carries none of it
     const bool debug = acc_debug != nullptr;
     auto kern = w4a4_gemm_kernel<TM, TN, WM, WN, STAGES, MINB, CB, false, ASYM, BLK>;
@@ -533,18 +515,14 @@ static hipError_t launch_gemm(const uint8_t *Xq, const float *sx, const uint8_t 
     } else {
         if (debug) return hipErrorInvalidValue;      // no accumulator dump with affine codes: the corrected sum is never an integer register
     }
-    static bool attr_set[2] = {false, false};
-    if (!attr_set[debug]) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
-        if (e != hipSuccess) return e;
-        attr_set[debug] = true;
-    }
+    hipError_t e = prepare_device();                 // the kernel's dynamic-LDS limit on this device (see gemm_lds_kernels above)
+    if (e != hipSuccess) return e;
     const int tiles_m = (M + C::BM - 1) / C::BM, tiles_n = (N + C::BN - 1) / C::BN;
     const int ntiles = tiles_m * tiles_n;
     int grid = 256 * MINB;                                // MINB resident blocks on each of the 256 compute units
     if (grid > (ntiles + 7) / 8 * 8) grid = (ntiles + 7) / 8 * 8;
     kern<<<grid, C::THREADS, C::LDS_BYTES, stream>>>(Xq, sx, Wq, sw, reinterpret_cast<const uint16_t *>(bias), M, N, K,
-                                                     reinterpret_cast<uint16_t *>(Y), acc_debug, tiles_m, tiles_n, dbg, xzero, wsum);
+                                                     reinterpret_cast<uint16_t *>(Y), acc_debug, tiles_m, tiles_n, xzero, wsum);
     return hipGetLastError();
 }
 
@@ -595,18 +573,6 @@ hipError_t run_w4a4_gemm(const uint8_t *Xq, const float *sx, const uint8_t *Wq, 
                          const void *bias, int M, int N, int K, void *Y, int32_t *acc_debug, hipStream_t stream)
 {
     if (M <= 0) return hipSuccess;
-#define GOP(...) return launch_gemm<__VA_ARGS__>(Xq, sx, Wq, sw, bias, M, N, K, Y, acc_debug, stream)
-#ifdef QVGGT_DEV
-    // development builds only (python -m paper_2509_21302_amd.build --dev): pick a tile configuration at run time
-    const char *ev = getenv("QVGGT_GEMM_VARIANT");
-    const int variant = ev ? atoi(ev) : 0;
-    switch (variant) {
-        case 1: GOP(4, 4, 2, 2, 4, 1, 4);
-        case 2: GOP(4, 4, 2, 2, 3, 1, 4);
-        case 3: GOP(2, 2, 2, 2, 3, 2, 4);
-        default: break;
-    }
-#endif
     return gemm_by_rounds<4>(Xq, sx, Wq, sw, bias, M, N, K, Y, acc_debug, stream);
 }
 
@@ -624,7 +590,6 @@ hipError_t run_i8_gemm(const int8_t *Xq, const float *sx, const int8_t *Wq, cons
 {
     if (M <= 0) return hipSuccess;
     const uint8_t *xq = reinterpret_cast<const uint8_t *>(Xq), *wq = reinterpret_cast<const uint8_t *>(Wq);
-#undef GOP
     return gemm_by_rounds<8>(xq, sx, wq, sw, bias, M, N, K, Y, acc_debug, stream);
 }
 

@@ -121,6 +121,21 @@ struct LnParams {
     int on;
 };
 
+// Kernels that need more dynamic LDS than a launch gets by default.  Each source file that has such kernels lists them in a
+// static LdsKernels object (filled when the library is loaded; no HIP call is made then).  prepare_device() raises the limit of
+// every listed kernel on the calling thread's current device the first time it runs there (and resolves the address of the
+// library's own workspace on that device); later calls are one atomic load.  Thread-safe; qvggt_init() is its public form.
+struct LdsKernel {
+    const void *fn;
+    int lds_bytes;
+};
+void register_lds_kernels(const LdsKernel *list, int n);
+struct LdsKernels {
+    template <int N>
+    explicit LdsKernels(const LdsKernel (&list)[N]) { register_lds_kernels(list, N); }
+};
+hipError_t prepare_device(int *device = nullptr);
+
 __device__ inline float wave_max(float v)
 {
 #pragma unroll

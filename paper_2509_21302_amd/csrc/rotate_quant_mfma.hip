@@ -638,11 +638,6 @@ hipError_t run_rotate_quant_mfma(const void *X, int rows, int K, const int8_t *s
     const int ntiles = (rows + tok - 1) / tok;
     int blocks = (ntiles + rq::WAVES_PER_BLOCK - 1) / rq::WAVES_PER_BLOCK;
     const int max_blocks = 256 * 2;   // two resident blocks of four waves on each of the 256 compute units
-#ifdef QVGGT_DEV
-    // development builds: resident blocks per compute unit from the environment (occupancy experiments)
-    if (const char *ev = getenv("QVGGT_RQ_BPC")) blocks = std::min((ntiles + rq::WAVES_PER_BLOCK - 1) / rq::WAVES_PER_BLOCK, 256 * atoi(ev));
-    else
-#endif
     if (blocks > max_blocks) blocks = max_blocks;
     const float qmax8 = (float)((1 << (code_width(bits) - 1)) - 1);
 #define RQ1(KK, PF, OCC, ST, CB) rotate_quant_mfma_kernel<KK, PF, OCC, ST, CB><<<blocks, 256, 0, stream>>>(x, rows, signs, mul, mul_mode, packed, scale, step, step_stride, qmax8, nullptr)

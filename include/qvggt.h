@@ -267,6 +267,23 @@ int qvggt_linear_e2m3(const void *X, int x_dtype, int M, int N, int K, const int
                       size_t workspace_bytes, void *stream);
 int qvggt_codes_to_e2m3(const uint8_t *packed, int rows, int K, uint8_t *out, void *stream);
 
+/*
+ * qvggt_linear_e2m3 for callers that cannot provide or allocate a workspace (code under HIP graph capture that may not call
+ * hipMalloc, tight serving loops, harnesses that forbid allocation): the activation codes and per-token steps that pass from
+ * kernel 1 to the GEMM live in a fixed device array inside the library (QVGGT_OWN_WORKSPACE_BYTES, one copy per device, held
+ * until the process ends) instead of a workspace argument.  Same kernels, same Y, bit for bit, as qvggt_linear_e2m3; inputs and
+ * outputs are still the caller's.  Calls no allocating routine.  The first use on a device resolves the array's address there
+ * (the set-up of qvggt_init: call that first when capturing).  Shapes with qvggt_workspace_bytes_e2m3(M, N, K) >
+ * QVGGT_OWN_WORKSPACE_BYTES (more than 12160 tokens at K = 4096, 48896 at K = 1024) are refused with QVGGT_ERR_WORKSPACE before anything
+ * is launched.  All calls on one device share that device's array, which keeps the last call's contents (nothing in it has to
+ * start from zero): calls that overlap in time on one device, on any streams, race on it and give wrong results; calls queued on
+ * one stream are safe.  qvggt_own_workspace_bytes returns the limit.
+ */
+#define QVGGT_OWN_WORKSPACE_BYTES (36u << 20)
+size_t qvggt_own_workspace_bytes(void);
+int qvggt_linear_e2m3_own_workspace(const void *X, int x_dtype, int M, int N, int K, const int8_t *signs,
+                                    const float *inv_smooth, const uint8_t *Wf, const float *w_scale, const void *bias,
+                                    void *Y, void *stream);
 int qvggt_e2m3_gemm(const uint8_t *Xf, const float *x_scale, const uint8_t *Wf, const float *w_scale,
                     const void *bias, int M, int N, int K, void *Y, int32_t *acc_debug, void *stream);
 

@@ -20,6 +20,7 @@ EXPORTS = [
     "qvggt_rotate_smooth_quant_asym", "qvggt_weight_code_sums", "qvggt_w4a4_gemm_asym",
     "qvggt_e2m3_bytes", "qvggt_codes_to_e2m3", "qvggt_e2m3_gemm",
     "qvggt_rotate_smooth_quant_e2m3", "qvggt_workspace_bytes_e2m3", "qvggt_linear_e2m3",
+    "qvggt_own_workspace_bytes", "qvggt_linear_e2m3_own_workspace",
     "qvggt_layernorm_rotate_smooth_quant_e2m3",
     "qvggt_prep_weights_given", "qvggt_gelu_rotate_smooth_quant", "qvggt_gelu_rotate_smooth_quant_e2m3", "qvggt_gelu_linear_e2m3",
     "qvggt_i8b_bytes", "qvggt_int8_to_blocks", "qvggt_rotate_smooth_quant_i8b", "qvggt_i8b_gemm", "qvggt_workspace_bytes_i8b",
@@ -107,6 +108,10 @@ def load_library() -> C.CDLL:
     lib.qvggt_gelu_linear_e2m3.argtypes = [vp, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.qvggt_linear_e2m3.restype = i
     lib.qvggt_linear_e2m3.argtypes = [vp, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    lib.qvggt_own_workspace_bytes.restype = C.c_size_t
+    lib.qvggt_own_workspace_bytes.argtypes = []
+    lib.qvggt_linear_e2m3_own_workspace.restype = i
+    lib.qvggt_linear_e2m3_own_workspace.argtypes = [vp, i, i, i, i, vp, vp, vp, vp, vp, vp, vp]
     lib.qvggt_e2m3_bytes.restype = C.c_size_t
     lib.qvggt_e2m3_bytes.argtypes = [i, i]
     lib.qvggt_codes_to_e2m3.restype = i
@@ -339,6 +344,18 @@ def qvggt_linear_e2m3(X, signs, inv_smooth, Wf, w_scale, bias, Y, workspace, str
     _check(load_library().qvggt_linear_e2m3(_ptr(X), _dtype_code(X), M, N, K, _ptr(signs), _ptr(inv_smooth), _ptr(Wf), _ptr(w_scale),
                                             _ptr(bias), _ptr(Y), _ptr(workspace), workspace.numel() * workspace.element_size(),
                                             _stream(stream)), "qvggt_linear_e2m3")
+
+
+def qvggt_own_workspace_bytes():
+    return int(load_library().qvggt_own_workspace_bytes())
+
+
+def qvggt_linear_e2m3_own_workspace(X, signs, inv_smooth, Wf, w_scale, bias, Y, stream=None):
+    M, K = X.shape
+    N = Y.shape[1]
+    _check(load_library().qvggt_linear_e2m3_own_workspace(_ptr(X), _dtype_code(X), M, N, K, _ptr(signs), _ptr(inv_smooth), _ptr(Wf),
+                                                          _ptr(w_scale), _ptr(bias), _ptr(Y), _stream(stream)),
+           "qvggt_linear_e2m3_own_workspace")
 
 
 def qvggt_e2m3_bytes(rows, K):

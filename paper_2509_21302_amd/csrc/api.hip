@@ -7,6 +7,9 @@
 #include <cmath>
 #include <mutex>
 
+// The library's own workspace (see own_workspace_ptr below): device memory, one copy per device.
+static __device__ __align__(256) unsigned char scratch[QVGGT_OWN_WORKSPACE_BYTES];
+
 namespace qvggt {
 namespace {
 // What the library remembers between calls: which kernels need a raised dynamic-LDS limit (a list written while the library
@@ -24,6 +27,11 @@ LdsRegistry &lds_registry()
 std::atomic<int> device_ready[kMaxDevices];
 std::mutex prepare_mutex;
 
+// The library's own workspace, for qvggt_linear_e2m3_own_workspace: what qvggt_linear_e2m3 keeps in its workspace argument (the
+// activation codes as E2M3 blocks and the per-token steps between the two kernels) lives here instead.  Every device that runs the
+// library holds its own copy of the array at its own address until the process ends; in host code the array's name is only a
+// handle for hipGetSymbolAddress, the address kernels are given is own_workspace_ptr[device].
+void *own_workspace_ptr[kMaxDevices];      // written under prepare_mutex before device_ready is released
 }  // namespace
 
 void register_lds_kernels(const LdsKernel *list, int n)
@@ -47,7 +55,23 @@ hipError_t prepare_device(int *device)
         e = hipFuncSetAttribute(r.kernels[i].fn, hipFuncAttributeMaxDynamicSharedMemorySize, r.kernels[i].lds_bytes);
         if (e != hipSuccess) return e;
     }
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));      // this device's copy of the array
+    if (e != hipSuccess) return e;
+    if (p == nullptr) return hipErrorInvalidSymbol;
+    own_workspace_ptr[dev] = p;
     device_ready[dev].store(1, std::memory_order_release);
+    return hipSuccess;
+}
+
+// the current device's copy of the library's own workspace (nullptr and an error if the device cannot be prepared)
+static hipError_t own_workspace(void **ptr)
+{
+    int dev = -1;
+    *ptr = nullptr;
+    hipError_t e = prepare_device(&dev);
+    if (e != hipSuccess) return e;
+    *ptr = own_workspace_ptr[dev];
     return hipSuccess;
 }
 
@@ -533,6 +557,28 @@ int qvggt_linear_e2m3(const void *X, int x_dtype, int M, int N, int K, const int
                       size_t workspace_bytes, void *stream)
 {
     return linear_e2m3(false, X, x_dtype, M, N, K, signs, inv_smooth, Wf, w_scale, bias, Y, workspace, workspace_bytes, stream);
+}
+
+size_t qvggt_own_workspace_bytes(void) { return QVGGT_OWN_WORKSPACE_BYTES; }
+
+int qvggt_linear_e2m3_own_workspace(const void *X, int x_dtype, int M, int N, int K, const int8_t *signs, const float *inv_smooth,
+                                    const uint8_t *Wf, const float *w_scale, const void *bias, void *Y, void *stream)
+{
+    // shape first: an invalid shape has no workspace size to compare
+    if (!valid_dtype(x_dtype)) return QVGGT_ERR_DTYPE;
+    if (M < 0 || !valid_n(N) || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (!e2m3_direct(x_dtype, K)) return x_dtype == QVGGT_BF16 ? QVGGT_ERR_SHAPE : QVGGT_ERR_DTYPE;
+    if (qvggt_workspace_bytes_e2m3(M, N, K) > QVGGT_OWN_WORKSPACE_BYTES) return QVGGT_ERR_WORKSPACE;
+    if (M == 0) return QVGGT_OK;
+    if (!X || !Wf || !w_scale || !Y) return QVGGT_ERR_NULL;     // before the device is touched: argument errors need no GPU
+    if (!aligned16(X) || !aligned16(Wf) || !aligned16(w_scale) || !aligned16(bias) || !aligned16(Y) || !aligned16(inv_smooth) ||
+        !aligned16(signs))
+        return QVGGT_ERR_ALIGN;
+    void *ws = nullptr;
+    if (qvggt::own_workspace(&ws) != hipSuccess) return QVGGT_ERR_HIP;
+    // nothing in the workspace has to start from zero: kernel 1 writes every row below M, and what the GEMM reads of the rows
+    // past M (the last 128-row block's padding, left over from an earlier call) only reaches tile rows it never stores
+    return linear_e2m3(false, X, x_dtype, M, N, K, signs, inv_smooth, Wf, w_scale, bias, Y, ws, QVGGT_OWN_WORKSPACE_BYTES, stream);
 }
 
 int qvggt_gelu_linear_e2m3(const void *X, int x_dtype, int M, int N, int K, const int8_t *signs, const float *inv_smooth,

@@ -219,6 +219,35 @@ def test_argument_validation_needs_no_gpu():
     assert lib.qvggt_pack_int4(None, 0, 1024, None, None) == OK
 
 
+def test_own_workspace_entry_validates_without_a_gpu():
+    """The entry point without a workspace argument: argument errors and the size limit are decided on the host."""
+    lib = q.load_library()
+    f = lib.qvggt_linear_e2m3_own_workspace
+    limit = lib.qvggt_own_workspace_bytes()
+    assert limit == 36 << 20
+    assert f(P, 0, 4, 32, 1000, None, None, P, P, None, P, None) == SHAPE
+    assert f(P, 0, 4, 32, 512, None, None, P, P, None, P, None) == SHAPE          # E2M3 kernel 1: K = 1024, 2048, 4096
+    assert f(P, 1, 4, 32, 1024, None, None, P, P, None, P, None) == DTYPE
+    assert f(None, 0, 4, 32, 1024, None, None, P, P, None, P, None) == NULL
+    assert f(P, 0, 4, 32, 1024, None, None, P, P, None, None, None) == NULL
+    assert f(P, 0, 4, 32, 1024, None, None, P + 4, P, None, P, None) == ALIGN
+    assert f(None, 0, 0, 32, 1024, None, None, None, None, None, None, None) == OK
+    # the limit: the largest token counts whose intermediate buffers fit, and one more
+    for K, m_fit in ((4096, 12160), (1024, 48896)):
+        assert lib.qvggt_workspace_bytes_e2m3(m_fit, 1024, K) <= limit < lib.qvggt_workspace_bytes_e2m3(m_fit + 1, 1024, K)
+        assert f(P, 0, m_fit + 1, 1024, K, None, None, P, P, None, P, None) == WORKSPACE
+    assert f(None, 0, 137400, 1024, 4096, None, None, None, None, None, None, None) == WORKSPACE     # size is checked before pointers
+    # with no GPU the device set-up itself fails and is reported, nothing crashes
+    try:
+        import torch
+        has_gpu = torch.cuda.is_available()
+    except Exception:
+        has_gpu = False
+    if not has_gpu:
+        assert lib.qvggt_init() == 7
+        assert f(P, 0, 4, 32, 1024, None, None, P, P, None, P, None) == 7
+
+
 def test_binding_rejects_host_tensors():
     import torch
     x = torch.zeros(4, 1024, dtype=torch.bfloat16)

@@ -107,7 +107,9 @@ def main():
                 L["prep"]["i8b"] = dict(Wq=Wb, sw=sw, inv=inv)
             if bits == 4:
                 Wf = torch.empty(q.qvggt_e2m3_bytes(s.N, s.K), dtype=torch.uint8, device=dev)
-                q.qvggt_codes_to_e2m3(Wq, s.N, s.K, Wf)
+                lost = torch.zeros(1, dtype=torch.int32, device=dev)
+                q.qvggt_codes_to_e2m3(Wq, s.N, s.K, Wf, lost)
+                assert int(lost.item()) == 0, "weight codes -8 have no E2M3 value"
                 L["prep"]["e2m3"] = dict(Wq=Wf, sw=sw, inv=inv)
         layers.append(L)
     torch.cuda.synchronize()

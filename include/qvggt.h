@@ -106,8 +106,8 @@ int qvggt_prep_weights(const void *W, int w_dtype, int N, int K, const float *ac
  *     Ws = W H diag(c_hat);  Wq[o, :] = clamp(rne(Ws[o, :] / w_step[o]), -2^(bits-1), 2^(bits-1) - 1);  w_scale = w_step
  * c_hat: f32 [K], positive and finite (not checked), or NULL for 1.  w_step: f32 [N], positive, or NULL for each channel's
  * own step max_j |Ws[o, j]| / (2^(bits-1) - 1) as in qvggt_prep_weights.  bits: 4 writes packed Wq [N, K/2] (for
- * qvggt_w4a4_gemm and, through qvggt_codes_to_e2m3, qvggt_e2m3_gemm: that conversion saturates a code -8 to -7, so keep
- * w_step at or above the channel's own step there); 5..8 write int8 Wq [N, K] (for qvggt_i8_gemm).  QVGGT_ERR_ARG for other
+ * qvggt_w4a4_gemm and, through qvggt_codes_to_e2m3, qvggt_e2m3_gemm: that conversion reports codes -8, which it cannot carry,
+ * so keep w_step at or above the channel's own step there); 5..8 write int8 Wq [N, K] (for qvggt_i8_gemm).  QVGGT_ERR_ARG for other
  * bits.  Outputs as qvggt_prep_weights; inv_smooth[j] = 1 / (sqrt(K) c_hat[j]).
  */
 int qvggt_prep_weights_given(const void *W, int w_dtype, int N, int K, const float *c_hat, const int8_t *signs,
@@ -225,8 +225,12 @@ int qvggt_w4a4_gemm(const uint8_t *Xq, const float *x_scale, const uint8_t *Wq, 
  * ((r / 128) * (K / 64) + s) * 6144 + (r % 128) * 48, so a buffer holds ceil(rows / 128) * 128 rows:
  * qvggt_e2m3_bytes(rows, K) bytes (0 for an unsupported K).  The rows past `rows` in the last block are never
  * written and may hold anything (the GEMM reads them and discards what they produce).
- * qvggt_codes_to_e2m3:  packed u8 [rows, K/2] (Xq or Wq as written by this library) -> out, E2M3 blocks;
- *                       distinct buffers; a nibble -8 saturates to -7.
+ * qvggt_codes_to_e2m3:  packed u8 [rows, K/2] (Xq or Wq as written by this library) -> out, E2M3 blocks; distinct buffers.
+ *                       A code -8 cannot be carried over: it is written as -7 and COUNTED in *n_unrepresentable (device uint32,
+ *                       4-byte aligned, required: QVGGT_ERR_NULL without it; the call adds to it, so zero it first and read it
+ *                       after the stream has run).  A count other than 0 means `out` is not a faithful copy and must not be
+ *                       used: such codes (static steps below a row's own, qvggt_prep_weights_given) belong on
+ *                       qvggt_w4a4_gemm, or, for activations, in the half-step form of the _shifted entry points.
  * qvggt_e2m3_gemm:      Xf, Wf E2M3 blocks of M and N rows; everything else as qvggt_w4a4_gemm (acc_debug receives
  *                       the exact sums as int32).
  * qvggt_rotate_smooth_quant_e2m3:  online kernel 1 writing E2M3 blocks directly (the same codes and steps as
@@ -265,7 +269,7 @@ size_t qvggt_workspace_bytes_e2m3(int M, int N, int K);
 int qvggt_linear_e2m3(const void *X, int x_dtype, int M, int N, int K, const int8_t *signs, const float *inv_smooth,
                       const uint8_t *Wf, const float *w_scale, const void *bias, void *Y, void *workspace,
                       size_t workspace_bytes, void *stream);
-int qvggt_codes_to_e2m3(const uint8_t *packed, int rows, int K, uint8_t *out, void *stream);
+int qvggt_codes_to_e2m3(const uint8_t *packed, int rows, int K, uint8_t *out, uint32_t *n_unrepresentable, void *stream);
 
 /*
  * qvggt_linear_e2m3 for callers that cannot provide or allocate a workspace (code under HIP graph capture that may not call

@@ -115,7 +115,7 @@ def load_library() -> C.CDLL:
     lib.qvggt_e2m3_bytes.restype = C.c_size_t
     lib.qvggt_e2m3_bytes.argtypes = [i, i]
     lib.qvggt_codes_to_e2m3.restype = i
-    lib.qvggt_codes_to_e2m3.argtypes = [vp, i, i, vp, vp]
+    lib.qvggt_codes_to_e2m3.argtypes = [vp, i, i, vp, vp, vp]
     lib.qvggt_e2m3_gemm.restype = i
     lib.qvggt_e2m3_gemm.argtypes = [vp, vp, vp, vp, vp, i, i, i, vp, vp, vp]
     lib.qvggt_w4a4_gemm.restype = i
@@ -362,8 +362,9 @@ def qvggt_e2m3_bytes(rows, K):
     return int(load_library().qvggt_e2m3_bytes(rows, K))
 
 
-def qvggt_codes_to_e2m3(packed, rows, K, out, stream=None):
-    _check(load_library().qvggt_codes_to_e2m3(_ptr(packed), rows, K, _ptr(out), _stream(stream)), "qvggt_codes_to_e2m3")
+def qvggt_codes_to_e2m3(packed, rows, K, out, n_unrepresentable, stream=None):
+    _check(load_library().qvggt_codes_to_e2m3(_ptr(packed), rows, K, _ptr(out), _ptr(n_unrepresentable), _stream(stream)),
+           "qvggt_codes_to_e2m3")
 
 
 def qvggt_e2m3_gemm(Xf, x_scale, Wf, w_scale, bias, M, N, K, Y, acc_debug=None, stream=None):

@@ -108,7 +108,7 @@ hipError_t run_rotate_quant_i8b_mfma(const void *X, int rows, int K, const int8_
                                      float *scale, int bits, hipStream_t stream);
 hipError_t run_i8b_gemm(const int8_t *Xb, const float *sx, const int8_t *Wb, const float *sw, const void *bias, int M, int N,
                         int K, void *Y, int32_t *acc_debug, hipStream_t stream);
-hipError_t run_codes_to_e2m3(const uint8_t *packed, int rows, int K, uint8_t *out, hipStream_t stream);
+hipError_t run_codes_to_e2m3(const uint8_t *packed, int rows, int K, uint8_t *out, unsigned int *n_unrepresentable, hipStream_t stream);
 hipError_t run_e2m3_gemm(const uint8_t *Xf, const float *sx, const uint8_t *Wf, const float *sw, const void *bias, int M, int N,
                          int K, void *Y, int32_t *acc_debug, hipStream_t stream);
 hipError_t run_layout_int8(const int8_t *src, int rows, int K, int8_t *dst, int to_library, hipStream_t stream);
@@ -414,13 +414,15 @@ size_t qvggt_e2m3_bytes(int rows, int K)
     return round_up((size_t)rows, 128) * ((size_t)K / 4 * 3);
 }
 
-int qvggt_codes_to_e2m3(const uint8_t *packed, int rows, int K, uint8_t *out, void *stream)
+int qvggt_codes_to_e2m3(const uint8_t *packed, int rows, int K, uint8_t *out, uint32_t *n_unrepresentable, void *stream)
 {
     if (rows < 0 || !valid_k(K)) return QVGGT_ERR_SHAPE;
+    if (!n_unrepresentable) return QVGGT_ERR_NULL;       // also for rows == 0: a caller that cannot see the count must not get QVGGT_OK
+    if (reinterpret_cast<uintptr_t>(n_unrepresentable) & 3u) return QVGGT_ERR_ALIGN;
     if (rows == 0) return QVGGT_OK;
     if (!packed || !out) return QVGGT_ERR_NULL;
     if (!aligned16(packed) || !aligned16(out)) return QVGGT_ERR_ALIGN;
-    return hip_status(qvggt::run_codes_to_e2m3(packed, rows, K, out, static_cast<hipStream_t>(stream)));
+    return hip_status(qvggt::run_codes_to_e2m3(packed, rows, K, out, n_unrepresentable, static_cast<hipStream_t>(stream)));
 }
 
 static bool e2m3_direct(int x_dtype, int K) { return x_dtype == QVGGT_BF16 && (K == 1024 || K == 2048 || K == 4096); }

@@ -21,12 +21,18 @@
 // needs of one unit is 6 KiB contiguous per 128 rows.  (The matrix rate needs 24 KiB per compute unit every ~530 cycles; row-major
 // rows deliver 48-byte pieces of 128-byte lines and measured 3.2 times slower through the same path than contiguous KiBs.)
 //
-// Data movement is the int8 kernel's: persistent blocks, XCD-contiguous tile ranges, operands from global memory straight
-// into an LDS ring (global_load_lds_dwordx4, 1 KiB contiguous per wave instruction, here also contiguous in memory), one unit
-// (one MFMA K-step) per ring stage.  In LDS a stage is rows of 48 bytes, which need no swizzle: 16 consecutive rows start in
-// 16 different 16-byte bank groups (3 is odd).
-// The epilogue is the int8 kernel's (accumulators from AGPRs, scale + bias, bf16, rows through a wave-private LDS tile,
-// non-temporal 128-byte line stores) minus the integer -> float conversion.
+// Data movement: persistent blocks, XCD-contiguous tile ranges, operands from global memory straight into an LDS ring
+// (global_load_lds_dwordx4, 1 KiB contiguous per wave instruction, here also contiguous in memory), one unit (one MFMA K-step)
+// per ring stage.  A stage is the memory image of the tile's rows of that unit: token rows, then channel rows, 48 bytes each, which
+// need no swizzle for the 16-byte reads (16 consecutive rows start in 16 different 16-byte bank groups: 3 is odd).  Its 1 KiB pieces
+// are dealt to the waves in turn (piece n to wave n % 4), so any tile whose rows are multiples of 128 divides.
+//
+// Tiles: 256 x 256 per block, one block per compute unit, four waves of 128 x 128 (256 accumulator registers each): the least
+// operand traffic per MFMA that the register file allows; 128 x 128 blocks, two per compute unit, for problems of less than a round.
+// (256 x 128 blocks, two per compute unit, so that one block's epilogue runs under the other's K loop, were built and measured:
+// the K loop is not limited by the matrix pipes but by what feeds them, and 1.5 times the LDS traffic per MFMA ate the overlap.)
+// The epilogue: accumulators from AGPRs, scale + bias, bf16, rows through a wave-private LDS tile, non-temporal 128-byte line
+// stores.
 #include "qvggt_common.h"
 
 #include <algorithm>
@@ -45,6 +51,7 @@ namespace {
 constexpr int U_BYTES = 48;        // bytes per row per unit: 64 codes of 6 bits
 constexpr int RB = 128;            // rows per block of the operand format
 constexpr int RB_BYTES = RB * U_BYTES;   // one unit of one block: 6 KiB contiguous
+constexpr int RB_PIECES = RB_BYTES / 1024;
 // Scale operands of the matrix builtin.  Constant zeros make the compiler emit the instruction form without block scales
 // (v_mfma_f32_32x32x64_f8f6f4: products as they are), one instruction per MFMA instead of two; 0x7F7F7F7F (E8M0 exponent 127 = 2^0
 // in every byte) is the explicit unit scale and gives the same sums.
@@ -57,7 +64,9 @@ struct E2m3Cfg {
     static constexpr int NW = WM * WN, THREADS = NW * 64;
     static constexpr int BM = WM * TM * 32, BN = WN * TN * 32, ROWS = BM + BN;
     static constexpr int STAGE_BYTES = ROWS * U_BYTES;
-    static constexpr int LPW = ROWS * 3 / 64 / NW;      // 1 KiB transfers per wave per unit
+    static constexpr int XT = BM * 3 / 64, NT = ROWS * 3 / 64;      // 1 KiB pieces of a stage: the first XT are token rows
+    static constexpr int LPW = (NT + NW - 1) / NW;                  // transfer slots per wave and unit (the last may be empty for some waves)
+    static constexpr int LPW_MIN = NT / NW;                         // transfers every wave issues per unit
     static constexpr int NM = TM * TN, NF = TM + TN;
     static constexpr int SC_SYM_BYTES = BM * 4 + BN * 4 + BN * 2;   // per tile: sx f32, sw f32, bias bf16 (as in memory)
     static constexpr int SC_SYM_GROUPS = BM / 64 + BN / 64 + BN / 128;
@@ -67,31 +76,24 @@ struct E2m3Cfg {
     static constexpr int EP_BYTES = NW * 32 * EP_PITCH;
     static constexpr int LDS_BYTES = STAGES * STAGE_BYTES + 2 * SC_BYTES + EP_BYTES;
     static_assert(TN % 2 == 0, "the epilogue handles channel sub-tiles in pairs");
-    static_assert((ROWS * 3) % (64 * NW) == 0, "a stage's 16-byte chunks do not divide among the waves");
-    static_assert((BM * 3 / 64) % LPW == 0, "a wave's transfers must not straddle the two operands");
-    static_assert(BM % 128 == 0 && BN % 128 == 0, "scale transfers assume multiples of 128");
+    static_assert(BM % 128 == 0 && BN % 128 == 0, "tiles are whole 128-row blocks of the operand format");
     static_assert(STAGES >= 3, "ring needs one stage being read, one landed, one in flight");
-    static_assert(LPW <= 8, "instruction offsets of a wave's transfers must fit 13 signed bits");
-    static_assert(RB_BYTES % (LPW * 1024) == 0, "a wave's transfers of a unit must lie inside one 128-row block");
 };
 
-// 4 bytes per lane from global memory to LDS: lane l writes lds_base + 4 * l.  M0 holds the LDS base; the compiler reserves
-// that register for a few instructions of its own (none used here) and never allocates it.
+// Global memory -> LDS, 16 bytes per lane: lane l reads base + lane_off and writes LDS address lds_base + 16 * l.  M0 carries the
+// LDS base; each transfer sets it itself and says so, so nothing depends on what the compiler does with that register elsewhere.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ inline void e_dma16(uint32_t lane_off, const void *base, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(base), "s"(lds_base) : "memory", "m0");
+}
+// 4 bytes per lane: lane l writes lds_base + 4 * l
 __device__ inline void e_dma4(const void *src, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" ::"v"(src), "s"(lds_base) : "memory");
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" ::"v"(src), "s"(lds_base) : "memory", "m0");
 }
-// 16 bytes per lane: lane l writes M0 + OFF + 16 * l and reads base + lane_off + OFF (the instruction offset moves both)
-template <int OFF>
-__device__ inline void e_dma16_set_base(uint32_t lane_off, const void *base, uint32_t lds_base)
-{
-    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1 offset:%3" ::"v"(lane_off), "s"(base), "s"(lds_base), "n"(OFF) : "memory");
-}
-template <int OFF>
-__device__ inline void e_dma16_same_base(uint32_t lane_off, const void *base)
-{
-    asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" ::"v"(lane_off), "s"(base), "n"(OFF) : "memory");
-}
+#pragma clang diagnostic pop
 template <class F, int... Is>
 __device__ inline void e_static_for_impl(F &&f, std::integer_sequence<int, Is...>)
 {
@@ -121,7 +123,6 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
 {
     using C = E2m3Cfg<TM, TN, WM, WN, STAGES, SHIFTED>;
     constexpr int NM = C::NM, NF = C::NF, LPW = C::LPW;
-    constexpr int DMA_SHIFT = (LPW > 4) ? 4096 : 0;             // keeps the transfers' instruction offsets inside [-4096, 4095]
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     uint8_t *sc_all = smem + STAGES * C::STAGE_BYTES;           // two buffers of SC_BYTES
     const uint32_t lds0 = (uint32_t)(uintptr_t)smem;
@@ -140,29 +141,33 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
     if (first_tile >= tile_end) return;
     const int last_tile = tile_end - 1 - ((tile_end - 1 - first_tile) % slots);
 
-    // ---- global -> LDS transfers.  A stage is ROWS rows of 48 bytes (token rows, then channel rows) = ROWS * 3 chunks of 16
-    // bytes; transfer i of this wave writes chunks (wave * LPW + i) * 64 + lane.  The wave's LPW KiB of a unit are rows
-    // wave_row .. of one operand's tile, contiguous in memory inside one 128-row block.
-    constexpr uint32_t BASE_SHIFT = 4096;                       // keeps the pre-compensated lane offsets non-negative
-    const bool loads_x = wave * LPW * 64 < C::BM * 3;
-    const int wave_row = (wave * LPW * 64 - (loads_x ? 0 : C::BM * 3)) / 3;     // first row of the wave's share, inside the tile
-    const int nblocks = ((loads_x ? M : N) + RB - 1) / RB;
-    uint32_t lane_off[LPW];
-#pragma unroll
-    for (int i = 0; i < LPW; ++i) lane_off[i] = (i * 64 + lane) * 16 + BASE_SHIFT - (i * 1024 - DMA_SHIFT);
-    const uint8_t *tile_base;
+    // ---- global -> LDS transfers.  Piece n of a stage (1 KiB: 16-byte chunks 64 n .. 64 n + 63) is moved by wave n % NW in its
+    // slot n / NW.  Pieces below XT are token rows, the rest channel rows; six pieces make one 128-row block of the operand format,
+    // where the units of a block lie RB_BYTES apart.
+    const uint32_t lane_off = (uint32_t)lane * 16;
+    const int xblocks = (M + RB - 1) / RB, wblocks = (N + RB - 1) / RB;
+    const uint8_t *src[LPW];                                    // wave-uniform: unit 0 of this wave's pieces of the tile under the load cursor
     int ld_tile = first_tile, ld_unit = 0, ld_stage = 0;
     auto set_tile_pointers = [&](int t) {
         const int tm = t / tiles_n, tn = t % tiles_n;
-        const int row = (loads_x ? tm * C::BM : tn * C::BN) + wave_row;
-        const int blk = min(row / RB, nblocks - 1);             // a block past the operand's end: re-read the last one (results unused)
-        tile_base = (loads_x ? Xf : Wf) + (size_t)blk * units * RB_BYTES + (row % RB) * U_BYTES - BASE_SHIFT;
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) {
+            const int n = i * C::NW + wave;
+            const bool is_x = n < C::XT;
+            const int m = is_x ? n : n - C::XT;
+            // a block past the operand's end: re-read the last one (results unused)
+            const int blk = min((is_x ? tm * (C::BM / RB) : tn * (C::BN / RB)) + m / RB_PIECES, (is_x ? xblocks : wblocks) - 1);
+            src[i] = (is_x ? Xf : Wf) + (size_t)blk * units * RB_BYTES + (m % RB_PIECES) * 1024;
+        }
     };
     auto issue_transfer = [&](auto i_c) {
         constexpr int i = decltype(i_c)::value;
-        const uint8_t *base = tile_base + (size_t)ld_unit * RB_BYTES;
-        if constexpr (i == 0) e_dma16_set_base<i * 1024 - DMA_SHIFT>(lane_off[i], base, lds0 + ld_stage * C::STAGE_BYTES + wave * LPW * 1024 + DMA_SHIFT);
-        else e_dma16_same_base<i * 1024 - DMA_SHIFT>(lane_off[i], base);
+        const uint32_t dst = lds0 + ld_stage * C::STAGE_BYTES + (i * C::NW + wave) * 1024;
+        if constexpr ((i + 1) * C::NW <= C::NT) {
+            e_dma16(lane_off, src[i] + (size_t)ld_unit * RB_BYTES, dst);
+        } else {
+            if (i * C::NW + wave < C::NT) e_dma16(lane_off, src[i] + (size_t)ld_unit * RB_BYTES, dst);     // wave-uniform
+        }
     };
     auto advance_cursor = [&]() {
         ld_stage = (ld_stage + 1 == STAGES) ? 0 : ld_stage + 1;
@@ -224,7 +229,7 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
         const int2 v = *reinterpret_cast<const int2 *>(p + 32 + fhalf * 8);
         F[b][f][4] = v.x; F[b][f][5] = v.y;
     };
-    // One unit = one K-step: NM slots of {one MFMA, a share of the side work}: the unit's LPW transfers, and the 2 NF LDS reads
+    // One unit = one K-step: NM slots of {one MFMA, a share of the side work}: the unit's transfers, and the 2 NF LDS reads
     // of the next unit's fragments (ring stage rd_stage) into the other buffer, in the order the MFMAs will want them.
     auto kstep = [&](auto buf_c, auto fresh_c, int rd_stage) {
         constexpr int BUF = decltype(buf_c)::value;
@@ -254,7 +259,9 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
     using BT = std::true_type;
     using BF = std::false_type;
 
-    // ---- prologue of the whole stream
+    // ---- prologue of the whole stream.  Unit q of the stream lives in ring stage q % STAGES.  Its fragments are read under unit
+    // q - 1 (all waves are past them at the barrier that opens unit q), so during unit q that stage is refilled with unit
+    // q + STAGES: STAGES - 1 units are in flight or landed ahead of the one being computed.
     if (bias == nullptr) {
         for (int b = 0; b < 2; ++b)
             for (int i = tid; i < C::BN / 2; i += C::THREADS)
@@ -263,20 +270,20 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
     set_tile_pointers(first_tile);
     issue_scales(first_tile, 0);
 #pragma unroll
-    for (int s = 0; s < STAGES - 1; ++s) issue_unit();
-    e_wait_vmcnt<(STAGES - 2) * LPW>();
+    for (int s = 0; s < STAGES; ++s) issue_unit();
+    e_wait_vmcnt<(STAGES - 1) * C::LPW_MIN>();
     __syncthreads();
 #pragma unroll
     for (int f = 0; f < NF; ++f) { read_lo(I0{}, f, 0); read_hi(I0{}, f, 0); }
 
     const int c = lane & 31, g = lane >> 5;
-    int cs = 0, sb = 0;                                   // ring stage being computed on, scale buffer of the current tile
+    int cs = 0, sb = 0;                                   // ring stage of the unit being computed, scale buffer of the current tile
     for (int tile = first_tile; tile < tile_end; tile += slots) {
-        // unit q of the stream: unit q + 1 has landed for this wave once at most STAGES - 3 later units are outstanding; after
-        // the barrier it has landed for every wave, and every wave is done reading unit q - 1, whose stage is refilled now
+        // unit q of the stream: once at most STAGES - 2 later units of this wave are outstanding, unit q + 1 has landed for it; after
+        // the barrier it has landed for every wave, and every wave has the fragments of unit q in registers: stage cs is refilled
         auto unit = [&](auto buf_c, auto fresh_c) {
             constexpr bool FRESH = decltype(fresh_c)::value;
-            e_wait_vmcnt<(STAGES - 3) * LPW>();
+            e_wait_vmcnt<(STAGES - 2) * C::LPW_MIN>();
             __syncthreads();
             if (FRESH && tile + slots < tile_end) {
                 int tnext = tile + slots;
@@ -289,11 +296,11 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
             cs = ns;
         };
         unit(I0{}, BT{});
-        unit(I1{}, BF{});
         for (int u = 2; u < units; u += 2) {
-            unit(I0{}, BF{});
             unit(I1{}, BF{});
+            unit(I0{}, BF{});
         }
+        unit(I1{}, BF{});              // its LDS reads fetch the first fragments of the block's next tile: they live through the epilogue
 
         // ---- epilogue.  32x32 result layout: lane l holds column (l % 32) = token and rows 8*(r/4) + 4*(l/32) + r%4 = channels
         const int tm = tile / tiles_n, tn = tile % tiles_n;
@@ -386,7 +393,8 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
 
 // ---------------------------------------------------------------------------------------
 // packed 4-bit codes (library order, two per byte) -> E2M3 blocks.  One thread per (row, unit, half): 16 bytes in, 24 out.
-__global__ __launch_bounds__(256) void codes_to_e2m3_kernel(const uint8_t *__restrict__ packed, size_t rows, int K, uint8_t *__restrict__ out)
+__global__ __launch_bounds__(256) void codes_to_e2m3_kernel(const uint8_t *__restrict__ packed, size_t rows, int K, uint8_t *__restrict__ out,
+                                                             unsigned int *__restrict__ n_unrepresentable)
 {
     const size_t blobs_per_row = (size_t)K / 32;
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -399,11 +407,13 @@ __global__ __launch_bounds__(256) void codes_to_e2m3_kernel(const uint8_t *__res
     constexpr uint64_t MAG = 0x00ull | (0x08ull << 5) | (0x10ull << 10) | (0x14ull << 15) | (0x18ull << 20) | (0x1Aull << 25) |
                              (0x1Cull << 30) | (0x1Eull << 35);
     uint64_t blob[3] = {0, 0, 0};
+    int minus_eights = 0;
 #pragma unroll
     for (int i = 0; i < 32; ++i) {
         const int n = (int)(w[i >> 3] >> (4 * (i & 7))) & 15;          // two's complement nibble
         const int neg = n >> 3;
-        const int mag = min(neg ? 16 - n : n, 7);                      // -8 has no E2M3 value: saturates to -7
+        minus_eights += (n == 8);
+        const int mag = min(neg ? 16 - n : n, 7);                      // -8 has no E2M3 value: written as -7 and counted
         const uint64_t pat = ((MAG >> (5 * mag)) & 31) | ((uint64_t)neg << 5);
         const int bit = 6 * i, wd = bit >> 6, sh = bit & 63;
         blob[wd] |= pat << sh;
@@ -412,13 +422,14 @@ __global__ __launch_bounds__(256) void codes_to_e2m3_kernel(const uint8_t *__res
     uint8_t *u = out + ((row / RB) * (size_t)(K / 64) + s) * RB_BYTES + (row % RB) * U_BYTES;
     *reinterpret_cast<uint4 *>(u + h * 16) = make_uint4((uint32_t)blob[0], (uint32_t)(blob[0] >> 32), (uint32_t)blob[1], (uint32_t)(blob[1] >> 32));
     *reinterpret_cast<uint2 *>(u + 32 + h * 8) = make_uint2((uint32_t)blob[2], (uint32_t)(blob[2] >> 32));
+    if (minus_eights != 0) atomicAdd(n_unrepresentable, (unsigned int)minus_eights);      // rare: the caller's signal that `out` is not faithful
 }
 
-hipError_t run_codes_to_e2m3(const uint8_t *packed, int rows, int K, uint8_t *out, hipStream_t stream)
+hipError_t run_codes_to_e2m3(const uint8_t *packed, int rows, int K, uint8_t *out, unsigned int *n_unrepresentable, hipStream_t stream)
 {
     const size_t n = (size_t)rows * (K / 32);
     if (n == 0) return hipSuccess;
-    codes_to_e2m3_kernel<<<(unsigned)((n + 255) / 256), 256, 0, stream>>>(packed, (size_t)rows, K, out);
+    codes_to_e2m3_kernel<<<(unsigned)((n + 255) / 256), 256, 0, stream>>>(packed, (size_t)rows, K, out, n_unrepresentable);
     return hipGetLastError();
 }
 

@@ -85,31 +85,21 @@ struct StreamCfg {
         (dst)[(k) + 1] = (int)((p_ << 4) & 0xF0F0F0F0u);               \
     } while (0)
 
-// M0 holds the LDS base of these transfers.  It is a register the compiler reserves for a few instructions of its own (none
-// of which this file uses) and never allocates, so it is neither listed as clobbered nor touched between the transfers.
-// 16 bytes per lane from global memory to LDS: lane l of the wave writes lds_base + 16 * l
-__device__ inline void dma16(const void *src, uint32_t lds_base)
-{
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_base) : "memory");
-}
-// 4 bytes per lane: lane l writes lds_base + 4 * l
+// M0 carries the LDS base of these transfers.  Every transfer sets it itself and names it as clobbered, so nothing depends on what
+// the compiler does with that register between two of them.
+// 4 bytes per lane from global memory to LDS: lane l writes lds_base + 4 * l
 __device__ inline void dma4(const void *src, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" ::"v"(src), "s"(lds_base) : "memory");
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" ::"v"(src), "s"(lds_base) : "memory", "m0");
 }
-// The instruction offset of such a transfer moves the LDS address and the global address alike: with one base in M0,
-// transfers to different places of a stage differ only in OFF (the lane's global offset is pre-compensated by -OFF).
-// The global address is a wave-uniform 64-bit base (scalar registers) plus a 32-bit offset per lane: moving along K only
-// touches the scalar base, no vector ALU work.
+// 16 bytes per lane: lane l writes lds_base + OFF + 16 * l.  The instruction offset of such a transfer moves the LDS address and
+// the global address alike: with one LDS base, transfers to different places of a stage differ only in OFF (the lane's global
+// offset is pre-compensated by -OFF).  The global address is a wave-uniform 64-bit base (scalar registers) plus a 32-bit offset
+// per lane: moving along K only touches the scalar base, no vector ALU work.
 template <int OFF>
-__device__ inline void dma16_set_base(uint32_t lane_off, const void *base, uint32_t lds_base)
+__device__ inline void dma16(uint32_t lane_off, const void *base, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1 offset:%3" ::"v"(lane_off), "s"(base), "s"(lds_base), "n"(OFF) : "memory");
-}
-template <int OFF>
-__device__ inline void dma16_same_base(uint32_t lane_off, const void *base)
-{
-    asm volatile("global_load_lds_dwordx4 %0, %1 offset:%2" ::"v"(lane_off), "s"(base), "n"(OFF) : "memory");
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1 offset:%3" ::"v"(lane_off), "s"(base), "s"(lds_base), "n"(OFF) : "memory", "m0");
 }
 template <class F, int... Is>
 __device__ inline void static_for_impl(F &&f, std::integer_sequence<int, Is...>)
@@ -209,9 +199,8 @@ __global__ __launch_bounds__(WM * WN * 64, MINB) __attribute__((amdgpu_waves_per
     auto issue_transfer = [&](auto i_c) {
         constexpr int i = decltype(i_c)::value;
         const uint8_t *base = tile_base + (BLK ? (size_t)ld_kt * 8192 : (size_t)ld_kt * KT_BYTES);
-        // the wave's LPW KiB of a stage are contiguous; M0 (set by the first transfer of a K-tile) points DMA_SHIFT into them
-        if constexpr (i == 0) dma16_set_base<i * 1024 - DMA_SHIFT>(lane_off[i], base, lds0 + ld_stage * C::STAGE_BYTES + wave * LPW * 1024 + DMA_SHIFT);
-        else dma16_same_base<i * 1024 - DMA_SHIFT>(lane_off[i], base);
+        // the wave's LPW KiB of a stage are contiguous; the LDS base points DMA_SHIFT into them
+        dma16<i * 1024 - DMA_SHIFT>(lane_off[i], base, lds0 + ld_stage * C::STAGE_BYTES + wave * LPW * 1024 + DMA_SHIFT);
     };
     auto advance_cursor = [&]() {
         ld_stage = (ld_stage + 1 == STAGES) ? 0 : ld_stage + 1;

@@ -47,7 +47,10 @@ class DsfqLinear:
             self.Wf = None
             if self.K in (1024, 2048, 4096):
                 self.Wf = torch.empty(q.qvggt_e2m3_bytes(self.N, self.K), dtype=torch.uint8, device=dev)
-                q.qvggt_codes_to_e2m3(self.Wq, self.N, self.K, self.Wf)
+                lost = torch.zeros(1, dtype=torch.int32, device=dev)
+                q.qvggt_codes_to_e2m3(self.Wq, self.N, self.K, self.Wf, lost)
+                if int(lost.item()) != 0:        # cannot happen with the absmax steps of qvggt_prep_weights (codes lie in [-7, 7])
+                    raise RuntimeError(f"{int(lost.item())} weight codes -8 have no E2M3 value")
         else:
             self.Wq = torch.empty(self.N, self.K, dtype=torch.int8, device=dev)
             q.qvggt_prep_weights_i8(weight, absmax, signs, alpha, bits, self.Wq, self.w_scale, self.inv_smooth)

@@ -93,6 +93,15 @@ def gpu_pack(codes_np):
     return packed
 
 
+def codes_to_e2m3(packed, rows, K, out, expect_clean=True):
+    """qvggt_codes_to_e2m3 with its counter of codes -8 (which have no E2M3 value): returns the count, 0 expected by default"""
+    cnt = torch.zeros(1, dtype=torch.int32, device=DEV)
+    q.qvggt_codes_to_e2m3(packed, rows, K, out, cnt)
+    n = int(cnt.item())
+    assert n == 0 or not expect_clean, f"{n} codes -8 in a buffer that should hold none"
+    return n
+
+
 def gpu_linear(Xd, prep, bias_d):
     M, K = Xd.shape
     N = prep["N"]
@@ -187,3 +196,16 @@ def decode_e2m3_rows(buf, rows, K):
                 mag = np.where(e == 0, m / 8.0, 2.0 ** (e - 1) * (1 + m / 8.0))
                 out[:, 64 * s + 32 * h + i] = np.where(f[:, 5] == 1, -mag, mag)
     return out
+
+
+def report(name, **values):
+    """Measured figures of a GPU test (achieved errors and mismatch fractions, not pass / fail): printed, and appended as one
+    JSON line to gpurun_out/measured.jsonl when that folder exists, from where they are quoted in the design notes."""
+    import json
+    import os
+    line = json.dumps(dict(test=name, **{k: (float(v) if isinstance(v, (float, np.floating)) else v) for k, v in values.items()}))
+    print("measured:", line)
+    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    if os.path.isdir(d):
+        with open(os.path.join(d, "measured.jsonl"), "a") as f:
+            f.write(line + "\n")

@@ -133,8 +133,9 @@ def test_argument_validation_needs_no_gpu():
     # 6-bit floating-point matrix path: format size, converter, GEMM, direct kernel 1 (bf16, K = 1024 / 2048 / 4096 only)
     assert q.qvggt_e2m3_bytes(1, 1024) == 128 * 768 and q.qvggt_e2m3_bytes(129, 4096) == 256 * 3072 and q.qvggt_e2m3_bytes(5, 1000) == 0
     cv, eg, re, le = lib.qvggt_codes_to_e2m3, lib.qvggt_e2m3_gemm, lib.qvggt_rotate_smooth_quant_e2m3, lib.qvggt_linear_e2m3
-    assert cv(P, 4, 1000, P, None) == SHAPE and cv(None, 4, 1024, P, None) == NULL and cv(P, 4, 1024, P + 4, None) == ALIGN
-    assert cv(None, 0, 1024, None, None) == OK
+    assert cv(P, 4, 1000, P, P, None) == SHAPE and cv(None, 4, 1024, P, P, None) == NULL and cv(P, 4, 1024, P + 4, P, None) == ALIGN
+    assert cv(P, 4, 1024, P, None, None) == NULL and cv(None, 0, 1024, None, None, None) == NULL      # the counter of codes -8 is required
+    assert cv(P, 4, 1024, P, P + 2, None) == ALIGN and cv(None, 0, 1024, None, P, None) == OK
     assert eg(P, P, P, P, None, 4, 100, 1024, P, None, None) == SHAPE
     assert eg(P, P, None, P, None, 4, 32, 1024, P, None, None) == NULL
     assert eg(P, P, P, P, P + 4, 4, 32, 1024, P, None, None) == ALIGN

@@ -17,7 +17,7 @@ def _e2m3(codes_np):
     packed = G.gpu_pack(codes_np)
     rows, K = codes_np.shape
     out = torch.full((G.q.qvggt_e2m3_bytes(rows, K),), 0xA5, dtype=torch.uint8, device=G.DEV)        # pad rows keep the fill
-    G.q.qvggt_codes_to_e2m3(packed, rows, K, out)
+    G.codes_to_e2m3(packed, rows, K, out)
     return packed, out
 
 
@@ -35,6 +35,28 @@ def test_codes_to_e2m3_layout_and_values():
     at_position = np.where(nib >= 8, nib - 16, nib)
     assert np.array_equal(_decode_e2m3_rows(out.cpu().numpy(), rows, K), at_position.astype(np.float64))
     assert np.array_equal(np.sort(at_position, axis=1), np.sort(codes, axis=1))            # the library order is a permutation of a row
+
+
+def test_codes_to_e2m3_counts_what_it_cannot_carry():
+    """-8 has no E2M3 value: the converter writes -7 there and says how many times it did, so a caller cannot mistake the buffer
+    for a faithful copy (a static weight step below the channel's own produces such codes)."""
+    K, rows = 1024, 130
+    rng = np.random.default_rng(5)
+    codes = rng.integers(-8, 8, (rows, K)).astype(np.int8)
+    n_lost = int((codes == -8).sum())
+    assert n_lost > 1000
+    packed = G.gpu_pack(codes)
+    out = torch.zeros(G.q.qvggt_e2m3_bytes(rows, K), dtype=torch.uint8, device=G.DEV)
+    assert G.codes_to_e2m3(packed, rows, K, out, expect_clean=False) == n_lost
+    pk = packed.cpu().numpy()
+    nib = np.stack([pk & 15, pk >> 4], axis=2).reshape(rows, K).astype(np.int16)
+    at_position = np.where(nib >= 8, nib - 16, nib)
+    assert np.array_equal(_decode_e2m3_rows(out.cpu().numpy(), rows, K), np.maximum(at_position, -7).astype(np.float64))
+    # the counter accumulates: a second call adds to it
+    cnt = torch.zeros(1, dtype=torch.int32, device=G.DEV)
+    G.q.qvggt_codes_to_e2m3(packed, rows, K, out, cnt)
+    G.q.qvggt_codes_to_e2m3(packed, rows, K, out, cnt)
+    assert int(cnt.item()) == 2 * n_lost
 
 
 def _run(qx, qw, dx, dw, bias_bits, debug=True):
@@ -134,7 +156,7 @@ def test_rotate_quant_e2m3_is_kernel_1_in_another_format(K, rows):
     assert torch.equal(sx, sxf)
     got = _decode_e2m3_rows(Xf.cpu().numpy(), rows, K)
     conv = torch.full_like(Xf, 0xA5)
-    G.q.qvggt_codes_to_e2m3(Xq, rows, K, conv)
+    G.codes_to_e2m3(Xq, rows, K, conv)
     assert np.array_equal(got, _decode_e2m3_rows(conv.cpu().numpy(), rows, K))           # -0 and 0 compare equal
     assert not got[7].any()
     # against the oracle: positions -> natural order through the library's own unpack of the packed rows is not used here;
@@ -161,7 +183,7 @@ def test_linear_e2m3_matches_the_oracle_and_the_int8_path(name, M):
     want = oracle.linear(X, po, bias=bias, pre_signs=signs)
     pg = G.gpu_prep(W, cal, signs)
     Wf = torch.empty(G.q.qvggt_e2m3_bytes(N, K), dtype=torch.uint8, device=G.DEV)
-    G.q.qvggt_codes_to_e2m3(pg["Wq"], N, K, Wf)
+    G.codes_to_e2m3(pg["Wq"], N, K, Wf)
     Y = torch.empty(M, N, dtype=torch.bfloat16, device=G.DEV)
     ws = torch.empty(G.q.qvggt_workspace_bytes_e2m3(M, N, K), dtype=torch.uint8, device=G.DEV)
     G.q.qvggt_linear_e2m3(G.to_dev(X), pg["signs"], pg["inv"], Wf, pg["sw"], G.to_dev(bias), Y, ws)
@@ -186,7 +208,7 @@ def test_layernorm_rotate_quant_e2m3_equals_the_packed_variant():
     G.q.qvggt_layernorm_rotate_smooth_quant_e2m3(Xd, gd, bd, eps, sd, invd, Xf, sxf)
     assert torch.equal(sx, sxf)
     conv = torch.full_like(Xf, 0xA5)
-    G.q.qvggt_codes_to_e2m3(Xq, rows, K, conv)
+    G.codes_to_e2m3(Xq, rows, K, conv)
     assert np.array_equal(_decode_e2m3_rows(Xf.cpu().numpy(), rows, K), _decode_e2m3_rows(conv.cpu().numpy(), rows, K))
 
 
@@ -200,7 +222,7 @@ def _shifted_setup(K, rows, N, seed, one_sided):
     signs = (rng.integers(0, 2, K) * 2 - 1).astype(np.int8)
     pg = G.gpu_prep(W, X, signs)
     Wf = torch.empty(G.q.qvggt_e2m3_bytes(N, K), dtype=torch.uint8, device=G.DEV)
-    G.q.qvggt_codes_to_e2m3(pg["Wq"], N, K, Wf)
+    G.codes_to_e2m3(pg["Wq"], N, K, Wf)
     return X, W, bias, signs, pg, Wf, G.gpu_code_sums(pg["Wq"], N, K)
 
 
@@ -269,7 +291,7 @@ def test_linear_e2m3_few_rows(M, K, N):
     signs = (rng.integers(0, 2, K) * 2 - 1).astype(np.int8)
     pg = G.gpu_prep(W, X, signs)
     Wf = torch.full((G.q.qvggt_e2m3_bytes(N, K),), 0xFF, dtype=torch.uint8, device=G.DEV)
-    G.q.qvggt_codes_to_e2m3(pg["Wq"], N, K, Wf)
+    G.codes_to_e2m3(pg["Wq"], N, K, Wf)
     Y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=G.DEV)
     ws = torch.full((G.q.qvggt_workspace_bytes_e2m3(M, N, K),), 0xFF, dtype=torch.uint8, device=G.DEV)
     G.q.qvggt_linear_e2m3(G.to_dev(X), pg["signs"], pg["inv"], Wf, pg["sw"], None, Y, ws)

@@ -65,7 +65,7 @@ def test_gelu_rotate_quant(K, rows):
     G.q.qvggt_gelu_rotate_smooth_quant_e2m3(Xd, sd, invd, Xf, sxf)
     assert torch.equal(sx, sxf)
     conv = torch.full_like(Xf, 0xA5)
-    G.q.qvggt_codes_to_e2m3(Xq, rows, K, conv)
+    G.codes_to_e2m3(Xq, rows, K, conv)
     assert np.array_equal(G.decode_e2m3_rows(Xf.cpu().numpy(), rows, K), G.decode_e2m3_rows(conv.cpu().numpy(), rows, K))
 
 
@@ -108,7 +108,7 @@ def test_mlp_chain_without_an_activation_pass():
     cal = torch.nn.functional.gelu(hd[:1374].float()).to(torch.bfloat16)          # calibration input only (offline side)
     g2 = G.gpu_prep(W2, G.bf16_bits(cal), signs2)
     Wf = torch.empty(G.q.qvggt_e2m3_bytes(s2.N, s2.K), dtype=torch.uint8, device=G.DEV)
-    G.q.qvggt_codes_to_e2m3(g2["Wq"], s2.N, s2.K, Wf)
+    G.codes_to_e2m3(g2["Wq"], s2.N, s2.K, Wf)
     Xf = torch.empty(G.q.qvggt_e2m3_bytes(M, s2.K), dtype=torch.uint8, device=G.DEV)
     sx = torch.empty(M, dtype=torch.float32, device=G.DEV)
     G.q.qvggt_gelu_rotate_smooth_quant_e2m3(hd, g2["signs"], g2["inv"], Xf, sx)
@@ -123,7 +123,7 @@ def test_mlp_chain_without_an_activation_pass():
     layer = q.DsfqLinear(G.to_dev(W2), G.to_dev(b2), G.to_dev(signs2), cal, alpha=0.5, bits=4, pre_gelu=True)
     assert torch.equal(layer(hd), Y)
     err = G.rel_fro(G.bf16_bits(Y), want.Y)
-    assert err <= 3 * G.Y_REL_FRO, err      # two quantized layers in sequence, as in the chain with a separate activation pass
+    assert err <= G.Y_REL_FRO, err          # two quantized layers in sequence at the stated bar (all 8 frames: tests/test_gpu_config3_chain.py)
     # and the fused kernel equals the unfused sequence on the GPU's own fc1 output up to the bf16 rounding flips of the activation
     actd = torch.nn.functional.gelu(hd.float()).to(torch.bfloat16)
     Y2 = G.gpu_linear(actd, g2, G.to_dev(b2))
@@ -155,11 +155,11 @@ def test_gelu_rotate_quant_full_size():
     N = 256
     Wq = torch.from_numpy(rng.integers(0, 256, (N, s.K // 2)).astype(np.uint8)).to(G.DEV)
     Wf = torch.empty(G.q.qvggt_e2m3_bytes(N, s.K), dtype=torch.uint8, device=G.DEV)
-    G.q.qvggt_codes_to_e2m3(Wq, N, s.K, Wf)
+    G.codes_to_e2m3(Wq, N, s.K, Wf)
     sw = torch.full((N,), 1e-3, dtype=torch.float32, device=G.DEV)
     Y1 = torch.empty(s.M, N, dtype=torch.bfloat16, device=G.DEV)
     G.q.qvggt_e2m3_gemm(Xf, sx, Wf, sw, None, s.M, N, s.K, Y1, None)
-    G.q.qvggt_codes_to_e2m3(Xq, s.M, s.K, Xf)
+    G.codes_to_e2m3(Xq, s.M, s.K, Xf)
     Y2 = torch.empty_like(Y1)
     G.q.qvggt_e2m3_gemm(Xf, sx, Wf, sw, None, s.M, N, s.K, Y2, None)
     assert torch.equal(Y1, Y2)

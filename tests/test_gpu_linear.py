@@ -91,7 +91,7 @@ def test_linear_e2m3_full_size_sampled_rows(config, name, n_random):
     del X
     want = oracle.linear(Xs, prep_o, bias=bias, pre_signs=signs)
     Wf = torch.empty(G.q.qvggt_e2m3_bytes(s.N, s.K), dtype=torch.uint8, device=G.DEV)
-    G.q.qvggt_codes_to_e2m3(prep_g["Wq"], s.N, s.K, Wf)
+    G.codes_to_e2m3(prep_g["Wq"], s.N, s.K, Wf)
     Yd = torch.full((s.M, s.N), float("nan"), dtype=torch.bfloat16, device=G.DEV)
     ws = torch.empty(G.q.qvggt_workspace_bytes_e2m3(s.M, s.N, s.K), dtype=torch.uint8, device=G.DEV)
     G.q.qvggt_linear_e2m3(Xd, prep_g["signs"], prep_g["inv"], Wf, prep_g["sw"], G.to_dev(bias), Yd, ws)
@@ -146,7 +146,7 @@ def test_chained_mlp_fc1_gelu_fc2():
     Yd = G.gpu_linear(actd, g2, G.to_dev(b2))
     assert G.rel_fro(G.bf16_bits(actd), act) <= G.Y_REL_FRO
     err = G.rel_fro(G.bf16_bits(Yd), want.Y)
-    assert err <= 3 * G.Y_REL_FRO, err   # two quantized layers in sequence: rows whose fc1 codes flipped differ by a few percent after the second quantizer
+    assert err <= G.Y_REL_FRO, err       # the stated bar holds for the two layers in sequence too (all 8 frames: tests/test_gpu_config3_chain.py)
 
 
 def test_linear_matches_its_two_kernels():
@@ -203,7 +203,7 @@ def test_linear_e2m3_under_hip_graph_capture():
     X0 = G.to_dev(synth.make_activation_frames(s))
     import paper_2509_21302_amd as q
     Wf = torch.empty(q.qvggt_e2m3_bytes(s.N, s.K), dtype=torch.uint8, device=G.DEV)
-    q.qvggt_codes_to_e2m3(prep["Wq"], s.N, s.K, Wf)
+    G.codes_to_e2m3(prep["Wq"], s.N, s.K, Wf)
     Xbuf = X0.clone()
     Y = torch.empty(s.M, s.N, dtype=torch.bfloat16, device=G.DEV)
     ws = torch.empty(q.qvggt_workspace_bytes_e2m3(s.M, s.N, s.K), dtype=torch.uint8, device=G.DEV)
@@ -246,7 +246,7 @@ def test_further_whole_path_entry_points_under_hip_graph_capture(which):
     else:
         pg = _gpu_prep(s)
         Wf = torch.empty(q.qvggt_e2m3_bytes(s.N, s.K), dtype=torch.uint8, device=G.DEV)
-        q.qvggt_codes_to_e2m3(pg["Wq"], s.N, s.K, Wf)
+        G.codes_to_e2m3(pg["Wq"], s.N, s.K, Wf)
         need = q.qvggt_workspace_bytes_e2m3(s.M, s.N, s.K)
         call = lambda X, Y, ws: q.qvggt_gelu_linear_e2m3(X, pg["signs"], pg["inv"], Wf, pg["sw"], bias, Y, ws)
     Xbuf = X0.clone()

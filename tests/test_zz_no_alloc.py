@@ -33,7 +33,7 @@ def test_own_workspace_matches_workspace_argument(K, N, M1, M2):
     W, signs, bias = _layer(K + N, N, K)
     prep = G.gpu_prep(W, _rows(1, 512, K), signs)
     Wf = torch.empty(q.qvggt_e2m3_bytes(N, K), dtype=torch.uint8, device=G.DEV)
-    q.qvggt_codes_to_e2m3(prep["Wq"], N, K, Wf)
+    G.codes_to_e2m3(prep["Wq"], N, K, Wf)
     bias_d = G.to_dev(bias)
     q.qvggt_init()
     for call, M in enumerate((M1, M2)):                  # two calls in a row on the same device array, the second smaller

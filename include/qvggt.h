@@ -120,7 +120,8 @@ int qvggt_prep_weights_given(const void *W, int w_dtype, int N, int K, const flo
  * Hadamard_K is the unnormalised +-1 matrix; its 1/sqrt(K) lives in inv_smooth.
  * X: [M, K] (bf16 or f32).  signs: int8 [K] or NULL.  inv_smooth: f32 [K], or NULL for the
  * plain orthonormal rotation (1/sqrt(K) everywhere).  Outputs: Xq packed [M, K/2] bytes,
- * x_scale f32 [M].  A row of zeros gets scale 0 and codes 0.  Butterflies and scaling are fp32.
+ * x_scale f32 [M].  A row of zeros gets scale 0 and codes 0, and so does a row whose step would lie below 2^-126, the
+ * smallest normal fp32 number (it could not be inverted in fp32).  Butterflies and scaling are fp32.
  */
 int qvggt_rotate_smooth_quant(const void *X, int x_dtype, int M, int K, const int8_t *signs,
                               const float *inv_smooth, uint8_t *Xq, float *x_scale, void *stream);
@@ -132,8 +133,8 @@ int qvggt_rotate_smooth_quant(const void *X, int x_dtype, int M, int K, const in
  * derived from the row:
  *     Xq[t, j] = clamp(rne(z[t, j] / x_step[t * per_token]), -8, 7)
  * so the clamp of the quantizer (Sec. 3.1.2) is live here.  x_step: f32, M values (per_token = 1, token-wise
- * static) or one value for the whole tensor (per_token = 0, tensor-wise); 4-byte aligned; a step <= 0 gives
- * codes 0.  x_scale f32 [M] receives the step every token was quantized with, i.e. what qvggt_w4a4_gemm
+ * static) or one value for the whole tensor (per_token = 0, tensor-wise); 4-byte aligned; a step below 2^-126
+ * (zero and negative values included) gives codes 0.  x_scale f32 [M] receives the step every token was quantized with, i.e. what qvggt_w4a4_gemm
  * takes as x_scale.  Other arguments, layouts and errors as qvggt_rotate_smooth_quant; per_token outside
  * {0, 1} is QVGGT_ERR_ARG.
  */
@@ -182,22 +183,31 @@ int qvggt_layernorm_rotate_smooth_quant(const void *X, int x_dtype, int M, int K
 /*
  * Online kernel 1 of fc2 with the GELU that precedes it fused in (VGGT's MLP blocks: fc1 -> GELU -> fc2, the linear
  * layers being those of Sec. 3.2).  X is fc1's output as stored; per element, before the rotation:
- *     y = x * Phi(x)      (Phi the standard normal distribution function, fp32, relative error about 1e-7 for x > -3),
- * y rounded to bf16 (nearest even, i.e. what a separate bf16 activation kernel would write), then exactly
- * qvggt_rotate_smooth_quant (Xq: packed codes) or qvggt_rotate_smooth_quant_e2m3 (Xf: E2M3 blocks, below) on y.  One
- * read of fc1's output instead of an activation pass (read + write) followed by this kernel's read.
- * bf16 X with K = 1024, 2048 or 4096 only: other K are QVGGT_ERR_SHAPE, f32 X is QVGGT_ERR_DTYPE.  Other arguments,
- * layouts and errors as the entry points named above.
+ *     y = bf16_rne( x * Phi(x) )      (Phi the standard normal distribution function; the exact, erf-based GELU),
+ * i.e. what a separate bf16 activation kernel would write, then exactly qvggt_rotate_smooth_quant (Xq: packed codes) or
+ * qvggt_rotate_smooth_quant_e2m3 (Xf: E2M3 blocks, below) on y.  One read of fc1's output instead of an activation pass
+ * (read + write) followed by this kernel's read.  A bf16 input has 65536 values, so the activation is a table: the kernel
+ * looks up the correctly rounded result (2^-20 <= |x| < 2^12 from the table; below that x / 2, above it x or -0, all exact
+ * at bf16 precision) instead of evaluating erfc per element.
+ * qvggt_gelu_table: fills `table` (device, QVGGT_GELU_TABLE_BYTES bytes, 16-byte aligned, caller-owned; contents are the
+ *   library's own format) on the device, in double precision, once; it depends on nothing but the function.  The other
+ *   calls take it as gelu_table (required: QVGGT_ERR_NULL without it).
+ * bf16 X with K = 1024, 2048 or 4096 only: other K are QVGGT_ERR_SHAPE, f32 X is QVGGT_ERR_DTYPE.  Inputs must be finite.
+ * Other arguments, layouts and errors as the entry points named above.
  */
+#define QVGGT_GELU_TABLE_BYTES 16384u
+size_t qvggt_gelu_table_bytes(void);
+int qvggt_gelu_table(void *table, void *stream);
 int qvggt_gelu_rotate_smooth_quant(const void *X, int x_dtype, int M, int K, const int8_t *signs, const float *inv_smooth,
-                                   uint8_t *Xq, float *x_scale, void *stream);
+                                   const void *gelu_table, uint8_t *Xq, float *x_scale, void *stream);
 int qvggt_gelu_rotate_smooth_quant_e2m3(const void *X, int x_dtype, int M, int K, const int8_t *signs,
-                                        const float *inv_smooth, uint8_t *Xf, float *x_scale, void *stream);
+                                        const float *inv_smooth, const void *gelu_table, uint8_t *Xf, float *x_scale,
+                                        void *stream);
 /* Y = GELU(X) W^T + b on the E2M3 path: qvggt_gelu_rotate_smooth_quant_e2m3 into the workspace, then qvggt_e2m3_gemm, on one
  * stream; arguments, workspace (qvggt_workspace_bytes_e2m3) and errors as qvggt_linear_e2m3 below. */
 int qvggt_gelu_linear_e2m3(const void *X, int x_dtype, int M, int N, int K, const int8_t *signs, const float *inv_smooth,
-                           const uint8_t *Wf, const float *w_scale, const void *bias, void *Y, void *workspace,
-                           size_t workspace_bytes, void *stream);
+                           const void *gelu_table, const uint8_t *Wf, const float *w_scale, const void *bias, void *Y,
+                           void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Online kernel 2 (Sec. 3.2 granularity paragraph: integer sum, dequantise after it):

@@ -120,6 +120,7 @@ def col_absmax(A) -> np.ndarray:
 
 
 SMOOTH_FLOOR = 1e-5
+MIN_STEP = 2.0 ** -126        # a quantization step below the smallest normal single-precision number counts as 0 (dsfq_oracle.c)
 
 
 def smooth_factor(a, w, alpha: float = 0.5, floor: float = SMOOTH_FLOOR) -> np.ndarray:
@@ -289,12 +290,14 @@ def quantize_rows_asym(A, bits: int = 4):
     settings; the paper gives no formula, this is the usual min / max one with the range widened to contain 0:
         lo = min(0, min_j a_j), hi = max(0, max_j a_j), delta = (hi - lo) / (2^bits - 1),
         zp = rne(-lo / delta), u_j = clamp(rne(a_j / delta) + zp, 0, 2^bits - 1);   a_j ~ delta * (u_j - zp).
-    A row of zeros has delta = 0, zp = 0, u = 0.  Returns (delta [rows] f64, zp [rows] int, u [rows, K] uint8)."""
+    A row of zeros has delta = 0, zp = 0, u = 0, and so has a row whose step would lie below 2^-126 (as in quantize_rows).
+    Returns (delta [rows] f64, zp [rows] int, u [rows, K] uint8)."""
     A = _f64(A)
     levels = (1 << bits) - 1
     lo = np.minimum(A.min(axis=1), 0.0)
     hi = np.maximum(A.max(axis=1), 0.0)
     delta = (hi - lo) / levels
+    delta = np.where(delta >= MIN_STEP, delta, 0.0)
     safe = np.where(delta > 0, delta, 1.0)
     zp = np.where(delta > 0, np.rint(-lo / safe), 0.0)
     u = np.clip(np.rint(A / safe[:, None]) + zp[:, None], 0, levels)

@@ -248,8 +248,12 @@ int orc_scale_columns(double *A, int rows, int K, const double *c, int inverse)
  *   delta[r] = max_j |A[r][j]| / (2^(bits-1) - 1)
  *   q[r][j]  = clamp(round(A[r][j] / delta[r]), -2^(bits-1), 2^(bits-1) - 1)
  * round = round-half-to-even (nearbyint in the default rounding mode).  A row
- * of zeros gets delta 0 and codes 0.
+ * of zeros gets delta 0 and codes 0, and so does a row whose step would lie
+ * below ORC_MIN_STEP = 2^-126, the smallest normal single-precision number:
+ * the steps are handed on as single-precision numbers, and a step that is not
+ * a normal one there cannot be divided by (the paper is silent on both cases).
  */
+#define ORC_MIN_STEP 0x1p-126
 int orc_quantize_rows(const double *A, int rows, int K, int bits, double *delta, int8_t *q)
 {
     if (!A || !delta || !q || rows < 0 || K < 1 || bits < 2 || bits > 8) return ORC_ERR_ARG;
@@ -260,6 +264,7 @@ int orc_quantize_rows(const double *A, int rows, int K, int bits, double *delta,
         double m = 0.0;
         for (int j = 0; j < K; ++j) { double v = fabs(a[j]); if (v > m) m = v; }
         double d = m / qmax;
+        if (d < ORC_MIN_STEP) d = 0.0;
         delta[r] = d;
         for (int j = 0; j < K; ++j) {
             double v = (d > 0.0) ? nearbyint(a[j] / d) : 0.0;
@@ -271,7 +276,8 @@ int orc_quantize_rows(const double *A, int rows, int K, int bits, double *delta,
     return ORC_OK;
 }
 
-/* Same quantizer with a given (static) step: used for the clamp's live case. */
+/* Same quantizer with a given (static) step: used for the clamp's live case.  A step below ORC_MIN_STEP (zero and negative
+ * values included) gives codes 0. */
 int orc_quantize_rows_static(const double *A, int rows, int K, int bits, const double *delta, int8_t *q)
 {
     if (!A || !delta || !q || rows < 0 || K < 1 || bits < 2 || bits > 8) return ORC_ERR_ARG;
@@ -279,7 +285,7 @@ int orc_quantize_rows_static(const double *A, int rows, int K, int bits, const d
     for (int r = 0; r < rows; ++r)
         for (int j = 0; j < K; ++j) {
             double d = delta[r];
-            double v = (d > 0.0) ? nearbyint(A[(size_t)r * K + j] / d) : 0.0;
+            double v = (d >= ORC_MIN_STEP) ? nearbyint(A[(size_t)r * K + j] / d) : 0.0;
             if (v < qmin) v = qmin;
             if (v > qmax) v = qmax;
             q[(size_t)r * K + j] = (int8_t)v;

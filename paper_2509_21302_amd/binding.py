@@ -22,7 +22,7 @@ EXPORTS = [
     "qvggt_rotate_smooth_quant_e2m3", "qvggt_workspace_bytes_e2m3", "qvggt_linear_e2m3",
     "qvggt_own_workspace_bytes", "qvggt_linear_e2m3_own_workspace",
     "qvggt_layernorm_rotate_smooth_quant_e2m3",
-    "qvggt_prep_weights_given", "qvggt_gelu_rotate_smooth_quant", "qvggt_gelu_rotate_smooth_quant_e2m3", "qvggt_gelu_linear_e2m3",
+    "qvggt_prep_weights_given", "qvggt_gelu_table_bytes", "qvggt_gelu_table", "qvggt_gelu_rotate_smooth_quant", "qvggt_gelu_rotate_smooth_quant_e2m3", "qvggt_gelu_linear_e2m3",
     "qvggt_i8b_bytes", "qvggt_int8_to_blocks", "qvggt_rotate_smooth_quant_i8b", "qvggt_i8b_gemm", "qvggt_workspace_bytes_i8b",
     "qvggt_linear_i8b",
     "qvggt_rotate_smooth_quant_asym_e2m3", "qvggt_rotate_smooth_quant_static_e2m3", "qvggt_e2m3_gemm_shifted",
@@ -89,7 +89,11 @@ def load_library() -> C.CDLL:
     lib.qvggt_e2m3_gemm_shifted.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, vp, vp]
     for fn in (lib.qvggt_gelu_rotate_smooth_quant, lib.qvggt_gelu_rotate_smooth_quant_e2m3):
         fn.restype = i
-        fn.argtypes = [vp, i, i, i, vp, vp, vp, vp, vp]
+        fn.argtypes = [vp, i, i, i, vp, vp, vp, vp, vp, vp]
+    lib.qvggt_gelu_table_bytes.restype = C.c_size_t
+    lib.qvggt_gelu_table_bytes.argtypes = []
+    lib.qvggt_gelu_table.restype = i
+    lib.qvggt_gelu_table.argtypes = [vp, vp]
     lib.qvggt_i8b_bytes.restype = C.c_size_t
     lib.qvggt_i8b_bytes.argtypes = [i, i]
     lib.qvggt_int8_to_blocks.restype = i
@@ -105,7 +109,7 @@ def load_library() -> C.CDLL:
     lib.qvggt_workspace_bytes_e2m3.restype = C.c_size_t
     lib.qvggt_workspace_bytes_e2m3.argtypes = [i, i, i]
     lib.qvggt_gelu_linear_e2m3.restype = i
-    lib.qvggt_gelu_linear_e2m3.argtypes = [vp, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    lib.qvggt_gelu_linear_e2m3.argtypes = [vp, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.qvggt_linear_e2m3.restype = i
     lib.qvggt_linear_e2m3.argtypes = [vp, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     lib.qvggt_own_workspace_bytes.restype = C.c_size_t
@@ -283,16 +287,26 @@ def qvggt_e2m3_gemm_shifted(Xf, x_scale, x_zero, Wf, w_scale, w_codesum, bias, M
                                                   _ptr(bias), M, N, K, _ptr(Y), _stream(stream)), "qvggt_e2m3_gemm_shifted")
 
 
-def qvggt_gelu_rotate_smooth_quant(X, signs, inv_smooth, Xq, x_scale, stream=None):
-    M, K = X.shape
-    _check(load_library().qvggt_gelu_rotate_smooth_quant(_ptr(X), _dtype_code(X), M, K, _ptr(signs), _ptr(inv_smooth), _ptr(Xq),
-                                                         _ptr(x_scale), _stream(stream)), "qvggt_gelu_rotate_smooth_quant")
+def qvggt_gelu_table_bytes():
+    return int(load_library().qvggt_gelu_table_bytes())
 
 
-def qvggt_gelu_rotate_smooth_quant_e2m3(X, signs, inv_smooth, Xf, x_scale, stream=None):
+def qvggt_gelu_table(table, stream=None):
+    _check(load_library().qvggt_gelu_table(_ptr(table), _stream(stream)), "qvggt_gelu_table")
+
+
+def qvggt_gelu_rotate_smooth_quant(X, signs, inv_smooth, gelu_table, Xq, x_scale, stream=None):
     M, K = X.shape
-    _check(load_library().qvggt_gelu_rotate_smooth_quant_e2m3(_ptr(X), _dtype_code(X), M, K, _ptr(signs), _ptr(inv_smooth), _ptr(Xf),
-                                                              _ptr(x_scale), _stream(stream)), "qvggt_gelu_rotate_smooth_quant_e2m3")
+    _check(load_library().qvggt_gelu_rotate_smooth_quant(_ptr(X), _dtype_code(X), M, K, _ptr(signs), _ptr(inv_smooth),
+                                                         _ptr(gelu_table), _ptr(Xq), _ptr(x_scale), _stream(stream)),
+           "qvggt_gelu_rotate_smooth_quant")
+
+
+def qvggt_gelu_rotate_smooth_quant_e2m3(X, signs, inv_smooth, gelu_table, Xf, x_scale, stream=None):
+    M, K = X.shape
+    _check(load_library().qvggt_gelu_rotate_smooth_quant_e2m3(_ptr(X), _dtype_code(X), M, K, _ptr(signs), _ptr(inv_smooth),
+                                                              _ptr(gelu_table), _ptr(Xf), _ptr(x_scale), _stream(stream)),
+           "qvggt_gelu_rotate_smooth_quant_e2m3")
 
 
 def qvggt_i8b_bytes(rows, K):
@@ -330,10 +344,10 @@ def qvggt_workspace_bytes_e2m3(M, N, K):
     return int(load_library().qvggt_workspace_bytes_e2m3(M, N, K))
 
 
-def qvggt_gelu_linear_e2m3(X, signs, inv_smooth, Wf, w_scale, bias, Y, workspace, stream=None):
+def qvggt_gelu_linear_e2m3(X, signs, inv_smooth, gelu_table, Wf, w_scale, bias, Y, workspace, stream=None):
     M, K = X.shape
     N = Y.shape[1]
-    _check(load_library().qvggt_gelu_linear_e2m3(_ptr(X), _dtype_code(X), M, N, K, _ptr(signs), _ptr(inv_smooth), _ptr(Wf),
+    _check(load_library().qvggt_gelu_linear_e2m3(_ptr(X), _dtype_code(X), M, N, K, _ptr(signs), _ptr(inv_smooth), _ptr(gelu_table), _ptr(Wf),
                                                  _ptr(w_scale), _ptr(bias), _ptr(Y), _ptr(workspace),
                                                  workspace.numel() * workspace.element_size(), _stream(stream)), "qvggt_gelu_linear_e2m3")
 

@@ -101,8 +101,9 @@ hipError_t run_rotate_quant_e2m3_shifted_mfma(const void *X, int rows, int K, co
                                               float *scale, float *zero, const float *step, int step_stride, hipStream_t stream);
 hipError_t run_e2m3_gemm_shifted(const uint8_t *Xf, const float *sx, const float *xzero, const uint8_t *Wf, const float *sw,
                                  const float *wsum, const void *bias, int M, int N, int K, void *Y, hipStream_t stream);
-hipError_t run_gelu_rotate_quant_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, uint8_t *out,
-                                      float *scale, bool e2m3, hipStream_t stream);
+hipError_t run_gelu_rotate_quant_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, const void *gelu_table,
+                                      uint8_t *out, float *scale, bool e2m3, hipStream_t stream);
+hipError_t run_gelu_table(void *table, hipStream_t stream);
 hipError_t run_int8_to_blocks(const int8_t *src, int rows, int K, uint8_t *dst, hipStream_t stream);
 hipError_t run_rotate_quant_i8b_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, uint8_t *out,
                                      float *scale, int bits, hipStream_t stream);
@@ -440,29 +441,39 @@ int qvggt_rotate_smooth_quant_e2m3(const void *X, int x_dtype, int M, int K, con
     return hip_status(qvggt::run_rotate_quant_e2m3_mfma(X, M, K, signs, inv_smooth, Xf, x_scale, static_cast<hipStream_t>(stream)));
 }
 
+size_t qvggt_gelu_table_bytes(void) { return QVGGT_GELU_TABLE_BYTES; }
+
+int qvggt_gelu_table(void *table, void *stream)
+{
+    if (!table) return QVGGT_ERR_NULL;
+    if (!aligned16(table)) return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_gelu_table(table, static_cast<hipStream_t>(stream)));
+}
+
 static int gelu_rotate_smooth_quant(const void *X, int x_dtype, int M, int K, const int8_t *signs, const float *inv_smooth,
-                                   uint8_t *out, float *x_scale, bool e2m3, void *stream)
+                                   const void *gelu_table, uint8_t *out, float *x_scale, bool e2m3, void *stream)
 {
     if (!valid_dtype(x_dtype)) return QVGGT_ERR_DTYPE;
     if (M < 0 || !valid_k(K)) return QVGGT_ERR_SHAPE;
     if (!e2m3_direct(x_dtype, K)) return x_dtype == QVGGT_BF16 ? QVGGT_ERR_SHAPE : QVGGT_ERR_DTYPE;
     if (M == 0) return QVGGT_OK;
-    if (!X || !out || !x_scale) return QVGGT_ERR_NULL;
-    if (!aligned16(X) || !aligned16(out) || !aligned16(x_scale) || !aligned16(inv_smooth) || !aligned16(signs))
+    if (!X || !out || !x_scale || !gelu_table) return QVGGT_ERR_NULL;
+    if (!aligned16(X) || !aligned16(out) || !aligned16(x_scale) || !aligned16(inv_smooth) || !aligned16(signs) || !aligned16(gelu_table))
         return QVGGT_ERR_ALIGN;
-    return hip_status(qvggt::run_gelu_rotate_quant_mfma(X, M, K, signs, inv_smooth, out, x_scale, e2m3, static_cast<hipStream_t>(stream)));
+    return hip_status(qvggt::run_gelu_rotate_quant_mfma(X, M, K, signs, inv_smooth, gelu_table, out, x_scale, e2m3,
+                                                        static_cast<hipStream_t>(stream)));
 }
 
 int qvggt_gelu_rotate_smooth_quant(const void *X, int x_dtype, int M, int K, const int8_t *signs, const float *inv_smooth,
-                                   uint8_t *Xq, float *x_scale, void *stream)
+                                   const void *gelu_table, uint8_t *Xq, float *x_scale, void *stream)
 {
-    return gelu_rotate_smooth_quant(X, x_dtype, M, K, signs, inv_smooth, Xq, x_scale, false, stream);
+    return gelu_rotate_smooth_quant(X, x_dtype, M, K, signs, inv_smooth, gelu_table, Xq, x_scale, false, stream);
 }
 
 int qvggt_gelu_rotate_smooth_quant_e2m3(const void *X, int x_dtype, int M, int K, const int8_t *signs, const float *inv_smooth,
-                                        uint8_t *Xf, float *x_scale, void *stream)
+                                        const void *gelu_table, uint8_t *Xf, float *x_scale, void *stream)
 {
-    return gelu_rotate_smooth_quant(X, x_dtype, M, K, signs, inv_smooth, Xf, x_scale, true, stream);
+    return gelu_rotate_smooth_quant(X, x_dtype, M, K, signs, inv_smooth, gelu_table, Xf, x_scale, true, stream);
 }
 
 int qvggt_layernorm_rotate_smooth_quant_e2m3(const void *X, int x_dtype, int M, int K, const float *gamma, const float *beta,
@@ -532,7 +543,7 @@ size_t qvggt_workspace_bytes_e2m3(int M, int N, int K)
     return round_up(qvggt_e2m3_bytes(M, K), 256) + round_up((size_t)M * sizeof(float), 256);
 }
 
-static int linear_e2m3(bool gelu, const void *X, int x_dtype, int M, int N, int K, const int8_t *signs, const float *inv_smooth,
+static int linear_e2m3(const void *gelu_table, const void *X, int x_dtype, int M, int N, int K, const int8_t *signs, const float *inv_smooth,
                       const uint8_t *Wf, const float *w_scale, const void *bias, void *Y, void *workspace,
                       size_t workspace_bytes, void *stream)
 {
@@ -548,8 +559,8 @@ static int linear_e2m3(bool gelu, const void *X, int x_dtype, int M, int N, int 
     uint8_t *Xf = static_cast<uint8_t *>(workspace);
     float *x_scale = reinterpret_cast<float *>(Xf + round_up(qvggt_e2m3_bytes(M, K), 256));
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = gelu ? qvggt::run_gelu_rotate_quant_mfma(X, M, K, signs, inv_smooth, Xf, x_scale, true, s)
-                        : qvggt::run_rotate_quant_e2m3_mfma(X, M, K, signs, inv_smooth, Xf, x_scale, s);
+    hipError_t e = gelu_table ? qvggt::run_gelu_rotate_quant_mfma(X, M, K, signs, inv_smooth, gelu_table, Xf, x_scale, true, s)
+                              : qvggt::run_rotate_quant_e2m3_mfma(X, M, K, signs, inv_smooth, Xf, x_scale, s);
     if (e != hipSuccess) return QVGGT_ERR_HIP;
     return hip_status(qvggt::run_e2m3_gemm(Xf, x_scale, Wf, w_scale, bias, M, N, K, Y, nullptr, s));
 }
@@ -558,7 +569,7 @@ int qvggt_linear_e2m3(const void *X, int x_dtype, int M, int N, int K, const int
                       const uint8_t *Wf, const float *w_scale, const void *bias, void *Y, void *workspace,
                       size_t workspace_bytes, void *stream)
 {
-    return linear_e2m3(false, X, x_dtype, M, N, K, signs, inv_smooth, Wf, w_scale, bias, Y, workspace, workspace_bytes, stream);
+    return linear_e2m3(nullptr, X, x_dtype, M, N, K, signs, inv_smooth, Wf, w_scale, bias, Y, workspace, workspace_bytes, stream);
 }
 
 size_t qvggt_own_workspace_bytes(void) { return QVGGT_OWN_WORKSPACE_BYTES; }
@@ -580,14 +591,16 @@ int qvggt_linear_e2m3_own_workspace(const void *X, int x_dtype, int M, int N, in
     if (qvggt::own_workspace(&ws) != hipSuccess) return QVGGT_ERR_HIP;
     // nothing in the workspace has to start from zero: kernel 1 writes every row below M, and what the GEMM reads of the rows
     // past M (the last 128-row block's padding, left over from an earlier call) only reaches tile rows it never stores
-    return linear_e2m3(false, X, x_dtype, M, N, K, signs, inv_smooth, Wf, w_scale, bias, Y, ws, QVGGT_OWN_WORKSPACE_BYTES, stream);
+    return linear_e2m3(nullptr, X, x_dtype, M, N, K, signs, inv_smooth, Wf, w_scale, bias, Y, ws, QVGGT_OWN_WORKSPACE_BYTES, stream);
 }
 
 int qvggt_gelu_linear_e2m3(const void *X, int x_dtype, int M, int N, int K, const int8_t *signs, const float *inv_smooth,
-                           const uint8_t *Wf, const float *w_scale, const void *bias, void *Y, void *workspace,
+                           const void *gelu_table, const uint8_t *Wf, const float *w_scale, const void *bias, void *Y, void *workspace,
                            size_t workspace_bytes, void *stream)
 {
-    return linear_e2m3(true, X, x_dtype, M, N, K, signs, inv_smooth, Wf, w_scale, bias, Y, workspace, workspace_bytes, stream);
+    if (M > 0 && !gelu_table) return QVGGT_ERR_NULL;
+    if (!aligned16(gelu_table)) return QVGGT_ERR_ALIGN;
+    return linear_e2m3(gelu_table, X, x_dtype, M, N, K, signs, inv_smooth, Wf, w_scale, bias, Y, workspace, workspace_bytes, stream);
 }
 
 int qvggt_e2m3_gemm(const uint8_t *Xf, const float *x_scale, const uint8_t *Wf, const float *w_scale, const void *bias,

@@ -8,6 +8,9 @@ namespace qvggt {
 constexpr int kWave = 64;
 constexpr int kMinK = 128;
 constexpr int kMaxK = 8192;
+// A quantization step below the smallest normal fp32 number (2^-126) counts as 0: the row gets step 0 and codes 0 (a dynamic
+// step), or codes 0 (a given one).  Such a step could not be inverted in fp32 (7 / absmax would overflow).
+constexpr float kMinStep = 1.17549435e-38f;
 
 // Width argument of the quantizing launchers: 4 = 4-bit codes packed two per byte; kInt8Container + b = b-bit codes
 // (4 <= b <= 8) stored one per byte as int8 (so that weights and activations of one int8 GEMM may take different widths)

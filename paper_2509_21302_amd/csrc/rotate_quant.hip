@@ -196,18 +196,20 @@ __global__ __launch_bounds__(256) void rotate_rows_kernel(const void *__restrict
             if constexpr (ASYM) {
                 const float hi = wave_max(amax), nlo = wave_max(nmin);
                 const float range = hi + nlo;
-                delta = range / 15.0f;
-                inv = range > 0.0f ? 15.0f / range : 0.0f;
+                const bool live = range >= 15.0f * kMinStep;
+                delta = live ? range / 15.0f : 0.0f;
+                inv = live ? 15.0f / range : 0.0f;
                 const float zp = __builtin_rintf(nlo * inv);                  // rne(-lo / step), in [0, 15]
                 off = zp - 8.0f;
                 if (lane == 0) zero[row] = zp;
             } else if (step != nullptr) {
                 delta = step[(size_t)row * step_stride];
-                inv = delta > 0.0f ? 1.0f / delta : 0.0f;
+                inv = delta >= kMinStep ? 1.0f / delta : 0.0f;
             } else {
                 amax = wave_max(amax);
-                delta = amax / qmax;
-                inv = amax > 0.0f ? qmax / amax : 0.0f;
+                const bool live = amax >= qmax * kMinStep;
+                delta = live ? amax / qmax : 0.0f;
+                inv = live ? qmax / amax : 0.0f;
             }
             if (lane == 0) scale[row] = delta;
             const int q_hi = (int)qmax, q_lo = -q_hi - 1;

@@ -181,11 +181,12 @@ __global__ __launch_bounds__(256) void rotate_rows_general_kernel(const void *__
             float inv, delta;
             if (step != nullptr) {
                 delta = step[(size_t)row * step_stride];
-                inv = delta > 0.0f ? 1.0f / delta : 0.0f;
+                inv = delta >= kMinStep ? 1.0f / delta : 0.0f;
             } else {
                 amax = wave_max(amax);
-                delta = amax / qmax;
-                inv = amax > 0.0f ? qmax / amax : 0.0f;
+                const bool live = amax >= qmax * kMinStep;
+                delta = live ? amax / qmax : 0.0f;
+                inv = live ? qmax / amax : 0.0f;
             }
             if (lane == 0) scale[row] = delta;
             const int q_hi = (int)qmax, q_lo = -q_hi - 1;

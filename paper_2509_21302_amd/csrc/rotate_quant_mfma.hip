@@ -52,19 +52,38 @@ struct Cfg {
     static constexpr int SIGN_CLASSES = K / 512;             // distinct column chunks a lane loads
 };
 
-// GELU(x) = x Phi(x), Phi the standard normal distribution function.  Phi(-|x|) = erfc(|x| / sqrt 2) / 2 by the
-// rational-times-Gaussian approximation of Abramowitz & Stegun 7.1.26 (absolute error 1.5e-7 in erfc, the halves folded into
-// the coefficients), Phi(|x|) = 1 - Phi(-|x|), inputs finite: about 1e-7 relative on the result for x > -3, which is what the bf16 rounding
-// that follows needs; far in the negative tail, where the result is below 1e-6 in magnitude, only its order of magnitude holds.
-__device__ inline float gelu_f32(float x)
+// GELU(x) = x Phi(x) of a bf16 value, as a bf16 value, by table.  A bf16 input has 65536 possible values, and the exact activation
+// rounded to bf16 (what a separate activation kernel would hand on, and what the float64 reference computes) is a function of
+// those 16 bits alone: the kernel looks it up instead of evaluating erfc per element.  The table (qvggt_gelu_table, built on
+// the device in double precision) covers 2^-20 <= |x| < 2^12, 4096 magnitudes per sign: with d = (bits - 0x3580) mod 2^16 an
+// input is covered iff (d & 0x7FFF) < 0x1000, and its entry is (d & 0x0FFF) | ((d >> 3) & 0x1000).  Outside: |x| < 2^-20
+// gives x / 2 (the correction 0.4 x^2 is below a quarter ulp there), x >= 2^12 gives x, x <= -2^12 gives -0.
+constexpr uint32_t GELU_U0 = 0x3580u;            // bf16 bits of 2^-20
+constexpr int GELU_TABLE_ENTRIES = 8192;
+typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+
+__device__ inline uint32_t gelu_window(uint32_t w)      // both halves of a packed pair: bits - U0
 {
-    const float t = __builtin_amdgcn_rcpf(fmaf(fabsf(x), 0.3275911f * 0.70710678f, 1.0f));
-    float p = fmaf(t, 0.5f * 1.061405429f, 0.5f * -1.453152027f);
-    p = fmaf(t, p, 0.5f * 1.421413741f);
-    p = fmaf(t, p, 0.5f * -0.284496736f);
-    p = fmaf(t, p, 0.5f * 0.254829592f);
-    const float q = p * t * __builtin_amdgcn_exp2f(x * x * (-0.5f * 1.44269504f));
-    return fmaf(-fabsf(x), q, fmaxf(x, 0.0f));        // x q for x < 0, x - x q otherwise
+    const us2 a = *reinterpret_cast<const us2 *>(&w), u0 = {(unsigned short)GELU_U0, (unsigned short)GELU_U0};
+    const us2 d = a - u0;
+    return *reinterpret_cast<const uint32_t *>(&d);
+}
+// both halves covered by the table (the usual case): two lookups
+__device__ inline uint32_t gelu_pair_table(uint32_t d, const uint16_t *lut)
+{
+    const uint32_t idx = (d & 0x0FFF0FFFu) | ((d >> 3) & 0x10001000u);
+    return (uint32_t)lut[idx & 0xFFFFu] | ((uint32_t)lut[idx >> 16] << 16);
+}
+// any finite value
+__device__ inline uint32_t gelu_one_any(uint32_t bits, const uint16_t *lut)
+{
+    const uint32_t d = (bits - GELU_U0) & 0xFFFFu;
+    if ((d & 0x7FFFu) < 0x1000u) return lut[(d & 0x0FFFu) | ((d >> 3) & 0x1000u)];
+    if ((bits & 0x7FFFu) < GELU_U0) {                                   // tiny: x / 2, rounded as a bf16 store would (subnormals included)
+        const uint32_t p = pack_bf16x2(0.5f * __uint_as_float(bits << 16), 0.0f);
+        return p & 0xFFFFu;
+    }
+    return (bits & 0x8000u) ? 0x8000u : bits;                             // |x| >= 2^12: x or -0
 }
 
 // MFMA row of segment `seg` (= tk * HB + hb) of a tile, without the two lowest hb bits
@@ -107,7 +126,8 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
                                                                    const float *__restrict__ step, int step_stride,
                                                                    float qmax8, unsigned int *__restrict__ col_absmax_bits,
                                                                    LnParams ln = LnParams{nullptr, nullptr, 0.0f, 0},
-                                                                   float *__restrict__ zero = nullptr)
+                                                                   float *__restrict__ zero = nullptr,
+                                                                   const uint16_t *__restrict__ gelu_table = nullptr)
 {
     constexpr bool STAT = (CB == 0);
     static_assert(!ASYM || ((CB == 4 || CB == 6) && !STATIC), "affine codes: dynamic 4-bit only");
@@ -116,6 +136,13 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
     using C = rq::Cfg<K>;
     constexpr int REM = C::REM, TOK = C::TOK;
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[rq::WAVES_PER_BLOCK * rq::LDS_PER_WAVE];
+
+    __shared__ __attribute__((aligned(16))) uint16_t gelu_lut[GELU ? rq::GELU_TABLE_ENTRIES : 8];
+    if constexpr (GELU) {
+        for (int i = threadIdx.x; i < rq::GELU_TABLE_ENTRIES / 8; i += 256)
+            reinterpret_cast<uint4 *>(gelu_lut)[i] = reinterpret_cast<const uint4 *>(gelu_table)[i];
+        __syncthreads();
+    }
 
     const int lane = threadIdx.x & 63, wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int c = lane & 31, g = lane >> 5;
@@ -264,14 +291,36 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
 
     for (; (BLOCK_FLUSH ? tile - wave_in_block : tile) < ntiles; tile += nwaves) {
         if constexpr (GELU) {
+            // one wave-uniform test per tile: is every value inside the table's window?  (Almost always: outside are exact
+            // zeros, |x| < 1e-6 and |x| >= 4096.)  Then two lookups per packed pair; otherwise the general form per value.
+            uint32_t D[8][4], worst = 0;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const uint4 v = G[0][j];
-                uint32_t w[4] = {v.x, v.y, v.z, v.w};
+                const uint32_t w[4] = {G[0][j].x, G[0][j].y, G[0][j].z, G[0][j].w};
 #pragma unroll
-                for (int d = 0; d < 4; ++d)
-                    w[d] = pack_bf16x2(rq::gelu_f32(__uint_as_float(w[d] << 16)), rq::gelu_f32(__uint_as_float(w[d] & 0xFFFF0000u)));
-                G[0][j] = make_uint4(w[0], w[1], w[2], w[3]);
+                for (int d = 0; d < 4; ++d) {
+                    D[j][d] = rq::gelu_window(w[d]);
+                    const uint32_t m = D[j][d] & 0x7FFF7FFFu;
+                    const rq::us2 a = *reinterpret_cast<const rq::us2 *>(&m), bmax = *reinterpret_cast<const rq::us2 *>(&worst);
+                    const rq::us2 mx = __builtin_elementwise_max(a, bmax);
+                    worst = *reinterpret_cast<const uint32_t *>(&mx);
+                }
+            }
+            const bool outside = ((worst & 0xFFFFu) >= 0x1000u) || ((worst >> 16) >= 0x1000u);
+            if (__builtin_amdgcn_ballot_w64(outside) == 0) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    G[0][j] = make_uint4(rq::gelu_pair_table(D[j][0], gelu_lut), rq::gelu_pair_table(D[j][1], gelu_lut),
+                                         rq::gelu_pair_table(D[j][2], gelu_lut), rq::gelu_pair_table(D[j][3], gelu_lut));
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    uint32_t w[4] = {G[0][j].x, G[0][j].y, G[0][j].z, G[0][j].w};
+#pragma unroll
+                    for (int d = 0; d < 4; ++d)
+                        w[d] = rq::gelu_one_any(w[d] & 0xFFFFu, gelu_lut) | (rq::gelu_one_any(w[d] >> 16, gelu_lut) << 16);
+                    G[0][j] = make_uint4(w[0], w[1], w[2], w[3]);
+                }
             }
         }
         if constexpr (LN) {
@@ -419,18 +468,20 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
                 // step (hi - lo) / 15, zero point rne(-lo / step) in [0, 15]; u = rne(z / step) + zp is formed as the low mantissa
                 // bits of z * inv + (MAGIC - 8 + zp) (MAGIC carries the + 8 of the symmetric codes) and clamped to [0, 15] there
                 const float range = amax[t] + nmin[t];
-                delta = range / 15.0f;
-                inv = range > 0.0f ? 15.0f * __builtin_amdgcn_rcpf(range) : 0.0f;
+                const bool live = range >= 15.0f * kMinStep;
+                delta = live ? range / 15.0f : 0.0f;
+                inv = live ? 15.0f * __builtin_amdgcn_rcpf(range) : 0.0f;
                 zp = __builtin_rintf(nmin[t] * inv);
                 magic = rq::MAGIC - 8.0f + zp;
             } else if constexpr (STATIC) {
                 delta = step[(size_t)min(row, rows - 1) * step_stride];
-                inv = delta > 0.0f ? 1.0f / delta : 0.0f;
+                inv = delta >= kMinStep ? 1.0f / delta : 0.0f;
             } else {
                 // hardware reciprocal (1 ulp) instead of two IEEE divisions: |z| * inv <= qmax (1 + 2^-22) still rounds to qmax
                 const float qmax = (CB == 4 || CB == 6) ? 7.0f : qmax8;
-                delta = amax[t] / qmax;
-                inv = amax[t] > 0.0f ? qmax * __builtin_amdgcn_rcpf(amax[t]) : 0.0f;
+                const bool live = amax[t] >= qmax * kMinStep;
+                delta = live ? amax[t] / qmax : 0.0f;
+                inv = live ? qmax * __builtin_amdgcn_rcpf(amax[t]) : 0.0f;
             }
             if constexpr (CB == 6) {
                 // The lane's NL codes are positions P0 .. P0 + NL - 1 of the row, i.e. NL / 32 whole blobs; field f of a blob is local
@@ -681,9 +732,40 @@ hipError_t run_rotate_quant_asym_mfma(const void *X, int rows, int K, const int8
     return hipGetLastError();
 }
 
+// The activation table: entry e (sign = e >> 12, magnitude bits 0x3580 + (e & 0xFFF)) = bf16(x Phi(x)), evaluated in double
+// (Phi(x) = erfc(-x / sqrt 2) / 2, so that the negative tail keeps its relative accuracy) and rounded once, to nearest even,
+// subnormal results included.
+__global__ __launch_bounds__(256) void gelu_table_kernel(uint16_t *__restrict__ table)
+{
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= rq::GELU_TABLE_ENTRIES) return;
+    const uint32_t bits = ((uint32_t)(e >> 12) << 15) | (rq::GELU_U0 + (uint32_t)(e & 0xFFF));
+    const double x = (double)__uint_as_float(bits << 16);
+    const double y = x * (0.5 * erfc(-x * 0.70710678118654752440));
+    const double a = fabs(y);
+    uint32_t r = 0;
+    if (a > 0.0) {
+        int ex;
+        (void)frexp(a, &ex);                               // a = m 2^ex, 0.5 <= m < 1: the leading bit has weight 2^(ex - 1)
+        if (ex - 1 >= -126) {                              // normal bf16: 8 significant bits; a carry out of them bumps the exponent field
+            const uint32_t q = (uint32_t)rint(ldexp(a, 7 - (ex - 1)));     // 128 .. 256
+            r = ((uint32_t)(ex - 1 + 127) << 7) + (q - 128u);
+        } else {
+            r = (uint32_t)rint(ldexp(a, 133));             // subnormal: multiples of 2^-133; 128 is the smallest normal
+        }
+    }
+    table[e] = (uint16_t)(r | (signbit(y) ? 0x8000u : 0u));
+}
+
+hipError_t run_gelu_table(void *table, hipStream_t stream)
+{
+    gelu_table_kernel<<<rq::GELU_TABLE_ENTRIES / 256, 256, 0, stream>>>(reinterpret_cast<uint16_t *>(table));
+    return hipGetLastError();
+}
+
 // GELU + rotation + smoothing + per-token 4-bit codes, packed rows (e2m3 = false) or E2M3 blocks, bf16 rows, K = 1024 / 2048 / 4096
-hipError_t run_gelu_rotate_quant_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, uint8_t *out,
-                                      float *scale, bool e2m3, hipStream_t stream)
+hipError_t run_gelu_rotate_quant_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, const void *gelu_table,
+                                      uint8_t *out, float *scale, bool e2m3, hipStream_t stream)
 {
     if (rows <= 0) return hipSuccess;
     const uint16_t *x = reinterpret_cast<const uint16_t *>(X);
@@ -692,7 +774,7 @@ hipError_t run_gelu_rotate_quant_mfma(const void *X, int rows, int K, const int8
     int blocks = (ntiles + rq::WAVES_PER_BLOCK - 1) / rq::WAVES_PER_BLOCK;
     if (blocks > 256 * 2) blocks = 256 * 2;
     const LnParams no_ln{nullptr, nullptr, 0.0f, 0};
-#define RQG(KK, CB) rotate_quant_mfma_kernel<KK, 1, 2, false, CB, false, false, false, true><<<blocks, 256, 0, stream>>>(x, rows, signs, mul, 0, out, scale, nullptr, 0, 7.0f, nullptr, no_ln, nullptr)
+#define RQG(KK, CB) rotate_quant_mfma_kernel<KK, 1, 2, false, CB, false, false, false, true><<<blocks, 256, 0, stream>>>(x, rows, signs, mul, 0, out, scale, nullptr, 0, 7.0f, nullptr, no_ln, nullptr, reinterpret_cast<const uint16_t *>(gelu_table))
     switch (K) {
         case 1024: if (e2m3) RQG(1024, 6); else RQG(1024, 4); break;
         case 2048: if (e2m3) RQG(2048, 6); else RQG(2048, 4); break;

@@ -31,6 +31,10 @@ class DsfqLinear:
         if pre_gelu and not (bits == 4 and act_bits == 4 and self.K in (1024, 2048, 4096)):
             raise ValueError("pre_gelu needs the 4-bit setting and K = 1024, 2048 or 4096")
         self.pre_gelu = pre_gelu
+        self.gelu_table = None
+        if pre_gelu:         # the activation as a table of correctly rounded bf16 results, built on the device once
+            self.gelu_table = torch.empty(q.qvggt_gelu_table_bytes(), dtype=torch.uint8, device=weight.device)
+            q.qvggt_gelu_table(self.gelu_table)
         self.bits, self.act_bits, self.bias, self.signs = bits, act_bits, bias, signs
         self.packed = bits == 4 and act_bits == 4            # both 4-bit: two codes per byte; otherwise int8 codes
         dev = weight.device
@@ -79,7 +83,7 @@ class DsfqLinear:
         if self.pre_gelu:
             if X.dtype != torch.bfloat16:
                 raise ValueError("pre_gelu needs bf16 input")
-            q.qvggt_gelu_linear_e2m3(X, self.signs, self.inv_smooth, self.Wf, self.w_scale, self.bias, Y, ws)
+            q.qvggt_gelu_linear_e2m3(X, self.signs, self.inv_smooth, self.gelu_table, self.Wf, self.w_scale, self.bias, Y, ws)
         elif self.packed and self.Wf is not None and X.dtype == torch.bfloat16:
             q.qvggt_linear_e2m3(X, self.signs, self.inv_smooth, self.Wf, self.w_scale, self.bias, Y, ws)      # same Y, bit for bit
         elif self.packed:

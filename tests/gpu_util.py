@@ -93,6 +93,18 @@ def gpu_pack(codes_np):
     return packed
 
 
+_gelu_table = None
+
+
+def gelu_table():
+    """the device table of qvggt_gelu_table (built once per test process)"""
+    global _gelu_table
+    if _gelu_table is None:
+        _gelu_table = torch.empty(q.qvggt_gelu_table_bytes(), dtype=torch.uint8, device=DEV)
+        q.qvggt_gelu_table(_gelu_table)
+    return _gelu_table
+
+
 def codes_to_e2m3(packed, rows, K, out, expect_clean=True):
     """qvggt_codes_to_e2m3 with its counter of codes -8 (which have no E2M3 value): returns the count, 0 expected by default"""
     cnt = torch.zeros(1, dtype=torch.int32, device=DEV)

@@ -167,12 +167,15 @@ def test_argument_validation_needs_no_gpu():
     assert pg(P, 0, 32, 1024, None, None, P + 8, 4, P, P, P, None) == ALIGN
     # GELU fused into kernel 1: bf16, K = 1024 / 2048 / 4096 only
     for ge in (lib.qvggt_gelu_rotate_smooth_quant, lib.qvggt_gelu_rotate_smooth_quant_e2m3):
-        assert ge(P, 0, 4, 512, None, None, P, P, None) == SHAPE and ge(P, 1, 4, 1024, None, None, P, P, None) == DTYPE
-        assert ge(P, 0, 4, 1024, None, None, None, P, None) == NULL and ge(P, 0, 4, 1024, None, None, P, P + 4, None) == ALIGN
-        assert ge(None, 0, 0, 1024, None, None, None, None, None) == OK
+        assert ge(P, 0, 4, 512, None, None, P, P, P, None) == SHAPE and ge(P, 1, 4, 1024, None, None, P, P, P, None) == DTYPE
+        assert ge(P, 0, 4, 1024, None, None, P, None, P, None) == NULL and ge(P, 0, 4, 1024, None, None, P, P, P + 4, None) == ALIGN
+        assert ge(P, 0, 4, 1024, None, None, None, P, P, None) == NULL and ge(P, 0, 4, 1024, None, None, P + 8, P, P, None) == ALIGN     # the table
+        assert ge(None, 0, 0, 1024, None, None, None, None, None, None) == OK
     gl = lib.qvggt_gelu_linear_e2m3
-    assert gl(P, 0, 100, 32, 1024, None, None, P, P, None, P, P, q.qvggt_workspace_bytes_e2m3(100, 32, 1024) - 1, None) == WORKSPACE
-    assert gl(P, 0, 100, 32, 768, None, None, P, P, None, P, P, 1 << 20, None) == SHAPE and gl(P, 1, 100, 32, 1024, None, None, P, P, None, P, P, 1 << 20, None) == DTYPE
+    assert gl(P, 0, 100, 32, 1024, None, None, P, P, P, None, P, P, q.qvggt_workspace_bytes_e2m3(100, 32, 1024) - 1, None) == WORKSPACE
+    assert gl(P, 0, 100, 32, 768, None, None, P, P, P, None, P, P, 1 << 20, None) == SHAPE and gl(P, 1, 100, 32, 1024, None, None, P, P, P, None, P, P, 1 << 20, None) == DTYPE
+    assert gl(P, 0, 100, 32, 1024, None, None, None, P, P, None, P, P, 1 << 20, None) == NULL
+    assert lib.qvggt_gelu_table_bytes() == 16384 and lib.qvggt_gelu_table(None, None) == NULL and lib.qvggt_gelu_table(P + 4, None) == ALIGN
     # int8 blocks: format size, converter, direct kernel 1 (bf16, K = 1024 / 2048 / 4096 only), GEMM, whole path
     assert q.qvggt_i8b_bytes(1, 1024) == 128 * 1024 and q.qvggt_i8b_bytes(129, 4096) == 256 * 4096 and q.qvggt_i8b_bytes(5, 1000) == 0
     tb, rb, gb, lb = lib.qvggt_int8_to_blocks, lib.qvggt_rotate_smooth_quant_i8b, lib.qvggt_i8b_gemm, lib.qvggt_linear_i8b

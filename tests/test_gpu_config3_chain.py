@@ -53,8 +53,10 @@ def _linear(path, Xd, prep, bias_d, N, gelu=False):
         prep["Wf"] = torch.empty(q.qvggt_e2m3_bytes(N, K), dtype=torch.uint8, device=G.DEV)
         G.codes_to_e2m3(prep["Wq"], N, K, prep["Wf"])
     ws = torch.empty(q.qvggt_workspace_bytes_e2m3(M, N, K), dtype=torch.uint8, device=G.DEV)
-    fn = q.qvggt_gelu_linear_e2m3 if gelu else q.qvggt_linear_e2m3
-    fn(Xd, prep["signs"], prep["inv"], prep["Wf"], prep["sw"], bias_d, Y, ws)
+    if gelu:
+        q.qvggt_gelu_linear_e2m3(Xd, prep["signs"], prep["inv"], G.gelu_table(), prep["Wf"], prep["sw"], bias_d, Y, ws)
+    else:
+        q.qvggt_linear_e2m3(Xd, prep["signs"], prep["inv"], prep["Wf"], prep["sw"], bias_d, Y, ws)
     return Y
 
 

@@ -198,6 +198,37 @@ def test_zero_rows_and_single_row():
     assert np.array_equal(G.gpu_unpack(Xq1, K), codes[:1])
 
 
+@pytest.mark.parametrize("K,dtype", [(1024, "bf16"), (4096, "bf16"), (256, "f32"), (768, "bf16")])
+def test_rows_at_the_bottom_of_the_fp32_range(K, dtype):
+    """A row whose step would fall below 2^-126 is a zero row on both sides (7 / absmax would overflow in fp32); rows a few
+    binades above that line quantize like any other.  Covers the matrix-core kernel, the generic and the general one."""
+    rows = 12
+    x = np.zeros((rows, K), dtype=np.float32)
+    x[0, 3] = 2.0 ** -120           # one-hot: every rotated value is +-2^-120 / sqrt(K): step below the line -> zero row
+    x[1, 5] = -(2.0 ** -104)        # the same shape well above it: codes +-7 everywhere
+    rng = np.random.default_rng(K)
+    x[2] = rng.standard_normal(K) * 2.0 ** -128          # dense, below the normal range throughout
+    x[3] = rng.standard_normal(K) * 2.0 ** -112          # dense, small but normal
+    x[4] = rng.standard_normal(K)
+    x[5:] = rng.standard_normal((rows - 5, K)) * np.exp2(rng.integers(-110, -90, (rows - 5, 1))).astype(np.float32)
+    X = synth.f32_to_bf16_bits(x) if dtype == "bf16" else x
+    dx, qx, _ = oracle.rotate_smooth_quant(X)
+    assert dx[0] == 0.0 and dx[2] == 0.0 and dx[1] > 0 and dx[3] > 0
+    Xq, sx = G.gpu_rsq(G.to_dev(X), None, None)
+    codes, got = G.gpu_unpack(Xq, K), sx.cpu().numpy().astype(np.float64)
+    assert got[0] == 0.0 and got[2] == 0.0 and not codes[0].any() and not codes[2].any()
+    assert np.all(np.abs(codes[1]) == 7)
+    G.check_codes(codes, qx, f"K={K}")
+    G.check_scales(got, dx, f"K={K}")
+    # a given step below the line: codes 0 (it cannot be inverted either)
+    step = np.array([2.0 ** -127, 2.0 ** -130, 0.0, -1.0] + [2.0 ** -100] * (rows - 4), dtype=np.float32)
+    Xq2, sx2 = G.gpu_rsq_static(G.to_dev(X), None, None, G.to_dev(step), 1)
+    codes2 = G.gpu_unpack(Xq2, K)
+    assert not codes2[:4].any()
+    _, _, Xs = oracle.rotate_smooth_quant(X)
+    G.check_codes(codes2, oracle.quantize_rows_static(Xs, step.astype(np.float64)), f"static K={K}")
+
+
 def test_one_hot_row_is_dispersed_exactly():
     # a single outlier spreads to +-v/sqrt(K) everywhere: every code is +-7 and follows the Hadamard row
     K = 4096

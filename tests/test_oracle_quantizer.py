@@ -150,6 +150,29 @@ def test_quantizer_clamp_is_live_with_a_static_step():
 
 
 # ----------------------------------------------------------------- integer GEMM
+def test_steps_below_the_single_precision_normal_range_count_as_zero():
+    """The steps are handed on as fp32 numbers: a row whose step absmax / qmax falls below 2^-126 (the smallest normal one) is
+    quantized like a row of zeros, the row just above that line like any other; a given step below the line gives codes 0."""
+    tiny = 2.0 ** -126
+    for bits in (4, 8):
+        qmax = (1 << (bits - 1)) - 1
+        A = np.zeros((4, 8))
+        A[0, :4] = [qmax * tiny * 0.999, -tiny, tiny / 3, 0.0]           # step just below the line
+        A[1, :4] = [qmax * tiny, -qmax * tiny / 2, tiny, 0.0]             # step exactly on it
+        A[2, :4] = [1e-30, -5e-31, 2.5e-31, 0.0]                          # far above
+        A[3, :4] = [1e-39, -1e-40, 3e-41, 0.0]                            # what a GELU of x ~ -13 hands on
+        d, q = oracle.quantize_rows(A, bits)
+        assert d[0] == 0.0 and not q[0].any() and d[3] == 0.0 and not q[3].any()
+        assert d[1] == tiny and q[1, 0] == qmax and q[1, 1] == -(qmax + 1) // 2 and q[1, 2] == 1      # -3.5 -> -4, -63.5 -> -64: ties to even
+        assert d[2] == 1e-30 / qmax and q[2, 0] == qmax
+        qs = oracle.quantize_rows_static(A, np.array([tiny * 0.5, tiny, -1.0, 0.0]), bits)
+        assert not qs[0].any() and not qs[2].any() and not qs[3].any()
+        assert qs[1, 0] == qmax and qs[1, 2] == 1
+    d, zp, u = oracle.quantize_rows_asym(np.array([[15 * tiny * 0.99, 0.0, 0.0], [15 * tiny, 0.0, -0.0]]), 4)
+    assert d[0] == 0.0 and zp[0] == 0 and not u[0].any()
+    assert d[1] == tiny and zp[1] == 0 and u[1, 0] == 15
+
+
 def test_int_gemm_brute_force_and_library():
     rng = np.random.default_rng(6)
     M, N, K = 5, 7, 12

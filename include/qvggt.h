@@ -414,6 +414,15 @@ int qvggt_nfds_keep_lowest(const float *score, int D, double p, uint8_t *keep, v
 int qvggt_nfds_kmeans_step(const float *c, int n, int dim, int K, const float *centres_in, float *centres_out,
                            int32_t *labels, void *stream);
 
+/*
+ * Measurement helper (used by the benchmark, not by the path): a register-only loop of the matrix instruction a GEMM is
+ * built on, to state what the matrix pipes of this board sustain when nothing has to be fed to them.  One launch runs
+ * 256 blocks x 4 waves x iters x 16 instructions; kind 0: v_mfma_i32_32x32x32_i8 (2 * 32 * 32 * 32 operations each), kind 1:
+ * v_mfma_f32_32x32x64_f8f6f4 on E2M3 operands (2 * 32 * 32 * 64 each).  sink: device f32 [65536], overwritten.  QVGGT_ERR_ARG
+ * for another kind or iters outside 1 .. 2^24.
+ */
+int qvggt_mfma_ceiling(int kind, int iters, float *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 QVGGT_BF16, QVGGT_F32 = 0, 1
 
 EXPORTS = [
-    "qvggt_status_string", "qvggt_init", "qvggt_rotated_col_absmax", "qvggt_prep_weights", "qvggt_rotate_smooth_quant",
+    "qvggt_status_string", "qvggt_init", "qvggt_mfma_ceiling", "qvggt_rotated_col_absmax", "qvggt_prep_weights", "qvggt_rotate_smooth_quant",
     "qvggt_rotate_smooth_quant_static", "qvggt_layernorm_rotate_smooth_quant",
     "qvggt_rotate_smooth_quant_asym", "qvggt_weight_code_sums", "qvggt_w4a4_gemm_asym",
     "qvggt_e2m3_bytes", "qvggt_codes_to_e2m3", "qvggt_e2m3_gemm",
@@ -61,6 +61,8 @@ def load_library() -> C.CDLL:
     lib.qvggt_status_string.argtypes = [i]
     lib.qvggt_init.restype = i
     lib.qvggt_init.argtypes = []
+    lib.qvggt_mfma_ceiling.restype = i
+    lib.qvggt_mfma_ceiling.argtypes = [i, i, vp, vp]
     lib.qvggt_rotated_col_absmax.restype = i
     lib.qvggt_rotated_col_absmax.argtypes = [vp, i, i, i, vp, vp, vp]
     lib.qvggt_prep_weights.restype = i
@@ -202,6 +204,10 @@ def qvggt_status_string(status: int) -> str:
 
 def qvggt_init():
     _check(load_library().qvggt_init(), "qvggt_init")
+
+
+def qvggt_mfma_ceiling(kind, iters, sink, stream=None):
+    _check(load_library().qvggt_mfma_ceiling(int(kind), int(iters), _ptr(sink), _stream(stream)), "qvggt_mfma_ceiling")
 
 
 def qvggt_rotated_col_absmax(X_cal, signs, absmax_rot, stream=None):

@@ -104,6 +104,7 @@ hipError_t run_e2m3_gemm_shifted(const uint8_t *Xf, const float *sx, const float
 hipError_t run_gelu_rotate_quant_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, const void *gelu_table,
                                       uint8_t *out, float *scale, bool e2m3, hipStream_t stream);
 hipError_t run_gelu_table(void *table, hipStream_t stream);
+hipError_t run_mfma_ceiling(int kind, int iters, float *sink, hipStream_t stream);
 hipError_t run_int8_to_blocks(const int8_t *src, int rows, int K, uint8_t *dst, hipStream_t stream);
 hipError_t run_rotate_quant_i8b_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, uint8_t *out,
                                      float *scale, int bits, hipStream_t stream);
@@ -172,6 +173,14 @@ int prep_weights(const void *W, int w_dtype, int N, int K, const float *act_absm
 extern "C" {
 
 int qvggt_init(void) { return hip_status(qvggt::prepare_device()); }
+
+int qvggt_mfma_ceiling(int kind, int iters, float *sink, void *stream)
+{
+    if ((kind != 0 && kind != 1) || iters < 1 || iters > (1 << 24)) return QVGGT_ERR_ARG;
+    if (!sink) return QVGGT_ERR_NULL;
+    if (!aligned16(sink)) return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_mfma_ceiling(kind, iters, sink, static_cast<hipStream_t>(stream)));
+}
 
 const char *qvggt_status_string(int status)
 {

@@ -79,6 +79,8 @@ def _check_ln(Xq, sx, K, qx, dx, dtype, what):
     assert (d != 0).mean() <= LN_BF16_CODE_FRACTION, f"{what}: {(d != 0).mean():.3e} of the codes differ"
     err = np.abs(got - dx) / np.maximum(dx, 1e-300)
     err[dx == 0] = np.abs(got[dx == 0])
+    G.report("layernorm_fused_bf16", what=what, rows=int(codes.shape[0]), code_mismatch_fraction=float((d != 0).mean()),
+             step_err_max=float(err.max(initial=0)), steps_within_1e5=float((err <= G.SCALE_RTOL).mean()))
     assert err.max(initial=0) <= LN_BF16_SCALE_RTOL_ALL, f"{what}: step rel err {err.max():.3e}"
     assert (err <= G.SCALE_RTOL).mean() >= 0.9, f"{what}: only {(err <= G.SCALE_RTOL).mean():.2f} of the steps within {G.SCALE_RTOL}"
 

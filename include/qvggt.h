@@ -415,6 +415,36 @@ int qvggt_nfds_kmeans_step(const float *c, int n, int dim, int K, const float *c
                            int32_t *labels, void *stream);
 
 /*
+ * Refinement of the smoothing factor and the quantization steps of one layer on a calibration batch (appendix "Experiment
+ * Settings": during calibration c_hat and the steps Delta are learnable, learning rates 5e-3 and 5e-2; Sec. 3.1.2, Eq.
+ * "loss_ori_overall": the objective is the squared distance between the full-precision and the quantized function over the
+ * calibration set).  Offline.  The paper gives no update rule; this library's reading:
+ *     z = (X H) / c,  x_hat = step_x * clamp(rne(z / step_x)),     v = (W H) * c,  w_hat[o] = step_w[o] * clamp(rne(v[o] / step_w[o])),
+ *     y_q = x_hat . w_hat^T + b,     L = (1 / T) sum_t || y_q[t] - y_ref[t] ||^2     (clamp to [-2^(bits-1), 2^(bits-1) - 1]);
+ *   derivatives by the straight-through rules: rounding passes 1; a value whose ROUNDED code leaves the range passes nothing;
+ *   d(quantized value) / d(its step) = rne(u) - u inside the range, the clamp bound outside; c_hat moves through both operands
+ *   (d v / d c = V, d z / d c = -z / c); with x_step == NULL the activation steps are the dynamic per-token ones, max_j |z| / qmax,
+ *   recomputed from each row and held constant in the derivative; with x_step given it is one static step for the tensor and learnable.
+ * qvggt_rotate_rows:  R [M, K] f32 = X . H, H = diag(signs) . Hhat_K (orthonormal), natural channel order: what the loss takes as
+ *   R = X_cal H and V = W H (computed once per layer; they do not change while c_hat and the steps move).  K a power of two in
+ *   [128, 8192].
+ * qvggt_calib_loss_grad:  R [T, K], V [N, K], y_ref [T, N] f32 (the full-precision layer's output on the batch, bias included),
+ *   bias bf16 [N] or NULL, c_hat f32 [K] and w_step f32 [N] positive, x_step f32 [1] or NULL, bits in 4..8.  Outputs f32: loss [1],
+ *   grad_c [K], grad_w_step [N], grad_x_step [1] (given exactly when x_step is: QVGGT_ERR_NULL otherwise).  T, N >= 1, K a
+ *   multiple of 4 up to 8192 (QVGGT_ERR_SHAPE).  workspace: qvggt_calib_workspace_bytes(T, N, K) bytes (0 for an invalid shape),
+ *   16-byte aligned.  fp32 arithmetic, sums in a fixed order (the same call gives the same bits).
+ * qvggt_calib_descent_step:  theta[i] <- max(theta[i] - lr * grad[i], floor), floor > 0 keeping factors and steps positive
+ *   (plain gradient descent with the paper's learning rates; which optimiser the paper's pipeline runs it does not say).
+ * The refined values are deployed by qvggt_prep_weights_given (c_hat, w_step) and qvggt_rotate_smooth_quant_static (x_step).
+ */
+int qvggt_rotate_rows(const void *X, int x_dtype, int M, int K, const int8_t *signs, float *R, void *stream);
+size_t qvggt_calib_workspace_bytes(int T, int N, int K);
+int qvggt_calib_loss_grad(const float *R, const float *V, const float *y_ref, const void *bias, const float *c_hat,
+                          const float *w_step, const float *x_step, int T, int N, int K, int bits, float *loss, float *grad_c,
+                          float *grad_w_step, float *grad_x_step, void *workspace, size_t workspace_bytes, void *stream);
+int qvggt_calib_descent_step(float *theta, const float *grad, int n, float lr, float floor, void *stream);
+
+/*
  * Measurement helper (used by the benchmark, not by the path): a register-only loop of the matrix instruction a GEMM is
  * built on, to state what the matrix pipes of this board sustain when nothing has to be fed to them.  One launch runs
  * 256 blocks x 4 waves x iters x 16 instructions; kind 0: v_mfma_i32_32x32x32_i8 (2 * 32 * 32 * 32 operations each), kind 1:

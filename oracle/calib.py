@@ -8,9 +8,10 @@ The paper gives the objective and the two learning rates and nothing else; the r
     model): L = (1 / T) sum_t || y_ref[t] - y_q[t] ||^2 over the T calibration tokens, y_ref handed in (the full-precision output),
     y_q = x_hat . w_hat^T + b with
         z = (X H) / c,  x_hat = step_x * clamp(round(z / step_x)),      v = (W H) * c,  w_hat[o] = step_w[o] * clamp(round(v[o] / step_w[o]));
-  * rounding is passed straight through: d round(u) / du = 1, and a clamped value passes nothing (d clamp / du = 0 outside
-    [-2^(b-1), 2^(b-1) - 1]); the derivative of a quantized value with respect to its step is round(u) - u inside the range
-    and the clamp bound outside (the usual learned-step-size rule);
+  * rounding is passed straight through: d round(u) / du = 1, and a clamped value passes nothing: a value counts as clamped
+    when its ROUNDED code leaves [-2^(b-1), 2^(b-1) - 1] (so the largest element of a row quantized with its own absmax step,
+    u = +-qmax up to rounding error, is inside whichever way that quotient rounds); the derivative of a quantized value with
+    respect to its step is round(u) - u inside the range and the clamp bound outside (the usual learned-step-size rule);
   * what moves: c_hat (through both operands: the weights are multiplied, the activations divided by it), the per-channel
     weight steps, and the activation step when it is a static one (a single value for the tensor).  A dynamic per-token
     activation step (the paper's default) is recomputed from the row, max |z| / qmax, and treated as a constant in the derivative;
@@ -41,7 +42,7 @@ def fake_quantize(v, step, bits: int = 4, rounding: bool = True):
     u = v / safe
     r = np.rint(u) if rounding else u
     q = np.clip(r, lo, hi)
-    inside = (u >= lo) & (u <= hi) & live
+    inside = (np.rint(u) >= lo) & (np.rint(u) <= hi) & live
     dstep = np.where(inside, q - u, q) * live
     return np.where(live, safe * q, 0.0), inside, dstep
 

@@ -31,6 +31,7 @@ EXPORTS = [
     "qvggt_workspace_bytes_i8", "qvggt_layout_int8",
     "qvggt_nfds_workspace_bytes", "qvggt_nfds_moments", "qvggt_nfds_frame_correlation", "qvggt_nfds_scores",
     "qvggt_nfds_keep_lowest", "qvggt_nfds_kmeans_step",
+    "qvggt_rotate_rows", "qvggt_calib_workspace_bytes", "qvggt_calib_loss_grad", "qvggt_calib_descent_step",
 ]
 
 
@@ -155,6 +156,14 @@ def load_library() -> C.CDLL:
     lib.qvggt_nfds_keep_lowest.argtypes = [vp, i, dbl, vp, vp]
     lib.qvggt_nfds_kmeans_step.restype = i
     lib.qvggt_nfds_kmeans_step.argtypes = [vp, i, i, i, vp, vp, vp, vp]
+    lib.qvggt_rotate_rows.restype = i
+    lib.qvggt_rotate_rows.argtypes = [vp, i, i, i, vp, vp, vp]
+    lib.qvggt_calib_workspace_bytes.restype = sz
+    lib.qvggt_calib_workspace_bytes.argtypes = [i, i, i]
+    lib.qvggt_calib_loss_grad.restype = i
+    lib.qvggt_calib_loss_grad.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, vp, vp, vp, vp, vp, sz, vp]
+    lib.qvggt_calib_descent_step.restype = i
+    lib.qvggt_calib_descent_step.argtypes = [vp, vp, i, f, f, vp]
     lib.qvggt_workspace_bytes.restype = sz
     lib.qvggt_workspace_bytes.argtypes = [i, i, i]
     lib.qvggt_pack_int4.restype = i
@@ -497,3 +506,26 @@ def qvggt_nfds_kmeans_step(c, centres_in, centres_out, labels, stream=None):
     n, dim = c.shape
     _check(load_library().qvggt_nfds_kmeans_step(_ptr(c), n, dim, centres_in.shape[0], _ptr(centres_in), _ptr(centres_out),
                                                  _ptr(labels), _stream(stream)), "qvggt_nfds_kmeans_step")
+
+
+# ---- calibration: learnable smoothing factor and steps (appendix "Experiment Settings")
+def qvggt_rotate_rows(X, signs, R, stream=None):
+    M, K = X.shape
+    _check(load_library().qvggt_rotate_rows(_ptr(X), _dtype_code(X), M, K, _ptr(signs), _ptr(R), _stream(stream)), "qvggt_rotate_rows")
+
+
+def qvggt_calib_workspace_bytes(T: int, N: int, K: int) -> int:
+    return int(load_library().qvggt_calib_workspace_bytes(T, N, K))
+
+
+def qvggt_calib_loss_grad(R, V, y_ref, bias, c_hat, w_step, x_step, bits, loss, grad_c, grad_w_step, grad_x_step, workspace, stream=None):
+    T, K = R.shape
+    N = V.shape[0]
+    _check(load_library().qvggt_calib_loss_grad(_ptr(R), _ptr(V), _ptr(y_ref), _ptr(bias), _ptr(c_hat), _ptr(w_step), _ptr(x_step), T, N, K,
+                                                int(bits), _ptr(loss), _ptr(grad_c), _ptr(grad_w_step), _ptr(grad_x_step), _ptr(workspace),
+                                                workspace.numel() * workspace.element_size(), _stream(stream)), "qvggt_calib_loss_grad")
+
+
+def qvggt_calib_descent_step(theta, grad, lr, floor=1e-8, stream=None):
+    _check(load_library().qvggt_calib_descent_step(_ptr(theta), _ptr(grad), theta.numel(), float(lr), float(floor), _stream(stream)),
+           "qvggt_calib_descent_step")

@@ -16,7 +16,7 @@ BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libqvggt.so")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 SOURCES = ["api.hip", "rotate_quant.hip", "rotate_quant_mfma.hip", "gemm_w4a4.hip", "nfds.hip",
-           "rotate_quant_general.hip", "gemm_e2m3.hip", "ceilings.hip"]
+           "rotate_quant_general.hip", "gemm_e2m3.hip", "ceilings.hip", "calib.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -105,6 +105,12 @@ hipError_t run_gelu_rotate_quant_mfma(const void *X, int rows, int K, const int8
                                       uint8_t *out, float *scale, bool e2m3, hipStream_t stream);
 hipError_t run_gelu_table(void *table, hipStream_t stream);
 hipError_t run_mfma_ceiling(int kind, int iters, float *sink, hipStream_t stream);
+hipError_t run_rotate_only(const void *X, bool f32, int rows, int K, const int8_t *signs, float *out, hipStream_t stream);
+size_t calib_workspace_bytes(int T, int N, int K);
+hipError_t run_calib_loss_grad(const float *R, const float *V, const float *y_ref, const void *bias, const float *c_hat,
+                               const float *w_step, const float *x_step, int T, int N, int K, int bits, float *loss, float *grad_c,
+                               float *grad_w_step, float *grad_x_step, void *workspace, hipStream_t stream);
+hipError_t run_descent_step(float *theta, const float *grad, int n, float lr, float floor_, hipStream_t stream);
 hipError_t run_int8_to_blocks(const int8_t *src, int rows, int K, uint8_t *dst, hipStream_t stream);
 hipError_t run_rotate_quant_i8b_mfma(const void *X, int rows, int K, const int8_t *signs, const float *mul, uint8_t *out,
                                      float *scale, int bits, hipStream_t stream);
@@ -717,6 +723,53 @@ int qvggt_unpack_int4(const uint8_t *packed, int rows, int K, int8_t *codes, voi
     if (!codes || !packed) return QVGGT_ERR_NULL;
     if (!aligned16(codes) || !aligned16(packed)) return QVGGT_ERR_ALIGN;
     return hip_status(qvggt::run_unpack_int4(packed, rows, K, codes, static_cast<hipStream_t>(stream)));
+}
+
+// ---- calibration: the learnable smoothing factor and steps (appendix "Experiment Settings")
+static bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
+static bool valid_calib_shape(int T, int N, int K) { return T >= 1 && T <= (1 << 22) && N >= 1 && N <= (1 << 20) && K >= 4 && K <= qvggt::kMaxK && K % 4 == 0; }
+
+int qvggt_rotate_rows(const void *X, int x_dtype, int M, int K, const int8_t *signs, float *R, void *stream)
+{
+    if (!valid_dtype(x_dtype)) return QVGGT_ERR_DTYPE;
+    if (M < 0 || K < qvggt::kMinK || K > qvggt::kMaxK || (K & (K - 1)) != 0) return QVGGT_ERR_SHAPE;
+    if (M == 0) return QVGGT_OK;
+    if (!X || !R) return QVGGT_ERR_NULL;
+    if (!aligned16(X) || !aligned16(R) || !aligned16(signs)) return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_rotate_only(X, x_dtype == QVGGT_F32, M, K, signs, R, static_cast<hipStream_t>(stream)));
+}
+
+size_t qvggt_calib_workspace_bytes(int T, int N, int K)
+{
+    if (!valid_calib_shape(T, N, K)) return 0;
+    return qvggt::calib_workspace_bytes(T, N, K) + 256;
+}
+
+int qvggt_calib_loss_grad(const float *R, const float *V, const float *y_ref, const void *bias, const float *c_hat, const float *w_step,
+                          const float *x_step, int T, int N, int K, int bits, float *loss, float *grad_c, float *grad_w_step,
+                          float *grad_x_step, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!valid_calib_shape(T, N, K)) return QVGGT_ERR_SHAPE;
+    if (!valid_wide_bits(bits)) return QVGGT_ERR_ARG;
+    if (!R || !V || !y_ref || !c_hat || !w_step || !loss || !grad_c || !grad_w_step || !workspace) return QVGGT_ERR_NULL;
+    if ((x_step != nullptr) != (grad_x_step != nullptr)) return QVGGT_ERR_NULL;      // a static step and its derivative come together
+    if (!aligned16(R) || !aligned16(V) || !aligned16(y_ref) || !aligned16(workspace) || !aligned4(c_hat) || !aligned4(w_step) ||
+        !aligned4(x_step) || !aligned4(loss) || !aligned4(grad_c) || !aligned4(grad_w_step) || !aligned4(grad_x_step) ||
+        (reinterpret_cast<uintptr_t>(bias) & 1u))
+        return QVGGT_ERR_ALIGN;
+    if (workspace_bytes < qvggt_calib_workspace_bytes(T, N, K)) return QVGGT_ERR_WORKSPACE;
+    return hip_status(qvggt::run_calib_loss_grad(R, V, y_ref, bias, c_hat, w_step, x_step, T, N, K, bits, loss, grad_c, grad_w_step,
+                                                 grad_x_step, workspace, static_cast<hipStream_t>(stream)));
+}
+
+int qvggt_calib_descent_step(float *theta, const float *grad, int n, float lr, float floor, void *stream)
+{
+    if (n < 0) return QVGGT_ERR_SHAPE;
+    if (!std::isfinite(lr) || !(floor > 0.0f) || !std::isfinite(floor)) return QVGGT_ERR_ARG;
+    if (n == 0) return QVGGT_OK;
+    if (!theta || !grad) return QVGGT_ERR_NULL;
+    if (!aligned4(theta) || !aligned4(grad)) return QVGGT_ERR_ALIGN;
+    return hip_status(qvggt::run_descent_step(theta, grad, n, lr, floor, static_cast<hipStream_t>(stream)));
 }
 
 // ---- calibration-set arithmetic (Sec. 3.3)

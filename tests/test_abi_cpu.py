@@ -252,6 +252,24 @@ def test_own_workspace_entry_validates_without_a_gpu():
         assert f(P, 0, 4, 32, 1024, None, None, P, P, None, P, None) == 7
 
 
+def test_calibration_entry_points_validate_without_a_gpu():
+    lib = q.load_library()
+    rr, lg, ds = lib.qvggt_rotate_rows, lib.qvggt_calib_loss_grad, lib.qvggt_calib_descent_step
+    assert rr(P, 0, 4, 1000, None, P, None) == SHAPE and rr(P, 0, 4, 768, None, P, None) == SHAPE and rr(P, 3, 4, 1024, None, P, None) == DTYPE
+    assert rr(None, 0, 4, 1024, None, P, None) == NULL and rr(P, 0, 4, 1024, None, P + 4, None) == ALIGN and rr(None, 0, 0, 1024, None, None, None) == OK
+    need = lib.qvggt_calib_workspace_bytes(100, 32, 1024)
+    assert need >= 4 * (2 * 100 * 1024 + 2 * 32 * 1024 + 100 * 32) and lib.qvggt_calib_workspace_bytes(0, 32, 1024) == 0
+    assert lib.qvggt_calib_workspace_bytes(100, 32, 1026) == 0
+    args = lambda **kw: [kw.get("R", P), P, P, None, P, P, kw.get("xs", None), kw.get("T", 100), 32, kw.get("K", 1024), kw.get("bits", 4),
+                         P, P, P, kw.get("gx", None), P, kw.get("wsb", need), None]
+    assert lg(*args(T=0)) == SHAPE and lg(*args(K=1026)) == SHAPE and lg(*args(bits=3)) == ARG and lg(*args(bits=9)) == ARG
+    assert lg(*args(R=None)) == NULL and lg(*args(R=P + 4)) == ALIGN and lg(*args(wsb=need - 1)) == WORKSPACE
+    assert lg(*args(xs=P)) == NULL and lg(*args(gx=P)) == NULL            # a static step and its derivative come together
+    assert ds(P, P, -1, C.c_float(0.1), C.c_float(1e-8), None) == SHAPE and ds(None, P, 4, C.c_float(0.1), C.c_float(1e-8), None) == NULL
+    assert ds(P, P, 4, C.c_float(float("nan")), C.c_float(1e-8), None) == ARG and ds(P, P, 4, C.c_float(0.1), C.c_float(0.0), None) == ARG
+    assert ds(P + 2, P, 4, C.c_float(0.1), C.c_float(1e-8), None) == ALIGN and ds(None, None, 0, C.c_float(0.1), C.c_float(1e-8), None) == OK
+
+
 def test_binding_rejects_host_tensors():
     import torch
     x = torch.zeros(4, 1024, dtype=torch.bfloat16)

@@ -15,6 +15,14 @@ def test_fake_quantize_values_and_rules():
     assert np.allclose(ds[0], [0.0, 0.0, -3 + 2.52, 0.0, 7.0, -8.0])
     y, inside, ds = calib.fake_quantize(v, np.array([0.0]), bits=4)          # a dead step: nothing
     assert not y.any() and not inside.any() and not ds.any()
+    # the clamp is judged on the rounded code: 7.4 rounds to 7 and is inside, 7.6 rounds to 8 and is clamped, and a row's own
+    # absmax step puts its largest element inside however 7 * (x / x) rounds
+    y, inside, ds = calib.fake_quantize(np.array([[7.4, 7.6, -8.4, -8.6]]), 1.0, bits=4)
+    assert y[0].tolist() == [7.0, 7.0, -8.0, -8.0] and inside[0].tolist() == [True, False, True, False]
+    assert np.allclose(ds[0], [7 - 7.4, 7.0, -8 + 8.4, -8.0])
+    for x in (0.1, 1 / 3, 2.7e-5, 123.456):
+        _, inside, _ = calib.fake_quantize(np.array([[x, -x]]), np.array([x / 7]), bits=4)
+        assert inside.all()
     # per-row steps
     y, _, _ = calib.fake_quantize(np.array([[1.0, 2.0], [1.0, 2.0]]), np.array([1.0, 0.8]), bits=4)
     assert np.allclose(y, [[1.0, 2.0], [0.8, 1.6]])                          # 1.25 -> 1, 2.5 -> 2 (ties to even)

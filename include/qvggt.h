@@ -32,7 +32,11 @@
  *     permutation of 0..K-1 that depends only on K, the same for Xq and Wq, so the integer
  *     dot products are unaffected); qvggt_pack_int4 / qvggt_unpack_int4 convert between this
  *     layout and plain int8 codes in natural order and are the only supported way to read
- *     or write such buffers from outside.
+ *     or write such buffers from outside.  For reference, the permutation is the identity except
+ *     for K = 1024, 2048 and 4096, where natural channel e = 128 hb + 32 nt + c (c < 32, nt < 4)
+ *     sits at position c (K / 32) + nt + 4 hb', with hb' = hb except at K = 4096, where bits 3 and
+ *     4 of hb change places (the order in which the matrix-core rotation kernel holds a token);
+ *     position p is the low nibble of byte p / 2 for even p, the high nibble for odd p.
  */
 #ifndef QVGGT_H
 #define QVGGT_H

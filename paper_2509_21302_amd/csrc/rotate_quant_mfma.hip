@@ -269,7 +269,10 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
     // pieces cost 190 us more at 137400 tokens).  The block then iterates as one: same trip count, barriers inside the loop.
     static_assert(!BLK8 || CB == 8, "int8 blocks hold int8 codes");
     constexpr bool BLOCK_FLUSH = ((CB == 6 || BLK8) && REM == 5);
-    __shared__ __attribute__((aligned(16))) uint8_t flush_all[BLOCK_FLUSH ? 4 * 64 * (BLK8 ? 64 : 48) : 16];
+    // a unit's (K-tile's) four pieces start FLUSH_PITCH apart: one 16-byte bank group more than they fill, so that the lanes of a
+    // write (consecutive units) and of a read spread over the banks
+    constexpr int FLUSH_PITCH = (BLK8 ? 256 : 192) + 16;
+    __shared__ __attribute__((aligned(16))) uint8_t flush_all[BLOCK_FLUSH ? 64 * FLUSH_PITCH : 16];
     uint4 G[PF][8];
     int tile = wave;
 #pragma unroll
@@ -517,7 +520,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
                     if constexpr (REM == 5) {
                         // K = 4096: the lane holds both blobs of unit 2 c + g, i.e. that unit's 48 bytes of this wave's token; they go
                         // to the block's flush area [unit][wave][48 bytes]
-                        uint8_t *slot = flush_all + (2 * c + g) * 192 + wave_in_block * 48;
+                        uint8_t *slot = flush_all + (2 * c + g) * FLUSH_PITCH + wave_in_block * 48;
                         if (bb == 0) {
                             *reinterpret_cast<uint4 *>(slot) = make_uint4(blob[0], blob[1], blob[2], blob[3]);
                             *reinterpret_cast<uint2 *>(slot + 32) = make_uint2(blob[4], blob[5]);
@@ -548,7 +551,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
                             // there as dirty lines while the GEMM that follows runs (measured: that GEMM 365 -> 312 us, this kernel + 4 us);
                             // the direct stores of the smaller K stay cached: their pieces are partial lines and their output fits the
                             // memory-side cache, where the GEMM finds it
-                            const uint4 fv = *reinterpret_cast<const uint4 *>(flush_all + j * 16);
+                            const uint4 fv = *reinterpret_cast<const uint4 *>(flush_all + unit * FLUSH_PITCH + within * 16);
                             const v4u nv = {fv.x, fv.y, fv.z, fv.w};
                             __builtin_nontemporal_store(nv, reinterpret_cast<v4u *>(rb + (size_t)unit * 6144 + within * 16));
                         }
@@ -585,7 +588,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
                     if constexpr (REM == 5) {
                         // K = 4096: the lane holds K-tile 2 c + g of this wave's token, 64 bytes; the block's four tokens leave together
                         // (flush area [K-tile][wave][64 bytes]) in runs of 256 bytes, see the 6-bit variant
-                        uint8_t *slot = flush_all + (P0 / 64) * 256 + wave_in_block * 64;
+                        uint8_t *slot = flush_all + (P0 / 64) * FLUSH_PITCH + wave_in_block * 64;
 #pragma unroll
                         for (int d4 = 0; d4 < 4; ++d4)
                             *reinterpret_cast<uint4 *>(slot + ((d4 ^ swz) * 16)) = make_uint4(words[4 * d4], words[4 * d4 + 1], words[4 * d4 + 2], words[4 * d4 + 3]);
@@ -596,7 +599,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
                         for (int i = 0; i < 4; ++i) {
                             const int j = i * 256 + (int)threadIdx.x, kt = j / 16, within = j - 16 * kt;      // 16-byte chunk j of 1024
                             if (row4 + within / 4 < rows) {
-                                const uint4 fv = *reinterpret_cast<const uint4 *>(flush_all + j * 16);
+                                const uint4 fv = *reinterpret_cast<const uint4 *>(flush_all + kt * FLUSH_PITCH + within * 16);
                                 const v4u nv = {fv.x, fv.y, fv.z, fv.w};
                                 __builtin_nontemporal_store(nv, reinterpret_cast<v4u *>(rb + (size_t)kt * 8192 + within * 16));     // as the 6-bit variant
                             }

@@ -62,10 +62,13 @@ def test_rotate_quant_static_step(K, per_token, dtype):
 # bars hold.  With bf16 rows the normalised value is rounded to bf16, and the kernel's fp32 value (relative error about
 # 2e-7) lands on the other side of a rounding midpoint (spaced 2^-8 .. 2^-7 relative) than the oracle's fp64 value for about
 # 5e-5 of the elements.  Such an element then differs by one bf16 ulp, every rotated value of its row moves by up to
-# ulp / sqrt(K), and a row that holds one can see a few codes and its step move: the bars for bf16 are a code off by one
-# on at most 5e-4 of the elements, steps within 1e-5 on nine rows of ten and within 2e-3 on all.
-LN_BF16_CODE_FRACTION = 5e-4
-LN_BF16_SCALE_RTOL_ALL = 2e-3
+# ulp / sqrt(K), and a row that holds one can see a few codes and its step move.  Measured over the cases below (the
+# figures go to the measured-values log on every run): a code off by one on at most 2.9e-5 of the elements (4.7e-6 at
+# the 1031-row case), the worst step 2.2e-4 off, 98.5 % of the steps within 1e-5 in the worst case (one row of 67).  The
+# bars sit a factor of about four above those: 1e-4 of the codes, 1e-3 on every step, 95 % of the steps within 1e-5.
+LN_BF16_CODE_FRACTION = 1e-4
+LN_BF16_SCALE_RTOL_ALL = 1e-3
+LN_BF16_STEPS_EXACT = 0.95
 
 
 def _check_ln(Xq, sx, K, qx, dx, dtype, what):
@@ -82,7 +85,7 @@ def _check_ln(Xq, sx, K, qx, dx, dtype, what):
     G.report("layernorm_fused_bf16", what=what, rows=int(codes.shape[0]), code_mismatch_fraction=float((d != 0).mean()),
              step_err_max=float(err.max(initial=0)), steps_within_1e5=float((err <= G.SCALE_RTOL).mean()))
     assert err.max(initial=0) <= LN_BF16_SCALE_RTOL_ALL, f"{what}: step rel err {err.max():.3e}"
-    assert (err <= G.SCALE_RTOL).mean() >= 0.9, f"{what}: only {(err <= G.SCALE_RTOL).mean():.2f} of the steps within {G.SCALE_RTOL}"
+    assert (err <= G.SCALE_RTOL).mean() >= LN_BF16_STEPS_EXACT, f"{what}: only {(err <= G.SCALE_RTOL).mean():.2f} of the steps within {G.SCALE_RTOL}"
 
 
 @pytest.mark.parametrize("K", [128, 512, 1024, 2048, 4096])

@@ -775,7 +775,7 @@ int qvggt_calib_descent_step(float *theta, const float *grad, int n, float lr, f
 // ---- calibration-set arithmetic (Sec. 3.3)
 namespace {
 // a row of `count` elements must be a whole number of 16-byte vectors, and the totals must stay addressable
-bool valid_row(long long count, int dtype) { return count > 0 && (count * (dtype == QVGGT_F32 ? 4 : 2)) % 16 == 0 && count <= (1LL << 40); }
+bool valid_row(long long count, int dtype) { return count > 0 && count <= (1LL << 40) && (count * (dtype == QVGGT_F32 ? 4 : 2)) % 16 == 0; }
 }  // namespace
 
 size_t qvggt_nfds_workspace_bytes(int rows, long long count, int dtype)

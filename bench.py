@@ -13,7 +13,8 @@ one the throughput targets are stated on.  --bits 8 / 6 time the same layers in 
 codes in 128-row blocks, qvggt_linear_i8b); the default 4-bit run also reports the 8-bit setting as a side measurement
 ("w8a8", and "w8a8_row_major" for the same setting on row-major codes).
 
-Beside the headline (exactly K steps after W warm-up steps) the line carries: the same step repeated back to back for
+Beside the headline (exactly K steps after W warm-up steps; by default 200 after 50, about a quarter of a second of work, so
+that the figure is a steady-state one) the line carries: the same step repeated back to back for
 about two seconds ("sustained": the board settles under its power limit), mean / median / min per kernel from HIP events,
 machine ceilings measured in the run ("ceilings": an elementwise copy, register-only loops of the two matrix instructions),
 the other single-GPU configurations in short ("other_configs"), and the CPU oracle timed per stage on all cores and on one.
@@ -37,8 +38,8 @@ METRIC = "W4A4 GEMM TOPS (% int8 MFMA peak) + rotate-quant GB/s at VGGT-1B shape
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--config", type=int, default=5, choices=[2, 3, 4, 5])
     ap.add_argument("--bits", type=int, default=4, choices=[4, 6, 8], help="quantization setting timed as the headline")
     ap.add_argument("--matrix-path", default="e2m3", choices=["e2m3", "int8"],
@@ -231,7 +232,7 @@ def main():
             rq_ms_all += rq; gemm_ms_all += gm; rq_bytes_all += rq_bytes; rq_method_bytes_all += rq_method_bytes; gemm_ops_all += gemm_ops
         return per_layer, rq_ms_all, gemm_ms_all, rq_bytes_all, gemm_ops_all, rq_method_bytes_all
 
-    per_layer, rq_ms_all, gemm_ms_all, rq_bytes_all, gemm_ops_all, rq_method_bytes_all = per_kernel(layers, headline, args.steps)
+    per_layer, rq_ms_all, gemm_ms_all, rq_bytes_all, gemm_ops_all, rq_method_bytes_all = per_kernel(layers, headline, min(args.steps, 50))
     n_layers = len(layers)
     gemm_tops = gemm_ops_all / gemm_ms_all / 1e9
     rq_gbps = rq_bytes_all / rq_ms_all / 1e6
@@ -239,7 +240,7 @@ def main():
 
     # side measurement: another setting on the same layers (whole path, then per kernel), outside the headline's timed region
     def side_run(ls, key, n=None):
-        n = n or max(3, args.steps // 4)
+        n = n or max(3, min(args.steps // 4, 20))
         timed_steps(ls, key, 2)
         ms8 = timed_steps(ls, key, n) * 1e3 / n
         pl8, rq8, gm8, rqb8, ops8, rqm8 = per_kernel(ls, key, n)

@@ -152,3 +152,19 @@ def test_rows_split_between_the_two_tile_shapes(M, N, K, wide):
     ulp_off = np.abs(G.bf16_bits(Y[idx]).astype(np.int32) - Yo.astype(np.int32))
     assert ulp_off.max() <= 1 and (ulp_off != 0).mean() < 5e-3
     assert not torch.isnan(Y.float()).any().item()                      # every row of Y was written by one of the launches
+
+
+@pytest.mark.parametrize("kind", [0, 1])
+def test_matrix_ceiling_helper_runs_and_repeats(kind):
+    """The benchmark's register-only matrix loop: finishes, writes every slot of its sink, and gives the same sums twice
+    (integer sums for kind 0; the fp32 sums of kind 1 are order-independent only by being the same instruction stream)."""
+    import paper_2509_21302_amd as q
+    sink = torch.full((65536,), float("nan"), dtype=torch.float32, device=G.DEV)
+    q.qvggt_mfma_ceiling(kind, 50, sink)
+    torch.cuda.synchronize()
+    first = sink.clone()
+    assert torch.isfinite(first).all().item()
+    sink.fill_(float("nan"))
+    q.qvggt_mfma_ceiling(kind, 50, sink)
+    torch.cuda.synchronize()
+    assert torch.equal(first, sink)

@@ -212,12 +212,13 @@ def decode_e2m3_rows(buf, rows, K):
 
 def report(name, **values):
     """Measured figures of a GPU test (achieved errors and mismatch fractions, not pass / fail): printed, and appended as one
-    JSON line to gpurun_out/measured.jsonl when that folder exists, from where they are quoted in the design notes."""
+    JSON line to measured.jsonl in the folder QVGGT_MEASURED_DIR names (default: the run's output folder at the repository root)
+    when that folder exists; the bars of the fused-neighbour tests were set from these figures."""
     import json
     import os
     line = json.dumps(dict(test=name, **{k: (float(v) if isinstance(v, (float, np.floating)) else v) for k, v in values.items()}))
     print("measured:", line)
-    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    d = os.environ.get("QVGGT_MEASURED_DIR") or os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
     if os.path.isdir(d):
         with open(os.path.join(d, "measured.jsonl"), "a") as f:
             f.write(line + "\n")

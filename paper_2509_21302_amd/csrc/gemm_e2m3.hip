@@ -466,12 +466,44 @@ static hipError_t launch_e2m3(const uint8_t *Xf, const float *sx, const uint8_t 
     return hipGetLastError();
 }
 
+// Which tile shape runs where.  Both configurations work in rounds (256 big tiles, or 512 small ones: two blocks per compute
+// unit), and a last round that is mostly empty costs as much as a full one.  A round of small tiles does half the work of a round
+// of big ones and measured 0.50 - 0.54 of its duration at K = 1024 and 0.6 - 0.75 at K = 4096.  Three plans are priced in
+// hundredths of a big round: everything big, everything small, or the token rows that fill whole big rounds through the big kernel
+// and the rest through the small one in a second launch on the same stream (rows are independent; the two launches write disjoint
+// rows of Y, and row offsets that are multiples of 256 are whole 128-row blocks of the operand format).  The split has to win by
+// 3 % to be taken.  Measured: 32976 x 4096 -> 1024 (2.02 big rounds) 85.5 -> 78.3 us; at K = 1024 the same token count is left as it
+// was (a split that ignored the launch cost made 32976 x 1024 -> 1024 11 % slower), and so is 137400 x 4096 -> 1024 (8.4 rounds).
+template <class Big, class Small>
+static hipError_t e2m3_by_rounds(int M, int N, int K, Big &&big, Small &&small)
+{
+    const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
+    // the second launch costs about 6 us whatever the shape; a big round takes about 4.7 + 6.7 K / 1024 us (11 us at K = 1024, 31 at 4096)
+    const long long small_unit = (K <= 2048 ? 55 : 70), launch_cost = 600000 / (4700 + 6700LL * K / 1024);
+    const long long big_tiles = (long long)tiles_m * tiles_n;
+    const long long big_cost = (big_tiles + 255) / 256 * 100;
+    const long long small_cost = (((long long)((M + 127) / 128) * ((N + 127) / 128) + 511) / 512) * small_unit;
+    const long long whole_cost = small_cost < big_cost ? small_cost : big_cost;
+    const int main_tile_rows = (int)std::min<long long>(tiles_m, big_tiles / 256 * 256 / tiles_n);
+    if (main_tile_rows > 0 && main_tile_rows < tiles_m) {
+        const int rows_main = main_tile_rows * 256, rows_rem = M - rows_main;
+        const long long main_cost = ((long long)main_tile_rows * tiles_n + 255) / 256 * 100;
+        const long long rem_cost = (((long long)((rows_rem + 127) / 128) * ((N + 127) / 128) + 511) / 512) * small_unit;
+        if ((main_cost + rem_cost + launch_cost) * 100 < whole_cost * 97) {
+            const hipError_t e = big(0, rows_main);
+            if (e != hipSuccess) return e;
+            return small(rows_main, rows_rem);
+        }
+    }
+    return small_cost < big_cost ? small(0, M) : big(0, M);
+}
+
 // E2M3 blocks of both operands -> Y.
 hipError_t run_e2m3_gemm(const uint8_t *Xf, const float *sx, const uint8_t *Wf, const float *sw, const void *bias, int M, int N,
                          int K, void *Y, int32_t *acc_debug, hipStream_t stream)
 {
     if (M <= 0) return hipSuccess;
-    const size_t KB = (size_t)K / 4 * 3;                  // row0 below is a multiple of 256: whole 128-row blocks
+    const size_t KB = (size_t)K / 4 * 3;                  // bytes per row: row0 below is a multiple of 256, i.e. whole 128-row blocks
     auto big = [&](int row0, int rows) {
         return launch_e2m3<4, 4, 2, 2, 5, 1>(Xf + (size_t)row0 * KB, sx + row0, Wf, sw, bias, rows, N, K,
                                              static_cast<uint16_t *>(Y) + (size_t)row0 * N,
@@ -482,14 +514,7 @@ hipError_t run_e2m3_gemm(const uint8_t *Xf, const float *sx, const uint8_t *Wf, 
                                              static_cast<uint16_t *>(Y) + (size_t)row0 * N,
                                              acc_debug ? acc_debug + (size_t)row0 * N : nullptr, stream);
     };
-    // Both configurations work in rounds (256 big tiles, or 512 small ones: two blocks per compute unit), and a last round that is
-    // mostly empty costs as much as a full one.  A round of small tiles does half the work of a round of big ones and measured
-    // 0.50 - 0.54 of its duration at K = 1024 and 0.6 - 0.75 at K = 4096; the cheaper estimate wins (it reproduces the faster choice
-    // on every shape of the five configurations: the small tiles win for a one-frame launch and for 32976 x 1024 -> 1024).
-    const long long big_rounds = ((long long)((M + 255) / 256) * ((N + 255) / 256) + 255) / 256;
-    const long long small_rounds = ((long long)((M + 127) / 128) * ((N + 127) / 128) + 511) / 512;
-    const long long small_cost = small_rounds * (K <= 2048 ? 55 : 70), big_cost = big_rounds * 100;
-    return small_cost < big_cost ? small(0, M) : big(0, M);
+    return e2m3_by_rounds(M, N, K, big, small);
 }
 
 // Activations as u - 7.5 with a zero point per token (xzero), weights as before, wsum their code sums per channel.
@@ -497,11 +522,16 @@ hipError_t run_e2m3_gemm_shifted(const uint8_t *Xf, const float *sx, const float
                                  const float *wsum, const void *bias, int M, int N, int K, void *Y, hipStream_t stream)
 {
     if (M <= 0) return hipSuccess;
-    const long long big_rounds = ((long long)((M + 255) / 256) * ((N + 255) / 256) + 255) / 256;
-    const long long small_rounds = ((long long)((M + 127) / 128) * ((N + 127) / 128) + 511) / 512;
-    if (small_rounds * (K <= 2048 ? 55 : 70) < big_rounds * 100)
-        return launch_e2m3<2, 2, 2, 2, 4, 2, true>(Xf, sx, Wf, sw, bias, M, N, K, Y, nullptr, stream, xzero, wsum);
-    return launch_e2m3<4, 4, 2, 2, 5, 1, true>(Xf, sx, Wf, sw, bias, M, N, K, Y, nullptr, stream, xzero, wsum);
+    const size_t KB = (size_t)K / 4 * 3;
+    auto big = [&](int row0, int rows) {
+        return launch_e2m3<4, 4, 2, 2, 5, 1, true>(Xf + (size_t)row0 * KB, sx + row0, Wf, sw, bias, rows, N, K,
+                                                   static_cast<uint16_t *>(Y) + (size_t)row0 * N, nullptr, stream, xzero + row0, wsum);
+    };
+    auto small = [&](int row0, int rows) {
+        return launch_e2m3<2, 2, 2, 2, 4, 2, true>(Xf + (size_t)row0 * KB, sx + row0, Wf, sw, bias, rows, N, K,
+                                                   static_cast<uint16_t *>(Y) + (size_t)row0 * N, nullptr, stream, xzero + row0, wsum);
+    };
+    return e2m3_by_rounds(M, N, K, big, small);
 }
 
 }  // namespace qvggt

@@ -68,11 +68,14 @@ __device__ inline uint32_t gelu_window(uint32_t w)      // both halves of a pack
     const us2 d = a - u0;
     return *reinterpret_cast<const uint32_t *>(&d);
 }
-// both halves covered by the table (the usual case): two lookups
+// both halves covered by the table (the usual case): two lookups.  Inside the window bits 12..14 of a half are zero, so twice the
+// entry number, the byte offset into the table, is (low 12 bits) << 1 | (bit 15) >> 2, formed for both halves at once (what the
+// shifts carry across the middle is masked out)
 __device__ inline uint32_t gelu_pair_table(uint32_t d, const uint16_t *lut)
 {
-    const uint32_t idx = (d & 0x0FFF0FFFu) | ((d >> 3) & 0x10001000u);
-    return (uint32_t)lut[idx & 0xFFFFu] | ((uint32_t)lut[idx >> 16] << 16);
+    const uint32_t off = ((d << 1) & 0x1FFE1FFEu) | ((d >> 2) & 0x20002000u);
+    const uint8_t *t = reinterpret_cast<const uint8_t *>(lut);
+    return (uint32_t) * reinterpret_cast<const uint16_t *>(t + (off & 0xFFFFu)) | ((uint32_t) * reinterpret_cast<const uint16_t *>(t + (off >> 16)) << 16);
 }
 // any finite value
 __device__ inline uint32_t gelu_one_any(uint32_t bits, const uint16_t *lut)
@@ -296,20 +299,16 @@ __global__ __launch_bounds__(256, OCC) void rotate_quant_mfma_kernel(const uint1
         if constexpr (GELU) {
             // one wave-uniform test per tile: is every value inside the table's window?  (Almost always: outside are exact
             // zeros, |x| < 1e-6 and |x| >= 4096.)  Then two lookups per packed pair; otherwise the general form per value.
-            uint32_t D[8][4], worst = 0;
+            // (a half is inside iff bits 12..14 of its offset from the window's start are zero: OR them all and look once)
+            uint32_t D[8][4], any = 0;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const uint32_t w[4] = {G[0][j].x, G[0][j].y, G[0][j].z, G[0][j].w};
-#pragma unroll
-                for (int d = 0; d < 4; ++d) {
-                    D[j][d] = rq::gelu_window(w[d]);
-                    const uint32_t m = D[j][d] & 0x7FFF7FFFu;
-                    const rq::us2 a = *reinterpret_cast<const rq::us2 *>(&m), bmax = *reinterpret_cast<const rq::us2 *>(&worst);
-                    const rq::us2 mx = __builtin_elementwise_max(a, bmax);
-                    worst = *reinterpret_cast<const uint32_t *>(&mx);
-                }
+                D[j][0] = rq::gelu_window(G[0][j].x); D[j][1] = rq::gelu_window(G[0][j].y);
+                D[j][2] = rq::gelu_window(G[0][j].z); D[j][3] = rq::gelu_window(G[0][j].w);
+                any = any | D[j][0] | D[j][1];
+                any = any | D[j][2] | D[j][3];
             }
-            const bool outside = ((worst & 0xFFFFu) >= 0x1000u) || ((worst >> 16) >= 0x1000u);
+            const bool outside = (any & 0x70007000u) != 0u;
             if (__builtin_amdgcn_ballot_w64(outside) == 0) {
 #pragma unroll
                 for (int j = 0; j < 8; ++j)

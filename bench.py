@@ -350,8 +350,13 @@ def main():
         P2 = L2["prep"]["e2m3"]
         gelu_table = torch.empty(q.qvggt_gelu_table_bytes(), dtype=torch.uint8, device=dev)
         q.qvggt_gelu_table(gelu_table)
-        t_f = event_ms(lambda: q.qvggt_gelu_rotate_smooth_quant_e2m3(L1["Y"], L2["signs"], P2["inv"], gelu_table, L2["Xf"], L2["sx"]), 5)
-        t_p = event_ms(lambda: q.qvggt_rotate_smooth_quant_e2m3(L1["Y"], L2["signs"], P2["inv"], L2["Xf"], L2["sx"]), 5)
+        fused = lambda: q.qvggt_gelu_rotate_smooth_quant_e2m3(L1["Y"], L2["signs"], P2["inv"], gelu_table, L2["Xf"], L2["sx"])
+        plain = lambda: q.qvggt_rotate_smooth_quant_e2m3(L1["Y"], L2["signs"], P2["inv"], L2["Xf"], L2["sx"])
+        # the two in turn, twice, 20 launches each after a launch that is not timed: neither gets the colder board
+        t_f = t_p = 0.0
+        for _ in range(2):
+            t_f += event_ms(fused, 20) / 2
+            t_p += event_ms(plain, 20) / 2
         s2 = L2["spec"]
         gelu_side = dict(tensor=f"fc1 output {s2.M} x {s2.K} bf16", gelu_rotate_quant_ms=t_f, rotate_quant_ms=t_p,
                          activation_pass_bytes_saved=4.0 * s2.M * s2.K,
